@@ -1,0 +1,230 @@
+/*
+ * nbos.h — C ABI of the batched NotebookOS policy replay for AMD MI355X (gfx950).
+ *
+ * What the library computes
+ * -------------------------
+ * Many independent trace-driven replays of NotebookOS's replica-placement and
+ * dynamic GPU-binding policy (paper Sections 3.2.1-3.2.3, 3.3, 3.4.1, 3.4.2).
+ * One replay = one simulated cluster of GPU servers ("hosts") that is fed one
+ * time-ordered trace of notebook-session events:
+ *
+ *   SESSION_START  place R = 3 kernel replicas on 3 distinct hosts. Replicas
+ *                  subscribe to GPUs, they do not commit them (Section 3.2.1).
+ *                  A host is a candidate when its subscription ratio
+ *                  S / (G * R) stays at or below the replay's cap after adding
+ *                  the replica (Section 3.4.1). Among candidates the hosts with
+ *                  the most idle GPUs win, then the lowest subscription, then
+ *                  the lowest host index. Fewer than 3 candidates: scale out or
+ *                  reject (Section 3.4.2).
+ *   CELL           executor election by outcome: the replica whose host is
+ *                  ready and has enough uncommitted GPUs executes, and the GPUs
+ *                  are committed for the cell's duration only (Sections 3.2.2,
+ *                  3.3). When every replica must yield, one replica is migrated
+ *                  to a host that can bind the GPUs at once (Section 3.2.3),
+ *                  else a host is added for it, else the cell is queued and
+ *                  retried periodically, and aborted after max_retries.
+ *   SESSION_END    the replicas give their subscriptions back (after the
+ *                  running cell, if there is one).
+ *
+ * All times are int32 milliseconds, all results are integers; no floating point
+ * is used anywhere, so results are exact and reproducible.
+ *
+ * Pointers
+ * --------
+ * nbos_config / nbos_inputs structs themselves live in HOST memory.
+ * Every array named in nbos_inputs is a DEVICE pointer (HBM). The library
+ * borrows them: it never copies, frees or writes them, and they must stay valid
+ * and unchanged until nbos_replay_destroy. nbos_stats / decision outputs are
+ * written to HOST memory supplied by the caller.
+ *
+ * Errors
+ * ------
+ * Every int32_t entry point returns NBOS_OK (0) or a negative nbos_status.
+ * Nothing throws, aborts or prints. Policy outcomes of a replay (rejected
+ * sessions, aborted cells) are counts in nbos_stats, not errors.
+ */
+#ifndef NBOS_H
+#define NBOS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- limits of this build ------------------------------------------------ */
+#define NBOS_MAX_HOSTS        1024    /* hosts_max upper bound (10-bit host ids)      */
+#define NBOS_MAX_SESSIONS     65536   /* sessions per trace (16-bit ids in decisions) */
+#define NBOS_MAX_GPUS         8       /* G per host, Section 3.4.1: 1..8              */
+#define NBOS_MAX_RETRIES      15
+#define NBOS_MAX_CAP_MILLI    100000  /* subscription-ratio cap 100.0                 */
+#define NBOS_MAX_DUR_MS       86400000 /* one cell runs at most 24 h                  */
+
+typedef enum {
+  NBOS_OK      =  0,
+  NBOS_E_ARG   = -1,   /* null pointer, bad struct_size, parameter out of range        */
+  NBOS_E_RANGE = -2,   /* trace content invalid: unsorted times, time overflow, bad
+                          kind / session id / duration / GPU request / trace index      */
+  NBOS_E_LIMIT = -3,   /* beyond a compiled or device limit (hosts, sessions, LDS)      */
+  NBOS_E_HIP   = -4,   /* a HIP runtime call failed                                     */
+  NBOS_E_NOMEM = -5,   /* host or device allocation failed                              */
+  NBOS_E_STATE = -6    /* call not valid now (e.g. decisions without the log flag)      */
+} nbos_status;
+
+/* ---- flags --------------------------------------------------------------- */
+#define NBOS_F_MIGRATE       0x1u  /* failed election -> replica migration (Section 3.2.3)   */
+#define NBOS_F_SCALE_OUT     0x2u  /* failed placement / migration -> add hosts (3.4.2)      */
+#define NBOS_F_SCALE_IN      0x4u  /* periodic release of empty hosts (3.4.2, last par.)     */
+#define NBOS_F_DECISION_LOG  0x8u  /* keep every decision code per replay (debug, slower)    */
+
+/* ---- event encoding ------------------------------------------------------ */
+#define NBOS_EV_START  0
+#define NBOS_EV_CELL   1
+#define NBOS_EV_END    2
+/* ev_sess_kind = session_id | (kind << 24) */
+
+typedef struct nbos_replay nbos_replay;   /* opaque, owned by the library */
+
+/* Parameters common to all replays of one handle. */
+typedef struct {
+  uint32_t struct_size;         /* = sizeof(nbos_config)                                        */
+  int32_t  n_replays;           /* >= 0                                                         */
+  int32_t  n_traces;            /* >= 1 when n_replays > 0                                      */
+  int32_t  hosts_initial;       /* hosts 0..hosts_initial-1 are ready at time 0; >= 1           */
+  int32_t  hosts_max;           /* >= hosts_initial, <= NBOS_MAX_HOSTS; extra ones start off    */
+  int32_t  gpus_per_host;       /* G, 1..8 (Section 3.4.1)                                      */
+  int32_t  replicas;            /* R, must be 3 (Section 3.2)                                   */
+  uint32_t flags;               /* NBOS_F_*                                                     */
+  int32_t  migration_delay_ms;  /* >= 0; container start + state read of a migrated replica     */
+  int32_t  boot_delay_ms;       /* >= 0; a scaled-out host is ready this long after the request */
+  int32_t  retry_interval_ms;   /* >= 1; period of the retries of a queued cell (3.2.3)         */
+  int32_t  max_retries;         /* 0..NBOS_MAX_RETRIES; then the cell is aborted                */
+  int32_t  scale_interval_ms;   /* >= 1 with NBOS_F_SCALE_IN: auto-scaler period (3.4.2)        */
+  int32_t  scale_in_idle_pct;   /* 0..100: release while empty*100 > ready*pct                  */
+  int32_t  min_hosts;           /* scale-in never goes below this many ready hosts              */
+} nbos_config;
+
+/* The traces and per-replay parameters. All arrays are DEVICE pointers. */
+typedef struct {
+  const int64_t *ev_offset;       /* [n_traces+1] first event of each trace, ev_offset[0] = 0   */
+  const int32_t *ev_time_ms;      /* [ev_offset[n_traces]] >= 0, non-decreasing within a trace  */
+  const int32_t *ev_dur_ms;       /* CELL: 1..NBOS_MAX_DUR_MS; START / END: ignored             */
+  const int32_t *ev_sess_kind;    /* session id (bits 0..23, local to the trace) | kind << 24   */
+  const int32_t *sess_offset;     /* [n_traces+1] first session of each trace                   */
+  const uint8_t *sess_gpus;       /* [sess_offset[n_traces]] GPU request g, 1..gpus_per_host    */
+  const int32_t *trace_of_replay; /* [n_replays] which trace a replay consumes                  */
+  const int32_t *cap_milli;       /* [n_replays] subscription-ratio cap * 1000, 1..MAX_CAP_MILLI*/
+} nbos_inputs;
+
+/*
+ * Result of one replay. Counter semantics (paper Sections 5.2.2-5.2.4 for the
+ * metric definitions):
+ *   cells_immediate   cells whose GPUs were committed by election at submit time
+ *   executor_reused   cell executed by the same replica slot as the previous cell
+ *   delay             start of execution minus submission ("interactivity delay")
+ *   tct               completion minus submission ("task completion time")
+ *   delay_hist[b]     b = 0 for delay 0, else 1 + floor(log2(delay)), capped at 31
+ *   gpu_ms_executed   sum g * duration over started cells
+ *   gpu_ms_committed  sum g * (finish - commit): includes migration / boot waits
+ *   gpu_ms_provisioned integral over [0, t_end] of G * (hosts not off)
+ *   reservation_gpu_ms sum over placed sessions g * (end - start): what the
+ *                     Reservation baseline holds (end = END event time or t_end)
+ *   sub_gpu_ms        integral over [0, t_end] of the cluster's subscribed GPUs
+ *   digest            d = d * 0x100000001B3 + code over all decisions in order,
+ *                     starting from 0xCBF29CE484222325 (wrapping uint64)
+ * Decision code = host | slot << 10 | outcome << 12 | session << 16 | time << 32.
+ */
+typedef struct {
+  int32_t  status;              /* NBOS_OK, or NBOS_E_LIMIT: retry queue overflowed, rest invalid */
+  uint32_t n_decisions;
+  uint32_t sessions_placed, sessions_rejected;
+  uint32_t cells_total, cells_immediate, cells_started, cells_queued, cells_aborted;
+  uint32_t cells_dropped_busy, cells_dropped_unplaced;
+  uint32_t executor_reused, migrations;
+  uint32_t scale_out_hosts, scale_in_hosts, peak_hosts;
+  int32_t  max_delay_ms, t_end_ms;
+  uint32_t delay_hist[32];
+  int64_t  sum_delay_ms, sum_tct_ms;
+  int64_t  gpu_ms_executed, gpu_ms_committed, gpu_ms_provisioned;
+  int64_t  reservation_gpu_ms, sub_gpu_ms;
+  uint64_t digest;
+} nbos_stats;
+
+/* decision outcomes (bits 12..15 of a decision code) */
+#define NBOS_D_PLACE       1   /* replica slot placed on an existing host            */
+#define NBOS_D_PLACE_NEW   2   /* replica slot reserved on a host being booted       */
+#define NBOS_D_REJECT      3   /* session could not be placed                        */
+#define NBOS_D_START       4   /* cell started by election on (slot, host)           */
+#define NBOS_D_MIGRATE     5   /* replica slot migrated to host, cell starts there   */
+#define NBOS_D_SCALE_CELL  6   /* host added for the cell, replica slot moved there  */
+#define NBOS_D_ABORT       7   /* queued cell given up                               */
+#define NBOS_D_SCALE_IN    8   /* empty host released (session field 0)              */
+
+/*
+ * Create a replay batch (paper Sections 3.2-3.4 define the simulated policy).
+ *   cfg, in   host structs, copied. Arrays inside `in` are device pointers,
+ *             borrowed until destroy.
+ *   stream    a hipStream_t (or NULL for the default stream) on the current
+ *             device; all device work of this handle is ordered on it.
+ *   out       receives the handle.
+ * Validates parameters on the host and the trace contents with a device kernel
+ * (synchronises the stream once). Allocates only its own result buffers.
+ * Errors: NBOS_E_ARG, NBOS_E_RANGE, NBOS_E_LIMIT (hosts/sessions/LDS footprint
+ * beyond what one workgroup can hold), NBOS_E_HIP, NBOS_E_NOMEM. *out is NULL
+ * on error.
+ */
+int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in,
+                           void *stream, nbos_replay **out);
+
+/*
+ * Enqueue one full pass: every replay consumes its whole trace (placement,
+ * election, commit/release, migration, scale-out/in, queueing, final drain) and
+ * writes its nbos_stats into the handle's device buffer. Asynchronous on the
+ * handle's stream; may be called repeatedly, every call recomputes the same
+ * results from the same inputs.
+ * Errors: NBOS_E_ARG (null), NBOS_E_HIP.
+ */
+int32_t nbos_replay_run(nbos_replay *h);
+
+/*
+ * Copy the stats of replays [first, first+count) to host_out (host memory,
+ * count * sizeof(nbos_stats) bytes). Synchronises the handle's stream.
+ * Errors: NBOS_E_ARG (null, range), NBOS_E_STATE (never run), NBOS_E_HIP.
+ */
+int32_t nbos_replay_stats(nbos_replay *h, int32_t first, int32_t count,
+                          nbos_stats *host_out);
+
+/*
+ * Only with NBOS_F_DECISION_LOG: copy up to `cap` decision codes of one replay
+ * to host_out (host memory), in processing order. Returns the number of codes
+ * the replay logged (may exceed cap; a replay logs at most its own capacity of
+ * 3 * sessions + events + 4096 codes, n_decisions in the stats counts all).
+ * Negative return = nbos_status. Synchronises the stream.
+ */
+int64_t nbos_replay_decisions(nbos_replay *h, int32_t replay,
+                              uint64_t *host_out, int64_t cap);
+
+/*
+ * Milliseconds the most recent nbos_replay_run spent on the device, measured
+ * with HIP events recorded on the handle's stream around the replay kernel.
+ * Synchronises the stream. Errors: NBOS_E_ARG, NBOS_E_STATE, NBOS_E_HIP.
+ */
+int32_t nbos_replay_last_kernel_ms(nbos_replay *h, float *ms_out);
+
+/* Dynamic LDS bytes per workgroup and waves per workgroup chosen at create. */
+int32_t nbos_replay_launch_info(nbos_replay *h, int32_t *lds_bytes,
+                                int32_t *threads_per_group, int32_t *groups);
+
+/* Free the handle and its device buffers (synchronises the stream). NULL is a no-op. */
+void nbos_replay_destroy(nbos_replay *h);
+
+/* Static, NUL-terminated description of a status code. */
+const char *nbos_strerror(int32_t status);
+
+/* sizeof(nbos_stats) as compiled, for binding self-checks. */
+int32_t nbos_sizeof_stats(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NBOS_H */

@@ -1,0 +1,84 @@
+/*
+ * nbos_oracle.h — interface of the CPU oracle (TEST INFRASTRUCTURE, not product).
+ *
+ * A plain, single-threaded, eager discrete-event replay of NotebookOS's replica
+ * placement and dynamic GPU-binding policy (paper Sections 3.2.1-3.2.3, 3.3,
+ * 3.4.1, 3.4.2), written from the paper's description. It shares no code,
+ * header or table with the GPU library; its own types are declared here.
+ * Only tests, the smoke check and the CPU-baseline leg of the benchmark call it.
+ * All pointers are host pointers.
+ */
+#ifndef NBOS_ORACLE_H
+#define NBOS_ORACLE_H
+#include <stdint.h>
+
+enum { ORC_EV_START = 0, ORC_EV_CELL = 1, ORC_EV_END = 2 };
+
+enum { ORC_F_MIGRATE = 1, ORC_F_SCALE_OUT = 2, ORC_F_SCALE_IN = 4 };
+
+/* decision outcomes written to the log / folded into the digest */
+enum {
+  ORC_D_PLACE = 1, ORC_D_PLACE_NEW = 2, ORC_D_REJECT = 3, ORC_D_START = 4,
+  ORC_D_MIGRATE = 5, ORC_D_SCALE_CELL = 6, ORC_D_ABORT = 7, ORC_D_SCALE_IN = 8
+};
+
+/* error returns of orc_replay (0 = ok) */
+enum {
+  ORC_E_ARG = -1,        /* parameter out of range                                  */
+  ORC_E_INPUT = -2,      /* trace invalid (unsorted, bad kind / id / duration / g)  */
+  ORC_E_NOMEM = -5,
+  ORC_E_INVARIANT = -100 /* -100 - k: self-check k failed (only with check != 0)    */
+};
+
+typedef struct {
+  int32_t hosts_initial, hosts_max, gpus_per_host;
+  uint32_t flags;
+  int32_t migration_delay_ms, boot_delay_ms;
+  int32_t retry_interval_ms, max_retries;
+  int32_t scale_interval_ms, scale_in_idle_pct, min_hosts;
+  int32_t cap_milli;            /* subscription-ratio cap x 1000 of this replay */
+  int32_t check;                /* != 0: verify the invariants after every item */
+} orc_params;
+
+typedef struct {
+  uint32_t n_decisions;
+  uint32_t sessions_placed, sessions_rejected;
+  uint32_t cells_total, cells_immediate, cells_started, cells_queued, cells_aborted;
+  uint32_t cells_dropped_busy, cells_dropped_unplaced;
+  uint32_t executor_reused, migrations;
+  uint32_t scale_out_hosts, scale_in_hosts, peak_hosts;
+  int32_t  max_delay_ms, t_end_ms;
+  uint32_t delay_hist[32];
+  int64_t  sum_delay_ms, sum_tct_ms;
+  int64_t  gpu_ms_executed, gpu_ms_committed, gpu_ms_provisioned;
+  int64_t  reservation_gpu_ms, sub_gpu_ms;
+  uint64_t digest;
+} orc_result;
+
+/* optional dump of the final cluster state, for tests */
+typedef struct {
+  int32_t *host_state;     /* [hosts_max] 0 off, 1 booting, 2 ready                 */
+  int32_t *host_committed; /* [hosts_max] C                                          */
+  int32_t *host_subscribed;/* [hosts_max] S                                          */
+  int32_t *host_nrep;      /* [hosts_max]                                            */
+  int32_t *sess_state;     /* [n_sessions] 0 unplaced 1 idle 2 busy 3 rejected 4 ended */
+  int32_t *sess_hosts;     /* [n_sessions*3]                                         */
+} orc_final;
+
+/*
+ * Replay one trace on one simulated cluster.
+ *   ev_time / ev_dur / ev_sk  n_events entries; ev_sk = session | kind << 24
+ *   sess_gpus                 n_sessions GPU requests
+ *   log                       optional: receives up to log_cap decision codes
+ *   fin                       optional: final state (arrays owned by the caller)
+ * Returns 0 or a negative error.
+ */
+int orc_replay(const orc_params *p,
+               int64_t n_events, const int32_t *ev_time, const int32_t *ev_dur,
+               const int32_t *ev_sk,
+               int32_t n_sessions, const uint8_t *sess_gpus,
+               orc_result *out, uint64_t *log, int64_t log_cap, orc_final *fin);
+
+int orc_sizeof_result(void);
+
+#endif

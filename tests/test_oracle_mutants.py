@@ -1,0 +1,130 @@
+"""Do the pins bite?  Plant one plausible mistake at a time in a COPY of the oracle's C source
+(on the CPU, in a temp dir), rebuild, and require that at least one pin fails."""
+import os
+import subprocess
+import sys
+import types
+
+import pytest
+
+import test_oracle_pins as pins
+from helpers import GOLDEN
+
+MUTANTS = [
+    ("cap: request dropped from the sum", "(h->S + g) * 1000 <=", "(h->S) * 1000 <="),
+    ("cap: R dropped from S/(G*R)", "m->p->cap_milli * m->G * R", "m->p->cap_milli * m->G"),
+    ("placement prefers MORE committed GPUs", "if (x->C != y->C) return x->C < y->C;",
+     "if (x->C != y->C) return x->C > y->C;"),
+    ("placement prefers HIGHER subscription", "if (x->S != y->S) return x->S < y->S;",
+     "if (x->S != y->S) return x->S > y->S;"),
+    ("placement tie to the highest index", "  return a < b;\n}", "  return a > b;\n}"),
+    ("election tie to the highest host", "q->host[i] < q->host[lead]", "q->host[i] > q->host[lead]"),
+    ("election prefers the fullest host", "if (x->C < y->C || (x->C == y->C && q->host[i] < q->host[lead]))",
+     "if (x->C > y->C || (x->C == y->C && q->host[i] < q->host[lead]))"),
+    ("election off by one", "if (x->state != H_READY || m->G - x->C < g) continue;\n    if (lead",
+     "if (x->state != H_READY || m->G - x->C <= g) continue;\n    if (lead"),
+    ("victim is the emptiest host", "if (x->C > y->C || (x->C == y->C && q->host[i] < q->host[victim]))",
+     "if (x->C < y->C || (x->C == y->C && q->host[i] < q->host[victim]))"),
+    ("timer kinds in reverse order", "if (a->prio != b->prio) return a->prio < b->prio;",
+     "if (a->prio != b->prio) return a->prio > b->prio;"),
+    ("timers due AT an arrival run after it", "m.heap[0].time <= t && !m.err", "m.heap[0].time < t && !m.err"),
+    ("GPUs never released", "release(m, q->host[q->exec_slot], q->g);", ""),
+    ("finish ignores the start delay", "int32_t finish = start + q->dur;", "int32_t finish = m->clock + q->dur;"),
+    ("migration delay dropped", "start_cell(m, s, victim, m->clock + m->p->migration_delay_ms, ORC_D_MIGRATE)",
+     "start_cell(m, s, victim, m->clock, ORC_D_MIGRATE)"),
+    ("boot delay dropped for a scaled-out cell", "m->clock + m->p->boot_delay_ms + m->p->migration_delay_ms, ORC_D_SCALE_CELL",
+     "m->clock + m->p->migration_delay_ms, ORC_D_SCALE_CELL"),
+    ("migration ignores the cap", "if (m->G - x->C < g || !cap_ok(m, x, g)) continue;", "if (m->G - x->C < g) continue;"),
+    ("migration forgets to move the subscription", "unsubscribe(m, q->host[victim], g);\n      subscribe(m, dst, g);", "subscribe(m, dst, g);"),
+    ("histogram bucket off by one", "for (int32_t x = delay; x > 0; x >>= 1) b++;", "for (int32_t x = delay; x > 1; x >>= 1) b++;"),
+    ("scale-in releases 3 per period", "released < 2", "released < 3"),
+    ("scale-in releases the lowest empty host", "int h = m->H - 1;\n    while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h--;",
+     "int h = 0;\n    while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h++;"),
+    ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
+    ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
+    ("scale-out not all-or-nothing", "m->n_on + missing <= m->H", "m->n_on < m->H"),
+    ("every start counted immediate", "if (m->clock == q->t_submit) m->r.cells_immediate++;", "m->r.cells_immediate++;"),
+    ("END while busy ends at once", "if (!q->ending) { q->ending = 1; q->has_end = 1; q->end_time = m->clock; }",
+     "q->has_end = 1; q->end_time = m->clock; end_session(m, s);"),
+    ("retry budget off by one", "if (q->retries < m->p->max_retries) {", "if (q->retries <= m->p->max_retries) {"),
+    ("tick keeps running after the last timer", "if (m.heap[0].prio == T_TICK && m.n_heap == 1) break;",
+     "if (m.heap[0].prio == T_TICK && m.n_heap == 1 && m.clock > 100000000) break;"),
+    ("booting host takes part in elections", "if (x->state != H_READY || m->G - x->C < g) continue;\n    if (lead",
+     "if (x->state == H_OFF || m->G - x->C < g) continue;\n    if (lead"),
+    ("subscribed integral uses committed GPUs", "m->r.sub_gpu_ms += m->sum_S * dt;", "m->r.sub_gpu_ms += m->sum_C * dt;"),
+    ("provisioned integral ignores G", "(int64_t)m->n_on * m->G * dt", "(int64_t)m->n_on * dt"),
+    ("tct measured from the start", "m->r.sum_tct_ms += (int64_t)finish - q->t_submit;", "m->r.sum_tct_ms += (int64_t)finish - start;"),
+]
+
+
+def _shim(orc, lib_path):
+    ns = types.SimpleNamespace(**{k: getattr(orc, k) for k in dir(orc) if k.startswith(("D_", "F_", "EV_"))})
+    ns.decode = orc.decode
+    ns.replay = lambda *a, **kw: orc.replay(*a, lib_path=lib_path, **kw)
+
+    def replay_batch(batch, replays=None, check=False, threads=1):
+        out = []
+        for r in (range(batch.n_replays) if replays is None else replays):
+            t = int(batch.trace_of_replay[r])
+            a, b = int(batch.ev_offset[t]), int(batch.ev_offset[t + 1])
+            sa, sb = int(batch.sess_offset[t]), int(batch.sess_offset[t + 1])
+            out.append(ns.replay(batch.config, batch.ev_time[a:b], batch.ev_dur[a:b], batch.ev_sk[a:b],
+                                 batch.sess_gpus[sa:sb], int(batch.cap_milli[r]), check=check))
+        return out
+    ns.replay_batch = replay_batch
+    return ns
+
+
+def run_pins(lib_path):
+    """Exit status 0 iff every pin accepts the oracle build at lib_path (runs in a child process)."""
+    import oracle as orc
+    o = _shim(orc, lib_path)
+    checks = [lambda: pins.test_sr_worked_example(o), lambda: pins.test_sr_counts_idle_replicas_and_uses_R(o)]
+    checks += [lambda n=n: pins.test_hand_worked(o, n) for n in sorted(os.listdir(GOLDEN)) if n.startswith("hand_")]
+    checks += [lambda: pins.test_placement_brute_force(o), lambda: pins.test_election_brute_force(o),
+               lambda: pins.test_no_contention_closed_form(o), lambda: pins.test_single_session_textbook(o),
+               lambda: pins.test_reservation_and_subscription_closed_form(o)]
+    checks += [lambda s=s: pins.test_invariants_random(o, s) for s in range(12)]
+    for c in checks:
+        try:
+            c()
+        except (AssertionError, ValueError, KeyError, IndexError):
+            return 1
+    return 0
+
+
+def _pins_fail(lib_path):
+    here = os.path.dirname(os.path.abspath(__file__))
+    code = ("import sys; sys.path[:0] = [%r, %r]; import test_oracle_mutants as t; sys.exit(t.run_pins(%r))"
+            % (here, os.path.dirname(here), lib_path))
+    try:
+        rc = subprocess.run([sys.executable, "-c", code], timeout=120, stdout=subprocess.DEVNULL,
+                            stderr=subprocess.DEVNULL).returncode
+    except subprocess.TimeoutExpired:
+        return True
+    return rc != 0
+
+
+def _build(oracle, tmp_path, name, edit):
+    odir = os.path.dirname(oracle.__file__)
+    src = open(os.path.join(odir, "nbos_oracle.c")).read()
+    (tmp_path / "nbos_oracle.c").write_text(edit(src))
+    (tmp_path / "nbos_oracle.h").write_text(open(os.path.join(odir, "nbos_oracle.h")).read())
+    out = str(tmp_path / name)
+    subprocess.run(["gcc", "-std=c99", "-O1", "-w", "-fPIC", "-shared", "-o", out, "nbos_oracle.c"],
+                   check=True, cwd=tmp_path)
+    return out
+
+
+def test_unmutated_copy_passes(oracle, tmp_path):
+    assert not _pins_fail(_build(oracle, tmp_path, "clean.so", lambda s: s))
+
+
+@pytest.mark.parametrize("idx", range(len(MUTANTS)), ids=[m[0] for m in MUTANTS])
+def test_pins_catch_mutant(oracle, tmp_path, idx):
+    name, old, new = MUTANTS[idx]
+
+    def edit(src):
+        assert src.count(old) >= 1, f"mutation site gone: {name}"
+        return src.replace(old, new, 1)
+    assert _pins_fail(_build(oracle, tmp_path, f"mutant{idx}.so", edit)), f"no pin notices: {name}"

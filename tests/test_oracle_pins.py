@@ -1,0 +1,309 @@
+"""Pins of the CPU oracle against what the paper and plain arithmetic fix (no GPU).
+
+Each test names the passage it checks. Expected values come from the paper's worked
+example, from hand-worked traces under tests/golden/, from closed forms, from brute
+force on tiny clusters, or from invariants -- never from the oracle itself.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from helpers import code_of, digest_of, events_to_arrays, load_golden, GOLDEN
+from paper_2503_20591_amd import tracegen as tg
+
+S, CELL, END = 0, 1, 2
+BASE = dict(hosts_initial=3, hosts_max=3, gpus_per_host=8, flags=0, migration_delay_ms=0,
+            boot_delay_ms=0, retry_interval_ms=100, max_retries=0, scale_interval_ms=1000,
+            scale_in_idle_pct=0, min_hosts=0)
+
+
+def run(oracle, cfg, events, gpus, cap, **kw):
+    t, d, sk = events_to_arrays(events)
+    return oracle.replay(cfg, t, d, sk, np.asarray(gpus, np.uint8), cap, check=True, **kw)
+
+
+# ---- Section 3.4.1: SR = S / (G * R), printed example 16 / (8 * 3) = 0.667 ---------------------
+
+def test_sr_worked_example(oracle):
+    kv = {}
+    for line in open(os.path.join(GOLDEN, "sr_example.txt")):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=")
+            kv[k.strip()] = int(v)
+    G, n, g = kv["gpus_per_host"], kv["containers"], kv["gpus_per_container"]
+    assert n * g == kv["subscribed"]
+    cfg = dict(BASE, gpus_per_host=G)
+    # 3 hosts: every session puts one replica (container) on each host, so after k sessions
+    # each host serves k containers of g GPUs. The n-th needs SR >= 16/24 = 0.6667.
+    ev = [[i, S, i, 0] for i in range(n)]
+    ok = run(oracle, cfg, ev, [g] * n, kv["sr_milli_rounded"], want_final=True)
+    assert ok["sessions_placed"] == n and ok["sessions_rejected"] == 0
+    assert list(ok["final"]["host_subscribed"]) == [kv["subscribed"]] * 3
+    low = run(oracle, cfg, ev, [g] * n, kv["sr_milli_rounded"] - 1)
+    assert low["sessions_placed"] == n - 1 and low["sessions_rejected"] == 1
+    # exactly at the ratio: 16 * 1000 <= cap * 24  <=>  cap >= 666.67
+    assert run(oracle, cfg, ev, [g] * n, 666)["sessions_rejected"] == 1
+
+
+def test_sr_counts_idle_replicas_and_uses_R(oracle):
+    # S includes replicas that never run (Section 3.4.1). G=4, g=4, cap 1.0: S <= 4*3 = 12,
+    # so exactly 3 sessions fit per host; the 4th is rejected. With R dropped from the formula
+    # only 1 would fit, with S counting active replicas only all would fit.
+    cfg = dict(BASE, gpus_per_host=4)
+    r = run(oracle, cfg, [[0, S, i, 0] for i in range(5)], [4] * 5, 1000)
+    assert (r["sessions_placed"], r["sessions_rejected"]) == (3, 2)
+
+
+# ---- hand-worked traces --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", sorted(f for f in os.listdir(GOLDEN) if f.startswith("hand_")))
+def test_hand_worked(oracle, name):
+    g = load_golden(name)
+    r = run(oracle, g["config"], g["events"], g["sess_gpus"], g["cap_milli"], want_log=True)
+    for k, v in g["expect"].items():
+        assert r[k] == v, (name, k, r[k], v)
+    codes = [code_of(*d) for d in g["decisions"]]
+    assert [int(x) for x in r["log"]] == codes
+    assert r["digest"] == digest_of(codes)
+
+
+# ---- brute force: 3 successive argmins == best feasible triple (Sections 3.2.1, 3.4.1) ----------
+
+def test_placement_brute_force(oracle):
+    rng = np.random.default_rng(7)
+    for trial in range(60):
+        H = int(rng.integers(3, 5))
+        G = 8
+        cap = int(rng.choice([700, 1000, 1500, 2500]))
+        n = int(rng.integers(4, 14))
+        gp = rng.choice([1, 2, 4, 8], n)
+        cfg = dict(BASE, hosts_initial=H, hosts_max=H, gpus_per_host=G)
+        # one long cell right after each START varies the committed GPUs between placements
+        ev, t = [], 0
+        for s in range(n):
+            ev.append([t, S, s, 0]); t += 1
+            if rng.random() < 0.7:
+                ev.append([t, CELL, s, 10_000_000]); t += 1
+        r = run(oracle, cfg, ev, gp, cap, want_log=True)
+        Sh, Ch = [0] * H, [0] * H
+        placed = {}
+        for code in r["log"]:
+            d = oracle.decode(code)
+            s, g = d["session"], int(gp[d["session"]])
+            if d["outcome"] == oracle.D_START:
+                Ch[d["host"]] += g                       # book-keeping of the logged start
+            elif d["outcome"] in (oracle.D_PLACE, oracle.D_REJECT) and (
+                    d["slot"] == 0 or d["outcome"] == oracle.D_REJECT):
+                feas = [h for h in range(H) if (Sh[h] + g) * 1000 <= cap * G * 3]
+                best = None
+                for tri in itertools.combinations(feas, 3):
+                    keys = sorted((Ch[h], Sh[h], h) for h in tri)
+                    if best is None or keys < best:
+                        best = keys
+                if d["outcome"] == oracle.D_REJECT:
+                    assert best is None
+                else:
+                    assert best is not None
+                    placed[s] = [k[2] for k in best]
+                    assert d["host"] == placed[s][0]
+                    for h in placed[s]:
+                        Sh[h] += g
+            elif d["outcome"] == oracle.D_PLACE:
+                assert d["host"] == placed[s][d["slot"]]
+        assert r["sessions_placed"] == len(placed)
+
+
+def test_election_brute_force(oracle):
+    # Section 3.2.2: the executor is a replica whose host can bind g GPUs now; reading: fewest
+    # committed GPUs, then lowest host index. Track C per host from the log and re-derive.
+    rng = np.random.default_rng(11)
+    for trial in range(40):
+        H, G = int(rng.integers(3, 7)), 8
+        n = int(rng.integers(3, 10))
+        gp = rng.choice([1, 2, 4, 8], n)
+        cfg = dict(BASE, hosts_initial=H, hosts_max=H, gpus_per_host=G)
+        ev = [[0, S, s, 0] for s in range(n)]
+        order = rng.permutation(n)
+        ev += [[10 + i, CELL, int(s), 10_000_000] for i, s in enumerate(order)]
+        r = run(oracle, cfg, ev, gp, 100000, want_log=True, want_final=True)
+        hosts = r["final"]["sess_hosts"].reshape(n, 3)
+        Ch = [0] * H
+        started = {}
+        for code in r["log"]:
+            d = oracle.decode(code)
+            if d["outcome"] == oracle.D_START:
+                started[d["session"]] = (d["slot"], d["host"])
+        for s in order:
+            s, g = int(s), int(gp[s])
+            feas = [(Ch[hosts[s, i]], hosts[s, i], i) for i in range(3) if G - Ch[hosts[s, i]] >= g]
+            if feas:
+                c, h, i = min(feas)
+                assert started[s] == (i, h)
+                Ch[h] += g
+            else:
+                assert s not in started
+        assert list(r["final"]["host_committed"]) == [0] * H   # drained at the end
+
+
+# ---- closed forms ---------------------------------------------------------------------------------
+
+def test_no_contention_closed_form(oracle):
+    # cap <= 1/3 means S_h <= G_h: all replicas on a host can run at once (Section 3.4.1: an SR of
+    # 1 or lower guarantees GPUs for any replica; 1/3 guarantees them for every replica at once).
+    for seed in range(6):
+        b = tg.random_case(100 + seed, n_replays=3)
+        b.config["flags"] = tg.F_MIGRATE
+        for r in range(b.n_replays):
+            b.cap_milli[r] = 333
+        for r, res in enumerate(oracle.replay_batch(b, check=True)):
+            assert res["cells_immediate"] == res["cells_started"]
+            assert res["migrations"] == 0 and res["cells_queued"] == 0 and res["cells_aborted"] == 0
+            assert res["sum_delay_ms"] == 0 and res["max_delay_ms"] == 0
+            assert res["gpu_ms_committed"] == res["gpu_ms_executed"]
+            assert res["cells_total"] == (res["cells_started"] + res["cells_dropped_busy"]
+                                          + res["cells_dropped_unplaced"])
+
+
+def test_single_triple_never_migrates(oracle):
+    # H = 3: every placed session lives on all three hosts, so no migration target ever exists.
+    for seed in range(5):
+        b = tg.random_case(200 + seed, n_replays=2)
+        b.config.update(hosts_initial=3, hosts_max=3, flags=tg.F_MIGRATE, min_hosts=0)
+        for res in oracle.replay_batch(b, check=True):
+            assert res["migrations"] == 0
+
+
+def test_single_session_textbook(oracle):
+    # One session alone on an otherwise empty cluster: every cell starts at once on the lowest
+    # host; sums are plain sums over the accepted cells.
+    rng = np.random.default_rng(3)
+    t = np.cumsum(rng.integers(1, 2000, 200))
+    d = rng.integers(1, 1500, 200)
+    ev = [[0, S, 0, 0]] + [[int(a), CELL, 0, int(b)] for a, b in zip(t, d)]
+    r = run(oracle, dict(BASE, hosts_initial=5, hosts_max=5), ev, [2], 2000)
+    free_at, acc = 0, []
+    for a, b in zip(t, d):          # a cell is accepted iff the previous accepted one is over
+        if a >= free_at:
+            acc.append(int(b)); free_at = int(a + b)
+    assert r["cells_started"] == len(acc) == r["cells_immediate"]
+    assert r["cells_dropped_busy"] == 200 - len(acc)
+    assert r["sum_tct_ms"] == sum(acc) and r["gpu_ms_executed"] == 2 * sum(acc)
+    assert r["executor_reused"] == len(acc) - 1
+    assert r["t_end_ms"] == max(int(t[-1]), free_at)
+    assert r["gpu_ms_provisioned"] == 5 * 8 * r["t_end_ms"]
+    assert r["sub_gpu_ms"] == 6 * r["t_end_ms"] and r["reservation_gpu_ms"] == 2 * r["t_end_ms"]
+
+
+def test_reservation_and_subscription_closed_form(oracle):
+    # Reservation holds g GPUs from START to END (Section 5.1.3); with no cells in flight the
+    # subscription integral is 3 g (end - start) per session.
+    rng = np.random.default_rng(5)
+    n = 12
+    st = np.sort(rng.integers(0, 1000, n))
+    en = st + rng.integers(1, 5000, n)
+    gp = rng.choice([1, 2, 4], n)
+    ev = sorted([[int(st[i]), S, i, 0] for i in range(n)] + [[int(en[i]), END, i, 0] for i in range(n)])
+    r = run(oracle, dict(BASE, hosts_initial=6, hosts_max=6), ev, gp, 100000)
+    assert r["sessions_placed"] == n
+    assert r["reservation_gpu_ms"] == int(sum(gp * (en - st)))
+    assert r["sub_gpu_ms"] == 3 * r["reservation_gpu_ms"]
+    assert r["t_end_ms"] == int(en.max())
+
+
+# ---- invariants and identities on randomized cases (checked inside the oracle too) ---------------
+
+@pytest.mark.parametrize("seed", range(40))
+def test_invariants_random(oracle, seed):
+    b = tg.random_case(seed)
+    mig_delay = b.config["migration_delay_ms"]
+    boot = b.config["boot_delay_ms"]
+    for r in range(b.n_replays):
+        t = int(b.trace_of_replay[r])
+        a, e = int(b.ev_offset[t]), int(b.ev_offset[t + 1])
+        sa, se = int(b.sess_offset[t]), int(b.sess_offset[t + 1])
+        res = oracle.replay(b.config, b.ev_time[a:e], b.ev_dur[a:e], b.ev_sk[a:e], b.sess_gpus[sa:se],
+                            int(b.cap_milli[r]), check=True, want_log=True, want_final=True)
+        gp = b.sess_gpus[sa:se]
+        assert res["cells_total"] == (res["cells_started"] + res["cells_aborted"]
+                                      + res["cells_dropped_busy"] + res["cells_dropped_unplaced"])
+        assert sum(res["delay_hist"]) == res["cells_started"]
+        assert res["cells_total"] == int(((b.ev_sk[a:e].view(np.uint32) >> 24) == CELL).sum())
+        # conservation of GPU-milliseconds: waits are migration / boot delays only
+        wait = 0
+        for code in res["log"]:
+            d = oracle.decode(code)
+            if d["outcome"] == oracle.D_MIGRATE:
+                wait += int(gp[d["session"]]) * mig_delay
+            elif d["outcome"] == oracle.D_SCALE_CELL:
+                wait += int(gp[d["session"]]) * (mig_delay + boot)
+        assert res["gpu_ms_committed"] - res["gpu_ms_executed"] == wait
+        assert res["digest"] == digest_of(res["log"])
+        fin = res["final"]
+        assert (fin["host_committed"] == 0).all()
+        hosts = fin["sess_hosts"].reshape(-1, 3)
+        for s in range(len(gp)):
+            if fin["sess_state"][s] in (1, 2):
+                assert len(set(hosts[s])) == 3
+        if not (b.config["flags"] & tg.F_SCALE_OUT):
+            assert res["scale_out_hosts"] == 0 and res["peak_hosts"] == b.config["hosts_initial"]
+        if not (b.config["flags"] & tg.F_MIGRATE):
+            assert res["migrations"] == res["scale_out_hosts"] - sum(
+                1 for c in res["log"] if oracle.decode(c)["outcome"] == oracle.D_PLACE_NEW)
+        assert res["peak_hosts"] <= b.config["hosts_max"]
+
+
+# ---- metamorphic: doubling G and every request doubles GPU-ms and nothing else -------------------
+
+@pytest.mark.parametrize("seed", range(8))
+def test_scaling_gpus_is_a_pure_relabel(oracle, seed):
+    b = tg.random_case(300 + seed, n_replays=2)
+    b.config["gpus_per_host"] = 4
+    b.sess_gpus = np.minimum(b.sess_gpus, 4).astype(np.uint8)
+    one = oracle.replay_batch(b, check=True)
+    b.config["gpus_per_host"] = 8
+    b.sess_gpus = (b.sess_gpus * 2).astype(np.uint8)
+    two = oracle.replay_batch(b, check=True)
+    for x, y in zip(one, two):
+        for k in x:
+            if k.startswith("gpu_ms") or k in ("reservation_gpu_ms", "sub_gpu_ms"):
+                assert y[k] == 2 * x[k], k
+            else:
+                assert y[k] == x[k], k
+
+
+def test_time_shift(oracle):
+    # shifting every event by D shifts t_end by D and adds D * (initial hosts * G) provisioned
+    b = tg.random_case(17, n_replays=1)
+    b.config["flags"] &= ~tg.F_SCALE_IN          # ticks are anchored at time 0
+    x = oracle.replay_batch(b, check=True)[0]
+    D = 12345
+    b.ev_time = (b.ev_time + D).astype(np.int32)
+    y = oracle.replay_batch(b, check=True)[0]
+    for k in x:
+        if k == "t_end_ms":
+            assert y[k] == x[k] + (D if b.ev_time.size else 0)
+        elif k == "gpu_ms_provisioned":
+            assert y[k] == x[k] + (D * b.config["hosts_initial"] * b.config["gpus_per_host"]
+                                   if b.ev_time.size else 0)
+        elif k not in ("digest",):
+            assert y[k] == x[k], k
+
+
+# ---- input validation -----------------------------------------------------------------------------
+
+def test_rejects_bad_input(oracle):
+    def rc(cfg, ev, gp, cap=2000):
+        with pytest.raises(ValueError) as e:
+            run(oracle, cfg, ev, gp, cap)
+        return e.value.args[1]
+    assert rc(BASE, [[5, S, 0, 0], [4, CELL, 0, 1]], [1]) == -2            # unsorted
+    assert rc(BASE, [[0, CELL, 0, 0]], [1]) == -2                          # duration 0
+    assert rc(BASE, [[0, CELL, 1, 5]], [1]) == -2                          # session out of range
+    assert rc(BASE, [[0, 3, 0, 5]], [1]) == -2                             # kind out of range
+    assert rc(BASE, [[0, S, 0, 0]], [9]) == -2                             # g > G
+    assert rc(BASE, [[2_100_000_000, S, 0, 0]], [1]) == -2                 # time overflow
+    assert rc(dict(BASE, gpus_per_host=9), [], []) == -1
+    assert rc(dict(BASE, hosts_max=2), [], []) == -1
+    assert rc(BASE, [], [], cap=0) == -1
