@@ -1,0 +1,197 @@
+"""ctypes binding of libnbos.so: argument marshalling only, every step runs in the HIP kernels.
+
+    rp = Replay(config, device_inputs)     # nbos_replay_create
+    rp.run()                               # nbos_replay_run (async on the stream)
+    st = rp.stats()                        # nbos_replay_stats -> numpy structured array
+
+``device_inputs`` maps the field names of ``nbos_inputs`` to torch CUDA tensors (kept alive by the
+object); ``upload(batch)`` makes them from a host-side trace batch.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so")
+
+F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG = 1, 2, 4, 8
+E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
+
+EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
+           "nbos_replay_last_kernel_ms", "nbos_replay_launch_info", "nbos_replay_destroy",
+           "nbos_strerror", "nbos_sizeof_stats")
+
+
+class NbosConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_replays", C.c_int32), ("n_traces", C.c_int32),
+                ("hosts_initial", C.c_int32), ("hosts_max", C.c_int32), ("gpus_per_host", C.c_int32),
+                ("replicas", C.c_int32), ("flags", C.c_uint32), ("migration_delay_ms", C.c_int32),
+                ("boot_delay_ms", C.c_int32), ("retry_interval_ms", C.c_int32), ("max_retries", C.c_int32),
+                ("scale_interval_ms", C.c_int32), ("scale_in_idle_pct", C.c_int32), ("min_hosts", C.c_int32)]
+
+
+_INPUT_FIELDS = ("ev_offset", "ev_time_ms", "ev_dur_ms", "ev_sess_kind", "sess_offset", "sess_gpus",
+                 "trace_of_replay", "cap_milli")
+
+
+class NbosInputs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _INPUT_FIELDS]
+
+
+STATS_DTYPE = np.dtype(
+    [("status", "<i4"), ("n_decisions", "<u4"), ("sessions_placed", "<u4"), ("sessions_rejected", "<u4"),
+     ("cells_total", "<u4"), ("cells_immediate", "<u4"), ("cells_started", "<u4"), ("cells_queued", "<u4"),
+     ("cells_aborted", "<u4"), ("cells_dropped_busy", "<u4"), ("cells_dropped_unplaced", "<u4"),
+     ("executor_reused", "<u4"), ("migrations", "<u4"), ("scale_out_hosts", "<u4"), ("scale_in_hosts", "<u4"),
+     ("peak_hosts", "<u4"), ("max_delay_ms", "<i4"), ("t_end_ms", "<i4"), ("delay_hist", "<u4", (32,)),
+     ("sum_delay_ms", "<i8"), ("sum_tct_ms", "<i8"), ("gpu_ms_executed", "<i8"), ("gpu_ms_committed", "<i8"),
+     ("gpu_ms_provisioned", "<i8"), ("reservation_gpu_ms", "<i8"), ("sub_gpu_ms", "<i8"), ("digest", "<u8")],
+    align=True)
+
+_lib = None
+
+
+class NbosError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+def load():
+    """Load libnbos.so (built in-tree by ``build.build_library``). No fallback: raises if missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with paper_2503_20591_amd.build.build_library()")
+    lib = C.CDLL(_LIB_PATH)
+    lib.nbos_replay_create.restype = C.c_int32
+    lib.nbos_replay_create.argtypes = [C.POINTER(NbosConfig), C.POINTER(NbosInputs), C.c_void_p,
+                                       C.POINTER(C.c_void_p)]
+    lib.nbos_replay_run.restype = C.c_int32
+    lib.nbos_replay_run.argtypes = [C.c_void_p]
+    lib.nbos_replay_stats.restype = C.c_int32
+    lib.nbos_replay_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.nbos_replay_decisions.restype = C.c_int64
+    lib.nbos_replay_decisions.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]
+    lib.nbos_replay_last_kernel_ms.restype = C.c_int32
+    lib.nbos_replay_last_kernel_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+    lib.nbos_replay_launch_info.restype = C.c_int32
+    lib.nbos_replay_launch_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_int32)]
+    lib.nbos_replay_destroy.restype = None
+    lib.nbos_replay_destroy.argtypes = [C.c_void_p]
+    lib.nbos_strerror.restype = C.c_char_p
+    lib.nbos_strerror.argtypes = [C.c_int32]
+    lib.nbos_sizeof_stats.restype = C.c_int32
+    if lib.nbos_sizeof_stats() != STATS_DTYPE.itemsize:
+        raise RuntimeError("nbos_stats layout mismatch between the binding and libnbos.so")
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().nbos_strerror(int(code)).decode()
+
+
+def make_config(cfg: dict, n_replays: int, n_traces: int, extra_flags: int = 0) -> NbosConfig:
+    c = NbosConfig()
+    c.struct_size = C.sizeof(NbosConfig)
+    c.n_replays, c.n_traces = int(n_replays), int(n_traces)
+    c.replicas = int(cfg.get("replicas", 3))
+    for name in ("hosts_initial", "hosts_max", "gpus_per_host", "migration_delay_ms", "boot_delay_ms",
+                 "retry_interval_ms", "max_retries", "scale_interval_ms", "scale_in_idle_pct", "min_hosts"):
+        setattr(c, name, int(cfg.get(name, 0)))
+    c.flags = int(cfg.get("flags", 0)) | int(extra_flags)
+    return c
+
+
+def upload(batch, device="cuda:0") -> dict:
+    """Copy a host-side trace batch into device tensors named after the nbos_inputs fields."""
+    import torch
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+    return {"ev_offset": t(batch.ev_offset.astype(np.int64)), "ev_time_ms": t(batch.ev_time),
+            "ev_dur_ms": t(batch.ev_dur), "ev_sess_kind": t(batch.ev_sk),
+            "sess_offset": t(batch.sess_offset.astype(np.int32)), "sess_gpus": t(batch.sess_gpus),
+            "trace_of_replay": t(batch.trace_of_replay.astype(np.int32)),
+            "cap_milli": t(batch.cap_milli.astype(np.int32))}
+
+
+class Replay:
+    """Owns one nbos_replay handle. ``inputs``: dict of torch CUDA tensors (borrowed by the library,
+    kept referenced here). ``stream``: a torch.cuda.Stream or None for the current stream."""
+
+    def __init__(self, cfg: dict, inputs: dict, n_replays: int | None = None, n_traces: int | None = None,
+                 stream=None, decision_log: bool = False):
+        import torch
+        lib = load()
+        self._lib = lib
+        self._keep = dict(inputs)
+        n_replays = int(inputs["trace_of_replay"].numel()) if n_replays is None else n_replays
+        n_traces = int(inputs["ev_offset"].numel()) - 1 if n_traces is None else n_traces
+        self.n_replays = n_replays
+        self.config = make_config(cfg, n_replays, n_traces, F_DECISION_LOG if decision_log else 0)
+        ins = NbosInputs()
+        for name in _INPUT_FIELDS:
+            ten = inputs[name]
+            if not ten.is_cuda or not ten.is_contiguous():
+                raise ValueError(f"{name} must be a contiguous CUDA tensor")
+            setattr(ins, name, ten.data_ptr() if ten.numel() else None)
+        self._stream = stream if stream is not None else torch.cuda.current_stream(inputs["cap_milli"].device)
+        h = C.c_void_p()
+        with torch.cuda.device(inputs["cap_milli"].device):
+            rc = lib.nbos_replay_create(C.byref(self.config), C.byref(ins), C.c_void_p(self._stream.cuda_stream),
+                                        C.byref(h))
+        if rc != 0:
+            raise NbosError(rc, "nbos_replay_create")
+        self._h = h
+
+    def run(self):
+        rc = self._lib.nbos_replay_run(self._h)
+        if rc != 0:
+            raise NbosError(rc, "nbos_replay_run")
+
+    def stats(self, first: int = 0, count: int | None = None) -> np.ndarray:
+        count = self.n_replays - first if count is None else count
+        out = np.zeros(count, dtype=STATS_DTYPE)
+        rc = self._lib.nbos_replay_stats(self._h, first, count, out.ctypes.data)
+        if rc != 0:
+            raise NbosError(rc, "nbos_replay_stats")
+        return out
+
+    def decisions(self, replay: int, cap: int = 1 << 22) -> np.ndarray:
+        buf = np.zeros(cap, dtype=np.uint64)
+        n = self._lib.nbos_replay_decisions(self._h, replay, buf.ctypes.data, cap)
+        if n < 0:
+            raise NbosError(int(n), "nbos_replay_decisions")
+        return buf[: min(n, cap)].copy()
+
+    def last_kernel_ms(self) -> float:
+        ms = C.c_float()
+        rc = self._lib.nbos_replay_last_kernel_ms(self._h, C.byref(ms))
+        if rc != 0:
+            raise NbosError(rc, "nbos_replay_last_kernel_ms")
+        return float(ms.value)
+
+    def launch_info(self) -> dict:
+        a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+        self._lib.nbos_replay_launch_info(self._h, C.byref(a), C.byref(b), C.byref(c))
+        return {"lds_bytes": a.value, "threads_per_group": b.value, "groups": c.value}
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.nbos_replay_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def stats_to_dict(row) -> dict:
+    """One stats record as plain Python ints (delay_hist as a list)."""
+    return {n: ([int(x) for x in row[n]] if n == "delay_hist" else int(row[n])) for n in STATS_DTYPE.names}

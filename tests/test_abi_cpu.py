@@ -1,0 +1,84 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2503_20591_amd import replay
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(replay._LIB_PATH):
+        from paper_2503_20591_amd.build import build_library
+        build_library()
+    return replay.load()
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "nbos.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(nbos_[a-z_]+)\s*\(", hdr))
+    assert declared == set(replay.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes(lib):
+    assert lib.nbos_sizeof_stats() == replay.STATS_DTYPE.itemsize == 264
+    assert C.sizeof(replay.NbosConfig) == 15 * 4
+    assert C.sizeof(replay.NbosInputs) == 8 * 8
+
+
+def test_strerror(lib):
+    assert replay.strerror(0) == "ok"
+    seen = {replay.strerror(c) for c in range(-6, 1)}
+    assert len(seen) == 7 and replay.strerror(-99) == "unknown status"
+
+
+def _cfg(**kw):
+    base = dict(hosts_initial=4, hosts_max=4, gpus_per_host=8, flags=0, migration_delay_ms=0, boot_delay_ms=0,
+                retry_interval_ms=1000, max_retries=3, scale_interval_ms=1000, scale_in_idle_pct=10, min_hosts=0)
+    base.update(kw)
+    return base
+
+
+def _create(lib, cfg, n_replays=1, n_traces=1, inputs=True, struct_size=None, out=True):
+    c = replay.make_config(cfg, n_replays, n_traces)
+    if struct_size is not None:
+        c.struct_size = struct_size
+    ins = replay.NbosInputs()
+    h = C.c_void_p()
+    return lib.nbos_replay_create(C.byref(c), C.byref(ins) if inputs else None, None, C.byref(h) if out else None)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(replicas=2), dict(gpus_per_host=0), dict(gpus_per_host=9), dict(hosts_initial=0),
+    dict(hosts_max=3), dict(migration_delay_ms=-1), dict(boot_delay_ms=-1), dict(retry_interval_ms=0),
+    dict(max_retries=16), dict(max_retries=-1), dict(flags=16), dict(flags=4, scale_interval_ms=0),
+    dict(flags=4, scale_in_idle_pct=101), dict(retry_interval_ms=2_000_000_000, max_retries=15)])
+def test_create_rejects_bad_config(lib, bad):
+    assert _create(lib, _cfg(**bad)) == replay.E_ARG
+
+
+def test_create_rejects_null_and_size(lib):
+    assert _create(lib, _cfg(), inputs=False) == replay.E_ARG
+    assert _create(lib, _cfg(), out=False) == replay.E_ARG
+    assert _create(lib, _cfg(), struct_size=12) == replay.E_ARG
+    assert _create(lib, _cfg(), n_replays=-1) == replay.E_ARG
+    assert _create(lib, _cfg(), n_replays=1, n_traces=0) == replay.E_ARG
+    assert _create(lib, _cfg()) == replay.E_ARG                       # null arrays with n_replays > 0
+    assert _create(lib, _cfg(hosts_initial=4, hosts_max=1025)) == replay.E_LIMIT
+
+
+def test_null_handle_calls(lib):
+    assert lib.nbos_replay_run(None) == replay.E_ARG
+    assert lib.nbos_replay_stats(None, 0, 0, None) == replay.E_ARG
+    assert lib.nbos_replay_decisions(None, 0, None, 0) == replay.E_ARG
+    assert lib.nbos_replay_last_kernel_ms(None, None) == replay.E_ARG
+    assert lib.nbos_replay_launch_info(None, None, None, None) == replay.E_ARG
+    lib.nbos_replay_destroy(None)

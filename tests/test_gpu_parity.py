@@ -1,0 +1,234 @@
+"""GPU parity: the HIP replay (through the C ABI) against the CPU oracle, bit for bit.
+
+All outputs are integers, so the bar is exact equality of every field of the result record,
+including the digest of the decision sequence; where the decision log is on, the full sequence
+of decision codes is compared too.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from helpers import GOLDEN, code_of, digest_of, events_to_arrays, load_golden
+from paper_2503_20591_amd import tracegen as tg
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rp():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2503_20591_amd import replay
+    replay.load()          # fails loudly if libnbos.so has not been built
+    return replay
+
+
+def gpu_run(rp, batch, log=False):
+    dev = rp.upload(batch)
+    h = rp.Replay(batch.config, dev, decision_log=log)
+    h.run()
+    st = h.stats()
+    logs = [h.decisions(r) for r in range(batch.n_replays)] if log else None
+    h.close()
+    return st, logs
+
+
+def first_diff(a, b, orc):
+    for i, (x, y) in enumerate(zip(a, b)):
+        if int(x) != int(y):
+            return f"decision {i}: gpu {orc.decode(x)} oracle {orc.decode(y)}"
+    return f"lengths {len(a)} vs {len(b)}"
+
+
+def assert_same(rp, orc, batch, st, logs=None, replays=None, check=False):
+    idx = range(batch.n_replays) if replays is None else replays
+    for r in idx:
+        t = int(batch.trace_of_replay[r])
+        a, b = int(batch.ev_offset[t]), int(batch.ev_offset[t + 1])
+        sa, sb = int(batch.sess_offset[t]), int(batch.sess_offset[t + 1])
+        want = orc.replay(batch.config, batch.ev_time[a:b], batch.ev_dur[a:b], batch.ev_sk[a:b],
+                          batch.sess_gpus[sa:sb], int(batch.cap_milli[r]), check=check, want_log=logs is not None)
+        got = rp.stats_to_dict(st[r])
+        assert got["status"] == 0, (batch.name, r, got["status"])
+        if logs is not None and [int(x) for x in logs[r]] != [int(x) for x in want["log"]]:
+            raise AssertionError(f"{batch.name} replay {r}: {first_diff(logs[r], want['log'], orc)}")
+        for k in orc.RESULT_FIELDS:
+            assert got[k] == want[k], (batch.name, r, k, got[k], want[k])
+
+
+# ---- hand-worked traces straight through the GPU ---------------------------------------------------
+
+@pytest.mark.parametrize("name", sorted(f for f in os.listdir(GOLDEN) if f.startswith("hand_")))
+def test_hand_worked_gpu(rp, name):
+    g = load_golden(name)
+    t, d, sk = events_to_arrays(g["events"])
+    b = tg._pack(g["config"], [(t, d, sk, np.asarray(g["sess_gpus"], np.uint8))], [0], [g["cap_milli"]], name)
+    st, logs = gpu_run(rp, b, log=True)
+    got = rp.stats_to_dict(st[0])
+    for k, v in g["expect"].items():
+        assert got[k] == v, (name, k, got[k], v)
+    codes = [code_of(*x) for x in g["decisions"]]
+    assert [int(x) for x in logs[0]] == codes
+    assert got["digest"] == digest_of(codes)
+
+
+# ---- randomized small clusters: every flag combination, odd delays, END events, shared traces -----
+
+@pytest.mark.parametrize("seed", range(120))
+def test_random_cases(rp, oracle, seed):
+    b = tg.random_case(seed)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+
+
+def test_random_cases_without_log(rp, oracle):
+    for seed in range(120, 150):
+        b = tg.random_case(seed, n_replays=6)
+        st, _ = gpu_run(rp, b)
+        assert_same(rp, oracle, b, st)
+
+
+# ---- the five named workloads at reduced replay counts (full per-replay size) ----------------------
+
+@pytest.mark.parametrize("name,n", [("c1", 1), ("c2", 6), ("c3", 4), ("c5", 24)])
+def test_named_workloads(rp, oracle, name, n):
+    b = tg.workload(name, n_replays=n)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
+def test_named_workload_c4_many_hosts(rp, oracle):
+    # 512 -> 768 hosts: twelve hosts per lane, scale-out, scale-in, END events
+    b = tg.workload("c4", n_replays=2)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+    assert st["scale_out_hosts"].min() > 0
+
+
+# ---- the benchmark configuration at full size: sampled replays + properties that hold for all -----
+
+def test_full_size_bench_config(rp, oracle):
+    b = tg.workload("c2", workers=8)
+    assert b.n_replays == 1024
+    st, _ = gpu_run(rp, b)
+    assert (st["status"] == 0).all()
+    n_cells = 50_000
+    assert (st["cells_total"] == n_cells).all()
+    assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"] + st["cells_dropped_busy"]
+            + st["cells_dropped_unplaced"]).all()
+    assert (st["delay_hist"].sum(axis=1) == st["cells_started"]).all()
+    assert (st["sessions_placed"] + st["sessions_rejected"] == 400).all()
+    assert (st["gpu_ms_committed"] - st["gpu_ms_executed"] >= 0).all()
+    assert (st["gpu_ms_provisioned"] == 30 * 8 * st["t_end_ms"].astype(np.int64)).all()
+    sample = list(range(0, 1024, 64)) + [1, 511, 1023]
+    assert_same(rp, oracle, b, st, replays=sample)
+    # a second run of the same handle recomputes the same results
+    dev = rp.upload(b)
+    h = rp.Replay(b.config, dev)
+    h.run(); h.run()
+    st2 = h.stats()
+    h.close()
+    assert st2.tobytes() == st.tobytes()
+
+
+# ---- edge cases ---------------------------------------------------------------------------------------
+
+def _tiny(cfg, events, gpus, caps, tor=None):
+    t, d, sk = events_to_arrays(events)
+    return tg._pack(cfg, [(t, d, sk, np.asarray(gpus, np.uint8))], tor if tor is not None else [0] * len(caps), caps, "tiny")
+
+
+BASE = dict(hosts_initial=3, hosts_max=3, gpus_per_host=8, flags=0, migration_delay_ms=0, boot_delay_ms=0,
+            retry_interval_ms=100, max_retries=2, scale_interval_ms=1000, scale_in_idle_pct=0, min_hosts=0)
+
+
+def test_empty_trace_and_no_replays(rp, oracle):
+    b = _tiny(BASE, [], [1], [2000])
+    st, _ = gpu_run(rp, b)
+    assert_same(rp, oracle, b, st)
+    assert st["t_end_ms"][0] == 0 and st["digest"][0] == 0xCBF29CE484222325
+    b0 = _tiny(BASE, [[0, 0, 0, 0]], [1], [])
+    dev = rp.upload(b0)
+    h = rp.Replay(b0.config, dev)
+    h.run()
+    assert h.stats().shape == (0,)
+    h.close()
+
+
+def test_ragged_tail_sizes(rp, oracle):
+    # event counts around the 64-event tile: 1, 63, 64, 65, 127, 128, 129
+    traces = []
+    for n in (1, 63, 64, 65, 127, 128, 129):
+        ev = [[0, 0, 0, 0]] + [[10 * i, 1, 0, 7] for i in range(1, n)]
+        t, d, sk = events_to_arrays(ev)
+        traces.append((t, d, sk, np.asarray([2], np.uint8)))
+    b = tg._pack(BASE, traces, list(range(len(traces))), [2000] * len(traces), "ragged")
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
+def test_max_hosts_and_single_gpu(rp, oracle):
+    cfg = dict(BASE, hosts_initial=1000, hosts_max=1024, gpus_per_host=1, flags=7, boot_delay_ms=50,
+               migration_delay_ms=20, scale_interval_ms=500, scale_in_idle_pct=5, min_hosts=900)
+    rng = np.random.default_rng(1)
+    n = 600
+    ev = [[i, 0, i, 0] for i in range(n)]
+    tcur = n
+    for i in range(3000):
+        tcur += int(rng.integers(0, 3))
+        ev.append([tcur, 1, int(rng.integers(0, n)), int(rng.integers(1, 400))])
+    ev += [[tcur + 5, 2, i, 0] for i in range(0, n, 2)]
+    b = _tiny(cfg, ev, [1] * n, [334, 1000])
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
+def test_time_near_int32_limit(rp, oracle):
+    cfg = dict(BASE, flags=1, migration_delay_ms=15000, retry_interval_ms=10000, max_retries=6)
+    t0 = 2**31 - 2 - 86_400_000 - 6 * 10000 - 15000
+    ev = [[0, 0, 0, 0], [0, 0, 1, 0], [t0 - 5, 1, 0, 86_400_000], [t0, 1, 1, 86_400_000]]
+    b = _tiny(cfg, ev, [8, 8], [2000])
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
+def test_create_rejects_bad_traces(rp):
+    def rc(events, gpus, caps=(2000,), tor=None, cfg=BASE):
+        b = _tiny(cfg, events, gpus, list(caps), tor)
+        with pytest.raises(rp.NbosError) as e:
+            rp.Replay(b.config, rp.upload(b))
+        return e.value.code
+    assert rc([[5, 0, 0, 0], [4, 1, 0, 1]], [1]) == rp.E_RANGE          # unsorted
+    assert rc([[0, 1, 0, 0]], [1]) == rp.E_RANGE                        # duration 0
+    assert rc([[0, 1, 1, 5]], [1]) == rp.E_RANGE                        # session out of range
+    assert rc([[0, 3, 0, 5]], [1]) == rp.E_RANGE                        # kind out of range
+    assert rc([[0, 0, 0, 0]], [9]) == rp.E_RANGE                        # g > G
+    assert rc([[2_100_000_000, 0, 0, 0]], [1]) == rp.E_RANGE            # time overflow
+    assert rc([[0, 0, 0, 0]], [1], caps=(0,)) == rp.E_RANGE             # cap out of range
+    assert rc([[0, 0, 0, 0]], [1], tor=[1]) == rp.E_RANGE               # trace index out of range
+
+
+def test_stats_before_run_is_an_error(rp):
+    b = _tiny(BASE, [[0, 0, 0, 0]], [1], [2000])
+    h = rp.Replay(b.config, rp.upload(b))
+    with pytest.raises(rp.NbosError) as e:
+        h.stats()
+    assert e.value.code == rp.E_STATE
+    with pytest.raises(rp.NbosError):
+        h.decisions(0)
+    h.close()
+
+
+def test_runs_on_a_side_stream(rp, oracle):
+    import torch
+    b = tg.random_case(7)
+    dev = rp.upload(b)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    h = rp.Replay(b.config, dev, stream=s)
+    h.run()
+    st = h.stats()
+    assert h.last_kernel_ms() > 0
+    h.close()
+    assert_same(rp, oracle, b, st)
