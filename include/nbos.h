@@ -76,6 +76,9 @@ typedef enum {
 #define NBOS_F_SCALE_OUT     0x2u  /* failed placement / migration -> add hosts (3.4.2)      */
 #define NBOS_F_SCALE_IN      0x4u  /* periodic release of empty hosts (3.4.2, last par.)     */
 #define NBOS_F_DECISION_LOG  0x8u  /* keep every decision code per replay (debug, slower)    */
+#define NBOS_F_HOSTS_IN_LDS   0x10u /* use the any-size kernel (host state in LDS) even when
+                                      hosts_max <= 64 would allow the register kernel; same
+                                      results, for cross-checks and comparisons              */
 
 /* ---- event encoding ------------------------------------------------------ */
 #define NBOS_EV_START  0

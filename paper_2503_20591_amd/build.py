@@ -9,7 +9,9 @@ SRC = os.path.join(PKG, "csrc", "nbos_replay.hip")
 LIB = os.path.join(PKG, "libnbos.so")
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               # LDS counters are bumped by one lane on purpose; keep them single ds_add instructions
+               "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def build_library(verbose: bool = False) -> str:

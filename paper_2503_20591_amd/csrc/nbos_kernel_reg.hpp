@@ -1,0 +1,631 @@
+// nbos_kernel_reg.hpp — replay kernel for clusters of at most 64 hosts: host state in registers.
+//
+// One workgroup (one wave64) per replay.
+//
+// GPUs:   fin[j], j < NJ = ceil(hosts_max / 8). Lane L = (hl = L >> 3, k = L & 7) holds in fin[j] the
+//         "busy until" time of GPU k of host 8 j + hl. A GPU is committed at time t iff fin > t, so
+//         the ballot of (fin[j] > now) is a 64-bit word with one byte of busy-GPU bits per host.
+//         Binding g GPUs for a cell (paper Section 3.3) = writing its finish time into the g lowest
+//         free GPUs of the host byte (ballot + lane rank). Completions need no timer: every timer
+//         due at or before an item runs before that item and a completion only lowers C, so
+//         "released once the clock has passed fin" is exact.
+// Hosts:  lane h = host h holds ready_at (0 initial, NEVER while off: provisioning needs no timer
+//         either, Section 3.4.2) and S | replicas << 16 (Section 3.4.1). The committed count C of
+//         every host in lane = host layout comes from the NJ ballots by a byte extract + popcount.
+// Choice: feasibility by ballot; executor election (Section 3.2.2) tests 3 bits of that ballot;
+//         placement / migration target = wave minimum of the packed key (C, S, host), so ties go
+//         to the lowest host index.
+// Events: coalesced dword loads, one event per lane, next tile in flight while the current tile
+//         is consumed from registers (v_readlane). At tile start every lane prefetches the record of
+//         its event's session from LDS; events of sessions in a final state (rejected / ended) are
+//         counted in bulk and skipped. A record written during the tile marks the matching lanes
+//         dirty, and only those are read again from LDS.
+// Timers: RETRY of a queued cell (Section 3.2.3) and the END of a session that was busy when its END
+//         arrived are the only timers that change decisions. The 64 earliest live sorted in
+//         registers (insert = ballot + DPP wave shift, pop = DPP wave shift); later ones wait in an
+//         unsorted LDS array that is only touched when the registers run empty or full.
+// Sessions in LDS: hosts word (3 x 10 bits + last executor slot), time word (busy-until, or submit
+//         time while queued), flags, duration of the queued cell.
+#pragma once
+#include "nbos_common.hpp"
+
+namespace {
+namespace regk {
+
+// cold counters kept in LDS (lane 0 adds with ds_add, no return value)
+enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
+       CS_NON, CS_SUMS, CS_OPENG, CS_N32 };
+enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_N64 };
+
+struct Lds {
+  uint32_t *s_hosts, *s_flag;
+  int32_t *s_time, *s_dur;
+  int32_t *o_t, *o_d;          // overflow timers
+  uint32_t *o_k;
+  uint32_t *hist;
+  uint32_t *c32;
+  unsigned long long *c64;
+};
+
+// hot uniform registers
+struct Regs {
+  uint32_t n_dec, c_total, c_imm, c_started, c_busy, c_unplaced, reused;
+  int64_t sum_dur, g_exec;
+  uint64_t digest;
+  int32_t lazy_max, t_end;
+  int32_t q_n, q_head_t;                 // sorted register queue: size, time of lane 0
+  int32_t o_n, o_min_t, o_min_i;         // overflow: size, minimum
+  uint32_t o_min_k;
+  int32_t status;
+  uint64_t dirty;                        // lanes of the current tile whose prefetched record is stale
+};
+
+template <int NJ>
+struct Ctx {
+  const KParams &p;
+  Lds m;
+  int lane;
+  int32_t slim;              // floor(cap_milli * G * 3 / 1000): S + g <= slim is the cap test
+  uint64_t *dlog;
+  // per-lane state
+  int32_t fin[NJ];
+  int32_t hr;                // ready_at of host = lane
+  uint32_t hs;               // S | nrep << 16 of host = lane
+  int32_t qt, qd;            // sorted timers, entry i in lane i
+  uint32_t qk;
+  uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
+};
+
+__device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
+  if (lane == 0) atomicAdd(&m.c32[idx], v);
+}
+__device__ __forceinline__ void c32_max(Lds &m, int lane, int idx, uint32_t v) {
+  if (lane == 0) atomicMax(&m.c32[idx], v);
+}
+__device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
+  if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
+}
+
+template <int NJ>
+__device__ __forceinline__ void decide(Ctx<NJ> &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
+                                       uint32_t slot, uint32_t host) {
+  uint64_t code = (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) |
+                  ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
+  r.digest = r.digest * 0x100000001B3ULL + code;
+  if (c.dlog) {
+    if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
+  }
+  r.n_dec++;
+}
+
+// write a session record; lanes of the current tile that prefetched it go stale
+template <int NJ>
+__device__ __forceinline__ void sess_write(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
+  if (c.lane == 0) { c.m.s_hosts[s] = hw; c.m.s_time[s] = tm; c.m.s_flag[s] = fl; }
+  r.dirty |= __ballot(c.vsid == s);
+}
+template <int NJ>
+__device__ __forceinline__ void sess_write_flag(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t fl) {
+  if (c.lane == 0) c.m.s_flag[s] = fl;
+  r.dirty |= __ballot(c.vsid == s);
+}
+
+// ---- timers: overflow array in LDS (unsorted) ---------------------------------------------------
+template <int NJ>
+__device__ __forceinline__ void ovf_rescan(Ctx<NJ> &c, Regs &r) {
+  wave_sync();
+  uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
+  int bi = 0;
+  for (int i = c.lane; i < r.o_n; i += WAVE) {
+    uint32_t t = (uint32_t)c.m.o_t[i], l = c.m.o_k[i];
+    if (t < bt || (t == bt && l < bl)) { bt = t; bl = l; bi = i; }
+  }
+  uint32_t mt = wave_min(bt);
+  uint32_t ml = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
+  uint64_t who = __ballot(bt == mt && bl == ml);
+  int src = (int)__builtin_ctzll(who | (1ull << 63));
+  r.o_min_i = lane_get(bi, src);
+  r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
+  r.o_min_k = ml;
+}
+
+template <int NJ>
+__device__ __forceinline__ void ovf_push(Ctx<NJ> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
+  if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
+  if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
+  if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) {
+    r.o_min_t = t; r.o_min_k = k; r.o_min_i = r.o_n;
+  }
+  r.o_n++;
+}
+
+// ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
+// Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
+// registers are empty only if the overflow array is.
+template <int NJ>
+__device__ __forceinline__ void timer_push(Ctx<NJ> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
+  uint32_t k = (kind << 16) | id;
+  if (r.q_n == WAVE) {
+    int32_t mt = lane_get(c.qt, WAVE - 1);
+    uint32_t mk = (uint32_t)lane_get((int)c.qk, WAVE - 1);
+    if (t < mt || (t == mt && k < mk)) {
+      ovf_push(c, r, mt, mk, lane_get(c.qd, WAVE - 1));   // the latest register entry moves out
+      r.q_n = WAVE - 1;
+    } else {
+      ovf_push(c, r, t, k, d);
+      return;
+    }
+  } else if (r.o_n > 0 && !(t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k))) {
+    ovf_push(c, r, t, k, d);
+    return;
+  }
+  bool before = c.lane < r.q_n && (c.qt < t || (c.qt == t && c.qk < k));
+  int pos = __builtin_popcountll(__ballot(before));
+  int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x138, 0xF, 0xF, false);          // wave_shr:1
+  int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x138, 0xF, 0xF, false);
+  uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
+  if (c.lane > pos) { c.qt = st; c.qd = sd; c.qk = sk; }
+  if (c.lane == pos) { c.qt = t; c.qd = d; c.qk = k; }
+  r.q_n++;
+  if (pos == 0) r.q_head_t = t;
+}
+
+// remove the earliest timer (lane 0); refill from the overflow array when the registers run empty
+template <int NJ>
+__device__ __forceinline__ void timer_pop(Ctx<NJ> &c, Regs &r) {
+  c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                // wave_shl:1
+  c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
+  c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
+  r.q_n--;
+  if (r.q_n == 0 && r.o_n > 0) {
+    wave_sync();
+    int i = r.o_min_i, last = r.o_n - 1;
+    int32_t t = uni(c.m.o_t[i]), d = uni(c.m.o_d[i]);
+    uint32_t k = uni(c.m.o_k[i]);
+    int32_t lt = c.m.o_t[last], ld = c.m.o_d[last];
+    uint32_t lk = c.m.o_k[last];
+    if (i != last && c.lane == 0) { c.m.o_t[i] = lt; c.m.o_k[i] = lk; c.m.o_d[i] = ld; }
+    r.o_n = last;
+    if (c.lane == 0) { c.qt = t; c.qd = d; c.qk = k; }
+    r.q_n = 1;
+    ovf_rescan(c, r);
+  }
+  r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
+}
+
+// ---- hosts ----------------------------------------------------------------------------------------
+// committed GPUs of host = lane at time `now`
+template <int NJ>
+__device__ __forceinline__ int committed(const Ctx<NJ> &c, int32_t now) {
+  uint64_t msel = 0;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    uint64_t busy = __ballot(c.fin[j] > now);
+    msel = (c.lane >> 3) == j ? busy : msel;
+  }
+  return __builtin_popcount((uint32_t)(msel >> (8 * (c.lane & 7))) & 0xFFu);
+}
+
+// bind g free GPUs of host h until `finish`
+template <int NJ>
+__device__ __forceinline__ void bind_gpus(Ctx<NJ> &c, int h, int g, int32_t now, int32_t finish) {
+  const int j = h >> 3, hl = h & 7;
+  const bool mine = (c.lane >> 3) == hl && (c.lane & 7) < c.p.G;
+#pragma unroll
+  for (int jj = 0; jj < NJ; jj++) {
+    if (jj == j) {
+      bool fr = mine && c.fin[jj] <= now;
+      int rank = lane_rank(__ballot(fr));
+      if (fr && rank < g) c.fin[jj] = finish;
+    }
+  }
+}
+
+template <int NJ>
+__device__ __forceinline__ int boot_host(Ctx<NJ> &c, Regs &r, int32_t now, uint32_t hs_new) {
+  uint64_t off = __ballot(c.lane < c.p.Hmax && c.hr == NEVER);
+  int h = (int)__builtin_ctzll(off);                 // the caller has checked that one exists
+  int32_t ra = now + c.p.boot;
+  if (c.lane == h) { c.hr = ra; c.hs = hs_new; }
+  c32_add(c.m, c.lane, CS_NON, 1u);
+  c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
+  c32_add(c.m, c.lane, CS_SO, 1u);
+  r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
+  return h;
+}
+
+// ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
+template <int NJ>
+__device__ __forceinline__ void session_start(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
+  if ((fl & 7u) != SS_UNPLACED) return;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const int C = committed(c, now);
+  const int S = (int)(c.hs & 0xFFFFu);
+  uint32_t key = (c.hr <= now && S <= c.slim - g) ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane)
+                                                  : 0xFFFFFFFFu;
+  int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
+  uint32_t m0 = wave_min(key);
+  if (m0 != 0xFFFFFFFFu) {
+    pick0 = (int)(m0 & 1023u); k = 1;
+    key = c.lane == pick0 ? 0xFFFFFFFFu : key;
+    uint32_t m1 = wave_min(key);
+    if (m1 != 0xFFFFFFFFu) {
+      pick1 = (int)(m1 & 1023u); k = 2;
+      key = c.lane == pick1 ? 0xFFFFFFFFu : key;
+      uint32_t m2 = wave_min(key);
+      if (m2 != 0xFFFFFFFFu) { pick2 = (int)(m2 & 1023u); k = 3; }
+    }
+  }
+  const int missing = 3 - k;
+  if (missing > 0) {
+    wave_sync();
+    int n_on = (int)uni(c.m.c32[CS_NON]);
+    if (!((c.p.flags & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
+      sess_write_flag(c, r, s, (fl & ~7u) | SS_REJECTED);
+      c32_add(c.m, c.lane, CS_REJECTED, 1u);
+      decide(c, r, now, NBOS_D_REJECT, s, 0, 0);
+      return;
+    }
+  }
+  const uint32_t add = (uint32_t)g | (1u << 16);
+  uint32_t hw = 0;
+#pragma unroll
+  for (int i = 0; i < 3; i++) {
+    int h = i == 0 ? pick0 : (i == 1 ? pick1 : pick2);
+    if (i < k) {
+      if (c.lane == h) c.hs += add;
+      decide(c, r, now, NBOS_D_PLACE, s, (uint32_t)i, (uint32_t)h);
+    } else {
+      h = boot_host(c, r, now, add);
+      decide(c, r, now, NBOS_D_PLACE_NEW, s, (uint32_t)i, (uint32_t)h);
+    }
+    hw |= (uint32_t)h << (10 * i);
+  }
+  if (missing > 0) {
+    wave_sync();
+    c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
+  }
+  sess_write(c, r, s, hw, 0, (fl & ~7u) | SS_PLACED);
+  c32_add(c.m, c.lane, CS_PLACED, 1u);
+  c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(3 * g));
+  c32_add(c.m, c.lane, CS_OPENG, (uint32_t)g);
+  c64_add(c.m, c.lane, CL_SUB, -(int64_t)(3 * g) * now);
+  c64_add(c.m, c.lane, CL_RESV, -(int64_t)g * now);
+}
+
+// the replicas of session s give their subscriptions back at time `now`
+template <int NJ>
+__device__ __forceinline__ void end_session(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const uint32_t sub = (uint32_t)g | (1u << 16);
+  const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
+  if (c.lane == h0 || c.lane == h1 || c.lane == h2) c.hs -= sub;
+  sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
+  c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(-3 * g));
+  c64_add(c.m, c.lane, CL_SUB, (int64_t)(3 * g) * now);
+}
+
+// ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
+template <int NJ>
+__device__ __forceinline__ void start_cell(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
+                                           int32_t now, int32_t start, int32_t t_submit, int32_t dur,
+                                           uint32_t outcome) {
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const int32_t finish = start + dur;
+  const int32_t delay = start - t_submit;
+  r.c_started++;
+  r.sum_dur += dur;
+  r.g_exec += (int64_t)g * dur;
+  if (delay != 0) {
+    c64_add(c.m, c.lane, CL_SUMDELAY, delay);
+    c32_max(c.m, c.lane, CS_MAXDELAY, (uint32_t)delay);
+    if (start != now) c64_add(c.m, c.lane, CL_GWAIT, (int64_t)g * (start - now));
+  }
+  int b = delay == 0 ? 0 : 32 - __builtin_clz((uint32_t)delay);
+  b = b > 31 ? 31 : b;
+  if (c.lane == 0) atomicAdd(&c.m.hist[b], 1u);
+  const uint32_t last = hw >> 30;               // 0 none, else slot + 1
+  if (last == (uint32_t)slot + 1u) r.reused++;
+  hw = (hw & 0x3FFFFFFFu) | ((uint32_t)(slot + 1) << 30);
+  hw = (hw & ~(1023u << (10 * slot))) | ((uint32_t)host << (10 * slot));
+  sess_write(c, r, s, hw, finish, (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED);
+  r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
+  decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
+  if (fl & SF_ENDING) timer_push(c, r, finish, QK_END, s, 0);
+}
+
+// ---- one attempt to run the pending cell of session s at time `now` -----------------------------
+template <int NJ>
+__device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
+                                        int32_t t_submit, int32_t dur) {
+  const int G = c.p.G;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const int C = committed(c, now);
+  const uint64_t rdy = __ballot(c.hr <= now);
+  const uint64_t idle_ok = __ballot(c.hr <= now && C <= G - g);
+  const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
+  const int C0 = lane_get(C, h0), C1 = lane_get(C, h1), C2 = lane_get(C, h2);
+  // (a) election, Section 3.2.2: feasible replica with the fewest committed GPUs, then lowest host
+  const uint32_t k0 = ((idle_ok >> h0) & 1u) ? (((uint32_t)C0 << 12) | ((uint32_t)h0 << 2) | 0u) : 0xFFFFFFFFu;
+  const uint32_t k1 = ((idle_ok >> h1) & 1u) ? (((uint32_t)C1 << 12) | ((uint32_t)h1 << 2) | 1u) : 0xFFFFFFFFu;
+  const uint32_t k2 = ((idle_ok >> h2) & 1u) ? (((uint32_t)C2 << 12) | ((uint32_t)h2 << 2) | 2u) : 0xFFFFFFFFu;
+  const uint32_t kb = umin(k0, umin(k1, k2));
+  if (kb != 0xFFFFFFFFu) {
+    const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
+    bind_gpus(c, hl, g, now, now + dur);
+    if (now == t_submit) r.c_imm++;
+    start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
+    return;
+  }
+  // every replica yields: the replica on the fullest ready host would move (ties: lowest host)
+  const int ok0 = (int)((rdy >> h0) & 1u), ok1 = (int)((rdy >> h1) & 1u), ok2 = (int)((rdy >> h2) & 1u);
+  const int any_ready = ok0 | ok1 | ok2;
+  const uint32_t v0 = (!any_ready || ok0) ? (((uint32_t)(8 - C0) << 12) | ((uint32_t)h0 << 2) | 0u) : 0xFFFFFFFFu;
+  const uint32_t v1 = (!any_ready || ok1) ? (((uint32_t)(8 - C1) << 12) | ((uint32_t)h1 << 2) | 1u) : 0xFFFFFFFFu;
+  const uint32_t v2 = (!any_ready || ok2) ? (((uint32_t)(8 - C2) << 12) | ((uint32_t)h2 << 2) | 2u) : 0xFFFFFFFFu;
+  const uint32_t vb = umin(v0, umin(v1, v2));
+  const int victim = (int)(vb & 3u), hv = (int)((vb >> 2) & 1023u);
+  const uint32_t moved = (uint32_t)g | (1u << 16);
+  // (b) migration, Section 3.2.3: the target binds the GPUs at once. A ready host of this session
+  // with g idle GPUs would have won the election, so none of its hosts can show up as a target.
+  if (c.p.flags & NBOS_F_MIGRATE) {
+    const int S = (int)(c.hs & 0xFFFFu);
+    const bool ok = c.hr <= now && C <= G - g && S <= c.slim - g;
+    if (__ballot(ok)) {
+      uint32_t key = ok ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane) : 0xFFFFFFFFu;
+      const int dst = (int)(wave_min(key) & 1023u);
+      const int32_t start = now + c.p.migr;
+      if (c.lane == hv) c.hs -= moved;
+      if (c.lane == dst) c.hs += moved;
+      bind_gpus(c, dst, g, now, start + dur);
+      c32_add(c.m, c.lane, CS_MIGR, 1u);
+      start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
+      return;
+    }
+  }
+  // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
+  if (c.p.flags & NBOS_F_SCALE_OUT) {
+    wave_sync();
+    if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) {
+      const int32_t start = now + c.p.boot + c.p.migr;
+      if (c.lane == hv) c.hs -= moved;
+      const int h = boot_host(c, r, now, moved);
+      wave_sync();
+      c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
+      bind_gpus(c, h, g, now, start + dur);
+      c32_add(c.m, c.lane, CS_MIGR, 1u);
+      start_cell(c, r, s, hw, fl, victim, h, now, start, t_submit, dur, NBOS_D_SCALE_CELL);
+      return;
+    }
+  }
+  // (d) queue and retry periodically, then give up, Section 3.2.3
+  int retries = (int)((fl >> 8) & 15u);
+  if (retries < c.p.max_retries) {
+    retries++;
+    if (!(fl & SF_QONCE)) c32_add(c.m, c.lane, CS_QUEUED, 1u);
+    const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
+    sess_write(c, r, s, hw, t_submit, nfl);
+    timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
+    return;
+  }
+  c32_add(c.m, c.lane, CS_ABORTED, 1u);
+  decide(c, r, now, NBOS_D_ABORT, s, 0, 0);
+  const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
+  sess_write(c, r, s, hw, 0, nfl);
+  if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
+}
+
+// ---- auto-scaler period: release at most two empty hosts (Section 3.4.2, last paragraph) --------
+template <int NJ>
+__device__ __forceinline__ void tick(Ctx<NJ> &c, Regs &r, int32_t now) {
+  int A = __builtin_popcountll(__ballot(c.hr <= now));
+  int Z = __builtin_popcountll(__ballot(c.hr <= now && (c.hs >> 16) == 0));
+  int released = 0;
+  while ((int64_t)Z * 100 > (int64_t)A * c.p.idle_pct && A > c.p.min_hosts && released < 2) {
+    uint64_t e = __ballot(c.hr <= now && (c.hs >> 16) == 0);
+    int victim = 63 - (int)__builtin_clzll(e);
+    if (c.lane == victim) c.hr = NEVER;
+    c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
+    c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
+    c32_add(c.m, c.lane, CS_SI, 1u);
+    A--; Z--; released++;
+    decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
+  }
+}
+
+template <int NJ>
+__device__ __forceinline__ void on_session_end(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl,
+                                               int32_t now) {
+  const uint32_t st = fl & 7u;
+  if ((st != SS_PLACED && st != SS_QUEUED) || (fl & SF_ENDING)) return;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  c32_add(c.m, c.lane, CS_OPENG, (uint32_t)-g);         // the Reservation lifetime closes at the END event
+  c64_add(c.m, c.lane, CL_RESV, (int64_t)g * now);
+  if (st == SS_PLACED && tm <= now) {
+    end_session(c, r, s, hw, fl, now);
+  } else {
+    sess_write_flag(c, r, s, fl | SF_ENDING);
+    if (st == SS_PLACED) timer_push(c, r, tm, QK_END, s, 0);
+  }
+}
+
+template <int NJ>
+__global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int rep = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (rep >= p.n_replays) return;
+
+  const int trace = p.trace_of_replay[rep];
+  const int64_t ev_lo = p.ev_offset[trace], ev_hi = p.ev_offset[trace + 1];
+  const int s_lo = p.sess_offset[trace];
+  const int n_sess = p.sess_offset[trace + 1] - s_lo;
+
+  Lds m;
+  unsigned char *q = lds_raw;
+  m.c64 = (unsigned long long *)q; q += 8 * 8;
+  m.c32 = (uint32_t *)q;       q += 16 * 4;
+  m.hist = (uint32_t *)q;      q += 32 * 4;
+  m.s_hosts = (uint32_t *)q;   q += (size_t)p.n_cap * 4;
+  m.s_time = (int32_t *)q;     q += (size_t)p.n_cap * 4;
+  m.s_flag = (uint32_t *)q;    q += (size_t)p.n_cap * 4;
+  m.s_dur = (int32_t *)q;      q += (size_t)p.n_cap * 4;
+  m.o_t = (int32_t *)q;        q += (size_t)p.q_cap * 4;
+  m.o_k = (uint32_t *)q;       q += (size_t)p.q_cap * 4;
+  m.o_d = (int32_t *)q;
+
+  // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
+  if (lane < 8) m.c64[lane] = 0;
+  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
+  if (lane < 32) m.hist[lane] = 0;
+  for (int s = lane; s < n_sess; s += WAVE) {
+    uint32_t g = p.sess_gpus[s_lo + s];
+    m.s_hosts[s] = 0; m.s_time[s] = 0; m.s_flag[s] = SS_UNPLACED | ((g - 1u) << 3);
+  }
+  __syncthreads();
+
+  const int32_t caplim = p.cap_milli[rep] * p.G * 3;
+  Ctx<NJ> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+#pragma unroll
+  for (int j = 0; j < NJ; j++) c.fin[j] = 0;
+  c.hr = lane < p.H0 ? 0 : NEVER;
+  c.hs = 0;
+  c.qt = NEVER; c.qd = 0; c.qk = 0xFFFFFFFFu;
+  c.vsid = 0xFFFFFFFFu;
+  Regs r;
+  memset(&r, 0, sizeof r);
+  r.digest = 0xCBF29CE484222325ULL;
+  r.q_head_t = NEVER;
+  r.o_min_t = NEVER;
+
+  const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
+  int32_t tick_t = p.scale_iv;
+
+  // S1: stream the events, one per lane per tile, next tile in flight
+  int64_t base = ev_lo;                     // first event of the tile held in (nt, nd, ns)
+  int32_t vt = 0, vd = 0, vs = 0, nt = 0, nd = 0, ns = 0;
+  if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
+  // Outer loop: one iteration per tile of 64 events plus a last one (`final`) that drains the
+  // timers. Inner loop: one iteration per item (queued timer, auto-scaler period, or arrival); it
+  // never touches the registers of the tile in flight.
+  bool final = false;
+  while (r.status == NBOS_OK) {
+    uint32_t p_hw = 0, p_fl = 0;
+    int32_t p_tm = 0;
+    uint64_t todo = 0;
+    if (base < ev_hi) {
+      // the prefetched tile becomes current; start loading the one after it
+      vt = nt; vd = nd; vs = ns;
+      const int64_t cur = base;
+      base += WAVE;
+      if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
+      const bool valid = cur + lane < ev_hi;
+      const bool is_last = cur + lane == ev_hi - 1;
+      const uint32_t sid = (uint32_t)vs & 0xFFFFFFu, kind = (uint32_t)vs >> 24;
+      c.vsid = valid ? sid : 0xFFFFFFFFu;
+      wave_sync();
+      if (valid) { p_hw = m.s_hosts[sid]; p_tm = m.s_time[sid]; p_fl = m.s_flag[sid]; }
+      // events of sessions in a final state change nothing: count the cells, skip them all.
+      // The last event of the trace is never skipped, so timers due before it still run first.
+      const uint32_t st = p_fl & 7u;
+      const bool skip = valid && !is_last && (st == SS_REJECTED || st == SS_ENDED);
+      const uint32_t n_cells = (uint32_t)__builtin_popcountll(__ballot(skip && kind == NBOS_EV_CELL));
+      r.c_total += n_cells;
+      r.c_unplaced += n_cells;
+      todo = __ballot(valid && !skip);
+      r.dirty = 0;
+      if (ev_hi - cur <= WAVE) {
+        int32_t tl = lane_get(vt, (int)(ev_hi - cur - 1));
+        r.t_end = r.t_end > tl ? r.t_end : tl;
+      }
+    } else {
+      final = true;
+    }
+    while (r.status == NBOS_OK && (final || todo != 0)) {
+      wave_sync();
+      const int i = final ? 0 : (int)__builtin_ctzll(todo);
+      const int32_t t = final ? NEVER : lane_get(vt, i);
+      // which item is next: a queued timer, an auto-scaler period, or the arrival itself (S2)
+      bool q_due = r.q_n > 0 && (final || r.q_head_t <= t);
+      bool t_due = scale_in && (final ? (r.q_n > 0 ? tick_t < r.q_head_t : tick_t < r.lazy_max) : tick_t <= t);
+      if (q_due && t_due) { if (r.q_head_t <= tick_t) t_due = false; else q_due = false; }
+      if (t_due) {
+        tick(c, r, tick_t);
+        tick_t += p.scale_iv;
+        continue;
+      }
+      bool att = false;
+      uint32_t a_s = 0, a_hw = 0, a_fl = 0;
+      int32_t a_now = 0, a_sub = 0, a_dur = 0;
+      if (q_due) {
+        const int32_t now = r.q_head_t;
+        const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
+        const int32_t dur = lane_get(c.qd, 0);
+        timer_pop(c, r);
+        r.t_end = r.t_end > now ? r.t_end : now;
+        const uint32_t s = key & 0xFFFFu;
+        const uint32_t hw = uni(m.s_hosts[s]), fl = uni(m.s_flag[s]);
+        if ((key >> 16) == QK_RETRY) {
+          att = true; a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(m.s_time[s]); a_dur = dur;
+        } else {
+          end_session(c, r, s, hw, fl, now);
+        }
+      } else if (final) {
+        break;
+      } else {
+        todo &= todo - 1;
+        const int32_t d = lane_get(vd, i);
+        const uint32_t sk = (uint32_t)lane_get(vs, i);
+        const uint32_t s = sk & 0xFFFFFFu, kind = sk >> 24;
+        uint32_t hw, fl;
+        int32_t tm;
+        if ((r.dirty >> i) & 1u) { hw = uni(m.s_hosts[s]); tm = uni(m.s_time[s]); fl = uni(m.s_flag[s]); }
+        else { hw = (uint32_t)lane_get((int)p_hw, i); tm = lane_get(p_tm, i); fl = (uint32_t)lane_get((int)p_fl, i); }
+        if (kind == NBOS_EV_CELL) {             // S4-S8
+          r.c_total++;
+          const uint32_t st = fl & 7u;
+          if (st == SS_PLACED) {
+            if (tm > t) r.c_busy++;
+            else { att = true; a_s = s; a_hw = hw; a_fl = fl & ~(SF_QONCE | (15u << 8)); a_now = t; a_sub = t; a_dur = d; }
+          } else if (st == SS_QUEUED) {
+            r.c_busy++;
+          } else {
+            r.c_unplaced++;
+          }
+        } else if (kind == NBOS_EV_START) {     // S3, S7
+          session_start(c, r, s, fl, t);
+        } else {
+          on_session_end(c, r, s, hw, tm, fl, t);
+        }
+      }
+      if (att) attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+    }
+    if (final) break;
+  }
+
+  // S10: close the integrals at t_end and write the result record
+  __syncthreads();
+  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
+  nbos_stats *out = p.stats + rep;
+  if (lane < 32) out->delay_hist[lane] = m.hist[lane];
+  if (lane == 0) {
+    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
+    out->status = r.status; out->n_decisions = r.n_dec;
+    out->sessions_placed = m.c32[CS_PLACED]; out->sessions_rejected = m.c32[CS_REJECTED];
+    out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
+    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = m.c32[CS_ABORTED];
+    out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
+    out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
+    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
+    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
+    out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
+    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_exec + g_wait;
+    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
+    out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
+    out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
+    out->digest = r.digest;
+  }
+}
+
+}  // namespace regk
+}  // namespace

@@ -16,7 +16,7 @@ import numpy as np
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so")
 
-F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG = 1, 2, 4, 8
+F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG, F_HOSTS_IN_LDS = 1, 2, 4, 8, 16
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
@@ -124,7 +124,7 @@ class Replay:
     kept referenced here). ``stream``: a torch.cuda.Stream or None for the current stream."""
 
     def __init__(self, cfg: dict, inputs: dict, n_replays: int | None = None, n_traces: int | None = None,
-                 stream=None, decision_log: bool = False):
+                 stream=None, decision_log: bool = False, hosts_in_lds: bool = False):
         import torch
         lib = load()
         self._lib = lib
@@ -132,7 +132,8 @@ class Replay:
         n_replays = int(inputs["trace_of_replay"].numel()) if n_replays is None else n_replays
         n_traces = int(inputs["ev_offset"].numel()) - 1 if n_traces is None else n_traces
         self.n_replays = n_replays
-        self.config = make_config(cfg, n_replays, n_traces, F_DECISION_LOG if decision_log else 0)
+        self.config = make_config(cfg, n_replays, n_traces, (F_DECISION_LOG if decision_log else 0)
+                                  | (F_HOSTS_IN_LDS if hosts_in_lds else 0))
         ins = NbosInputs()
         for name in _INPUT_FIELDS:
             ten = inputs[name]

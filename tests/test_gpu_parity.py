@@ -24,9 +24,9 @@ def rp():
     return replay
 
 
-def gpu_run(rp, batch, log=False):
+def gpu_run(rp, batch, log=False, in_lds=False):
     dev = rp.upload(batch)
-    h = rp.Replay(batch.config, dev, decision_log=log)
+    h = rp.Replay(batch.config, dev, decision_log=log, hosts_in_lds=in_lds)
     h.run()
     st = h.stats()
     logs = [h.decisions(r) for r in range(batch.n_replays)] if log else None
@@ -59,12 +59,13 @@ def assert_same(rp, orc, batch, st, logs=None, replays=None, check=False):
 
 # ---- hand-worked traces straight through the GPU ---------------------------------------------------
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
 @pytest.mark.parametrize("name", sorted(f for f in os.listdir(GOLDEN) if f.startswith("hand_")))
-def test_hand_worked_gpu(rp, name):
+def test_hand_worked_gpu(rp, name, in_lds):
     g = load_golden(name)
     t, d, sk = events_to_arrays(g["events"])
     b = tg._pack(g["config"], [(t, d, sk, np.asarray(g["sess_gpus"], np.uint8))], [0], [g["cap_milli"]], name)
-    st, logs = gpu_run(rp, b, log=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
     got = rp.stats_to_dict(st[0])
     for k, v in g["expect"].items():
         assert got[k] == v, (name, k, got[k], v)
@@ -82,6 +83,14 @@ def test_random_cases(rp, oracle, seed):
     assert_same(rp, oracle, b, st, logs, check=True)
 
 
+@pytest.mark.parametrize("seed", range(0, 120, 3))
+def test_random_cases_hosts_in_lds(rp, oracle, seed):
+    # the any-size kernel on the same cases (it is chosen by itself only above 64 hosts)
+    b = tg.random_case(seed)
+    st, logs = gpu_run(rp, b, log=True, in_lds=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
@@ -91,10 +100,11 @@ def test_random_cases_without_log(rp, oracle):
 
 # ---- the five named workloads at reduced replay counts (full per-replay size) ----------------------
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
 @pytest.mark.parametrize("name,n", [("c1", 1), ("c2", 6), ("c3", 4), ("c5", 24)])
-def test_named_workloads(rp, oracle, name, n):
+def test_named_workloads(rp, oracle, name, n, in_lds):
     b = tg.workload(name, n_replays=n)
-    st, logs = gpu_run(rp, b, log=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
     assert_same(rp, oracle, b, st, logs)
 
 
