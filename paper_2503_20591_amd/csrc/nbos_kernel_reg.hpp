@@ -37,9 +37,9 @@ enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_
        CS_NON, CS_SUMS, CS_OPENG, CS_N32 };
 enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_N64 };
 
+// session record: x hosts word, y time word, z flags, w unused (keeps the record one 128-bit access)
 struct Lds {
-  uint32_t *s_hosts, *s_flag;
-  int32_t *s_time, *s_dur;
+  int4 *sess;
   int32_t *o_t, *o_d;          // overflow timers
   uint32_t *o_k;
   uint32_t *hist;
@@ -101,12 +101,12 @@ __device__ __forceinline__ void decide(Ctx<NJ> &c, Regs &r, int32_t now, uint32_
 // write a session record; lanes of the current tile that prefetched it go stale
 template <int NJ>
 __device__ __forceinline__ void sess_write(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
-  if (c.lane == 0) { c.m.s_hosts[s] = hw; c.m.s_time[s] = tm; c.m.s_flag[s] = fl; }
+  if (c.lane == 0) c.m.sess[s] = make_int4((int)hw, tm, (int)fl, 0);
   r.dirty |= __ballot(c.vsid == s);
 }
 template <int NJ>
 __device__ __forceinline__ void sess_write_flag(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t fl) {
-  if (c.lane == 0) c.m.s_flag[s] = fl;
+  if (c.lane == 0) c.m.sess[s].z = (int)fl;
   r.dirty |= __ballot(c.vsid == s);
 }
 
@@ -232,6 +232,36 @@ __device__ __forceinline__ int boot_host(Ctx<NJ> &c, Regs &r, int32_t now, uint3
   c32_add(c.m, c.lane, CS_SO, 1u);
   r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
   return h;
+}
+
+// Earliest time at which some host that is on could have g idle GPUs if nothing new were committed:
+// min over hosts of max(ready_at, g-th smallest busy-until time of the host's GPUs). Later commits
+// only push it back, so no election or migration for a request of g GPUs can succeed before it
+// (as long as no host is added). Each lane counts, inside its host's group of 8 lanes, the GPUs that
+// are free no later than its own GPU (DPP quad rotations of the value and of its half-row mirror
+// reach all 8 lanes of the group).
+template <int NJ>
+__device__ __forceinline__ int32_t earliest_idle(const Ctx<NJ> &c, int g) {
+  const bool used = (c.lane & 7) < c.p.G;
+  int32_t best = NEVER;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int32_t f = used ? c.fin[j] : NEVER;
+    const int32_t mir = __builtin_amdgcn_update_dpp(f, f, 0x141, 0xF, 0xF, false);   // row_half_mirror
+    int cnt = 1;
+    cnt += __builtin_amdgcn_update_dpp(f, f, 0x39, 0xF, 0xF, false) <= f ? 1 : 0;      // quad_perm [1,2,3,0]
+    cnt += __builtin_amdgcn_update_dpp(f, f, 0x4E, 0xF, 0xF, false) <= f ? 1 : 0;      // quad_perm [2,3,0,1]
+    cnt += __builtin_amdgcn_update_dpp(f, f, 0x93, 0xF, 0xF, false) <= f ? 1 : 0;      // quad_perm [3,0,1,2]
+    cnt += mir <= f ? 1 : 0;
+    cnt += __builtin_amdgcn_update_dpp(mir, mir, 0x39, 0xF, 0xF, false) <= f ? 1 : 0;
+    cnt += __builtin_amdgcn_update_dpp(mir, mir, 0x4E, 0xF, 0xF, false) <= f ? 1 : 0;
+    cnt += __builtin_amdgcn_update_dpp(mir, mir, 0x93, 0xF, 0xF, false) <= f ? 1 : 0;
+    const int32_t ra = __builtin_amdgcn_ds_bpermute((8 * j + (c.lane >> 3)) << 2, c.hr);  // ready_at of host 8j+hl
+    int32_t y = cnt >= g ? f : NEVER;
+    y = y > ra ? y : ra;
+    best = best < y ? best : y;
+  }
+  return (int32_t)wave_min((uint32_t)best);
 }
 
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
@@ -402,6 +432,13 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   int retries = (int)((fl >> 8) & 15u);
   if (retries < c.p.max_retries) {
     retries++;
+    // A retry that is bound to fail only bumps the retry count: skip straight to the first retry
+    // that could succeed (or to the last one, which aborts). Valid while no host can be added,
+    // i.e. unless hosts can be both released and provisioned.
+    if ((c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
+      const int32_t bound = earliest_idle(c, g);
+      while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
+    }
     if (!(fl & SF_QONCE)) c32_add(c.m, c.lane, CS_QUEUED, 1u);
     const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
     sess_write(c, r, s, hw, t_submit, nfl);
@@ -466,10 +503,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   m.c64 = (unsigned long long *)q; q += 8 * 8;
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
-  m.s_hosts = (uint32_t *)q;   q += (size_t)p.n_cap * 4;
-  m.s_time = (int32_t *)q;     q += (size_t)p.n_cap * 4;
-  m.s_flag = (uint32_t *)q;    q += (size_t)p.n_cap * 4;
-  m.s_dur = (int32_t *)q;      q += (size_t)p.n_cap * 4;
+  m.sess = (int4 *)q;          q += (size_t)p.n_cap * 16;
   m.o_t = (int32_t *)q;        q += (size_t)p.q_cap * 4;
   m.o_k = (uint32_t *)q;       q += (size_t)p.q_cap * 4;
   m.o_d = (int32_t *)q;
@@ -480,7 +514,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   if (lane < 32) m.hist[lane] = 0;
   for (int s = lane; s < n_sess; s += WAVE) {
     uint32_t g = p.sess_gpus[s_lo + s];
-    m.s_hosts[s] = 0; m.s_time[s] = 0; m.s_flag[s] = SS_UNPLACED | ((g - 1u) << 3);
+    m.sess[s] = make_int4(0, 0, (int)(SS_UNPLACED | ((g - 1u) << 3)), 0);
   }
   __syncthreads();
 
@@ -499,19 +533,21 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   r.o_min_t = NEVER;
 
   const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
-  int32_t tick_t = p.scale_iv;
+  int32_t tick_t = scale_in ? p.scale_iv : NEVER;
+  int32_t due_t = tick_t;                   // earliest queued timer or auto-scaler period
 
   // S1: stream the events, one per lane per tile, next tile in flight
   int64_t base = ev_lo;                     // first event of the tile held in (nt, nd, ns)
   int32_t vt = 0, vd = 0, vs = 0, nt = 0, nd = 0, ns = 0;
   if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
+
   // Outer loop: one iteration per tile of 64 events plus a last one (`final`) that drains the
   // timers. Inner loop: one iteration per item (queued timer, auto-scaler period, or arrival); it
   // never touches the registers of the tile in flight.
   bool final = false;
   while (r.status == NBOS_OK) {
-    uint32_t p_hw = 0, p_fl = 0;
-    int32_t p_tm = 0;
+    int4 rec = make_int4(0, 0, 0, 0);       // prefetched session record of this lane's event
+    uint32_t fast = 0;                      // this lane's event is a cell of an idle placed session
     uint64_t todo = 0;
     if (base < ev_hi) {
       // the prefetched tile becomes current; start loading the one after it
@@ -521,17 +557,23 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
       if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
       const bool valid = cur + lane < ev_hi;
       const bool is_last = cur + lane == ev_hi - 1;
-      const uint32_t sid = (uint32_t)vs & 0xFFFFFFu, kind = (uint32_t)vs >> 24;
+      const uint32_t sid = (uint32_t)vs & 0xFFFFFFu;
+      const bool is_cell = ((uint32_t)vs >> 24) == NBOS_EV_CELL;
       c.vsid = valid ? sid : 0xFFFFFFFFu;
       wave_sync();
-      if (valid) { p_hw = m.s_hosts[sid]; p_tm = m.s_time[sid]; p_fl = m.s_flag[sid]; }
-      // events of sessions in a final state change nothing: count the cells, skip them all.
-      // The last event of the trace is never skipped, so timers due before it still run first.
-      const uint32_t st = p_fl & 7u;
-      const bool skip = valid && !is_last && (st == SS_REJECTED || st == SS_ENDED);
-      const uint32_t n_cells = (uint32_t)__builtin_popcountll(__ballot(skip && kind == NBOS_EV_CELL));
-      r.c_total += n_cells;
-      r.c_unplaced += n_cells;
+      if (valid) rec = m.sess[sid];
+      // Cells of sessions in a final state (rejected / ended) and cells that arrive while the
+      // session's running cell lasts beyond them change nothing: count them, skip them. Neither
+      // condition can be undone before the event's time. The last event of the trace is never
+      // skipped, so timers due before it still run first.
+      const uint32_t st = (uint32_t)rec.z & 7u;
+      const bool dead = st == SS_REJECTED || st == SS_ENDED;
+      const bool running = st == SS_PLACED && rec.y > vt;
+      const bool skip = valid && !is_last && (dead || (is_cell && running));
+      r.c_total += (uint32_t)__builtin_popcountll(__ballot(valid && is_cell));
+      r.c_unplaced += (uint32_t)__builtin_popcountll(__ballot(skip && is_cell && dead));
+      r.c_busy += (uint32_t)__builtin_popcountll(__ballot(skip && is_cell && !dead));
+      fast = (valid && is_cell && st == SS_PLACED && !running && !((uint32_t)rec.z & SF_ENDING)) ? 1u : 0u;
       todo = __ballot(valid && !skip);
       r.dirty = 0;
       if (ev_hi - cur <= WAVE) {
@@ -541,64 +583,87 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
     } else {
       final = true;
     }
-    while (r.status == NBOS_OK && (final || todo != 0)) {
+    const uint64_t fastmask = __ballot(fast != 0);
+    for (;;) {
+      if (r.status != NBOS_OK) break;
+      int i = 0;
+      int32_t t = NEVER;
+      if (todo != 0) { i = (int)__builtin_ctzll(todo); t = lane_get(vt, i); }
+      else if (!final) break;
       wave_sync();
-      const int i = final ? 0 : (int)__builtin_ctzll(todo);
-      const int32_t t = final ? NEVER : lane_get(vt, i);
-      // which item is next: a queued timer, an auto-scaler period, or the arrival itself (S2)
-      bool q_due = r.q_n > 0 && (final || r.q_head_t <= t);
-      bool t_due = scale_in && (final ? (r.q_n > 0 ? tick_t < r.q_head_t : tick_t < r.lazy_max) : tick_t <= t);
-      if (q_due && t_due) { if (r.q_head_t <= tick_t) t_due = false; else q_due = false; }
-      if (t_due) {
-        tick(c, r, tick_t);
-        tick_t += p.scale_iv;
-        continue;
-      }
-      bool att = false;
-      uint32_t a_s = 0, a_hw = 0, a_fl = 0;
-      int32_t a_now = 0, a_sub = 0, a_dur = 0;
-      if (q_due) {
+      uint32_t a_s, a_hw, a_fl;
+      int32_t a_now, a_sub, a_dur;
+      if (__builtin_expect(t < due_t, 1)) {
+        // ---- arrival i ----
+        const uint64_t bit = 1ull << i;
+        todo &= ~bit;
+        const uint32_t sk = (uint32_t)lane_get(vs, i);
+        const uint32_t s = sk & 0xFFFFFFu;
+        if (__builtin_expect((fastmask & ~r.dirty & bit) != 0, 1)) {
+          // a cell of an idle placed session whose record nobody touched since the prefetch
+          a_s = s; a_hw = (uint32_t)lane_get(rec.x, i);
+          a_fl = (uint32_t)lane_get(rec.z, i);
+          a_now = t; a_sub = t; a_dur = lane_get(vd, i);
+        } else {
+          const uint32_t kind = sk >> 24;
+          uint32_t hw, fl;
+          int32_t tm;
+          if ((r.dirty >> i) & 1u) {
+            int4 cur = m.sess[s];
+            hw = uni((uint32_t)cur.x); tm = uni(cur.y); fl = uni((uint32_t)cur.z);
+          } else {
+            hw = (uint32_t)lane_get(rec.x, i); tm = lane_get(rec.y, i); fl = (uint32_t)lane_get(rec.z, i);
+          }
+          if (kind == NBOS_EV_CELL) {           // S4-S8 (counted in c_total at tile load)
+            const uint32_t st = fl & 7u;
+            if (st == SS_PLACED && tm <= t) {
+              a_s = s; a_hw = hw; a_fl = fl & ~(SF_QONCE | (15u << 8)); a_now = t; a_sub = t; a_dur = lane_get(vd, i);
+            } else {
+              if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++; else r.c_unplaced++;
+              continue;
+            }
+          } else {
+            if (kind == NBOS_EV_START) session_start(c, r, s, fl, t);      // S3, S7
+            else on_session_end(c, r, s, hw, tm, fl, t);
+            due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+            continue;
+          }
+        }
+      } else {
+        // ---- a timer may be due (S2); always taken while draining ----
+        bool fire_q = r.q_n > 0, fire_t = scale_in;
+        if (final) {
+          if (fire_t) fire_t = fire_q ? tick_t < r.q_head_t : tick_t < r.lazy_max;
+          if (fire_t) fire_q = false;
+        } else {
+          if (fire_q) fire_q = r.q_head_t <= t;
+          if (fire_t) fire_t = tick_t <= t;
+          if (fire_q && fire_t) { if (r.q_head_t <= tick_t) fire_t = false; else fire_q = false; }
+        }
+        if (fire_t) {
+          tick(c, r, tick_t);
+          tick_t += p.scale_iv;
+          due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          continue;
+        }
+        if (!fire_q) break;                   // only reached while draining: nothing is left
         const int32_t now = r.q_head_t;
         const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
         const int32_t dur = lane_get(c.qd, 0);
         timer_pop(c, r);
         r.t_end = r.t_end > now ? r.t_end : now;
         const uint32_t s = key & 0xFFFFu;
-        const uint32_t hw = uni(m.s_hosts[s]), fl = uni(m.s_flag[s]);
-        if ((key >> 16) == QK_RETRY) {
-          att = true; a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(m.s_time[s]); a_dur = dur;
-        } else {
+        const int4 cur = m.sess[s];
+        const uint32_t hw = uni((uint32_t)cur.x), fl = uni((uint32_t)cur.z);
+        if ((key >> 16) != QK_RETRY) {
           end_session(c, r, s, hw, fl, now);
+          due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          continue;
         }
-      } else if (final) {
-        break;
-      } else {
-        todo &= todo - 1;
-        const int32_t d = lane_get(vd, i);
-        const uint32_t sk = (uint32_t)lane_get(vs, i);
-        const uint32_t s = sk & 0xFFFFFFu, kind = sk >> 24;
-        uint32_t hw, fl;
-        int32_t tm;
-        if ((r.dirty >> i) & 1u) { hw = uni(m.s_hosts[s]); tm = uni(m.s_time[s]); fl = uni(m.s_flag[s]); }
-        else { hw = (uint32_t)lane_get((int)p_hw, i); tm = lane_get(p_tm, i); fl = (uint32_t)lane_get((int)p_fl, i); }
-        if (kind == NBOS_EV_CELL) {             // S4-S8
-          r.c_total++;
-          const uint32_t st = fl & 7u;
-          if (st == SS_PLACED) {
-            if (tm > t) r.c_busy++;
-            else { att = true; a_s = s; a_hw = hw; a_fl = fl & ~(SF_QONCE | (15u << 8)); a_now = t; a_sub = t; a_dur = d; }
-          } else if (st == SS_QUEUED) {
-            r.c_busy++;
-          } else {
-            r.c_unplaced++;
-          }
-        } else if (kind == NBOS_EV_START) {     // S3, S7
-          session_start(c, r, s, fl, t);
-        } else {
-          on_session_end(c, r, s, hw, tm, fl, t);
-        }
+        a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(cur.y); a_dur = dur;
       }
-      if (att) attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+      attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+      due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
     }
     if (final) break;
   }
