@@ -81,7 +81,7 @@ __device__ __forceinline__ void queue_rescan(Ctx &c, Regs &r) {
   }
   uint32_t mt = wave_min(bt);
   uint32_t ml = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
-  uint64_t who = __ballot(bt == mt && bl == ml);
+  uint64_t who = wballot(bt == mt && bl == ml);
   int src = (int)__builtin_ctzll(who | (1ull << 63));
   r.q_min_i = lane_get(bi, src);
   r.q_min_t = r.q_n > 0 ? (int32_t)mt : NEVER;
@@ -114,7 +114,7 @@ __device__ __forceinline__ void bind_gpus(Ctx &c, int h, int g, int32_t now, int
   bool mine = c.lane < c.p.G;
   int32_t f = mine ? c.m.fin[c.lane * c.p.HP + h] : NEVER;
   bool fr = mine && f <= now;
-  int rank = lane_rank(__ballot(fr));
+  int rank = lane_rank(wballot(fr));
   if (fr && rank < g) c.m.fin[c.lane * c.p.HP + h] = finish;
 }
 
@@ -123,7 +123,7 @@ __device__ __forceinline__ int find_off_host(const Ctx &c) {
   wave_sync();
   for (int base = 0; base < c.p.HP; base += WAVE) {
     int h = base + c.lane;
-    uint64_t off = __ballot(h < c.p.Hmax && c.m.ready_at[h] == NEVER);
+    uint64_t off = wballot(h < c.p.Hmax && c.m.ready_at[h] == NEVER);
     if (off) return base + (int)__builtin_ctzll(off);
   }
   return -1;
@@ -264,8 +264,8 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
   bool act = c.lane < 24 && k < G;
   int32_t f = c.m.fin[k * c.p.HP + hr];
   int32_t ra = c.m.ready_at[hr];
-  uint64_t busy = __ballot(act && f > now);
-  uint64_t rdy = __ballot(ra <= now);
+  uint64_t busy = wballot(act && f > now);
+  uint64_t rdy = wballot(ra <= now);
   const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
   const int C0 = __builtin_popcount((uint32_t)busy & 0xFFu), C1 = __builtin_popcount((uint32_t)(busy >> 8) & 0xFFu),
             C2 = __builtin_popcount((uint32_t)(busy >> 16) & 0xFFu);
@@ -279,7 +279,7 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
     const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
     int32_t finish = now + dur;
     bool fr = act && (c.lane >> 3) == lead && f <= now;
-    int rank = lane_rank(__ballot(fr));
+    int rank = lane_rank(wballot(fr));
     if (fr && rank < g) c.m.fin[k * c.p.HP + hr] = finish;
     if (now == t_submit) r.c_imm++;
     start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
@@ -370,8 +370,8 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
   for (int base = 0; base < c.p.HP; base += WAVE) {
     int h = base + c.lane;
     bool ready = c.m.ready_at[h] <= now;
-    A += __builtin_popcountll(__ballot(ready));
-    Z += __builtin_popcountll(__ballot(ready && (c.m.hsn[h] >> 16) == 0));
+    A += __builtin_popcountll(wballot(ready));
+    Z += __builtin_popcountll(wballot(ready && (c.m.hsn[h] >> 16) == 0));
   }
   int released = 0;
   while ((int64_t)Z * 100 > (int64_t)A * c.p.idle_pct && A > c.p.min_hosts && released < 2) {
@@ -379,7 +379,7 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
     wave_sync();
     for (int base = c.p.HP - WAVE; base >= 0 && victim < 0; base -= WAVE) {
       int h = base + c.lane;
-      uint64_t e = __ballot(c.m.ready_at[h] <= now && (c.m.hsn[h] >> 16) == 0);
+      uint64_t e = wballot(c.m.ready_at[h] <= now && (c.m.hsn[h] >> 16) == 0);
       if (e) victim = base + 63 - (int)__builtin_clzll(e);
     }
     if (c.lane == 0) c.m.ready_at[victim] = NEVER;

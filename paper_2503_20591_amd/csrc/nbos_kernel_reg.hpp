@@ -49,7 +49,7 @@ struct Lds {
 
 // hot uniform registers
 struct Regs {
-  uint32_t n_dec, c_total, c_imm, c_started, c_busy, c_unplaced, reused;
+  uint32_t n_dec, c_total, c_imm, c_started, c_busy, c_unplaced, reused, h0;
   int64_t sum_dur, g_exec;
   uint64_t digest;
   int32_t lazy_max, t_end;
@@ -102,12 +102,12 @@ __device__ __forceinline__ void decide(Ctx<NJ> &c, Regs &r, int32_t now, uint32_
 template <int NJ>
 __device__ __forceinline__ void sess_write(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
   if (c.lane == 0) c.m.sess[s] = make_int4((int)hw, tm, (int)fl, 0);
-  r.dirty |= __ballot(c.vsid == s);
+  r.dirty |= wballot(c.vsid == s);
 }
 template <int NJ>
 __device__ __forceinline__ void sess_write_flag(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t fl) {
   if (c.lane == 0) c.m.sess[s].z = (int)fl;
-  r.dirty |= __ballot(c.vsid == s);
+  r.dirty |= wballot(c.vsid == s);
 }
 
 // ---- timers: overflow array in LDS (unsorted) ---------------------------------------------------
@@ -122,7 +122,7 @@ __device__ __forceinline__ void ovf_rescan(Ctx<NJ> &c, Regs &r) {
   }
   uint32_t mt = wave_min(bt);
   uint32_t ml = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
-  uint64_t who = __ballot(bt == mt && bl == ml);
+  uint64_t who = wballot(bt == mt && bl == ml);
   int src = (int)__builtin_ctzll(who | (1ull << 63));
   r.o_min_i = lane_get(bi, src);
   r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
@@ -160,7 +160,7 @@ __device__ __forceinline__ void timer_push(Ctx<NJ> &c, Regs &r, int32_t t, uint3
     return;
   }
   bool before = c.lane < r.q_n && (c.qt < t || (c.qt == t && c.qk < k));
-  int pos = __builtin_popcountll(__ballot(before));
+  int pos = __builtin_popcountll(wballot(before));
   int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x138, 0xF, 0xF, false);          // wave_shr:1
   int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x138, 0xF, 0xF, false);
   uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
@@ -194,16 +194,18 @@ __device__ __forceinline__ void timer_pop(Ctx<NJ> &c, Regs &r) {
 }
 
 // ---- hosts ----------------------------------------------------------------------------------------
-// committed GPUs of host = lane at time `now`
+// committed GPUs of host = lane at time `now`: byte (lane & 7) of the ballot of register (lane >> 3)
 template <int NJ>
 __device__ __forceinline__ int committed(const Ctx<NJ> &c, int32_t now) {
-  uint64_t msel = 0;
+  const int sh = 8 * (c.lane & 7), grp = c.lane >> 3;
+  uint32_t bits = 0;
 #pragma unroll
   for (int j = 0; j < NJ; j++) {
-    uint64_t busy = __ballot(c.fin[j] > now);
-    msel = (c.lane >> 3) == j ? busy : msel;
+    const uint64_t busy = wballot(c.fin[j] > now);
+    const uint32_t mine = (uint32_t)(busy >> sh);
+    bits = grp == j ? mine : bits;
   }
-  return __builtin_popcount((uint32_t)(msel >> (8 * (c.lane & 7))) & 0xFFu);
+  return __builtin_popcount(bits & 0xFFu);
 }
 
 // bind g free GPUs of host h until `finish`
@@ -215,7 +217,7 @@ __device__ __forceinline__ void bind_gpus(Ctx<NJ> &c, int h, int g, int32_t now,
   for (int jj = 0; jj < NJ; jj++) {
     if (jj == j) {
       bool fr = mine && c.fin[jj] <= now;
-      int rank = lane_rank(__ballot(fr));
+      int rank = lane_rank(wballot(fr));
       if (fr && rank < g) c.fin[jj] = finish;
     }
   }
@@ -223,7 +225,7 @@ __device__ __forceinline__ void bind_gpus(Ctx<NJ> &c, int h, int g, int32_t now,
 
 template <int NJ>
 __device__ __forceinline__ int boot_host(Ctx<NJ> &c, Regs &r, int32_t now, uint32_t hs_new) {
-  uint64_t off = __ballot(c.lane < c.p.Hmax && c.hr == NEVER);
+  uint64_t off = wballot(c.lane < c.p.Hmax && c.hr == NEVER);
   int h = (int)__builtin_ctzll(off);                 // the caller has checked that one exists
   int32_t ra = now + c.p.boot;
   if (c.lane == h) { c.hr = ra; c.hs = hs_new; }
@@ -346,19 +348,29 @@ __device__ __forceinline__ void start_cell(Ctx<NJ> &c, Regs &r, uint32_t s, uint
   r.c_started++;
   r.sum_dur += dur;
   r.g_exec += (int64_t)g * dur;
-  if (delay != 0) {
-    c64_add(c.m, c.lane, CL_SUMDELAY, delay);
-    c32_max(c.m, c.lane, CS_MAXDELAY, (uint32_t)delay);
-    if (start != now) c64_add(c.m, c.lane, CL_GWAIT, (int64_t)g * (start - now));
-  }
-  int b = delay == 0 ? 0 : 32 - __builtin_clz((uint32_t)delay);
-  b = b > 31 ? 31 : b;
-  if (c.lane == 0) atomicAdd(&c.m.hist[b], 1u);
   const uint32_t last = hw >> 30;               // 0 none, else slot + 1
   if (last == (uint32_t)slot + 1u) r.reused++;
   hw = (hw & 0x3FFFFFFFu) | ((uint32_t)(slot + 1) << 30);
   hw = (hw & ~(1023u << (10 * slot))) | ((uint32_t)host << (10 * slot));
-  sess_write(c, r, s, hw, finish, (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED);
+  const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
+  if (delay == 0) {
+    r.h0++;                                     // histogram bin 0 lives in a register
+    if (c.lane == 0) {
+      c.m.sess[s].x = (int)hw; c.m.sess[s].y = finish;
+      if (nfl != fl) c.m.sess[s].z = (int)nfl;
+    }
+  } else {
+    int b = 32 - __builtin_clz((uint32_t)delay);
+    b = b > 31 ? 31 : b;
+    if (c.lane == 0) {
+      c.m.sess[s] = make_int4((int)hw, finish, (int)nfl, 0);
+      atomicAdd(&c.m.hist[b], 1u);
+      atomicAdd(&c.m.c64[CL_SUMDELAY], (unsigned long long)delay);
+      atomicMax(&c.m.c32[CS_MAXDELAY], (uint32_t)delay);
+      atomicAdd(&c.m.c64[CL_GWAIT], (unsigned long long)((int64_t)g * (start - now)));
+    }
+  }
+  r.dirty |= wballot(c.vsid == s);
   r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
   decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
   if (fl & SF_ENDING) timer_push(c, r, finish, QK_END, s, 0);
@@ -368,41 +380,54 @@ __device__ __forceinline__ void start_cell(Ctx<NJ> &c, Regs &r, uint32_t s, uint
 template <int NJ>
 __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                         int32_t t_submit, int32_t dur) {
-  const int G = c.p.G;
   const int g = (int)((fl >> 3) & 7u) + 1;
   const int C = committed(c, now);
-  const uint64_t rdy = __ballot(c.hr <= now);
-  const uint64_t idle_ok = __ballot(c.hr <= now && C <= G - g);
-  const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
-  const int C0 = lane_get(C, h0), C1 = lane_get(C, h1), C2 = lane_get(C, h2);
-  // (a) election, Section 3.2.2: feasible replica with the fewest committed GPUs, then lowest host
-  const uint32_t k0 = ((idle_ok >> h0) & 1u) ? (((uint32_t)C0 << 12) | ((uint32_t)h0 << 2) | 0u) : 0xFFFFFFFFu;
-  const uint32_t k1 = ((idle_ok >> h1) & 1u) ? (((uint32_t)C1 << 12) | ((uint32_t)h1 << 2) | 1u) : 0xFFFFFFFFu;
-  const uint32_t k2 = ((idle_ok >> h2) & 1u) ? (((uint32_t)C2 << 12) | ((uint32_t)h2 << 2) | 2u) : 0xFFFFFFFFu;
-  const uint32_t kb = umin(k0, umin(k1, k2));
-  if (kb != 0xFFFFFFFFu) {
-    const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
+  const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);     // ready hosts with g idle GPUs
+  const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+  // (a) election, Section 3.2.2: among the session's hosts in idle_ok, fewest committed GPUs, then
+  // lowest host index. At most three bits of `cand` are set: walk them.
+  uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
+  if (cand != 0) {
+    const uint32_t key = ((uint32_t)C << 6) | (uint32_t)c.lane;
+    uint32_t best = (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand));
+    cand &= cand - 1;
+    if (cand != 0) {
+      best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
+      cand &= cand - 1;
+      if (cand != 0) best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
+    }
+    const int hl = (int)(best & 63u);
+    const int lead = (uint32_t)hl == h0 ? 0 : ((uint32_t)hl == h1 ? 1 : 2);
     bind_gpus(c, hl, g, now, now + dur);
     if (now == t_submit) r.c_imm++;
     start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
     return;
   }
-  // every replica yields: the replica on the fullest ready host would move (ties: lowest host)
-  const int ok0 = (int)((rdy >> h0) & 1u), ok1 = (int)((rdy >> h1) & 1u), ok2 = (int)((rdy >> h2) & 1u);
-  const int any_ready = ok0 | ok1 | ok2;
-  const uint32_t v0 = (!any_ready || ok0) ? (((uint32_t)(8 - C0) << 12) | ((uint32_t)h0 << 2) | 0u) : 0xFFFFFFFFu;
-  const uint32_t v1 = (!any_ready || ok1) ? (((uint32_t)(8 - C1) << 12) | ((uint32_t)h1 << 2) | 1u) : 0xFFFFFFFFu;
-  const uint32_t v2 = (!any_ready || ok2) ? (((uint32_t)(8 - C2) << 12) | ((uint32_t)h2 << 2) | 2u) : 0xFFFFFFFFu;
-  const uint32_t vb = umin(v0, umin(v1, v2));
-  const int victim = (int)(vb & 3u), hv = (int)((vb >> 2) & 1023u);
-  const uint32_t moved = (uint32_t)g | (1u << 16);
-  // (b) migration, Section 3.2.3: the target binds the GPUs at once. A ready host of this session
-  // with g idle GPUs would have won the election, so none of its hosts can show up as a target.
-  if (c.p.flags & NBOS_F_MIGRATE) {
-    const int S = (int)(c.hs & 0xFFFFu);
-    const bool ok = c.hr <= now && C <= G - g && S <= c.slim - g;
-    if (__ballot(ok)) {
-      uint32_t key = ok ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane) : 0xFFFFFFFFu;
+  // (b), (c): a target exists? Only then is the replica to move worked out: the one on the fullest
+  // ready host (ties: lowest host); replicas on booting hosts only if all three are.
+  const int S = (int)(c.hs & 0xFFFFu);
+  const uint64_t target = (c.p.flags & NBOS_F_MIGRATE) ? (idle_ok & wballot(S <= c.slim - g)) : 0;
+  bool grow = false;
+  if (target == 0 && (c.p.flags & NBOS_F_SCALE_OUT)) {
+    wave_sync();
+    grow = (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
+  }
+  if (target != 0 || grow) {
+    const uint64_t rdy = wballot(c.hr <= now);
+    const int C0 = lane_get(C, (int)h0), C1 = lane_get(C, (int)h1), C2 = lane_get(C, (int)h2);
+    const int ok0 = (int)((rdy >> h0) & 1u), ok1 = (int)((rdy >> h1) & 1u), ok2 = (int)((rdy >> h2) & 1u);
+    const int any_ready = ok0 | ok1 | ok2;
+    const uint32_t v0 = (!any_ready || ok0) ? (((uint32_t)(8 - C0) << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
+    const uint32_t v1 = (!any_ready || ok1) ? (((uint32_t)(8 - C1) << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
+    const uint32_t v2 = (!any_ready || ok2) ? (((uint32_t)(8 - C2) << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
+    const uint32_t vb = umin(v0, umin(v1, v2));
+    const int victim = (int)(vb & 3u), hv = (int)((vb >> 2) & 1023u);
+    const uint32_t moved = (uint32_t)g | (1u << 16);
+    if (target != 0) {
+      // (b) migration, Section 3.2.3: the target binds the GPUs at once. A ready host of this session
+      // with g idle GPUs would have won the election, so none of its hosts can show up as a target.
+      const uint32_t key = ((target >> c.lane) & 1u) ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane)
+                                                      : 0xFFFFFFFFu;
       const int dst = (int)(wave_min(key) & 1023u);
       const int32_t start = now + c.p.migr;
       if (c.lane == hv) c.hs -= moved;
@@ -410,13 +435,8 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
-      return;
-    }
-  }
-  // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
-  if (c.p.flags & NBOS_F_SCALE_OUT) {
-    wave_sync();
-    if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) {
+    } else {
+      // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
       if (c.lane == hv) c.hs -= moved;
       const int h = boot_host(c, r, now, moved);
@@ -425,23 +445,29 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
       bind_gpus(c, h, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, h, now, start, t_submit, dur, NBOS_D_SCALE_CELL);
-      return;
     }
+    return;
   }
   // (d) queue and retry periodically, then give up, Section 3.2.3
   int retries = (int)((fl >> 8) & 15u);
   if (retries < c.p.max_retries) {
     retries++;
-    // A retry that is bound to fail only bumps the retry count: skip straight to the first retry
-    // that could succeed (or to the last one, which aborts). Valid while no host can be added,
-    // i.e. unless hosts can be both released and provisioned.
-    if ((c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
+    // A retry that is bound to fail only bumps the retry count: when no host at all has g idle GPUs
+    // now, skip straight to the first retry that could succeed (or to the last one, which aborts).
+    // Valid while no host can be added, i.e. unless hosts can be both released and provisioned.
+    if (idle_ok == 0 && retries < c.p.max_retries &&
+        (c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
       const int32_t bound = earliest_idle(c, g);
       while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
     }
-    if (!(fl & SF_QONCE)) c32_add(c.m, c.lane, CS_QUEUED, 1u);
     const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
-    sess_write(c, r, s, hw, t_submit, nfl);
+    if (!(fl & SF_QONCE)) {                      // first time in the queue: the submit time goes in
+      c32_add(c.m, c.lane, CS_QUEUED, 1u);
+      if (c.lane == 0) { c.m.sess[s].y = t_submit; c.m.sess[s].z = (int)nfl; }
+    } else {
+      if (c.lane == 0) c.m.sess[s].z = (int)nfl;
+    }
+    r.dirty |= wballot(c.vsid == s);
     timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
     return;
   }
@@ -455,11 +481,11 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
 // ---- auto-scaler period: release at most two empty hosts (Section 3.4.2, last paragraph) --------
 template <int NJ>
 __device__ __forceinline__ void tick(Ctx<NJ> &c, Regs &r, int32_t now) {
-  int A = __builtin_popcountll(__ballot(c.hr <= now));
-  int Z = __builtin_popcountll(__ballot(c.hr <= now && (c.hs >> 16) == 0));
+  int A = __builtin_popcountll(wballot(c.hr <= now));
+  int Z = __builtin_popcountll(wballot(c.hr <= now && (c.hs >> 16) == 0));
   int released = 0;
   while ((int64_t)Z * 100 > (int64_t)A * c.p.idle_pct && A > c.p.min_hosts && released < 2) {
-    uint64_t e = __ballot(c.hr <= now && (c.hs >> 16) == 0);
+    uint64_t e = wballot(c.hr <= now && (c.hs >> 16) == 0);
     int victim = 63 - (int)__builtin_clzll(e);
     if (c.lane == victim) c.hr = NEVER;
     c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
@@ -570,11 +596,11 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
       const bool dead = st == SS_REJECTED || st == SS_ENDED;
       const bool running = st == SS_PLACED && rec.y > vt;
       const bool skip = valid && !is_last && (dead || (is_cell && running));
-      r.c_total += (uint32_t)__builtin_popcountll(__ballot(valid && is_cell));
-      r.c_unplaced += (uint32_t)__builtin_popcountll(__ballot(skip && is_cell && dead));
-      r.c_busy += (uint32_t)__builtin_popcountll(__ballot(skip && is_cell && !dead));
+      r.c_total += (uint32_t)__builtin_popcountll(wballot(valid && is_cell));
+      r.c_unplaced += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && dead));
+      r.c_busy += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && !dead));
       fast = (valid && is_cell && st == SS_PLACED && !running && !((uint32_t)rec.z & SF_ENDING)) ? 1u : 0u;
-      todo = __ballot(valid && !skip);
+      todo = wballot(valid && !skip);
       r.dirty = 0;
       if (ev_hi - cur <= WAVE) {
         int32_t tl = lane_get(vt, (int)(ev_hi - cur - 1));
@@ -583,7 +609,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
     } else {
       final = true;
     }
-    const uint64_t fastmask = __ballot(fast != 0);
+    const uint64_t fastmask = wballot(fast != 0);
     for (;;) {
       if (r.status != NBOS_OK) break;
       int i = 0;
@@ -672,7 +698,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   __syncthreads();
   const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
   nbos_stats *out = p.stats + rep;
-  if (lane < 32) out->delay_hist[lane] = m.hist[lane];
+  if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
   if (lane == 0) {
     const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
     out->status = r.status; out->n_decisions = r.n_dec;
