@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--replays", type=int, default=None, help="truncate the batch (for quick looks)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 = skip")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = all host cores (at most 16)")
+    ap.add_argument("--hosts-in-lds", action="store_true", help="force the any-size kernel (comparison runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (replays are independent; a multi-GPU run "
@@ -70,7 +71,7 @@ def main():
     dev = replay.upload(batch, "cuda:0")
     torch.cuda.synchronize()
     t_up = time.perf_counter() - t0
-    h = replay.Replay(batch.config, dev)
+    h = replay.Replay(batch.config, dev, hosts_in_lds=args.hosts_in_lds)
     info = h.launch_info()
 
     for _ in range(args.warmup):

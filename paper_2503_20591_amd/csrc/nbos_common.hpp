@@ -32,6 +32,7 @@ struct KParams {
   uint32_t flags;
   int32_t migr, boot, retry_iv, max_retries, scale_iv, idle_pct, min_hosts;
   int32_t n_cap, q_cap;    // LDS capacity: sessions, queue entries
+  int32_t batch;           // event-parallel rounds on (LDS kernel)
 };
 
 __device__ __forceinline__ int32_t uni(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }

@@ -1,68 +1,106 @@
-// nbos_kernel_lds.hpp — replay kernel with host state in LDS: any cluster size up to
-// NBOS_MAX_HOSTS (several hosts per lane). Used when hosts_max > 64.
+// nbos_kernel_lds.hpp — replay kernel with host state in LDS: any cluster size up to NBOS_MAX_HOSTS.
+// Used when hosts_max > 64 (or on request). One workgroup (one wave64) per replay.
 //
-// One workgroup (one wave64) per replay. Per-replay state in LDS:
+// LDS per replay
+//   fin[h][8]    per-GPU "busy until" times, one 32-byte row per host. A GPU is committed at time t
+//                iff fin > t; binding g GPUs for a cell (paper Section 3.3) = writing its finish time
+//                into g free GPUs of the row. Completions need no timer: every timer due at or before
+//                an item runs before that item and a completion only lowers C, so "released once
+//                the clock has passed fin" is exact.
+//   ready_at[h]  0 for initial hosts, NEVER while off, boot completion time while provisioning
+//                (Section 3.4.2): readiness needs no timer either.
+//   hsn[h]       subscribed GPUs S | replica count << 16 (Section 3.4.1).
+//   mark[h]      scratch for the event-parallel rounds (lowest lane that chose the host), idle = ~0.
+//   sess[s]      12 bytes: hosts word (3 x 10 bits + last executor slot), time word (busy-until, or
+//                submit time while queued), flags.
+//   overflow     timers beyond the 64 that live sorted in registers.
 //
-//   fin[k][h]     per-GPU "busy until" time of GPU k on host h (k-major so that a scan over hosts
-//                 is a conflict-free stride-1 read). A GPU is committed at time t iff fin > t.
-//                 Dynamic GPU binding (paper Section 3.3) becomes: write the cell's finish time
-//                 into g free GPUs of the host. Completions need no timer: a GPU is released the
-//                 moment the clock passes its fin. This is exact because every timer due at or
-//                 before an item runs before that item, and a completion only lowers C.
-//   ready_at[h]   time the host becomes ready (0 for initial hosts, NEVER while off): hosts that
-//                 are being provisioned (Section 3.4.2) turn ready without a timer as well.
-//   hsn[h]        subscribed GPUs S (low 16 bits) and replica count (high 16 bits), Section 3.4.1.
-//   sessions      3 words each: replica hosts (3 x 10 bits) + last executor slot, a time word
-//                 (busy-until while running, submit time while queued), flags.
-//   queue         the few timers that do change decisions when they fire: RETRY of a queued cell
-//                 (Section 3.2.3) and the END of a session that was busy when its END arrived.
-//                 Unsorted array, minimum found by a wave-parallel scan.
+// Serial path: one item (arrival, queued timer, auto-scaler period) per loop iteration; lane = host
+// (strided) for every scan over hosts, ballot for feasibility, packed-key wave minimum for the choice
+// (committed, subscribed, index: ties to the lowest host index). The election (Section 3.2.2) reads
+// the 3 x 8 GPU words of the session's replica hosts with 24 lanes and counts with one ballot.
 //
-// Lane = host for every scan over hosts (placement, migration target, scale-out, scale-in):
-// feasibility by ballot, choice by a packed-key wave minimum (committed, subscribed, index), so
-// ties break to the lowest host index. The election (Section 3.2.2) reads the 3 x 8 GPU words of
-// the session's replica hosts with 24 lanes and counts committed GPUs with one ballot.
-// The event stream is read with coalesced dword loads, one event per lane, the next tile in flight
-// while the current one is consumed straight from registers (v_readlane), so events never touch LDS.
+// Event-parallel rounds: lane = event. A run of consecutive cell arrivals of idle placed sessions
+// with no timer due before them is evaluated at once: every lane gathers the rows of its session's
+// three hosts, counts committed GPUs at its own time and elects. A lane's result equals the serial
+// one iff no earlier lane of the run binds GPUs on one of its three hosts (its inputs are then
+// untouched) and no earlier lane failed its election (a failed election may migrate anywhere). The
+// longest prefix with that property is committed at once - the chosen hosts are pairwise distinct
+// by construction - and the rest is evaluated again. Counters are reduced over the prefix; the
+// decision digest d*P + code is folded as d*P^n + sum(code_i * P^(n-1-i)) with a table of powers.
+//
+// Events: coalesced dword loads, one event per lane, next tile in flight while the current tile is
+// consumed from registers. At tile start every lane prefetches its event's session record; cells of
+// rejected / ended sessions and cells that arrive while their session's running cell outlasts them
+// are counted in bulk and skipped.
 #pragma once
 #include "nbos_common.hpp"
 
 namespace {
 namespace ldsk {
 
-// Uniform per-replay registers (the compiler keeps them on the scalar unit).
-struct Regs {
-  uint32_t n_dec, placed, rejected, c_total, c_imm, c_started, c_queued, c_aborted, c_busy, c_unplaced;
-  uint32_t reused, migrations, so_hosts, si_hosts, peak;
-  int32_t max_delay, t_end, lazy_max;
-  int64_t sum_delay, sum_tct, g_exec, g_commit, prov, resv, sub;
-  uint64_t digest;
-  int32_t n_on, sum_s, open_g;   // hosts not off, cluster subscription, GPUs of open Reservation lifetimes
-  int32_t q_n, q_min_t, q_min_i; // queue size, time and index of its minimum
-  int32_t status;
-};
+enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
+       CS_NON, CS_SUMS, CS_OPENG, CS_N32 };
+enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_N64 };
+
+constexpr int32_t MARK_FREE = 0x7FFFFFFF;
+
+struct SessRec { int32_t x, y, z; };      // hosts word, time word, flags
 
 struct Lds {
-  int32_t *fin, *ready_at;
-  uint32_t *hsn, *hist;
-  uint32_t *s_hosts, *s_flag;
-  int32_t *s_time;
-  int32_t *q_t, *q_d;
-  uint32_t *q_i;
+  unsigned long long *c64;
+  uint32_t *c32, *hist;
+  unsigned long long *ppow;    // P^0 .. P^64 of the digest multiplier
+  int4 *fin;                   // two int4 per host
+  int32_t *ready_at, *mark;
+  uint32_t *hsn;
+  SessRec *sess;
+  int32_t *o_t, *o_d;
+  uint32_t *o_k;
+};
+
+struct Regs {
+  uint32_t n_dec, c_total, c_imm, c_started, c_busy, c_unplaced, reused, h0;
+  int64_t sum_dur, g_exec;
+  uint64_t digest;
+  int32_t lazy_max, t_end;
+  int32_t q_n, q_head_t;
+  int32_t o_n, o_min_t, o_min_i;
+  uint32_t o_min_k;
+  int32_t status;
+  uint64_t dirty;
 };
 
 struct Ctx {
   const KParams &p;
   Lds m;
   int lane;
-  int32_t caplim;          // cap_milli * G * 3
+  int32_t slim;              // floor(cap_milli * G * 3 / 1000): S + g <= slim is the cap test
   uint64_t *dlog;
+  int32_t qt, qd;            // sorted timers, entry i in lane i
+  uint32_t qk;
+  uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
 };
+
+__device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
+  if (lane == 0) atomicAdd(&m.c32[idx], v);
+}
+__device__ __forceinline__ void c32_max(Lds &m, int lane, int idx, uint32_t v) {
+  if (lane == 0) atomicMax(&m.c32[idx], v);
+}
+__device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
+  if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
+}
+
+__device__ __forceinline__ uint64_t decision_code(int32_t now, uint32_t outcome, uint32_t s, uint32_t slot,
+                                                  uint32_t host) {
+  return (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) | ((uint64_t)s << 16) |
+         ((uint64_t)(uint32_t)now << 32);
+}
 
 __device__ __forceinline__ void decide(Ctx &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
                                        uint32_t slot, uint32_t host) {
-  uint64_t code = (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) |
-                  ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
+  const uint64_t code = decision_code(now, outcome, s, slot, host);
   r.digest = r.digest * 0x100000001B3ULL + code;
   if (c.dlog) {
     if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
@@ -70,72 +108,131 @@ __device__ __forceinline__ void decide(Ctx &c, Regs &r, int32_t now, uint32_t ou
   r.n_dec++;
 }
 
-// ---- queue of decision-changing timers ----------------------------------------------------------
-__device__ __forceinline__ void queue_rescan(Ctx &c, Regs &r) {
+__device__ __forceinline__ void sess_write(Ctx &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
+  if (c.lane == 0) { c.m.sess[s].x = (int)hw; c.m.sess[s].y = tm; c.m.sess[s].z = (int)fl; }
+  r.dirty |= wballot(c.vsid == s);
+}
+__device__ __forceinline__ void sess_write_flag(Ctx &c, Regs &r, uint32_t s, uint32_t fl) {
+  if (c.lane == 0) c.m.sess[s].z = (int)fl;
+  r.dirty |= wballot(c.vsid == s);
+}
+
+// ---- timers: overflow array in LDS (unsorted) ---------------------------------------------------
+__device__ __forceinline__ void ovf_rescan(Ctx &c, Regs &r) {
   wave_sync();
   uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
   int bi = 0;
-  for (int i = c.lane; i < r.q_n; i += WAVE) {
-    uint32_t t = (uint32_t)c.m.q_t[i], l = c.m.q_i[i];
+  for (int i = c.lane; i < r.o_n; i += WAVE) {
+    uint32_t t = (uint32_t)c.m.o_t[i], l = c.m.o_k[i];
     if (t < bt || (t == bt && l < bl)) { bt = t; bl = l; bi = i; }
   }
   uint32_t mt = wave_min(bt);
   uint32_t ml = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
   uint64_t who = wballot(bt == mt && bl == ml);
   int src = (int)__builtin_ctzll(who | (1ull << 63));
-  r.q_min_i = lane_get(bi, src);
-  r.q_min_t = r.q_n > 0 ? (int32_t)mt : NEVER;
+  r.o_min_i = lane_get(bi, src);
+  r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
+  r.o_min_k = ml;
 }
 
-__device__ __forceinline__ void queue_push(Ctx &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t dur) {
-  wave_sync();
-  if (r.q_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
-  uint32_t key = (kind << 16) | id;
-  if (c.lane == 0) { c.m.q_t[r.q_n] = t; c.m.q_i[r.q_n] = key; c.m.q_d[r.q_n] = dur; }
-  bool better = r.q_n == 0 || t < r.q_min_t;
-  if (!better && t == r.q_min_t) better = key < uni(c.m.q_i[r.q_min_i]);
-  if (better) { r.q_min_t = t; r.q_min_i = r.q_n; }
+__device__ __forceinline__ void ovf_push(Ctx &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
+  if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
+  if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
+  if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) {
+    r.o_min_t = t; r.o_min_k = k; r.o_min_i = r.o_n;
+  }
+  r.o_n++;
+}
+
+// ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
+// Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
+// registers are empty only if the overflow array is.
+__device__ __forceinline__ void timer_push(Ctx &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
+  uint32_t k = (kind << 16) | id;
+  if (r.q_n == WAVE) {
+    int32_t mt = lane_get(c.qt, WAVE - 1);
+    uint32_t mk = (uint32_t)lane_get((int)c.qk, WAVE - 1);
+    if (t < mt || (t == mt && k < mk)) {
+      ovf_push(c, r, mt, mk, lane_get(c.qd, WAVE - 1));   // the latest register entry moves out
+      r.q_n = WAVE - 1;
+    } else {
+      ovf_push(c, r, t, k, d);
+      return;
+    }
+  } else if (r.o_n > 0 && !(t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k))) {
+    ovf_push(c, r, t, k, d);
+    return;
+  }
+  bool before = c.lane < r.q_n && (c.qt < t || (c.qt == t && c.qk < k));
+  int pos = __builtin_popcountll(wballot(before));
+  int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x138, 0xF, 0xF, false);          // wave_shr:1
+  int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x138, 0xF, 0xF, false);
+  uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
+  if (c.lane > pos) { c.qt = st; c.qd = sd; c.qk = sk; }
+  if (c.lane == pos) { c.qt = t; c.qd = d; c.qk = k; }
   r.q_n++;
+  if (pos == 0) r.q_head_t = t;
+}
+
+__device__ __forceinline__ void timer_pop(Ctx &c, Regs &r) {
+  c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                // wave_shl:1
+  c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
+  c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
+  r.q_n--;
+  if (r.q_n == 0 && r.o_n > 0) {
+    wave_sync();
+    int i = r.o_min_i, last = r.o_n - 1;
+    int32_t t = uni(c.m.o_t[i]), d = uni(c.m.o_d[i]);
+    uint32_t k = uni(c.m.o_k[i]);
+    int32_t lt = c.m.o_t[last], ld = c.m.o_d[last];
+    uint32_t lk = c.m.o_k[last];
+    if (i != last && c.lane == 0) { c.m.o_t[i] = lt; c.m.o_k[i] = lk; c.m.o_d[i] = ld; }
+    r.o_n = last;
+    if (c.lane == 0) { c.qt = t; c.qd = d; c.qk = k; }
+    r.q_n = 1;
+    ovf_rescan(c, r);
+  }
+  r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
 }
 
 // ---- host helpers -------------------------------------------------------------------------------
-// committed GPUs of host h at time `now` (one lane per host)
+// committed GPUs of host h at time `now` (GPUs beyond G keep fin = 0 and never count)
 __device__ __forceinline__ int committed(const Ctx &c, int h, int32_t now) {
-  int n = 0;
-#pragma unroll
-  for (int k = 0; k < NGPU; k++)
-    if (k < c.p.G) n += c.m.fin[k * c.p.HP + h] > now ? 1 : 0;
-  return n;
+  const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
+  return (a.x > now) + (a.y > now) + (a.z > now) + (a.w > now) + (b.x > now) + (b.y > now) + (b.z > now) + (b.w > now);
 }
 
 // bind g free GPUs of host h until `finish` (lanes 0..G-1 each look at one GPU)
 __device__ __forceinline__ void bind_gpus(Ctx &c, int h, int g, int32_t now, int32_t finish) {
   wave_sync();
-  bool mine = c.lane < c.p.G;
-  int32_t f = mine ? c.m.fin[c.lane * c.p.HP + h] : NEVER;
-  bool fr = mine && f <= now;
-  int rank = lane_rank(wballot(fr));
-  if (fr && rank < g) c.m.fin[c.lane * c.p.HP + h] = finish;
+  int32_t *row = (int32_t *)&c.m.fin[2 * h];
+  const bool mine = c.lane < c.p.G;
+  const int32_t f = mine ? row[c.lane] : NEVER;
+  const bool fr = mine && f <= now;
+  const int rank = lane_rank(wballot(fr));
+  if (fr && rank < g) row[c.lane] = finish;
 }
 
-// lowest host index that is off, or -1
+// lowest host index that is off (the caller has checked that one exists)
 __device__ __forceinline__ int find_off_host(const Ctx &c) {
   wave_sync();
   for (int base = 0; base < c.p.HP; base += WAVE) {
-    int h = base + c.lane;
-    uint64_t off = wballot(h < c.p.Hmax && c.m.ready_at[h] == NEVER);
+    const int h = base + c.lane;
+    const uint64_t off = wballot(h < c.p.Hmax && c.m.ready_at[h] == NEVER);
     if (off) return base + (int)__builtin_ctzll(off);
   }
-  return -1;
+  return 0;
 }
 
-__device__ __forceinline__ void boot_host(Ctx &c, Regs &r, int h, int32_t now) {
-  int32_t ra = now + c.p.boot;
-  if (c.lane == 0) c.m.ready_at[h] = ra;
-  r.n_on++;
-  r.peak = r.peak > (uint32_t)r.n_on ? r.peak : (uint32_t)r.n_on;
-  r.prov -= (int64_t)c.p.G * now;
+__device__ __forceinline__ int boot_host(Ctx &c, Regs &r, int32_t now, uint32_t hs_new) {
+  const int h = find_off_host(c);
+  const int32_t ra = now + c.p.boot;
+  if (c.lane == 0) { c.m.ready_at[h] = ra; c.m.hsn[h] = hs_new; }
+  c32_add(c.m, c.lane, CS_NON, 1u);
+  c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
+  c32_add(c.m, c.lane, CS_SO, 1u);
   r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
+  return h;
 }
 
 // Best host for one more replica with request g: ready, under the cap, optionally with g idle GPUs
@@ -145,222 +242,213 @@ __device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, 
   wave_sync();
   uint32_t best = 0xFFFFFFFFu;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
-    int32_t ra = c.m.ready_at[h];
-    int S = (int)(c.m.hsn[h] & 0xFFFFu);
-    int C = committed(c, h, now);
-    bool ok = ra <= now && (S + g) * 1000 <= c.caplim && h != ex0 && h != ex1;
-    if (need_idle) ok = ok && (c.p.G - C >= g);
-    uint32_t key = ((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)h;
+    const int32_t ra = c.m.ready_at[h];
+    const int S = (int)(c.m.hsn[h] & 0xFFFFu);
+    const int C = committed(c, h, now);
+    bool ok = ra <= now && S <= c.slim - g && h != ex0 && h != ex1;
+    if (need_idle) ok = ok && (C + g <= c.p.G);
+    const uint32_t key = ((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)h;
     if (ok) best = umin(best, key);
   }
   return wave_min(best);
 }
 
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
-__device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, int32_t now) {
-  wave_sync();
-  uint32_t fl = uni(c.m.s_flag[s]);
+__device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
   if ((fl & 7u) != SS_UNPLACED) return;
-  int g = (int)((fl >> 3) & 7u) + 1;
-  int pick[3] = {-1, -1, -1};
-  int k = 0;
-  for (int i = 0; i < 3; i++) {
-    uint32_t key = best_host(c, now, g, false, pick[0], pick[1]);
-    if (key == 0xFFFFFFFFu) break;
-    pick[i] = (int)(key & 1023u);
-    k++;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
+  uint32_t m0 = best_host(c, now, g, false, -1, -1);
+  if (m0 != 0xFFFFFFFFu) {
+    pick0 = (int)(m0 & 1023u); k = 1;
+    uint32_t m1 = best_host(c, now, g, false, pick0, -1);
+    if (m1 != 0xFFFFFFFFu) {
+      pick1 = (int)(m1 & 1023u); k = 2;
+      uint32_t m2 = best_host(c, now, g, false, pick0, pick1);
+      if (m2 != 0xFFFFFFFFu) { pick2 = (int)(m2 & 1023u); k = 3; }
+    }
   }
-  int missing = 3 - k;
-  if (missing > 0 && !((c.p.flags & NBOS_F_SCALE_OUT) && r.n_on + missing <= c.p.Hmax)) {
-    if (c.lane == 0) c.m.s_flag[s] = (fl & ~7u) | SS_REJECTED;
-    r.rejected++;
-    decide(c, r, now, NBOS_D_REJECT, s, 0, 0);
-    return;
+  const int missing = 3 - k;
+  if (missing > 0) {
+    wave_sync();
+    const int n_on = (int)uni(c.m.c32[CS_NON]);
+    if (!((c.p.flags & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
+      sess_write_flag(c, r, s, (fl & ~7u) | SS_REJECTED);
+      c32_add(c.m, c.lane, CS_REJECTED, 1u);
+      decide(c, r, now, NBOS_D_REJECT, s, 0, 0);
+      return;
+    }
   }
+  const uint32_t add = (uint32_t)g | (1u << 16);
   uint32_t hw = 0;
-  uint32_t add = (uint32_t)g | (1u << 16);
+#pragma unroll
   for (int i = 0; i < 3; i++) {
-    int h;
+    int h = i == 0 ? pick0 : (i == 1 ? pick1 : pick2);
     if (i < k) {
-      h = pick[i];
       if (c.lane == 0) c.m.hsn[h] += add;
       decide(c, r, now, NBOS_D_PLACE, s, (uint32_t)i, (uint32_t)h);
     } else {
-      h = find_off_host(c);
-      boot_host(c, r, h, now);
-      if (c.lane == 0) c.m.hsn[h] = add;
-      r.so_hosts++;
+      h = boot_host(c, r, now, add);
       decide(c, r, now, NBOS_D_PLACE_NEW, s, (uint32_t)i, (uint32_t)h);
     }
     hw |= (uint32_t)h << (10 * i);
   }
-  if (c.lane == 0) {
-    c.m.s_hosts[s] = hw;                     // last executor: none (bits 30..31 = 0)
-    c.m.s_flag[s] = (fl & ~7u) | SS_PLACED;
-    c.m.s_time[s] = 0;
+  if (missing > 0) {
+    wave_sync();
+    c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
   }
-  r.placed++;
-  r.sum_s += 3 * g;
-  r.open_g += g;
-  r.sub -= (int64_t)(3 * g) * now;
-  r.resv -= (int64_t)g * now;
+  sess_write(c, r, s, hw, 0, (fl & ~7u) | SS_PLACED);
+  c32_add(c.m, c.lane, CS_PLACED, 1u);
+  c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(3 * g));
+  c32_add(c.m, c.lane, CS_OPENG, (uint32_t)g);
+  c64_add(c.m, c.lane, CL_SUB, -(int64_t)(3 * g) * now);
+  c64_add(c.m, c.lane, CL_RESV, -(int64_t)g * now);
 }
 
 // the replicas of session s give their subscriptions back at time `now`
 __device__ __forceinline__ void end_session(Ctx &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
-  int g = (int)((fl >> 3) & 7u) + 1;
-  uint32_t sub = (uint32_t)g | (1u << 16);
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const uint32_t sub = (uint32_t)g | (1u << 16);
   if (c.lane < 3) {
-    int h = (int)((hw >> (10 * c.lane)) & 1023u);
-    c.m.hsn[h] -= sub;                        // three distinct hosts, one lane each
+    const int h = (int)((hw >> (10 * c.lane)) & 1023u);
+    c.m.hsn[h] -= sub;                          // three distinct hosts, one lane each
   }
-  if (c.lane == 0) c.m.s_flag[s] = (fl & ~(7u | SF_ENDING)) | SS_ENDED;
-  r.sum_s -= 3 * g;
-  r.sub += (int64_t)(3 * g) * now;
+  sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
+  c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(-3 * g));
+  c64_add(c.m, c.lane, CL_SUB, (int64_t)(3 * g) * now);
 }
 
 // ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
 __device__ __forceinline__ void start_cell(Ctx &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,
                                            uint32_t outcome) {
-  int g = (int)((fl >> 3) & 7u) + 1;
-  int32_t finish = start + dur;
-  int32_t delay = start - t_submit;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const int32_t finish = start + dur;
+  const int32_t delay = start - t_submit;
   r.c_started++;
-  r.sum_delay += delay;
-  r.max_delay = r.max_delay > delay ? r.max_delay : delay;
-  int b = delay == 0 ? 0 : 32 - __builtin_clz((uint32_t)delay);
-  b = b > 31 ? 31 : b;
-  if (c.lane == 0) atomicAdd(&c.m.hist[b], 1u);
-  r.sum_tct += (int64_t)finish - t_submit;
+  r.sum_dur += dur;
   r.g_exec += (int64_t)g * dur;
-  r.g_commit += (int64_t)g * ((int64_t)finish - now);
-  uint32_t last = hw >> 30;                   // 0 none, else slot + 1
+  const uint32_t last = hw >> 30;               // 0 none, else slot + 1
   if (last == (uint32_t)slot + 1u) r.reused++;
   hw = (hw & 0x3FFFFFFFu) | ((uint32_t)(slot + 1) << 30);
   hw = (hw & ~(1023u << (10 * slot))) | ((uint32_t)host << (10 * slot));
-  uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
-  if (c.lane == 0) {
-    c.m.s_hosts[s] = hw;
-    c.m.s_time[s] = finish;
-    c.m.s_flag[s] = nfl;
+  const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
+  if (delay == 0) {
+    r.h0++;                                     // histogram bin 0 lives in a register
+    if (c.lane == 0) {
+      c.m.sess[s].x = (int)hw; c.m.sess[s].y = finish;
+      if (nfl != fl) c.m.sess[s].z = (int)nfl;
+    }
+  } else {
+    int b = 32 - __builtin_clz((uint32_t)delay);
+    b = b > 31 ? 31 : b;
+    if (c.lane == 0) {
+      c.m.sess[s].x = (int)hw; c.m.sess[s].y = finish; c.m.sess[s].z = (int)nfl;
+      atomicAdd(&c.m.hist[b], 1u);
+      atomicAdd(&c.m.c64[CL_SUMDELAY], (unsigned long long)delay);
+      atomicMax(&c.m.c32[CS_MAXDELAY], (uint32_t)delay);
+      atomicAdd(&c.m.c64[CL_GWAIT], (unsigned long long)((int64_t)g * (start - now)));
+    }
   }
+  r.dirty |= wballot(c.vsid == s);
   r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
   decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
-  if (fl & SF_ENDING) queue_push(c, r, finish, QK_END, s, 0);
+  if (fl & SF_ENDING) timer_push(c, r, finish, QK_END, s, 0);
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
-// hw / fl are the session's current words; retries is the number of retries already scheduled.
 __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                         int32_t t_submit, int32_t dur) {
   wave_sync();
   const int G = c.p.G;
-  int g = (int)((fl >> 3) & 7u) + 1;
-  // (a) election, Section 3.2.2: lanes 0..23 = (replica r, GPU k) of the session's hosts
-  int rr = c.lane >> 3, k = c.lane & 7;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  // (a) election, Section 3.2.2: lanes 0..23 = (replica, GPU) of the session's hosts
+  int rr = c.lane >> 3;
   rr = rr > 2 ? 2 : rr;
-  int hr = (int)((hw >> (10 * rr)) & 1023u);
-  bool act = c.lane < 24 && k < G;
-  int32_t f = c.m.fin[k * c.p.HP + hr];
-  int32_t ra = c.m.ready_at[hr];
-  uint64_t busy = wballot(act && f > now);
-  uint64_t rdy = wballot(ra <= now);
-  const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
+  const int k = c.lane & 7;
+  const int hr = (int)((hw >> (10 * rr)) & 1023u);
+  const bool act = c.lane < 24;
+  int32_t *row = (int32_t *)&c.m.fin[2 * hr];
+  const int32_t f = row[k];
+  const int32_t ra = c.m.ready_at[hr];
+  const uint64_t busy = wballot(act && f > now);
+  const uint64_t rdy = wballot(ra <= now);
+  const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
   const int C0 = __builtin_popcount((uint32_t)busy & 0xFFu), C1 = __builtin_popcount((uint32_t)(busy >> 8) & 0xFFu),
             C2 = __builtin_popcount((uint32_t)(busy >> 16) & 0xFFu);
   const int ok0 = (int)(rdy & 1u), ok1 = (int)((rdy >> 8) & 1u), ok2 = (int)((rdy >> 16) & 1u);
-  // feasible replica with the fewest committed GPUs, then the lowest host index
-  const uint32_t k0 = (ok0 && G - C0 >= g) ? (((uint32_t)C0 << 12) | ((uint32_t)h0 << 2) | 0u) : 0xFFFFFFFFu;
-  const uint32_t k1 = (ok1 && G - C1 >= g) ? (((uint32_t)C1 << 12) | ((uint32_t)h1 << 2) | 1u) : 0xFFFFFFFFu;
-  const uint32_t k2 = (ok2 && G - C2 >= g) ? (((uint32_t)C2 << 12) | ((uint32_t)h2 << 2) | 2u) : 0xFFFFFFFFu;
+  const uint32_t k0 = (ok0 && C0 + g <= G) ? (((uint32_t)C0 << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
+  const uint32_t k1 = (ok1 && C1 + g <= G) ? (((uint32_t)C1 << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
+  const uint32_t k2 = (ok2 && C2 + g <= G) ? (((uint32_t)C2 << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
   const uint32_t kb = umin(k0, umin(k1, k2));
   if (kb != 0xFFFFFFFFu) {
     const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
-    int32_t finish = now + dur;
-    bool fr = act && (c.lane >> 3) == lead && f <= now;
-    int rank = lane_rank(wballot(fr));
-    if (fr && rank < g) c.m.fin[k * c.p.HP + hr] = finish;
+    const bool fr = act && (c.lane >> 3) == lead && k < G && f <= now;
+    const int rank = lane_rank(wballot(fr));
+    if (fr && rank < g) row[k] = now + dur;
     if (now == t_submit) r.c_imm++;
     start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
     return;
   }
-  // every replica yields: the replica on the fullest ready host would move (ties: lowest host).
-  // Key: committed GPUs descending, host ascending -> minimise (8 - C, host).
-  const int any_ready = ok0 | ok1 | ok2;
-  const uint32_t v0 = (!any_ready || ok0) ? (((uint32_t)(8 - C0) << 12) | ((uint32_t)h0 << 2) | 0u) : 0xFFFFFFFFu;
-  const uint32_t v1 = (!any_ready || ok1) ? (((uint32_t)(8 - C1) << 12) | ((uint32_t)h1 << 2) | 1u) : 0xFFFFFFFFu;
-  const uint32_t v2 = (!any_ready || ok2) ? (((uint32_t)(8 - C2) << 12) | ((uint32_t)h2 << 2) | 2u) : 0xFFFFFFFFu;
-  const uint32_t vb = umin(v0, umin(v1, v2));
-  const int victim = (int)(vb & 3u), hv = (int)((vb >> 2) & 1023u);
-  uint32_t moved = (uint32_t)g | (1u << 16);
-  // (b) migration, Section 3.2.3: the target binds the GPUs at once. A ready host of this session
-  // with g idle GPUs would have won the election, so none of its hosts can show up as a target.
-  if (c.p.flags & NBOS_F_MIGRATE) {
-    uint32_t key = best_host(c, now, g, true, -1, -1);
-    if (key != 0xFFFFFFFFu) {
-      int dst = (int)(key & 1023u);
-      int32_t start = now + c.p.migr;
+  // (b), (c): a target exists? Only then is the replica to move worked out.
+  uint32_t tkey = 0xFFFFFFFFu;
+  if (c.p.flags & NBOS_F_MIGRATE) tkey = best_host(c, now, g, true, -1, -1);
+  bool grow = false;
+  if (tkey == 0xFFFFFFFFu && (c.p.flags & NBOS_F_SCALE_OUT)) {
+    wave_sync();
+    grow = (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
+  }
+  if (tkey != 0xFFFFFFFFu || grow) {
+    // the replica on the fullest ready host moves (ties: lowest host); booting ones only if all are
+    const int any_ready = ok0 | ok1 | ok2;
+    const uint32_t v0 = (!any_ready || ok0) ? (((uint32_t)(8 - C0) << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
+    const uint32_t v1 = (!any_ready || ok1) ? (((uint32_t)(8 - C1) << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
+    const uint32_t v2 = (!any_ready || ok2) ? (((uint32_t)(8 - C2) << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
+    const uint32_t vb = umin(v0, umin(v1, v2));
+    const int victim = (int)(vb & 3u), hv = (int)((vb >> 2) & 1023u);
+    const uint32_t moved = (uint32_t)g | (1u << 16);
+    if (tkey != 0xFFFFFFFFu) {
+      // (b) migration, Section 3.2.3: the target binds the GPUs at once. A ready host of this session
+      // with g idle GPUs would have won the election, so none of its hosts can show up as a target.
+      const int dst = (int)(tkey & 1023u);
+      const int32_t start = now + c.p.migr;
       if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[dst] += moved; }
       bind_gpus(c, dst, g, now, start + dur);
-      r.migrations++;
+      c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
-      return;
+    } else {
+      // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
+      const int32_t start = now + c.p.boot + c.p.migr;
+      if (c.lane == 0) c.m.hsn[hv] -= moved;
+      const int h = boot_host(c, r, now, moved);
+      wave_sync();
+      c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
+      bind_gpus(c, h, g, now, start + dur);
+      c32_add(c.m, c.lane, CS_MIGR, 1u);
+      start_cell(c, r, s, hw, fl, victim, h, now, start, t_submit, dur, NBOS_D_SCALE_CELL);
     }
-  }
-  // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
-  if ((c.p.flags & NBOS_F_SCALE_OUT) && r.n_on < c.p.Hmax) {
-    int h = find_off_host(c);
-    int32_t start = now + c.p.boot + c.p.migr;
-    boot_host(c, r, h, now);
-    if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[h] = moved; }
-    bind_gpus(c, h, g, now, start + dur);
-    r.so_hosts++;
-    r.migrations++;
-    start_cell(c, r, s, hw, fl, victim, h, now, start, t_submit, dur, NBOS_D_SCALE_CELL);
     return;
   }
   // (d) queue and retry periodically, then give up, Section 3.2.3
   int retries = (int)((fl >> 8) & 15u);
   if (retries < c.p.max_retries) {
     retries++;
-    if (!(fl & SF_QONCE)) r.c_queued++;
-    uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
-    if (c.lane == 0) { c.m.s_flag[s] = nfl; c.m.s_time[s] = t_submit; }
-    queue_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
+    const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
+    if (!(fl & SF_QONCE)) {                      // first time in the queue: the submit time goes in
+      c32_add(c.m, c.lane, CS_QUEUED, 1u);
+      if (c.lane == 0) { c.m.sess[s].y = t_submit; c.m.sess[s].z = (int)nfl; }
+    } else {
+      if (c.lane == 0) c.m.sess[s].z = (int)nfl;
+    }
+    r.dirty |= wballot(c.vsid == s);
+    timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
     return;
   }
-  r.c_aborted++;
+  c32_add(c.m, c.lane, CS_ABORTED, 1u);
   decide(c, r, now, NBOS_D_ABORT, s, 0, 0);
-  uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
-  if (c.lane == 0) { c.m.s_flag[s] = nfl; c.m.s_time[s] = 0; }
+  const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
+  sess_write(c, r, s, hw, 0, nfl);
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
-}
-
-// ---- the earliest queued timer fires ------------------------------------------------------------
-__device__ __forceinline__ void queue_fire(Ctx &c, Regs &r) {
-  wave_sync();
-  int i = r.q_min_i;
-  int32_t now = r.q_min_t;
-  uint32_t key = uni(c.m.q_i[i]);
-  int32_t dur = uni(c.m.q_d[i]);
-  int last = r.q_n - 1;
-  if (i != last) {                            // fill the hole with the last entry
-    int32_t lt = c.m.q_t[last], ld = c.m.q_d[last];
-    uint32_t li = c.m.q_i[last];
-    if (c.lane == 0) { c.m.q_t[i] = lt; c.m.q_i[i] = li; c.m.q_d[i] = ld; }
-  }
-  r.q_n = last;
-  r.t_end = r.t_end > now ? r.t_end : now;
-  uint32_t s = key & 0xFFFFu;
-  uint32_t hw = uni(c.m.s_hosts[s]), fl = uni(c.m.s_flag[s]);
-  if ((key >> 16) == QK_RETRY) {
-    int32_t t_submit = uni(c.m.s_time[s]);
-    attempt(c, r, s, hw, fl, now, t_submit, dur);
-  } else {
-    end_session(c, r, s, hw, fl, now);
-  }
-  queue_rescan(c, r);
 }
 
 // ---- auto-scaler period: release at most two empty hosts (Section 3.4.2, last paragraph) --------
@@ -368,8 +456,8 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
   wave_sync();
   int A = 0, Z = 0;
   for (int base = 0; base < c.p.HP; base += WAVE) {
-    int h = base + c.lane;
-    bool ready = c.m.ready_at[h] <= now;
+    const int h = base + c.lane;
+    const bool ready = c.m.ready_at[h] <= now;
     A += __builtin_popcountll(wballot(ready));
     Z += __builtin_popcountll(wballot(ready && (c.m.hsn[h] >> 16) == 0));
   }
@@ -378,69 +466,127 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
     int victim = -1;
     wave_sync();
     for (int base = c.p.HP - WAVE; base >= 0 && victim < 0; base -= WAVE) {
-      int h = base + c.lane;
-      uint64_t e = wballot(c.m.ready_at[h] <= now && (c.m.hsn[h] >> 16) == 0);
+      const int h = base + c.lane;
+      const uint64_t e = wballot(c.m.ready_at[h] <= now && (c.m.hsn[h] >> 16) == 0);
       if (e) victim = base + 63 - (int)__builtin_clzll(e);
     }
     if (c.lane == 0) c.m.ready_at[victim] = NEVER;
-    r.n_on--;
-    r.prov += (int64_t)c.p.G * now;
+    c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
+    c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
+    c32_add(c.m, c.lane, CS_SI, 1u);
     A--; Z--; released++;
-    r.si_hosts++;
     decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
   }
 }
 
-// ---- arrivals -----------------------------------------------------------------------------------
-__device__ __forceinline__ void on_cell(Ctx &c, Regs &r, uint32_t s, int32_t now, int32_t dur) {
-  wave_sync();
-  r.c_total++;
-  uint32_t fl = uni(c.m.s_flag[s]);
-  uint32_t st = fl & 7u;
-  if (st == SS_PLACED) {
-    int32_t busy_until = uni(c.m.s_time[s]);
-    if (busy_until > now) { r.c_busy++; return; }
-    uint32_t hw = uni(c.m.s_hosts[s]);
-    attempt(c, r, s, hw, fl & ~(SF_QONCE | (15u << 8)), now, now, dur);
-  } else if (st == SS_QUEUED) {
-    r.c_busy++;
-  } else {
-    r.c_unplaced++;
-  }
-}
-
-__device__ __forceinline__ void on_session_end(Ctx &c, Regs &r, uint32_t s, int32_t now) {
-  wave_sync();
-  uint32_t fl = uni(c.m.s_flag[s]);
-  uint32_t st = fl & 7u;
+__device__ __forceinline__ void on_session_end(Ctx &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl,
+                                               int32_t now) {
+  const uint32_t st = fl & 7u;
   if ((st != SS_PLACED && st != SS_QUEUED) || (fl & SF_ENDING)) return;
-  int g = (int)((fl >> 3) & 7u) + 1;
-  int32_t busy_until = uni(c.m.s_time[s]);
-  r.open_g -= g;                              // the Reservation lifetime closes at the END event
-  r.resv += (int64_t)g * now;
-  if (st == SS_PLACED && busy_until <= now) {
-    end_session(c, r, s, uni(c.m.s_hosts[s]), fl, now);
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  c32_add(c.m, c.lane, CS_OPENG, (uint32_t)-g);         // the Reservation lifetime closes at the END event
+  c64_add(c.m, c.lane, CL_RESV, (int64_t)g * now);
+  if (st == SS_PLACED && tm <= now) {
+    end_session(c, r, s, hw, fl, now);
   } else {
-    if (c.lane == 0) c.m.s_flag[s] = fl | SF_ENDING;
-    if (st == SS_PLACED) queue_push(c, r, busy_until, QK_END, s, 0);
+    sess_write_flag(c, r, s, fl | SF_ENDING);
+    if (st == SS_PLACED) timer_push(c, r, tm, QK_END, s, 0);
   }
 }
 
-// run every queued timer and auto-scaler period due at or before t
-__device__ __forceinline__ void drain_until(Ctx &c, Regs &r, int32_t t, int32_t &tick_t) {
-  const bool scale_in = (c.p.flags & NBOS_F_SCALE_IN) != 0;
-  while (r.status == NBOS_OK) {
-    bool q_due = r.q_n > 0 && r.q_min_t <= t;
-    bool t_due = scale_in && tick_t <= t;
-    if (q_due && (!t_due || r.q_min_t <= tick_t)) {
-      queue_fire(c, r);
-    } else if (t_due) {
-      tick(c, r, tick_t);
-      tick_t += c.p.scale_iv;
-    } else {
-      break;
-    }
+// Sum of a small non-negative per-lane value (< 2^25) over the wave, returned uniform.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+  v += dpp<0xB1>(v);
+  v += dpp<0x4E>(v);
+  v += dpp<0x141>(v);
+  v += dpp<0x140>(v);
+  return (uint32_t)lane_get((int)v, 0) + (uint32_t)lane_get((int)v, 16) + (uint32_t)lane_get((int)v, 32) +
+         (uint32_t)lane_get((int)v, 48);
+}
+
+// ---- one event-parallel round over the lanes in `run` (see the file header) -----------------------
+// Returns the mask of lanes whose cells were started. rec = the lane's prefetched session record.
+__device__ __forceinline__ uint64_t batch_round(Ctx &c, Regs &r, uint64_t run, int32_t vt, int32_t vd, uint32_t sid,
+                                                const SessRec &rec) {
+  wave_sync();
+  const int G = c.p.G;
+  const bool in_run = (run >> c.lane) & 1u;
+  const uint32_t hw = (uint32_t)rec.x, fl = (uint32_t)rec.z;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+  // committed GPUs of the three hosts at this lane's own time
+  const int4 a0 = c.m.fin[2 * h0], b0 = c.m.fin[2 * h0 + 1];
+  const int4 a1 = c.m.fin[2 * h1], b1 = c.m.fin[2 * h1 + 1];
+  const int4 a2 = c.m.fin[2 * h2], b2 = c.m.fin[2 * h2 + 1];
+  const int32_t r0 = c.m.ready_at[h0], r1 = c.m.ready_at[h1], r2 = c.m.ready_at[h2];
+  const int C0 = (a0.x > vt) + (a0.y > vt) + (a0.z > vt) + (a0.w > vt) + (b0.x > vt) + (b0.y > vt) + (b0.z > vt) + (b0.w > vt);
+  const int C1 = (a1.x > vt) + (a1.y > vt) + (a1.z > vt) + (a1.w > vt) + (b1.x > vt) + (b1.y > vt) + (b1.z > vt) + (b1.w > vt);
+  const int C2 = (a2.x > vt) + (a2.y > vt) + (a2.z > vt) + (a2.w > vt) + (b2.x > vt) + (b2.y > vt) + (b2.z > vt) + (b2.w > vt);
+  const uint32_t k0 = (r0 <= vt && C0 + g <= G) ? (((uint32_t)C0 << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
+  const uint32_t k1 = (r1 <= vt && C1 + g <= G) ? (((uint32_t)C1 << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
+  const uint32_t k2 = (r2 <= vt && C2 + g <= G) ? (((uint32_t)C2 << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
+  const uint32_t kb = umin(k0, umin(k1, k2));
+  const bool won = in_run && kb != 0xFFFFFFFFu;
+  const int lead = (int)(kb & 3u);
+  const int ch = won ? (int)((kb >> 2) & 1023u) : 0;
+  // who binds where: the lowest lane that chose a host marks it
+  if (won) atomicMin(&c.m.mark[ch], c.lane);
+  wave_sync();
+  const int32_t m0 = c.m.mark[h0], m1 = c.m.mark[h1], m2 = c.m.mark[h2];
+  const int32_t first = m0 < m1 ? (m0 < m2 ? m0 : m2) : (m1 < m2 ? m1 : m2);
+  wave_sync();
+  if (won) c.m.mark[ch] = MARK_FREE;
+  const uint64_t bad = run & wballot(in_run && (!won || first < c.lane));
+  const uint64_t below = bad ? ((1ull << __builtin_ctzll(bad)) - 1ull) : ~0ull;
+  const uint64_t done = run & below;
+  if (done == 0) return 0;
+  const bool mine = (done >> c.lane) & 1u;
+  const int32_t finish = vt + vd;
+  if (mine) {
+    // bind g free GPUs of the chosen host: rewrite its row
+    int4 a = lead == 0 ? a0 : (lead == 1 ? a1 : a2);
+    int4 b = lead == 0 ? b0 : (lead == 1 ? b1 : b2);
+    int need = g;
+    if (need > 0 && a.x <= vt) { a.x = finish; need--; }
+    if (need > 0 && G > 1 && a.y <= vt) { a.y = finish; need--; }
+    if (need > 0 && G > 2 && a.z <= vt) { a.z = finish; need--; }
+    if (need > 0 && G > 3 && a.w <= vt) { a.w = finish; need--; }
+    if (need > 0 && G > 4 && b.x <= vt) { b.x = finish; need--; }
+    if (need > 0 && G > 5 && b.y <= vt) { b.y = finish; need--; }
+    if (need > 0 && G > 6 && b.z <= vt) { b.z = finish; need--; }
+    if (need > 0 && G > 7 && b.w <= vt) { b.w = finish; need--; }
+    c.m.fin[2 * ch] = a; c.m.fin[2 * ch + 1] = b;
+    const uint32_t nhw = (hw & 0x3FFFFFFFu) | ((uint32_t)(lead + 1) << 30);
+    c.m.sess[sid].x = (int)nhw; c.m.sess[sid].y = finish;
   }
+  // counters over the started lanes
+  const uint32_t n = (uint32_t)__builtin_popcountll(done);
+  const uint32_t dl = mine ? (uint32_t)vd : 0u;
+  const uint32_t gd = mine ? (uint32_t)(g * vd) : 0u;          // < 8 * 86.4e6 < 2^30
+  r.c_started += n; r.c_imm += n; r.h0 += n;
+  r.reused += (uint32_t)__builtin_popcountll(wballot(mine && (hw >> 30) == (uint32_t)lead + 1u));
+  r.sum_dur += (int64_t)wave_sum(dl & 0xFFFFu) + ((int64_t)wave_sum(dl >> 16) << 16);
+  r.g_exec += (int64_t)wave_sum(gd & 0xFFFFu) + ((int64_t)wave_sum(gd >> 16) << 16);
+  const uint32_t fmax = wave_min(mine ? ~(uint32_t)finish : 0xFFFFFFFFu);
+  const int32_t fm = (int32_t)~fmax;
+  r.lazy_max = r.lazy_max > fm ? r.lazy_max : fm;
+  // digest: d * P^n + sum over started lanes of code * P^(n - 1 - rank)
+  const int rank = lane_rank(done);
+  const uint64_t code = decision_code(vt, NBOS_D_START, sid, (uint32_t)lead, (uint32_t)ch);
+  const uint64_t term = mine ? code * c.m.ppow[mine ? n - 1u - (uint32_t)rank : 0u] : 0ull;
+  const uint32_t t0 = (uint32_t)term & 0xFFFFu, t1 = ((uint32_t)term >> 16), t2 = (uint32_t)(term >> 32) & 0xFFFFu,
+                 t3 = (uint32_t)(term >> 48);
+  const uint64_t sum = (uint64_t)wave_sum(t0) + ((uint64_t)wave_sum(t1) << 16) + ((uint64_t)wave_sum(t2) << 32) +
+                       ((uint64_t)wave_sum(t3) << 48);
+  const unsigned long long pn = c.m.ppow[n];
+  const uint64_t pnu = (uint64_t)uni((uint32_t)pn) | ((uint64_t)uni((uint32_t)(pn >> 32)) << 32);
+  r.digest = r.digest * pnu + sum;
+  if (c.dlog) {
+    const int64_t at = (int64_t)r.n_dec + rank;
+    if (mine && at < c.p.dlog_stride) c.dlog[at] = code;
+  }
+  r.n_dec += n;
+  return done;
 }
 
 __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
@@ -454,96 +600,225 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   const int s_lo = p.sess_offset[trace];
   const int n_sess = p.sess_offset[trace + 1] - s_lo;
 
-  // carve LDS
   Lds m;
   unsigned char *q = lds_raw;
-  m.fin = (int32_t *)q;        q += (size_t)NGPU * p.HP * 4;
-  m.ready_at = (int32_t *)q;   q += (size_t)p.HP * 4;
-  m.hsn = (uint32_t *)q;       q += (size_t)p.HP * 4;
-  m.hist = (uint32_t *)q;      q += 32 * 4;
-  m.s_hosts = (uint32_t *)q;   q += (size_t)p.n_cap * 4;
-  m.s_time = (int32_t *)q;     q += (size_t)p.n_cap * 4;
-  m.s_flag = (uint32_t *)q;    q += (size_t)p.n_cap * 4;
-  m.q_t = (int32_t *)q;        q += (size_t)p.q_cap * 4;
-  m.q_i = (uint32_t *)q;       q += (size_t)p.q_cap * 4;
-  m.q_d = (int32_t *)q;
+  m.c64 = (unsigned long long *)q;  q += 8 * 8;
+  m.c32 = (uint32_t *)q;            q += 16 * 4;
+  m.hist = (uint32_t *)q;           q += 32 * 4;
+  m.ppow = (unsigned long long *)q; q += 66 * 8;
+  m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
+  m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
+  m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
+  m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
+  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
+  m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
+  m.o_k = (uint32_t *)q;            q += (size_t)p.q_cap * 4;
+  m.o_d = (int32_t *)q;
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
-  for (int i = lane; i < NGPU * p.HP; i += WAVE) m.fin[i] = 0;
-  for (int h = lane; h < p.HP; h += WAVE) { m.ready_at[h] = h < p.H0 ? 0 : NEVER; m.hsn[h] = 0; }
+  if (lane < 8) m.c64[lane] = 0;
+  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
   if (lane < 32) m.hist[lane] = 0;
+  if (lane == 0) {
+    unsigned long long pw = 1;
+    for (int i = 0; i <= 64; i++) { m.ppow[i] = pw; pw *= 0x100000001B3ULL; }
+  }
+  for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
+  for (int h = lane; h < p.HP; h += WAVE) { m.ready_at[h] = h < p.H0 ? 0 : NEVER; m.mark[h] = MARK_FREE; m.hsn[h] = 0; }
   for (int s = lane; s < n_sess; s += WAVE) {
-    uint32_t g = p.sess_gpus[s_lo + s];
-    m.s_hosts[s] = 0; m.s_time[s] = 0; m.s_flag[s] = SS_UNPLACED | ((g - 1u) << 3);
+    const uint32_t g = p.sess_gpus[s_lo + s];
+    m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
   }
   __syncthreads();
 
-  Ctx c{p, m, lane, p.cap_milli[rep] * p.G * 3, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+  const int32_t caplim = p.cap_milli[rep] * p.G * 3;
+  Ctx c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
+        NEVER, 0, 0xFFFFFFFFu, 0xFFFFFFFFu};
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
-  r.n_on = p.H0;
-  r.peak = (uint32_t)p.H0;
-  r.q_min_t = NEVER;
-  int32_t tick_t = p.scale_iv;
-  int32_t t_last = 0;
+  r.q_head_t = NEVER;
+  r.o_min_t = NEVER;
+
+  const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
+  const bool batching = p.batch != 0;
+  // hash buckets (power of two <= HP) for spotting two events of one session in a tile
+  const uint32_t dup_mask = (1u << (31 - __builtin_clz((uint32_t)p.HP))) - 1u;
+  int32_t tick_t = scale_in ? p.scale_iv : NEVER;
+  int32_t due_t = tick_t;                   // earliest queued timer or auto-scaler period
+  int cooldown = 0;                         // serial items to go before the next parallel round
 
   // S1: stream the events, one per lane per tile, next tile in flight
-  int64_t base = ev_lo;
-  int32_t vt = 0, vd = 0, vs = 0;
-  if (base + lane < ev_hi) { vt = p.ev_time[base + lane]; vd = p.ev_dur[base + lane]; vs = p.ev_sk[base + lane]; }
-  while (base < ev_hi && r.status == NBOS_OK) {
-    int64_t nb = base + WAVE;
-    int32_t nt = 0, nd = 0, ns = 0;
-    if (nb + lane < ev_hi) { nt = p.ev_time[nb + lane]; nd = p.ev_dur[nb + lane]; ns = p.ev_sk[nb + lane]; }
-    int cnt = (int)(ev_hi - base < WAVE ? ev_hi - base : WAVE);
-    for (int i = 0; i < cnt && r.status == NBOS_OK; i++) {
-      int32_t t = lane_get(vt, i), d = lane_get(vd, i);
-      uint32_t sk = (uint32_t)lane_get(vs, i);
-      uint32_t s = sk & 0xFFFFFFu, kind = sk >> 24;
-      drain_until(c, r, t, tick_t);                       // S2
-      t_last = t;
-      if (kind == NBOS_EV_CELL) on_cell(c, r, s, t, d);    // S4-S8
-      else if (kind == NBOS_EV_START) session_start(c, r, s, t);   // S3, S7
-      else on_session_end(c, r, s, t);
-    }
-    vt = nt; vd = nd; vs = ns;
-    base = nb;
-  }
+  int64_t base = ev_lo;                     // first event of the tile held in (nt, nd, ns)
+  int32_t vt = 0, vd = 0, vs = 0, nt = 0, nd = 0, ns = 0;
+  if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
 
-  // S10: drain. An auto-scaler period runs only while another timer is still pending.
-  r.t_end = r.t_end > t_last ? r.t_end : t_last;
-  const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
+  bool final = false;
   while (r.status == NBOS_OK) {
-    if (r.q_n > 0) {
-      if (scale_in && tick_t < r.q_min_t) { tick(c, r, tick_t); tick_t += p.scale_iv; }
-      else queue_fire(c, r);
-    } else if (scale_in && tick_t < r.lazy_max) {
-      tick(c, r, tick_t); tick_t += p.scale_iv;
+    SessRec rec = {0, 0, 0};                // prefetched session record of this lane's event
+    bool fast = false;                      // this lane's event is a cell of an idle placed session
+    uint64_t todo = 0;
+    uint32_t sid = 0;
+    if (base < ev_hi) {
+      vt = nt; vd = nd; vs = ns;
+      const int64_t cur = base;
+      base += WAVE;
+      if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
+      const bool valid = cur + lane < ev_hi;
+      const bool is_last = cur + lane == ev_hi - 1;
+      sid = valid ? ((uint32_t)vs & 0xFFFFFFu) : 0u;
+      const bool is_cell = ((uint32_t)vs >> 24) == NBOS_EV_CELL;
+      c.vsid = valid ? sid : 0xFFFFFFFFu;
+      wave_sync();
+      if (valid) rec = m.sess[sid];
+      // Cells of sessions in a final state (rejected / ended) and cells that arrive while the
+      // session's running cell lasts beyond them change nothing: count them, skip them. Neither
+      // condition can be undone before the event's time. The last event of the trace is never
+      // skipped, so timers due before it still run first.
+      const uint32_t st = (uint32_t)rec.z & 7u;
+      const bool dead = st == SS_REJECTED || st == SS_ENDED;
+      const bool running = st == SS_PLACED && rec.y > vt;
+      const bool skip = valid && !is_last && (dead || (is_cell && running));
+      r.c_total += (uint32_t)__builtin_popcountll(wballot(valid && is_cell));
+      r.c_unplaced += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && dead));
+      r.c_busy += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && !dead));
+      fast = valid && is_cell && st == SS_PLACED && !running && !((uint32_t)rec.z & SF_ENDING);
+      todo = wballot(valid && !skip);
+      r.dirty = 0;
+      if (batching) {
+        // a lane whose session may also belong to an earlier lane of the tile keeps out of the rounds
+        const uint32_t b = sid & dup_mask;
+        if (valid) atomicMin(&m.mark[b], lane);
+        wave_sync();
+        const bool dup = valid && m.mark[b] < lane;
+        wave_sync();
+        if (valid) m.mark[b] = MARK_FREE;
+        r.dirty = wballot(dup);
+      }
+      if (ev_hi - cur <= WAVE) {
+        int32_t tl = lane_get(vt, (int)(ev_hi - cur - 1));
+        r.t_end = r.t_end > tl ? r.t_end : tl;
+      }
     } else {
-      break;
+      final = true;
     }
+    const uint64_t fastmask = wballot(fast);
+    for (;;) {
+      if (r.status != NBOS_OK) break;
+      int i = 0;
+      int32_t t = NEVER;
+      if (todo != 0) { i = (int)__builtin_ctzll(todo); t = lane_get(vt, i); }
+      else if (!final) break;
+      wave_sync();
+      uint32_t a_s, a_hw, a_fl;
+      int32_t a_now, a_sub, a_dur;
+      if (__builtin_expect(t < due_t, 1)) {
+        const uint64_t bit = 1ull << i;
+        const uint64_t clean = fastmask & ~r.dirty;
+        if (batching && cooldown == 0 && (clean & bit) != 0) {
+          // ---- event-parallel round over the run of fast arrivals that starts at lane i ----
+          const uint64_t eligible = clean & wballot(vt < due_t);
+          const uint64_t blockers = todo & ~eligible;
+          const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
+          if ((run & (run - 1)) != 0) {          // at least two lanes
+            const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec);
+            if ((done & (done - 1)) == 0) cooldown = 8;   // nothing or one event: not worth it for a while
+            if (done != 0) { todo &= ~done; continue; }
+          }
+        }
+        if (cooldown > 0) cooldown--;
+        // ---- arrival i, serial ----
+        todo &= ~bit;
+        const uint32_t sk = (uint32_t)lane_get(vs, i);
+        const uint32_t s = sk & 0xFFFFFFu;
+        if (__builtin_expect((clean & bit) != 0, 1)) {
+          a_s = s; a_hw = (uint32_t)lane_get(rec.x, i);
+          a_fl = (uint32_t)lane_get(rec.z, i);
+          a_now = t; a_sub = t; a_dur = lane_get(vd, i);
+        } else {
+          const uint32_t kind = sk >> 24;
+          uint32_t hw, fl;
+          int32_t tm;
+          if ((r.dirty >> i) & 1u) {
+            const SessRec cur = m.sess[s];
+            hw = uni((uint32_t)cur.x); tm = uni(cur.y); fl = uni((uint32_t)cur.z);
+          } else {
+            hw = (uint32_t)lane_get(rec.x, i); tm = lane_get(rec.y, i); fl = (uint32_t)lane_get(rec.z, i);
+          }
+          if (kind == NBOS_EV_CELL) {           // S4-S8 (counted in c_total at tile load)
+            const uint32_t st = fl & 7u;
+            if (st == SS_PLACED && tm <= t) {
+              a_s = s; a_hw = hw; a_fl = fl & ~(SF_QONCE | (15u << 8)); a_now = t; a_sub = t; a_dur = lane_get(vd, i);
+            } else {
+              if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++; else r.c_unplaced++;
+              continue;
+            }
+          } else {
+            if (kind == NBOS_EV_START) session_start(c, r, s, fl, t);      // S3, S7
+            else on_session_end(c, r, s, hw, tm, fl, t);
+            due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+            continue;
+          }
+        }
+      } else {
+        // ---- a timer may be due (S2); always taken while draining ----
+        bool fire_q = r.q_n > 0, fire_t = scale_in;
+        if (final) {
+          if (fire_t) fire_t = fire_q ? tick_t < r.q_head_t : tick_t < r.lazy_max;
+          if (fire_t) fire_q = false;
+        } else {
+          if (fire_q) fire_q = r.q_head_t <= t;
+          if (fire_t) fire_t = tick_t <= t;
+          if (fire_q && fire_t) { if (r.q_head_t <= tick_t) fire_t = false; else fire_q = false; }
+        }
+        if (fire_t) {
+          tick(c, r, tick_t);
+          tick_t += p.scale_iv;
+          due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          continue;
+        }
+        if (!fire_q) break;                   // only reached while draining: nothing is left
+        const int32_t now = r.q_head_t;
+        const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
+        const int32_t dur = lane_get(c.qd, 0);
+        timer_pop(c, r);
+        r.t_end = r.t_end > now ? r.t_end : now;
+        const uint32_t s = key & 0xFFFFu;
+        const SessRec cur = m.sess[s];
+        const uint32_t hw = uni((uint32_t)cur.x), fl = uni((uint32_t)cur.z);
+        if ((key >> 16) != QK_RETRY) {
+          end_session(c, r, s, hw, fl, now);
+          due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          continue;
+        }
+        a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(cur.y); a_dur = dur;
+      }
+      attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+      due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+    }
+    if (final) break;
   }
-  int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
-  r.prov += (int64_t)r.n_on * p.G * t_end;
-  r.sub += (int64_t)r.sum_s * t_end;
-  r.resv += (int64_t)r.open_g * t_end;
 
+  // S10: close the integrals at t_end and write the result record
   __syncthreads();
+  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
   nbos_stats *out = p.stats + rep;
-  if (lane < 32) out->delay_hist[lane] = m.hist[lane];
+  if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
   if (lane == 0) {
+    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
     out->status = r.status; out->n_decisions = r.n_dec;
-    out->sessions_placed = r.placed; out->sessions_rejected = r.rejected;
+    out->sessions_placed = m.c32[CS_PLACED]; out->sessions_rejected = m.c32[CS_REJECTED];
     out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
-    out->cells_queued = r.c_queued; out->cells_aborted = r.c_aborted;
+    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = m.c32[CS_ABORTED];
     out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
-    out->executor_reused = r.reused; out->migrations = r.migrations;
-    out->scale_out_hosts = r.so_hosts; out->scale_in_hosts = r.si_hosts; out->peak_hosts = r.peak;
-    out->max_delay_ms = r.max_delay; out->t_end_ms = t_end;
-    out->sum_delay_ms = r.sum_delay; out->sum_tct_ms = r.sum_tct;
-    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_commit;
-    out->gpu_ms_provisioned = r.prov; out->reservation_gpu_ms = r.resv; out->sub_gpu_ms = r.sub;
+    out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
+    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
+    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
+    out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
+    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_exec + g_wait;
+    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
+    out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
+    out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
     out->digest = r.digest;
   }
 }

@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #include <new>
 #include <vector>
@@ -181,7 +182,7 @@ int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in, void *
         default: h->kernel = (const void *)regk::nbos_replay_reg_kernel<8>; break;
       }
     } else {
-      size_t fixed = (size_t)NGPU * HP * 4 + (size_t)HP * 8 + 128 + (size_t)n_cap * 12;
+      size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12) + (size_t)n_cap * 12;
       if (fixed + 12 * 64 > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       if (fixed + q_cap * 12 > (size_t)maxlds) q_cap = ((size_t)maxlds - fixed) / 12;
       h->lds_bytes = fixed + q_cap * 12;
@@ -240,6 +241,8 @@ int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in, void *
     k.scale_iv = (cfg->flags & NBOS_F_SCALE_IN) ? cfg->scale_interval_ms : 1;
     k.idle_pct = cfg->scale_in_idle_pct; k.min_hosts = cfg->min_hosts;
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
+    const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
+    k.batch = (nb && nb[0] == '0') ? 0 : 1;
   }
   *out = h;
   return NBOS_OK;
