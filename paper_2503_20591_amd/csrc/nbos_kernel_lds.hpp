@@ -40,8 +40,8 @@ namespace {
 namespace ldsk {
 
 enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
-       CS_NON, CS_SUMS, CS_OPENG, CS_N32 };
-enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_N64 };
+       CS_NON, CS_SUMS, CS_OPENG, CS_BLAZY, CS_N32 };
+enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_BDUR, CL_BGEXEC, CL_N64 };   // B*: added by the rounds
 
 constexpr int32_t MARK_FREE = 0x7FFFFFFF;
 
@@ -68,6 +68,7 @@ struct Regs {
   int32_t o_n, o_min_t, o_min_i;
   uint32_t o_min_k;
   int32_t status;
+  int32_t min_s;             // least subscription among hosts that are on, or -1 when stale
   uint64_t dirty;
 };
 
@@ -80,6 +81,7 @@ struct Ctx {
   int32_t qt, qd;            // sorted timers, entry i in lane i
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
+  int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
 };
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
@@ -228,6 +230,8 @@ __device__ __forceinline__ int boot_host(Ctx &c, Regs &r, int32_t now, uint32_t 
   const int h = find_off_host(c);
   const int32_t ra = now + c.p.boot;
   if (c.lane == 0) { c.m.ready_at[h] = ra; c.m.hsn[h] = hs_new; }
+  c.fu = c.fu < ra ? c.fu : ra;               // a new host may have idle GPUs from then on
+  r.min_s = -1;
   c32_add(c.m, c.lane, CS_NON, 1u);
   c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
   c32_add(c.m, c.lane, CS_SO, 1u);
@@ -237,36 +241,104 @@ __device__ __forceinline__ int boot_host(Ctx &c, Regs &r, int32_t now, uint32_t 
 
 // Best host for one more replica with request g: ready, under the cap, optionally with g idle GPUs
 // now; smallest (committed, subscribed, index). Hosts ex0 / ex1 are skipped. Returns the packed key
-// (host in the low 10 bits) or 0xFFFFFFFF.
-__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, bool need_idle, int ex0, int ex1) {
+// (host in the low 10 bits) or 0xFFFFFFFF. any_idle: some ready host has g idle GPUs, cap aside.
+__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, bool need_idle, int ex0, int ex1,
+                                              bool &any_idle) {
   wave_sync();
   uint32_t best = 0xFFFFFFFFu;
+  bool idle_seen = false;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
     const int32_t ra = c.m.ready_at[h];
     const int S = (int)(c.m.hsn[h] & 0xFFFFu);
+    const bool capped = ra <= now && S <= c.slim - g && h != ex0 && h != ex1;
+    // the GPU rows are only read for a chunk of hosts in which somebody passes the cap (or while it
+    // is still open whether any host has g idle GPUs)
+    if (wballot(capped) == 0 && (idle_seen || !need_idle)) continue;
     const int C = committed(c, h, now);
-    bool ok = ra <= now && S <= c.slim - g && h != ex0 && h != ex1;
-    if (need_idle) ok = ok && (C + g <= c.p.G);
+    const bool roomy = ra <= now && C + g <= c.p.G;
+    idle_seen = idle_seen || wballot(roomy) != 0;
+    const bool ok = need_idle ? (capped && roomy) : capped;
     const uint32_t key = ((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)h;
     if (ok) best = umin(best, key);
   }
+  any_idle = idle_seen;
   return wave_min(best);
+}
+
+// least subscribed-GPU count among the hosts that are on (ready or being provisioned)
+__device__ __forceinline__ int32_t min_subscription(const Ctx &c) {
+  wave_sync();
+  uint32_t best = 0xFFFFu;
+  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+    const uint32_t S = c.m.hsn[h] & 0xFFFFu;
+    if (c.m.ready_at[h] != NEVER) best = umin(best, S);
+  }
+  return (int32_t)wave_min(best);
+}
+
+__device__ __forceinline__ void order2(int32_t &a, int32_t &b) {
+  const int32_t lo = a < b ? a : b, hi = a < b ? b : a;
+  a = lo; b = hi;
+}
+
+// Earliest time at which some host that is on could have g idle GPUs if nothing new were committed:
+// min over hosts of max(ready_at, g-th smallest busy-until time of the host's GPUs). Later commits
+// only push it back, so no election or migration for a request of g GPUs can succeed before it, as
+// long as no host is added (boot_host lowers the stored bound). One lane sorts one host's row with
+// the 19-comparator network for 8 inputs.
+__device__ __forceinline__ int32_t earliest_idle(const Ctx &c, int g) {
+  wave_sync();
+  const int G = c.p.G;
+  int32_t best = NEVER;
+  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+    const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
+    int32_t v0 = a.x, v1 = G > 1 ? a.y : NEVER, v2 = G > 2 ? a.z : NEVER, v3 = G > 3 ? a.w : NEVER;
+    int32_t v4 = G > 4 ? b.x : NEVER, v5 = G > 5 ? b.y : NEVER, v6 = G > 6 ? b.z : NEVER, v7 = G > 7 ? b.w : NEVER;
+    order2(v0, v1); order2(v2, v3); order2(v4, v5); order2(v6, v7);
+    order2(v0, v2); order2(v1, v3); order2(v4, v6); order2(v5, v7);
+    order2(v1, v2); order2(v5, v6);
+    order2(v0, v4); order2(v1, v5); order2(v2, v6); order2(v3, v7);
+    order2(v2, v4); order2(v3, v5);
+    order2(v1, v2); order2(v3, v4); order2(v5, v6);
+    int32_t y = g == 1 ? v0 : g == 2 ? v1 : g == 3 ? v2 : g == 4 ? v3 : g == 5 ? v4 : g == 6 ? v5 : g == 7 ? v6 : v7;
+    const int32_t ra = c.m.ready_at[h];
+    y = y > ra ? y : ra;
+    best = best < y ? best : y;
+  }
+  return (int32_t)wave_min((uint32_t)best);
 }
 
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
 __device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
   if ((fl & 7u) != SS_UNPLACED) return;
   const int g = (int)((fl >> 3) & 7u) + 1;
-  int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
-  uint32_t m0 = best_host(c, now, g, false, -1, -1);
-  if (m0 != 0xFFFFFFFFu) {
-    pick0 = (int)(m0 & 1023u); k = 1;
-    uint32_t m1 = best_host(c, now, g, false, pick0, -1);
-    if (m1 != 0xFFFFFFFFu) {
-      pick1 = (int)(m1 & 1023u); k = 2;
-      uint32_t m2 = best_host(c, now, g, false, pick0, pick1);
-      if (m2 != 0xFFFFFFFFu) { pick2 = (int)(m2 & 1023u); k = 3; }
+  // one pass computes every host's key (strided over the lanes), three minima pick the hosts
+  constexpr int MAXCH = NBOS_MAX_HOSTS / WAVE;
+  uint32_t keys[MAXCH];
+  wave_sync();
+#pragma unroll
+  for (int j = 0; j < MAXCH; j++) {
+    keys[j] = 0xFFFFFFFFu;
+    if (j * WAVE < c.p.HP) {
+      const int h = j * WAVE + c.lane;
+      const int S = (int)(c.m.hsn[h] & 0xFFFFu);
+      if (c.m.ready_at[h] <= now && S <= c.slim - g)
+        keys[j] = ((uint32_t)committed(c, h, now) << 22) | ((uint32_t)S << 10) | (uint32_t)h;
     }
+  }
+  int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
+#pragma unroll
+  for (int round = 0; round < 3; round++) {
+    uint32_t best = 0xFFFFFFFFu;
+#pragma unroll
+    for (int j = 0; j < MAXCH; j++) best = umin(best, keys[j]);
+    const uint32_t m = wave_min(best);
+    if (m == 0xFFFFFFFFu) break;
+    const int h = (int)(m & 1023u);
+    if (round == 0) pick0 = h; else if (round == 1) pick1 = h; else pick2 = h;
+    k = round + 1;
+#pragma unroll
+    for (int j = 0; j < MAXCH; j++) keys[j] = keys[j] == m ? 0xFFFFFFFFu : keys[j];
   }
   const int missing = 3 - k;
   if (missing > 0) {
@@ -285,6 +357,7 @@ __device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint3
   for (int i = 0; i < 3; i++) {
     int h = i == 0 ? pick0 : (i == 1 ? pick1 : pick2);
     if (i < k) {
+      r.min_s = -1;
       if (c.lane == 0) c.m.hsn[h] += add;
       decide(c, r, now, NBOS_D_PLACE, s, (uint32_t)i, (uint32_t)h);
     } else {
@@ -313,6 +386,7 @@ __device__ __forceinline__ void end_session(Ctx &c, Regs &r, uint32_t s, uint32_
     const int h = (int)((hw >> (10 * c.lane)) & 1023u);
     c.m.hsn[h] -= sub;                          // three distinct hosts, one lane each
   }
+  r.min_s = -1;
   sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
   c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(-3 * g));
   c64_add(c.m, c.lane, CL_SUB, (int64_t)(3 * g) * now);
@@ -362,6 +436,9 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
   wave_sync();
   const int G = c.p.G;
   const int g = (int)((fl >> 3) & 7u) + 1;
+  const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+  // Known in advance that no host has g idle GPUs yet? Then neither election nor migration can work.
+  const bool hopeless = now < lane_get(c.fu, g - 1);
   // (a) election, Section 3.2.2: lanes 0..23 = (replica, GPU) of the session's hosts
   int rr = c.lane >> 3;
   rr = rr > 2 ? 2 : rr;
@@ -373,26 +450,40 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
   const int32_t ra = c.m.ready_at[hr];
   const uint64_t busy = wballot(act && f > now);
   const uint64_t rdy = wballot(ra <= now);
-  const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
   const int C0 = __builtin_popcount((uint32_t)busy & 0xFFu), C1 = __builtin_popcount((uint32_t)(busy >> 8) & 0xFFu),
             C2 = __builtin_popcount((uint32_t)(busy >> 16) & 0xFFu);
   const int ok0 = (int)(rdy & 1u), ok1 = (int)((rdy >> 8) & 1u), ok2 = (int)((rdy >> 16) & 1u);
-  const uint32_t k0 = (ok0 && C0 + g <= G) ? (((uint32_t)C0 << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
-  const uint32_t k1 = (ok1 && C1 + g <= G) ? (((uint32_t)C1 << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
-  const uint32_t k2 = (ok2 && C2 + g <= G) ? (((uint32_t)C2 << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
-  const uint32_t kb = umin(k0, umin(k1, k2));
-  if (kb != 0xFFFFFFFFu) {
-    const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
-    const bool fr = act && (c.lane >> 3) == lead && k < G && f <= now;
-    const int rank = lane_rank(wballot(fr));
-    if (fr && rank < g) row[k] = now + dur;
-    if (now == t_submit) r.c_imm++;
-    start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
-    return;
+  if (!hopeless) {
+    const uint32_t k0 = (ok0 && C0 + g <= G) ? (((uint32_t)C0 << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
+    const uint32_t k1 = (ok1 && C1 + g <= G) ? (((uint32_t)C1 << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
+    const uint32_t k2 = (ok2 && C2 + g <= G) ? (((uint32_t)C2 << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
+    const uint32_t kb = umin(k0, umin(k1, k2));
+    if (kb != 0xFFFFFFFFu) {
+      const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
+      const bool fr = act && (c.lane >> 3) == lead && k < G && f <= now;
+      const int rank = lane_rank(wballot(fr));
+      if (fr && rank < g) row[k] = now + dur;
+      if (now == t_submit) r.c_imm++;
+      start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
+      return;
+    }
   }
   // (b), (c): a target exists? Only then is the replica to move worked out.
   uint32_t tkey = 0xFFFFFFFFu;
-  if (c.p.flags & NBOS_F_MIGRATE) tkey = best_host(c, now, g, true, -1, -1);
+  if (!hopeless && (c.p.flags & NBOS_F_MIGRATE)) {
+    // the cap alone may rule every host out: S_h + g <= limit fails even for the least subscribed
+    if (r.min_s < 0) r.min_s = min_subscription(c);
+    if (r.min_s <= c.slim - g) {
+      bool any_idle;
+      tkey = best_host(c, now, g, true, -1, -1, any_idle);
+      if (!any_idle) {
+        // No host at all with g idle GPUs: work out when the first one could have them, once, for
+        // every later attempt with a request of g or more.
+        const int32_t bound = earliest_idle(c, g);
+        if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
+      }
+    }
+  }
   bool grow = false;
   if (tkey == 0xFFFFFFFFu && (c.p.flags & NBOS_F_SCALE_OUT)) {
     wave_sync();
@@ -413,6 +504,7 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
       const int dst = (int)(tkey & 1023u);
       const int32_t start = now + c.p.migr;
       if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[dst] += moved; }
+      r.min_s = -1;
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
@@ -420,6 +512,7 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
       // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
       if (c.lane == 0) c.m.hsn[hv] -= moved;
+      r.min_s = -1;
       const int h = boot_host(c, r, now, moved);
       wave_sync();
       c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
@@ -471,6 +564,7 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
       if (e) victim = base + 63 - (int)__builtin_clzll(e);
     }
     if (c.lane == 0) c.m.ready_at[victim] = NEVER;
+    r.min_s = -1;
     c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
     c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
     c32_add(c.m, c.lane, CS_SI, 1u);
@@ -494,14 +588,15 @@ __device__ __forceinline__ void on_session_end(Ctx &c, Regs &r, uint32_t s, uint
   }
 }
 
-// Sum of a small non-negative per-lane value (< 2^25) over the wave, returned uniform.
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+// Sum of a per-lane value below 2^26 over the wave as a 64-bit uniform value: exact 32-bit sums per
+// row of 16 lanes (DPP butterfly), the four rows added on the scalar unit.
+__device__ __forceinline__ uint64_t wave_sum(uint32_t v) {
   v += dpp<0xB1>(v);
   v += dpp<0x4E>(v);
   v += dpp<0x141>(v);
   v += dpp<0x140>(v);
-  return (uint32_t)lane_get((int)v, 0) + (uint32_t)lane_get((int)v, 16) + (uint32_t)lane_get((int)v, 32) +
-         (uint32_t)lane_get((int)v, 48);
+  return (uint64_t)(uint32_t)lane_get((int)v, 0) + (uint64_t)(uint32_t)lane_get((int)v, 16) +
+         (uint64_t)(uint32_t)lane_get((int)v, 32) + (uint64_t)(uint32_t)lane_get((int)v, 48);
 }
 
 // ---- one event-parallel round over the lanes in `run` (see the file header) -----------------------
@@ -559,25 +654,21 @@ __device__ __forceinline__ uint64_t batch_round(Ctx &c, Regs &r, uint64_t run, i
     const uint32_t nhw = (hw & 0x3FFFFFFFu) | ((uint32_t)(lead + 1) << 30);
     c.m.sess[sid].x = (int)nhw; c.m.sess[sid].y = finish;
   }
-  // counters over the started lanes
+  // counters over the started lanes: order-free sums go to LDS accumulators (one ds_add per lane)
   const uint32_t n = (uint32_t)__builtin_popcountll(done);
-  const uint32_t dl = mine ? (uint32_t)vd : 0u;
-  const uint32_t gd = mine ? (uint32_t)(g * vd) : 0u;          // < 8 * 86.4e6 < 2^30
   r.c_started += n; r.c_imm += n; r.h0 += n;
   r.reused += (uint32_t)__builtin_popcountll(wballot(mine && (hw >> 30) == (uint32_t)lead + 1u));
-  r.sum_dur += (int64_t)wave_sum(dl & 0xFFFFu) + ((int64_t)wave_sum(dl >> 16) << 16);
-  r.g_exec += (int64_t)wave_sum(gd & 0xFFFFu) + ((int64_t)wave_sum(gd >> 16) << 16);
-  const uint32_t fmax = wave_min(mine ? ~(uint32_t)finish : 0xFFFFFFFFu);
-  const int32_t fm = (int32_t)~fmax;
-  r.lazy_max = r.lazy_max > fm ? r.lazy_max : fm;
-  // digest: d * P^n + sum over started lanes of code * P^(n - 1 - rank)
+  if (mine) {
+    atomicAdd(&c.m.c64[CL_BDUR], (unsigned long long)(uint32_t)vd);
+    atomicAdd(&c.m.c64[CL_BGEXEC], (unsigned long long)(uint32_t)(g * vd));
+    atomicMax(&c.m.c32[CS_BLAZY], (uint32_t)finish);
+  }
+  // digest: d * P^n + sum over started lanes of code * P^(n - 1 - rank), the sum in three limbs
   const int rank = lane_rank(done);
   const uint64_t code = decision_code(vt, NBOS_D_START, sid, (uint32_t)lead, (uint32_t)ch);
   const uint64_t term = mine ? code * c.m.ppow[mine ? n - 1u - (uint32_t)rank : 0u] : 0ull;
-  const uint32_t t0 = (uint32_t)term & 0xFFFFu, t1 = ((uint32_t)term >> 16), t2 = (uint32_t)(term >> 32) & 0xFFFFu,
-                 t3 = (uint32_t)(term >> 48);
-  const uint64_t sum = (uint64_t)wave_sum(t0) + ((uint64_t)wave_sum(t1) << 16) + ((uint64_t)wave_sum(t2) << 32) +
-                       ((uint64_t)wave_sum(t3) << 48);
+  const uint64_t sum = wave_sum((uint32_t)term & 0x3FFFFFu) + (wave_sum((uint32_t)(term >> 22) & 0x1FFFFFu) << 22) +
+                       (wave_sum((uint32_t)(term >> 43)) << 43);
   const unsigned long long pn = c.m.ppow[n];
   const uint64_t pnu = (uint64_t)uni((uint32_t)pn) | ((uint64_t)uni((uint32_t)(pn >> 32)) << 32);
   r.digest = r.digest * pnu + sum;
@@ -633,12 +724,13 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
   Ctx c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
-        NEVER, 0, 0xFFFFFFFFu, 0xFFFFFFFFu};
+        NEVER, 0, 0xFFFFFFFFu, 0xFFFFFFFFu, 0};
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
   r.q_head_t = NEVER;
   r.o_min_t = NEVER;
+  r.min_s = -1;
 
   const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
   const bool batching = p.batch != 0;
@@ -701,6 +793,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
       }
     } else {
       final = true;
+      wave_sync();
+      const int32_t bl = (int32_t)uni(m.c32[CS_BLAZY]);       // finish times bound by the rounds
+      r.lazy_max = r.lazy_max > bl ? r.lazy_max : bl;
     }
     const uint64_t fastmask = wballot(fast);
     for (;;) {
@@ -722,7 +817,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
           const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
           if ((run & (run - 1)) != 0) {          // at least two lanes
             const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec);
-            if ((done & (done - 1)) == 0) cooldown = 8;   // nothing or one event: not worth it for a while
+            cooldown = done == 0 ? 4 : ((done & (done - 1)) == 0 ? 2 : 0);   // poor yield: go serial for a bit
             if (done != 0) { todo &= ~done; continue; }
           }
         }
@@ -814,8 +909,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
     out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
     out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
     out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
-    out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
-    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_exec + g_wait;
+    const int64_t sum_dur = r.sum_dur + (int64_t)m.c64[CL_BDUR], g_exec = r.g_exec + (int64_t)m.c64[CL_BGEXEC];
+    out->sum_delay_ms = sum_delay; out->sum_tct_ms = sum_dur + sum_delay;
+    out->gpu_ms_executed = g_exec; out->gpu_ms_committed = g_exec + g_wait;
     out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
     out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
     out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;

@@ -37,11 +37,9 @@ enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_
        CS_NON, CS_SUMS, CS_OPENG, CS_N32 };
 enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_N64 };
 
-// session record: x hosts word, y time word, z flags, w unused (keeps the record one 128-bit access)
+// session record: x hosts word, y time word, z flags, w duration of the queued cell
 struct Lds {
   int4 *sess;
-  int32_t *o_t, *o_d;          // overflow timers
-  uint32_t *o_k;
   uint32_t *hist;
   uint32_t *c32;
   unsigned long long *c64;
@@ -54,7 +52,7 @@ struct Regs {
   uint64_t digest;
   int32_t lazy_max, t_end;
   int32_t q_n, q_head_t;                 // sorted register queue: size, time of lane 0
-  int32_t o_n, o_min_t, o_min_i;         // overflow: size, minimum
+  int32_t o_n, o_min_t;                  // timers outside the registers: how many, the earliest
   uint32_t o_min_k;
   int32_t status;
   uint64_t dirty;                        // lanes of the current tile whose prefetched record is stale
@@ -65,6 +63,7 @@ struct Ctx {
   const KParams &p;
   Lds m;
   int lane;
+  int n_sess;
   int32_t slim;              // floor(cap_milli * G * 3 / 1000): S + g <= slim is the cap test
   uint64_t *dlog;
   // per-lane state
@@ -74,6 +73,7 @@ struct Ctx {
   int32_t qt, qd;            // sorted timers, entry i in lane i
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
+  int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
 };
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
@@ -110,32 +110,35 @@ __device__ __forceinline__ void sess_write_flag(Ctx<NJ> &c, Regs &r, uint32_t s,
   r.dirty |= wballot(c.vsid == s);
 }
 
-// ---- timers: overflow array in LDS (unsorted) ---------------------------------------------------
+// ---- timers beyond the 64 sorted ones stay with their session -------------------------------------
+// Such a session carries SF_OVF. Its timer is implied by its record: a queued session retries at
+// submit time + retries * interval (duration in w), a placed session that is ending ends at its
+// busy-until time. The earliest of them is tracked; finding the next one scans the session table.
 template <int NJ>
 __device__ __forceinline__ void ovf_rescan(Ctx<NJ> &c, Regs &r) {
   wave_sync();
   uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
-  int bi = 0;
-  for (int i = c.lane; i < r.o_n; i += WAVE) {
-    uint32_t t = (uint32_t)c.m.o_t[i], l = c.m.o_k[i];
-    if (t < bt || (t == bt && l < bl)) { bt = t; bl = l; bi = i; }
+  for (int s = c.lane; s < c.n_sess; s += WAVE) {
+    const int4 rec = c.m.sess[s];
+    const uint32_t fl = (uint32_t)rec.z;
+    if (fl & SF_OVF) {
+      const bool retry = (fl & 7u) == SS_QUEUED;
+      const uint32_t t = (uint32_t)(retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y);
+      const uint32_t l = ((retry ? QK_RETRY : QK_END) << 16) | (uint32_t)s;
+      if (t < bt || (t == bt && l < bl)) { bt = t; bl = l; }
+    }
   }
-  uint32_t mt = wave_min(bt);
-  uint32_t ml = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
-  uint64_t who = wballot(bt == mt && bl == ml);
-  int src = (int)__builtin_ctzll(who | (1ull << 63));
-  r.o_min_i = lane_get(bi, src);
+  const uint32_t mt = wave_min(bt);
+  r.o_min_k = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
   r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
-  r.o_min_k = ml;
 }
 
 template <int NJ>
 __device__ __forceinline__ void ovf_push(Ctx<NJ> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
-  if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
-  if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
-  if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) {
-    r.o_min_t = t; r.o_min_k = k; r.o_min_i = r.o_n;
-  }
+  const uint32_t s = k & 0xFFFFu;
+  if (c.lane == 0) { atomicOr((unsigned int *)&c.m.sess[s].z, SF_OVF); c.m.sess[s].w = d; }
+  r.dirty |= wballot(c.vsid == s);
+  if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) { r.o_min_t = t; r.o_min_k = k; }
   r.o_n++;
 }
 
@@ -179,14 +182,11 @@ __device__ __forceinline__ void timer_pop(Ctx<NJ> &c, Regs &r) {
   r.q_n--;
   if (r.q_n == 0 && r.o_n > 0) {
     wave_sync();
-    int i = r.o_min_i, last = r.o_n - 1;
-    int32_t t = uni(c.m.o_t[i]), d = uni(c.m.o_d[i]);
-    uint32_t k = uni(c.m.o_k[i]);
-    int32_t lt = c.m.o_t[last], ld = c.m.o_d[last];
-    uint32_t lk = c.m.o_k[last];
-    if (i != last && c.lane == 0) { c.m.o_t[i] = lt; c.m.o_k[i] = lk; c.m.o_d[i] = ld; }
-    r.o_n = last;
-    if (c.lane == 0) { c.qt = t; c.qd = d; c.qk = k; }
+    const uint32_t s = r.o_min_k & 0xFFFFu;
+    const int32_t d = uni(c.m.sess[s].w);
+    if (c.lane == 0) { atomicAnd((unsigned int *)&c.m.sess[s].z, ~SF_OVF); c.qt = r.o_min_t; c.qd = d; c.qk = r.o_min_k; }
+    r.dirty |= wballot(c.vsid == s);
+    r.o_n--;
     r.q_n = 1;
     ovf_rescan(c, r);
   }
@@ -229,6 +229,7 @@ __device__ __forceinline__ int boot_host(Ctx<NJ> &c, Regs &r, int32_t now, uint3
   int h = (int)__builtin_ctzll(off);                 // the caller has checked that one exists
   int32_t ra = now + c.p.boot;
   if (c.lane == h) { c.hr = ra; c.hs = hs_new; }
+  c.fu = c.fu < ra ? c.fu : ra;               // a new host may have idle GPUs from then on
   c32_add(c.m, c.lane, CS_NON, 1u);
   c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
   c32_add(c.m, c.lane, CS_SO, 1u);
@@ -381,9 +382,15 @@ template <int NJ>
 __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                         int32_t t_submit, int32_t dur) {
   const int g = (int)((fl >> 3) & 7u) + 1;
-  const int C = committed(c, now);
-  const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);     // ready hosts with g idle GPUs
   const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+  // Known in advance that no host has g idle GPUs yet? Then neither election nor migration can work.
+  const bool hopeless = now < lane_get(c.fu, g - 1);
+  int C = 0;
+  uint64_t idle_ok = 0;
+  if (!hopeless) {
+    C = committed(c, now);
+    idle_ok = wballot(c.hr <= now && C + g <= c.p.G);     // ready hosts with g idle GPUs
+  }
   // (a) election, Section 3.2.2: among the session's hosts in idle_ok, fewest committed GPUs, then
   // lowest host index. At most three bits of `cand` are set: walk them.
   uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
@@ -403,6 +410,13 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
     start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
     return;
   }
+  // No host at all with g idle GPUs: work out when the first one could have them, once, for every
+  // later attempt with a request of g or more (commits only push that time back; a booted host
+  // lowers it again, see boot_host).
+  if (!hopeless && idle_ok == 0) {
+    const int32_t bound = earliest_idle(c, g);
+    if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
+  }
   // (b), (c): a target exists? Only then is the replica to move worked out: the one on the fullest
   // ready host (ties: lowest host); replicas on booting hosts only if all three are.
   const int S = (int)(c.hs & 0xFFFFu);
@@ -413,6 +427,7 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
     grow = (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
   }
   if (target != 0 || grow) {
+    if (hopeless) C = committed(c, now);
     const uint64_t rdy = wballot(c.hr <= now);
     const int C0 = lane_get(C, (int)h0), C1 = lane_get(C, (int)h1), C2 = lane_get(C, (int)h2);
     const int ok0 = (int)((rdy >> h0) & 1u), ok1 = (int)((rdy >> h1) & 1u), ok2 = (int)((rdy >> h2) & 1u);
@@ -452,12 +467,11 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   int retries = (int)((fl >> 8) & 15u);
   if (retries < c.p.max_retries) {
     retries++;
-    // A retry that is bound to fail only bumps the retry count: when no host at all has g idle GPUs
-    // now, skip straight to the first retry that could succeed (or to the last one, which aborts).
-    // Valid while no host can be added, i.e. unless hosts can be both released and provisioned.
-    if (idle_ok == 0 && retries < c.p.max_retries &&
-        (c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
-      const int32_t bound = earliest_idle(c, g);
+    // A retry that is bound to fail only bumps the retry count: skip straight to the first retry
+    // that could succeed (or to the last one, which aborts). Valid while no host can be added,
+    // i.e. unless hosts can be both released and provisioned.
+    if ((c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
+      const int32_t bound = lane_get(c.fu, g - 1);
       while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
     }
     const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
@@ -530,9 +544,6 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
   m.sess = (int4 *)q;          q += (size_t)p.n_cap * 16;
-  m.o_t = (int32_t *)q;        q += (size_t)p.q_cap * 4;
-  m.o_k = (uint32_t *)q;       q += (size_t)p.q_cap * 4;
-  m.o_d = (int32_t *)q;
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
   if (lane < 8) m.c64[lane] = 0;
@@ -545,13 +556,14 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   __syncthreads();
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
-  Ctx<NJ> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+  Ctx<NJ> c{p, m, lane, n_sess, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
 #pragma unroll
   for (int j = 0; j < NJ; j++) c.fin[j] = 0;
   c.hr = lane < p.H0 ? 0 : NEVER;
   c.hs = 0;
   c.qt = NEVER; c.qd = 0; c.qk = 0xFFFFFFFFu;
   c.vsid = 0xFFFFFFFFu;
+  c.fu = 0;
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;

@@ -169,7 +169,7 @@ int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in, void *
     const int n_cap = max_sess > 0 ? max_sess : 1;
     size_t q_cap = (size_t)n_cap + 1;               // at most one queued timer per session
     if (in_regs) {
-      h->lds_bytes = 64 + 64 + 128 + (size_t)n_cap * 16 + q_cap * 12;
+      h->lds_bytes = 64 + 64 + 128 + (size_t)n_cap * 16;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       switch ((cfg->hosts_max + 7) / 8) {
         case 1: h->kernel = (const void *)regk::nbos_replay_reg_kernel<1>; break;

@@ -194,6 +194,29 @@ def test_max_hosts_and_single_gpu(rp, oracle):
     assert_same(rp, oracle, b, st, logs)
 
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
+def test_many_pending_timers(rp, oracle, in_lds):
+    # far more than 64 timers pending at once (retries of queued cells and deferred ENDs), so the
+    # timers that do not fit the 64 sorted slots are exercised: refill, eviction, END while queued
+    rng = np.random.default_rng(9)
+    n = 400
+    cfg = dict(BASE, hosts_initial=5, hosts_max=5, gpus_per_host=8, flags=1, migration_delay_ms=700,
+               retry_interval_ms=3000, max_retries=6)
+    ev = [[i, 0, i, 0] for i in range(n)]
+    t = n
+    for rnd in range(6):
+        for s in rng.permutation(n):
+            t += int(rng.integers(0, 40))
+            ev.append([t, 1, int(s), int(rng.integers(2000, 60000))])
+            if rng.random() < 0.15:
+                ev.append([t + 1, 2, int(s), 0]); t += 1
+    gp = rng.choice([2, 4, 8], n)
+    b = _tiny(cfg, ev, gp, [2000, 100000])
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+    assert_same(rp, oracle, b, st, logs, check=True)
+    assert st["cells_queued"].max() > 500
+
+
 def test_time_near_int32_limit(rp, oracle):
     cfg = dict(BASE, flags=1, migration_delay_ms=15000, retry_interval_ms=10000, max_retries=6)
     t0 = 2**31 - 2 - 86_400_000 - 6 * 10000 - 15000
