@@ -23,6 +23,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per launch from the committed rocprofv3 counter runs (profiles/hbm_traffic.json),
+    or None when the kernel sources have changed since they were taken."""
+    import glob
+    import hashlib
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json"))).get(workload)
+    except OSError:
+        return None
+    if not rec:
+        return None
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2503_20591_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return rec["traffic_bytes"] if h.hexdigest() == rec["csrc_sha256"] else None
+
+
 def cpu_baseline(batch, budget_s: float, threads: int):
     """The CPU oracle, as it stands, timed on a bounded sample of the same batch."""
     import oracle
@@ -53,6 +71,8 @@ def main():
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 = skip")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = all host cores (at most 16)")
     ap.add_argument("--hosts-in-lds", action="store_true", help="force the any-size kernel (comparison runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (replays are independent; a multi-GPU run "
@@ -71,6 +91,12 @@ def main():
     dev = replay.upload(batch, "cuda:0")
     torch.cuda.synchronize()
     t_up = time.perf_counter() - t0
+    if args.calibrate_copy:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     h = replay.Replay(batch.config, dev, hosts_in_lds=args.hosts_in_lds)
     info = h.launch_info()
 
@@ -117,7 +143,8 @@ def main():
                    "lds_bytes_per_replay": info["lds_bytes"], "threads_per_group": info["threads_per_group"],
                    "gen_s": round(t_gen, 2), "upload_s": round(t_up, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None if (args.replays or args.hosts_in_lds) else measured_traffic(args.workload),
                      "kernel": "nbos_replay_kernel", "kernel_ms": avg_kernel_ms, "algorithmic_bytes": alg_bytes,
                      "ns_per_event_per_replay": avg_kernel_ms * 1e6 / (batch.n_events() / max(batch.n_replays, 1))},
         "cpu_baseline": cpu,
