@@ -18,15 +18,18 @@ _SRC = os.path.join(_DIR, "nbos_oracle.c")
 _LIB = os.path.join(_DIR, "libnbos_oracle.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
+F_AUTOSCALE, F_DYNAMIC_SR = 0x20, 0x40
 EV_START, EV_CELL, EV_END = 0, 1, 2
-D_PLACE, D_PLACE_NEW, D_REJECT, D_START, D_MIGRATE, D_SCALE_CELL, D_ABORT, D_SCALE_IN = range(1, 9)
+(D_PLACE, D_PLACE_NEW, D_REJECT, D_START, D_MIGRATE, D_SCALE_CELL, D_ABORT, D_SCALE_IN,
+ D_SCALE_AUTO) = range(1, 10)
 
 
 class _Params(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("hosts_initial", "hosts_max", "gpus_per_host")] + [
         ("flags", C.c_uint32)] + [(n, C.c_int32) for n in (
             "migration_delay_ms", "boot_delay_ms", "retry_interval_ms", "max_retries",
-            "scale_interval_ms", "scale_in_idle_pct", "min_hosts", "cap_milli", "check")]
+            "scale_interval_ms", "scale_in_idle_pct", "min_hosts", "cap_milli", "check",
+            "autoscale_f_milli", "scaling_buffer_hosts")]
 
 
 _U32 = ("n_decisions", "sessions_placed", "sessions_rejected", "cells_total", "cells_immediate",

@@ -13,6 +13,8 @@
  *   dynamic GPU binding: commit at start, release at completion .... 3.3
  *   failed election -> migration, retry queue, abort ............... 3.2.3
  *   scale-out on failed placement, periodic scale-in ............... 3.4.2
+ *   auto-scaler: expected capacity f * sum C, scaling buffer ....... 3.4.2
+ *   dynamic cluster-wide limit on the subscription ratio ........... 3.4.1
  *   metric definitions (delay, TCT, immediate, reuse, GPU-hours) ... 5.2.2-5.2.4
  *
  * Readings taken where the paper leaves a choice open (all deterministic):
@@ -30,6 +32,17 @@
  *     TICK, then by ascending session / host id; all timers due at or before an
  *     arrival run before it; arrivals keep input order.
  *   - a TICK runs only while an arrival or another timer is still pending.
+ *   - auto-scaler (ORC_F_AUTOSCALE): at every TICK the expected capacity is
+ *     want = ceil(f * sum C / G) + buffer hosts, sum C = GPUs committed at that
+ *     instant. Hosts that are booting count as capacity. Below want: boot the
+ *     difference at once (lowest unused indices, up to hosts_max). With
+ *     ORC_F_SCALE_IN also set and more than want hosts provisioned: release at
+ *     most 2 ready hosts without replicas per TICK, highest index first, never
+ *     below want or min_hosts (so a release is never undone by the next TICK).
+ *   - dynamic limit (ORC_F_DYNAMIC_SR): a host also passes the cap test when its
+ *     ratio after taking the replica is at most the cluster-wide ratio after
+ *     taking it, (S_h + g) / (G R) <= (sum S + g) / (n G R), n = hosts not off;
+ *     i.e. the limit in force is the larger of the configured cap and that mean.
  */
 #include "nbos_oracle.h"
 #include <stdlib.h>
@@ -143,7 +156,11 @@ static void advance(sim *m, int32_t t) {
 }
 
 static int cap_ok(const sim *m, const host_rec *h, int g) {
-  return (int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R;
+  if ((int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;
+  /* Section 3.4.1, third factor: the cluster-wide ratio sum S / (sum G * R) as the limit */
+  if (m->p->flags & ORC_F_DYNAMIC_SR)
+    return (int64_t)(h->S + g) * m->n_on <= m->sum_S + g;
+  return 0;
 }
 
 /* preference among hosts: fewer committed, then fewer subscribed, then lower index */
@@ -355,20 +372,43 @@ static void on_complete(sim *m, int s) {
   if (q->ending) end_session(m, s);
 }
 
-/* Section 3.4.2, last paragraph: release at most 2 empty hosts per period. */
+/* Release the highest-numbered ready host that holds no replica. */
+static void release_empty_host(sim *m) {
+  int h = m->H - 1;
+  while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h--;
+  m->hosts[h].state = H_OFF;
+  m->n_on--;
+  m->r.scale_in_hosts++;
+  decide(m, ORC_D_SCALE_IN, 0, 0, h);
+}
+
+/* Section 3.4.2: the periodic auto-scaler. */
 static void on_tick(sim *m) {
   int A = 0, Z = 0, released = 0;
   for (int h = 0; h < m->H; h++)
     if (m->hosts[h].state == H_READY) { A++; if (m->hosts[h].nrep == 0) Z++; }
+  if (m->p->flags & ORC_F_AUTOSCALE) {
+    /* expected capacity sum G' = f * sum C, in whole hosts, plus the scaling buffer */
+    int64_t gpus_milli = (int64_t)m->p->autoscale_f_milli * m->sum_C;
+    int64_t per_host = (int64_t)1000 * m->G;
+    int64_t want = (gpus_milli + per_host - 1) / per_host + m->p->scaling_buffer_hosts;
+    while (m->n_on < want && m->n_on < m->H) {
+      int h = boot_host(m);
+      m->r.scale_out_hosts++;
+      decide(m, ORC_D_SCALE_AUTO, 0, 0, h);
+    }
+    if (m->p->flags & ORC_F_SCALE_IN)
+      while (m->n_on > want && Z > 0 && A > m->p->min_hosts && released < 2) {
+        release_empty_host(m);
+        A--; Z--; released++;
+      }
+    return;
+  }
+  /* without the capacity test: release while too large a share of the hosts is empty */
   while ((int64_t)Z * 100 > (int64_t)A * m->p->scale_in_idle_pct &&
          A > m->p->min_hosts && released < 2) {
-    int h = m->H - 1;
-    while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h--;
-    m->hosts[h].state = H_OFF;
-    m->n_on--;
+    release_empty_host(m);
     A--; Z--; released++;
-    m->r.scale_in_hosts++;
-    decide(m, ORC_D_SCALE_IN, 0, 0, h);
   }
 }
 
@@ -434,9 +474,17 @@ static int validate(const orc_params *p, int64_t n_events, const int32_t *ev_tim
   if (p->migration_delay_ms < 0 || p->boot_delay_ms < 0 || p->retry_interval_ms < 1) return ORC_E_ARG;
   if (p->max_retries < 0 || p->max_retries > 15) return ORC_E_ARG;
   if (p->cap_milli < 1 || p->cap_milli > 100000) return ORC_E_ARG;
+  if (p->flags & ~(uint32_t)(ORC_F_MIGRATE | ORC_F_SCALE_OUT | ORC_F_SCALE_IN | ORC_F_AUTOSCALE |
+                            ORC_F_DYNAMIC_SR)) return ORC_E_ARG;
+  if (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) {
+    if (p->scale_interval_ms < 1 || p->min_hosts < 0) return ORC_E_ARG;
+  }
   if (p->flags & ORC_F_SCALE_IN) {
-    if (p->scale_interval_ms < 1 || p->scale_in_idle_pct < 0 || p->scale_in_idle_pct > 100) return ORC_E_ARG;
-    if (p->min_hosts < 0) return ORC_E_ARG;
+    if (p->scale_in_idle_pct < 0 || p->scale_in_idle_pct > 100) return ORC_E_ARG;
+  }
+  if (p->flags & ORC_F_AUTOSCALE) {
+    if (p->autoscale_f_milli < 0 || p->autoscale_f_milli > 100000) return ORC_E_ARG;
+    if (p->scaling_buffer_hosts < 0 || p->scaling_buffer_hosts > 1024) return ORC_E_ARG;
   }
   if (n_events < 0 || n_sessions < 0 || n_sessions > 65536) return ORC_E_ARG;
   for (int32_t s = 0; s < n_sessions; s++)
@@ -484,7 +532,7 @@ int orc_replay(const orc_params *p,
     m.sess[s].exec_slot = -1;
   }
   m.r.digest = 0xCBF29CE484222325ULL;
-  if (p->flags & ORC_F_SCALE_IN) heap_push(&m, p->scale_interval_ms, T_TICK, 0);
+  if (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) heap_push(&m, p->scale_interval_ms, T_TICK, 0);
 
   /* arrivals in input order; every timer due at or before an arrival runs first */
   for (int64_t i = 0; i < n_events && !m.err; i++) {

@@ -14,12 +14,17 @@
 
 enum { ORC_EV_START = 0, ORC_EV_CELL = 1, ORC_EV_END = 2 };
 
-enum { ORC_F_MIGRATE = 1, ORC_F_SCALE_OUT = 2, ORC_F_SCALE_IN = 4 };
+enum {
+  ORC_F_MIGRATE = 1, ORC_F_SCALE_OUT = 2, ORC_F_SCALE_IN = 4,
+  ORC_F_AUTOSCALE = 0x20,   /* Section 3.4.2: periodic expected-capacity test f * sum C    */
+  ORC_F_DYNAMIC_SR = 0x40   /* Section 3.4.1: cluster-wide subscription ratio as the limit */
+};
 
 /* decision outcomes written to the log / folded into the digest */
 enum {
   ORC_D_PLACE = 1, ORC_D_PLACE_NEW = 2, ORC_D_REJECT = 3, ORC_D_START = 4,
-  ORC_D_MIGRATE = 5, ORC_D_SCALE_CELL = 6, ORC_D_ABORT = 7, ORC_D_SCALE_IN = 8
+  ORC_D_MIGRATE = 5, ORC_D_SCALE_CELL = 6, ORC_D_ABORT = 7, ORC_D_SCALE_IN = 8,
+  ORC_D_SCALE_AUTO = 9   /* host added by the periodic auto-scaler (session field 0) */
 };
 
 /* error returns of orc_replay (0 = ok) */
@@ -38,6 +43,8 @@ typedef struct {
   int32_t scale_interval_ms, scale_in_idle_pct, min_hosts;
   int32_t cap_milli;            /* subscription-ratio cap x 1000 of this replay */
   int32_t check;                /* != 0: verify the invariants after every item */
+  int32_t autoscale_f_milli;    /* f x 1000 of the expected capacity f * sum C (paper: 1050) */
+  int32_t scaling_buffer_hosts; /* extra hosts kept on top of the expected capacity          */
 } orc_params;
 
 typedef struct {

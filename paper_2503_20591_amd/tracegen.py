@@ -174,7 +174,8 @@ def _pack(config, traces, trace_of_replay, cap_milli, name) -> TraceBatch:
 def _base_config(**kw) -> dict:
     cfg = dict(hosts_initial=8, hosts_max=8, gpus_per_host=8, flags=0, migration_delay_ms=15_000,
                boot_delay_ms=60_000, retry_interval_ms=10_000, max_retries=6,
-               scale_interval_ms=60_000, scale_in_idle_pct=10, min_hosts=0)
+               scale_interval_ms=60_000, scale_in_idle_pct=10, min_hosts=0,
+               autoscale_f_milli=0, scaling_buffer_hosts=0)
     cfg.update(kw)
     return cfg
 

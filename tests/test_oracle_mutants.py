@@ -37,9 +37,29 @@ MUTANTS = [
     ("migration ignores the cap", "if (m->G - x->C < g || !cap_ok(m, x, g)) continue;", "if (m->G - x->C < g) continue;"),
     ("migration forgets to move the subscription", "unsubscribe(m, q->host[victim], g);\n      subscribe(m, dst, g);", "subscribe(m, dst, g);"),
     ("histogram bucket off by one", "for (int32_t x = delay; x > 0; x >>= 1) b++;", "for (int32_t x = delay; x > 1; x >>= 1) b++;"),
-    ("scale-in releases 3 per period", "released < 2", "released < 3"),
-    ("scale-in releases the lowest empty host", "int h = m->H - 1;\n    while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h--;",
-     "int h = 0;\n    while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h++;"),
+    ("scale-in releases 3 per period", "A > m->p->min_hosts && released < 2) {\n    release_empty_host(m);\n    A--; Z--; released++;\n  }\n}",
+     "A > m->p->min_hosts && released < 3) {\n    release_empty_host(m);\n    A--; Z--; released++;\n  }\n}"),
+    ("scale-in releases the lowest empty host", "int h = m->H - 1;\n  while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h--;",
+     "int h = 0;\n  while (!(m->hosts[h].state == H_READY && m->hosts[h].nrep == 0)) h++;"),
+    ("auto-scaler: f applied upside down", "(int64_t)m->p->autoscale_f_milli * m->sum_C;", "(int64_t)1000000 / (m->p->autoscale_f_milli + 1) * m->sum_C;"),
+    ("auto-scaler: expected capacity rounded down", "(gpus_milli + per_host - 1) / per_host", "gpus_milli / per_host"),
+    ("auto-scaler: scaling buffer forgotten", "/ per_host + m->p->scaling_buffer_hosts;", "/ per_host;"),
+    ("auto-scaler: uses subscribed instead of committed GPUs", "m->p->autoscale_f_milli * m->sum_C", "m->p->autoscale_f_milli * m->sum_S"),
+    ("auto-scaler: per-GPU instead of per-host capacity", "int64_t per_host = (int64_t)1000 * m->G;", "int64_t per_host = (int64_t)1000;"),
+    ("auto-scaler: booting hosts not counted as capacity", "while (m->n_on < want && m->n_on < m->H) {", "while (A < want && m->n_on < m->H) { A++;"),
+    ("auto-scaler: adds one host per period", "      decide(m, ORC_D_SCALE_AUTO, 0, 0, h);\n    }", "      decide(m, ORC_D_SCALE_AUTO, 0, 0, h);\n      break;\n    }"),
+    ("auto-scaler: releases below the expected capacity", "while (m->n_on > want && Z > 0", "while (m->n_on >= want && Z > 0"),
+    ("auto-scaler: releases 3 per period", "while (m->n_on > want && Z > 0 && A > m->p->min_hosts && released < 2)",
+     "while (m->n_on > want && Z > 0 && A > m->p->min_hosts && released < 3)"),
+    ("auto-scaler: ignores min_hosts", "while (m->n_on > want && Z > 0 && A > m->p->min_hosts", "while (m->n_on > want && Z > 0"),
+    ("auto-scaler: releases without SCALE_IN", "    if (m->p->flags & ORC_F_SCALE_IN)\n      while (m->n_on > want", "    if (1)\n      while (m->n_on > want"),
+    ("auto-scaler never ticks on its own", "if (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) heap_push", "if (p->flags & ORC_F_SCALE_IN) heap_push"),
+    ("dynamic limit: request left out of the cluster sum", "m->n_on <= m->sum_S + g;", "m->n_on <= m->sum_S;"),
+    ("dynamic limit: request left out of the host sum", "return (int64_t)(h->S + g) * m->n_on <=", "return (int64_t)(h->S) * m->n_on <="),
+    ("dynamic limit: divides by hosts_max", "(h->S + g) * m->n_on <=", "(h->S + g) * m->H <="),
+    ("dynamic limit replaces the cap", "if ((int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*",
+     "if (!(m->p->flags & ORC_F_DYNAMIC_SR) && (int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*"),
+    ("dynamic limit always on", "if (m->p->flags & ORC_F_DYNAMIC_SR)\n    return", "if (1)\n    return"),
     ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
     ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
     ("scale-out not all-or-nothing", "m->n_on + missing <= m->H", "m->n_on < m->H"),
@@ -85,6 +105,14 @@ def run_pins(lib_path):
                lambda: pins.test_no_contention_closed_form(o), lambda: pins.test_single_session_textbook(o),
                lambda: pins.test_reservation_and_subscription_closed_form(o)]
     checks += [lambda s=s: pins.test_invariants_random(o, s) for s in range(12)]
+    for args in [(1050, 0, 1), (1050, 2, 1), (1050, 0, 3), (3000, 0, 2), (4100, 5, 3), (0, 4, 3)]:
+        checks.append(lambda a=args: pins.test_autoscale_adds_up_to_expected_capacity(o, *a))
+    for args in [(0, 0, [(1000, 8), (1000, 7), (2000, 6), (2000, 5), (3000, 4), (3000, 3)]),
+                 (0, 6, [(1000, 8), (1000, 7), (2000, 6)]), (5, 0, [(1000, 8), (1000, 7), (2000, 6)])]:
+        checks.append(lambda a=args: pins.test_autoscale_releases_two_per_tick_down_to_capacity(o, *a))
+    checks += [lambda s=s: pins.test_autoscale_with_f_zero_is_the_plain_policy(o, s) for s in range(6)]
+    checks += [lambda s=s: pins.test_dynamic_limit_is_vacuous_on_large_clusters(o, s) for s in range(8)]
+    checks.append(lambda: pins.test_dynamic_limit_brute_force(o))
     for c in checks:
         try:
             c()

@@ -291,6 +291,125 @@ def test_time_shift(oracle):
             assert y[k] == x[k], k
 
 
+# ---- Section 3.4.2, auto-scaler: closed forms for the expected-capacity test ---------------------
+
+AUTO, DYN = 0x20, 0x40
+
+
+@pytest.mark.parametrize("f_milli,buf,busy", [(1050, 0, 1), (1050, 2, 1), (1050, 0, 3), (3000, 0, 2),
+                                              (4100, 5, 3), (1000, 0, 3), (0, 4, 3), (1050, 0, 0)])
+def test_autoscale_adds_up_to_expected_capacity(oracle, f_milli, buf, busy):
+    # 3 hosts, three 8-GPU sessions (each has a replica on every host); `busy` of them run one long
+    # cell, each on its own host: sum C = 8 * busy at every TICK, so the cluster must grow to
+    # ceil(f * busy) + buffer hosts at the first TICK, and never again.
+    hmax = 12
+    cfg = dict(BASE, hosts_max=hmax, flags=AUTO, boot_delay_ms=2500, scale_interval_ms=1000,
+               autoscale_f_milli=f_milli, scaling_buffer_hosts=buf)
+    ev = [[0, S, i, 0] for i in range(3)] + [[10 + i, CELL, i, 20_000] for i in range(busy)]
+    r = run(oracle, cfg, ev, [8, 8, 8], 100000, want_log=True)
+    want = -(-f_milli * busy // 1000) + buf
+    grown = max(0, min(hmax, want) - 3)
+    assert r["scale_out_hosts"] == grown and r["peak_hosts"] == 3 + grown and r["scale_in_hosts"] == 0
+    auto = [oracle.decode(c) for c in r["log"] if oracle.decode(c)["outcome"] == oracle.D_SCALE_AUTO]
+    assert [(d["time"], d["host"], d["session"], d["slot"]) for d in auto] == [(1000, 3 + i, 0, 0) for i in range(grown)]
+    # provisioned integral: 3 hosts from 0, the new ones from the first TICK to the end
+    assert r["gpu_ms_provisioned"] == 8 * (3 * r["t_end_ms"] + grown * (r["t_end_ms"] - 1000))
+
+
+@pytest.mark.parametrize("buf,min_hosts,expect", [
+    (0, 0, [(1000, 8), (1000, 7), (2000, 6), (2000, 5), (3000, 4), (3000, 3)]),   # down to the hosts with replicas
+    (0, 6, [(1000, 8), (1000, 7), (2000, 6)]),                                    # floor min_hosts
+    (5, 0, [(1000, 8), (1000, 7), (2000, 6)]),                                    # want = 1 + 5 hosts
+    (9, 0, []),                                                                   # want above the cluster size
+])
+def test_autoscale_releases_two_per_tick_down_to_capacity(oracle, buf, min_hosts, expect):
+    # 9 hosts, one 1-GPU session on hosts 0,1,2 running one long cell: sum C = 1, ceil(1.05/8) = 1 host.
+    cfg = dict(BASE, hosts_initial=9, hosts_max=9 if buf < 9 else 12, flags=AUTO | 4, scale_interval_ms=1000,
+               autoscale_f_milli=1050, scaling_buffer_hosts=buf, min_hosts=min_hosts, scale_in_idle_pct=100)
+    ev = [[0, S, 0, 0], [5, CELL, 0, 10_500]]
+    r = run(oracle, cfg, ev, [1], 1000, want_log=True)
+    out = [oracle.decode(c) for c in r["log"] if oracle.decode(c)["outcome"] == oracle.D_SCALE_IN]
+    assert [(d["time"], d["host"]) for d in out] == expect
+    grown = 1 if buf == 9 else 0          # want = 10 hosts: one more is booted at the first TICK
+    assert r["scale_out_hosts"] == grown and r["scale_in_hosts"] == len(expect)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_autoscale_with_f_zero_is_the_plain_policy(oracle, seed):
+    # f = 0 and no buffer: expected capacity 0, nothing is ever added; without SCALE_IN nothing is
+    # released either, so the periodic TICK must not change any result.
+    b = tg.random_case(500 + seed, n_replays=2)
+    b.config["flags"] &= ~tg.F_SCALE_IN
+    x = oracle.replay_batch(b, check=True)
+    b.config["flags"] |= AUTO
+    b.config["autoscale_f_milli"] = 0
+    b.config["scaling_buffer_hosts"] = 0
+    assert oracle.replay_batch(b, check=True) == x
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_autoscale_release_rule_matches_idle_rule_when_both_say_everything(oracle, seed):
+    # f = 0, buffer 0 with SCALE_IN: "more hosts than expected" always holds, so every TICK releases
+    # up to 2 empty hosts above min_hosts -- exactly what the idle-share rule does at 0 %.
+    b = tg.random_case(520 + seed, n_replays=2)
+    b.config["flags"] |= tg.F_SCALE_IN
+    b.config["scale_in_idle_pct"] = 0
+    x = oracle.replay_batch(b, check=True)
+    b.config["flags"] |= AUTO
+    b.config["autoscale_f_milli"] = 0
+    b.config["scaling_buffer_hosts"] = 0
+    assert oracle.replay_batch(b, check=True) == x
+
+
+# ---- Section 3.4.1, dynamic limit: never looser than the cap on a cluster with more hosts than G --
+
+@pytest.mark.parametrize("seed", range(16))
+def test_dynamic_limit_is_vacuous_on_large_clusters(oracle, seed):
+    # If every host respects S <= floor(cap G R / 1000) =: L and L >= G (a fresh host can take any
+    # request), a host that fails the static test has S_h + g >= L + 1, hence (S_h + g) n >= n L + n
+    # > sum S + g as soon as n > g. So with more than G hosts the flag cannot change anything.
+    b = tg.random_case(540 + seed, n_replays=3)
+    G = b.config["gpus_per_host"]
+    b.config["flags"] &= ~tg.F_SCALE_IN                   # the cluster never shrinks to G hosts or fewer
+    if b.config["hosts_initial"] <= G:
+        b.config["hosts_max"] += G + 1 - b.config["hosts_initial"]
+        b.config["hosts_initial"] = G + 1
+    b.cap_milli = np.maximum(b.cap_milli, 334).astype(np.int32)     # L >= G  <=>  cap >= 1/3
+    x = oracle.replay_batch(b, check=True)
+    b.config["flags"] |= DYN
+    assert oracle.replay_batch(b, check=True) == x
+
+
+def test_dynamic_limit_brute_force(oracle):
+    # tiny clusters where the limit does bite: compare every placement with a direct evaluation of
+    # (S_h + g) / (G R) <= max(cap, (sum S + g) / (n G R)) in exact fractions
+    from fractions import Fraction
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        G = int(rng.choice([2, 4, 8]))
+        H = int(rng.integers(3, 7))
+        cap = int(rng.choice([50, 100, 200, 334, 500]))
+        n = int(rng.integers(2, 9))
+        gp = rng.integers(1, G + 1, n)
+        cfg = dict(BASE, hosts_initial=H, hosts_max=H, gpus_per_host=G, flags=DYN)
+        r = run(oracle, cfg, [[i, S, i, 0] for i in range(n)], gp, cap, want_log=True)
+        Sub = [0] * H
+        expect = []
+        for s in range(n):
+            g = int(gp[s])
+            lim = max(Fraction(cap, 1000), Fraction(sum(Sub) + g, H * G * 3))
+            cand = sorted((Sub[h], h) for h in range(H) if Fraction(Sub[h] + g, G * 3) <= lim)
+            if len(cand) < 3:
+                expect.append((s, oracle.D_REJECT, 0, 0))
+                continue
+            for slot, (_, h) in enumerate(cand[:3]):
+                expect.append((s, oracle.D_PLACE, slot, h))
+            for _, h in cand[:3]:
+                Sub[h] += g
+        got = [oracle.decode(c) for c in r["log"]]
+        assert [(d["session"], d["outcome"], d["slot"], d["host"]) for d in got] == expect
+
+
 # ---- input validation -----------------------------------------------------------------------------
 
 def test_rejects_bad_input(oracle):
