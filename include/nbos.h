@@ -79,6 +79,21 @@ typedef enum {
 #define NBOS_F_HOSTS_IN_LDS   0x10u /* use the any-size kernel (host state in LDS) even when
                                       hosts_max <= 64 would allow the register kernel; same
                                       results, for cross-checks and comparisons              */
+#define NBOS_F_AUTOSCALE     0x20u /* the periodic auto-scaler of Section 3.4.2 (second scale-out
+                                      scenario). Every scale_interval_ms the expected capacity is
+                                      want = ceil(f * sum C / G) + scaling_buffer_hosts hosts, with
+                                      sum C = GPUs committed at that instant and hosts being
+                                      provisioned counted as capacity. Fewer hosts than want: the
+                                      difference is provisioned at once (up to hosts_max). With
+                                      NBOS_F_SCALE_IN also set and more hosts than want: at most 2
+                                      ready hosts without replicas are released per period, highest
+                                      index first, never below want or min_hosts; this test then
+                                      replaces the scale_in_idle_pct rule.                     */
+#define NBOS_F_DYNAMIC_SR    0x40u /* dynamic cluster-wide limit on the subscription ratio
+                                      (Section 3.4.1, third factor): a host also passes the cap
+                                      test when (S_h + g) / (G R) <= (sum S + g) / (n G R), n =
+                                      hosts not off, i.e. the limit in force is the larger of the
+                                      replay's cap and the cluster-wide ratio after placing.  */
 
 /* ---- event encoding ------------------------------------------------------ */
 #define NBOS_EV_START  0
@@ -90,7 +105,8 @@ typedef struct nbos_replay nbos_replay;   /* opaque, owned by the library */
 
 /* Parameters common to all replays of one handle. */
 typedef struct {
-  uint32_t struct_size;         /* = sizeof(nbos_config)                                        */
+  uint32_t struct_size;         /* = sizeof(nbos_config); the 60-byte layout that ends at
+                                   min_hosts is accepted too, the missing fields read as 0      */
   int32_t  n_replays;           /* >= 0                                                         */
   int32_t  n_traces;            /* >= 1 when n_replays > 0                                      */
   int32_t  hosts_initial;       /* hosts 0..hosts_initial-1 are ready at time 0; >= 1           */
@@ -102,9 +118,12 @@ typedef struct {
   int32_t  boot_delay_ms;       /* >= 0; a scaled-out host is ready this long after the request */
   int32_t  retry_interval_ms;   /* >= 1; period of the retries of a queued cell (3.2.3)         */
   int32_t  max_retries;         /* 0..NBOS_MAX_RETRIES; then the cell is aborted                */
-  int32_t  scale_interval_ms;   /* >= 1 with NBOS_F_SCALE_IN: auto-scaler period (3.4.2)        */
+  int32_t  scale_interval_ms;   /* >= 1 with NBOS_F_SCALE_IN / _AUTOSCALE: auto-scaler period   */
   int32_t  scale_in_idle_pct;   /* 0..100: release while empty*100 > ready*pct                  */
   int32_t  min_hosts;           /* scale-in never goes below this many ready hosts              */
+  int32_t  autoscale_f_milli;   /* NBOS_F_AUTOSCALE: f * 1000 of the expected capacity f * sum C,
+                                   0..100000 (Section 3.4.2 uses f = 1.05, i.e. 1050)           */
+  int32_t  scaling_buffer_hosts;/* NBOS_F_AUTOSCALE: extra hosts kept on top of it, 0..1024     */
 } nbos_config;
 
 /* The traces and per-replay parameters. All arrays are DEVICE pointers. */
@@ -162,6 +181,7 @@ typedef struct {
 #define NBOS_D_SCALE_CELL  6   /* host added for the cell, replica slot moved there  */
 #define NBOS_D_ABORT       7   /* queued cell given up                               */
 #define NBOS_D_SCALE_IN    8   /* empty host released (session field 0)              */
+#define NBOS_D_SCALE_AUTO  9   /* host provisioned by the periodic auto-scaler       */
 
 /*
  * Create a replay batch (paper Sections 3.2-3.4 define the simulated policy).

@@ -32,6 +32,7 @@ struct KParams {
   int32_t n_replays, H0, Hmax, HP, G;
   uint32_t flags;
   int32_t migr, boot, retry_iv, max_retries, scale_iv, idle_pct, min_hosts;
+  int32_t f_milli, buffer; // auto-scaler: f * 1000 of the expected capacity, extra hosts
   int32_t n_cap, q_cap;    // LDS capacity: sessions, queue entries
   int32_t batch;           // event-parallel rounds on (LDS kernel)
 };

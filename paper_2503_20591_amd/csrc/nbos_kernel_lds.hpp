@@ -94,6 +94,22 @@ __device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
   if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
 }
 
+// Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
+// replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
+// (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
+__device__ __forceinline__ int32_t cap_room(const Ctx &c, int g) {
+  int32_t lim = c.slim;
+  if (c.p.flags & NBOS_F_DYNAMIC_SR) {
+    wave_sync();
+    const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
+    if (n_on > 0) {
+      const int32_t mean = (int32_t)((tot + (uint32_t)g) / n_on);
+      lim = lim > mean ? lim : mean;
+    }
+  }
+  return lim - g;
+}
+
 __device__ __forceinline__ uint64_t decision_code(int32_t now, uint32_t outcome, uint32_t s, uint32_t slot,
                                                   uint32_t host) {
   return (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) | ((uint64_t)s << 16) |
@@ -239,18 +255,18 @@ __device__ __forceinline__ int boot_host(Ctx &c, Regs &r, int32_t now, uint32_t 
   return h;
 }
 
-// Best host for one more replica with request g: ready, under the cap, optionally with g idle GPUs
-// now; smallest (committed, subscribed, index). Hosts ex0 / ex1 are skipped. Returns the packed key
+// Best host for one more replica with request g: ready, under the cap (S <= room), optionally with g
+// idle GPUs now; smallest (committed, subscribed, index). Hosts ex0 / ex1 are skipped. Returns the packed key
 // (host in the low 10 bits) or 0xFFFFFFFF. any_idle: some ready host has g idle GPUs, cap aside.
-__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, bool need_idle, int ex0, int ex1,
-                                              bool &any_idle) {
+__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, int32_t room, bool need_idle,
+                                              int ex0, int ex1, bool &any_idle) {
   wave_sync();
   uint32_t best = 0xFFFFFFFFu;
   bool idle_seen = false;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
     const int32_t ra = c.m.ready_at[h];
     const int S = (int)(c.m.hsn[h] & 0xFFFFu);
-    const bool capped = ra <= now && S <= c.slim - g && h != ex0 && h != ex1;
+    const bool capped = ra <= now && S <= room && h != ex0 && h != ex1;
     // the GPU rows are only read for a chunk of hosts in which somebody passes the cap (or while it
     // is still open whether any host has g idle GPUs)
     if (wballot(capped) == 0 && (idle_seen || !need_idle)) continue;
@@ -315,6 +331,7 @@ __device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint3
   // one pass computes every host's key (strided over the lanes), three minima pick the hosts
   constexpr int MAXCH = NBOS_MAX_HOSTS / WAVE;
   uint32_t keys[MAXCH];
+  const int32_t room = cap_room(c, g);
   wave_sync();
 #pragma unroll
   for (int j = 0; j < MAXCH; j++) {
@@ -322,7 +339,7 @@ __device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint3
     if (j * WAVE < c.p.HP) {
       const int h = j * WAVE + c.lane;
       const int S = (int)(c.m.hsn[h] & 0xFFFFu);
-      if (c.m.ready_at[h] <= now && S <= c.slim - g)
+      if (c.m.ready_at[h] <= now && S <= room)
         keys[j] = ((uint32_t)committed(c, h, now) << 22) | ((uint32_t)S << 10) | (uint32_t)h;
     }
   }
@@ -473,9 +490,10 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
   if (!hopeless && (c.p.flags & NBOS_F_MIGRATE)) {
     // the cap alone may rule every host out: S_h + g <= limit fails even for the least subscribed
     if (r.min_s < 0) r.min_s = min_subscription(c);
-    if (r.min_s <= c.slim - g) {
+    const int32_t room = cap_room(c, g);
+    if (r.min_s <= room) {
       bool any_idle;
-      tkey = best_host(c, now, g, true, -1, -1, any_idle);
+      tkey = best_host(c, now, g, room, true, -1, -1, any_idle);
       if (!any_idle) {
         // No host at all with g idle GPUs: work out when the first one could have them, once, for
         // every later attempt with a request of g or more.
@@ -544,32 +562,74 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
 }
 
-// ---- auto-scaler period: release at most two empty hosts (Section 3.4.2, last paragraph) --------
+// Sum of a per-lane value below 2^26 over the wave as a 64-bit uniform value: exact 32-bit sums per
+// row of 16 lanes (DPP butterfly), the four rows added on the scalar unit.
+__device__ __forceinline__ uint64_t wave_sum(uint32_t v) {
+  v += dpp<0xB1>(v);
+  v += dpp<0x4E>(v);
+  v += dpp<0x141>(v);
+  v += dpp<0x140>(v);
+  return (uint64_t)(uint32_t)lane_get((int)v, 0) + (uint64_t)(uint32_t)lane_get((int)v, 16) +
+         (uint64_t)(uint32_t)lane_get((int)v, 32) + (uint64_t)(uint32_t)lane_get((int)v, 48);
+}
+
+// ---- auto-scaler period (Section 3.4.2) -----------------------------------------------------------
+// release the highest-numbered ready host without replicas (the caller has checked that one exists)
+__device__ __forceinline__ void release_host(Ctx &c, Regs &r, int32_t now) {
+  int victim = -1;
+  wave_sync();
+  for (int base = c.p.HP - WAVE; base >= 0 && victim < 0; base -= WAVE) {
+    const int h = base + c.lane;
+    const uint64_t e = wballot(c.m.ready_at[h] <= now && (c.m.hsn[h] >> 16) == 0);
+    if (e) victim = base + 63 - (int)__builtin_clzll(e);
+  }
+  if (c.lane == 0) c.m.ready_at[victim] = NEVER;
+  r.min_s = -1;
+  c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
+  c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
+  c32_add(c.m, c.lane, CS_SI, 1u);
+  decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
+}
+
 __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
   wave_sync();
+  const bool autoscale = (c.p.flags & NBOS_F_AUTOSCALE) != 0;
   int A = 0, Z = 0;
+  uint32_t busy = 0;                       // this lane's share of sum C
   for (int base = 0; base < c.p.HP; base += WAVE) {
     const int h = base + c.lane;
     const bool ready = c.m.ready_at[h] <= now;
     A += __builtin_popcountll(wballot(ready));
     Z += __builtin_popcountll(wballot(ready && (c.m.hsn[h] >> 16) == 0));
+    if (autoscale) busy += (uint32_t)committed(c, h, now);
   }
   int released = 0;
-  while ((int64_t)Z * 100 > (int64_t)A * c.p.idle_pct && A > c.p.min_hosts && released < 2) {
-    int victim = -1;
-    wave_sync();
-    for (int base = c.p.HP - WAVE; base >= 0 && victim < 0; base -= WAVE) {
-      const int h = base + c.lane;
-      const uint64_t e = wballot(c.m.ready_at[h] <= now && (c.m.hsn[h] >> 16) == 0);
-      if (e) victim = base + 63 - (int)__builtin_clzll(e);
+  if (autoscale) {
+    // expected capacity f * sum C in whole hosts plus the scaling buffer; hosts being provisioned
+    // count as capacity
+    const uint32_t sum_c = (uint32_t)wave_sum(busy);
+    const uint32_t per_host = 1000u * (uint32_t)c.p.G;
+    const int want = (int)(((uint32_t)c.p.f_milli * sum_c + per_host - 1u) / per_host) + c.p.buffer;
+    int n_on = (int)uni(c.m.c32[CS_NON]);
+    const int before = n_on;
+    while (n_on < want && n_on < c.p.Hmax) {
+      const int h = boot_host(c, r, now, 0u);
+      n_on++;
+      decide(c, r, now, NBOS_D_SCALE_AUTO, 0, 0, (uint32_t)h);
     }
-    if (c.lane == 0) c.m.ready_at[victim] = NEVER;
-    r.min_s = -1;
-    c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
-    c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
-    c32_add(c.m, c.lane, CS_SI, 1u);
+    if (n_on != before) c32_max(c.m, c.lane, CS_PEAK, (uint32_t)n_on);
+    if (c.p.flags & NBOS_F_SCALE_IN) {
+      while (n_on > want && Z > 0 && A > c.p.min_hosts && released < 2) {
+        release_host(c, r, now);
+        n_on--; A--; Z--; released++;
+      }
+    }
+    return;
+  }
+  // without the capacity test: release at most two hosts while too large a share of them is empty
+  while ((int64_t)Z * 100 > (int64_t)A * c.p.idle_pct && A > c.p.min_hosts && released < 2) {
+    release_host(c, r, now);
     A--; Z--; released++;
-    decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
   }
 }
 
@@ -586,17 +646,6 @@ __device__ __forceinline__ void on_session_end(Ctx &c, Regs &r, uint32_t s, uint
     sess_write_flag(c, r, s, fl | SF_ENDING);
     if (st == SS_PLACED) timer_push(c, r, tm, QK_END, s, 0);
   }
-}
-
-// Sum of a per-lane value below 2^26 over the wave as a 64-bit uniform value: exact 32-bit sums per
-// row of 16 lanes (DPP butterfly), the four rows added on the scalar unit.
-__device__ __forceinline__ uint64_t wave_sum(uint32_t v) {
-  v += dpp<0xB1>(v);
-  v += dpp<0x4E>(v);
-  v += dpp<0x141>(v);
-  v += dpp<0x140>(v);
-  return (uint64_t)(uint32_t)lane_get((int)v, 0) + (uint64_t)(uint32_t)lane_get((int)v, 16) +
-         (uint64_t)(uint32_t)lane_get((int)v, 32) + (uint64_t)(uint32_t)lane_get((int)v, 48);
 }
 
 // ---- one event-parallel round over the lanes in `run` (see the file header) -----------------------
@@ -732,11 +781,11 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   r.o_min_t = NEVER;
   r.min_s = -1;
 
-  const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
+  const bool ticking = (p.flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   const bool batching = p.batch != 0;
   // hash buckets (power of two <= HP) for spotting two events of one session in a tile
   const uint32_t dup_mask = (1u << (31 - __builtin_clz((uint32_t)p.HP))) - 1u;
-  int32_t tick_t = scale_in ? p.scale_iv : NEVER;
+  int32_t tick_t = ticking ? p.scale_iv : NEVER;
   int32_t due_t = tick_t;                   // earliest queued timer or auto-scaler period
   int cooldown = 0;                         // serial items to go before the next parallel round
 
@@ -857,7 +906,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
         }
       } else {
         // ---- a timer may be due (S2); always taken while draining ----
-        bool fire_q = r.q_n > 0, fire_t = scale_in;
+        bool fire_q = r.q_n > 0, fire_t = ticking;
         if (final) {
           if (fire_t) fire_t = fire_q ? tick_t < r.q_head_t : tick_t < r.lazy_max;
           if (fire_t) fire_q = false;

@@ -86,6 +86,23 @@ __device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
   if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
 }
 
+// Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
+// replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
+// (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
+template <int NJ>
+__device__ __forceinline__ int32_t cap_room(const Ctx<NJ> &c, int g) {
+  int32_t lim = c.slim;
+  if (c.p.flags & NBOS_F_DYNAMIC_SR) {
+    wave_sync();
+    const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
+    if (n_on > 0) {
+      const int32_t mean = (int32_t)((tot + (uint32_t)g) / n_on);
+      lim = lim > mean ? lim : mean;
+    }
+  }
+  return lim - g;
+}
+
 template <int NJ>
 __device__ __forceinline__ void decide(Ctx<NJ> &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
                                        uint32_t slot, uint32_t host) {
@@ -274,8 +291,9 @@ __device__ __forceinline__ void session_start(Ctx<NJ> &c, Regs &r, uint32_t s, u
   const int g = (int)((fl >> 3) & 7u) + 1;
   const int C = committed(c, now);
   const int S = (int)(c.hs & 0xFFFFu);
-  uint32_t key = (c.hr <= now && S <= c.slim - g) ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane)
-                                                  : 0xFFFFFFFFu;
+  const int32_t room = cap_room(c, g);
+  uint32_t key = (c.hr <= now && S <= room) ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane)
+                                            : 0xFFFFFFFFu;
   int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
   uint32_t m0 = wave_min(key);
   if (m0 != 0xFFFFFFFFu) {
@@ -420,7 +438,8 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   // (b), (c): a target exists? Only then is the replica to move worked out: the one on the fullest
   // ready host (ties: lowest host); replicas on booting hosts only if all three are.
   const int S = (int)(c.hs & 0xFFFFu);
-  const uint64_t target = (c.p.flags & NBOS_F_MIGRATE) ? (idle_ok & wballot(S <= c.slim - g)) : 0;
+  uint64_t target = 0;
+  if ((c.p.flags & NBOS_F_MIGRATE) && idle_ok != 0) target = idle_ok & wballot(S <= cap_room(c, g));
   bool grow = false;
   if (target == 0 && (c.p.flags & NBOS_F_SCALE_OUT)) {
     wave_sync();
@@ -468,9 +487,10 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   if (retries < c.p.max_retries) {
     retries++;
     // A retry that is bound to fail only bumps the retry count: skip straight to the first retry
-    // that could succeed (or to the last one, which aborts). Valid while no host can be added,
-    // i.e. unless hosts can be both released and provisioned.
-    if ((c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
+    // that could succeed (or to the last one, which aborts). Valid while no host can be added:
+    // not with the periodic auto-scaler, and not when hosts can be both released and provisioned.
+    if (!(c.p.flags & NBOS_F_AUTOSCALE) &&
+        (c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
       const int32_t bound = lane_get(c.fu, g - 1);
       while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
     }
@@ -492,21 +512,53 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
 }
 
-// ---- auto-scaler period: release at most two empty hosts (Section 3.4.2, last paragraph) --------
+// ---- auto-scaler period (Section 3.4.2) -----------------------------------------------------------
+// release the highest-numbered ready host without replicas
+template <int NJ>
+__device__ __forceinline__ void release_host(Ctx<NJ> &c, Regs &r, int32_t now) {
+  const uint64_t e = wballot(c.hr <= now && (c.hs >> 16) == 0);
+  const int victim = 63 - (int)__builtin_clzll(e);
+  if (c.lane == victim) c.hr = NEVER;
+  c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
+  c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
+  c32_add(c.m, c.lane, CS_SI, 1u);
+  decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
+}
+
 template <int NJ>
 __device__ __forceinline__ void tick(Ctx<NJ> &c, Regs &r, int32_t now) {
   int A = __builtin_popcountll(wballot(c.hr <= now));
   int Z = __builtin_popcountll(wballot(c.hr <= now && (c.hs >> 16) == 0));
   int released = 0;
+  if (c.p.flags & NBOS_F_AUTOSCALE) {
+    // expected capacity f * sum C in whole hosts plus the scaling buffer; hosts being provisioned
+    // count as capacity
+    uint32_t sum_c = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) sum_c += (uint32_t)__builtin_popcountll(wballot(c.fin[j] > now));
+    const uint32_t per_host = 1000u * (uint32_t)c.p.G;
+    const int want = (int)(((uint32_t)c.p.f_milli * sum_c + per_host - 1u) / per_host) + c.p.buffer;
+    wave_sync();
+    int n_on = (int)uni(c.m.c32[CS_NON]);
+    const int before = n_on;
+    while (n_on < want && n_on < c.p.Hmax) {
+      const int h = boot_host(c, r, now, 0u);
+      n_on++;
+      decide(c, r, now, NBOS_D_SCALE_AUTO, 0, 0, (uint32_t)h);
+    }
+    if (n_on != before) c32_max(c.m, c.lane, CS_PEAK, (uint32_t)n_on);
+    if (c.p.flags & NBOS_F_SCALE_IN) {
+      while (n_on > want && Z > 0 && A > c.p.min_hosts && released < 2) {
+        release_host(c, r, now);
+        n_on--; A--; Z--; released++;
+      }
+    }
+    return;
+  }
+  // without the capacity test: release at most two hosts while too large a share of them is empty
   while ((int64_t)Z * 100 > (int64_t)A * c.p.idle_pct && A > c.p.min_hosts && released < 2) {
-    uint64_t e = wballot(c.hr <= now && (c.hs >> 16) == 0);
-    int victim = 63 - (int)__builtin_clzll(e);
-    if (c.lane == victim) c.hr = NEVER;
-    c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
-    c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
-    c32_add(c.m, c.lane, CS_SI, 1u);
+    release_host(c, r, now);
     A--; Z--; released++;
-    decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
   }
 }
 
@@ -570,8 +622,8 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   r.q_head_t = NEVER;
   r.o_min_t = NEVER;
 
-  const bool scale_in = (p.flags & NBOS_F_SCALE_IN) != 0;
-  int32_t tick_t = scale_in ? p.scale_iv : NEVER;
+  const bool ticking = (p.flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
+  int32_t tick_t = ticking ? p.scale_iv : NEVER;
   int32_t due_t = tick_t;                   // earliest queued timer or auto-scaler period
 
   // S1: stream the events, one per lane per tile, next tile in flight
@@ -669,7 +721,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
         }
       } else {
         // ---- a timer may be due (S2); always taken while draining ----
-        bool fire_q = r.q_n > 0, fire_t = scale_in;
+        bool fire_q = r.q_n > 0, fire_t = ticking;
         if (final) {
           if (fire_t) fire_t = fire_q ? tick_t < r.q_head_t : tick_t < r.lazy_max;
           if (fire_t) fire_q = false;

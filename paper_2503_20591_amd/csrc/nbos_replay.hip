@@ -5,6 +5,7 @@
 // Everything is integer arithmetic; all control flow is wave-uniform.
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -104,10 +105,17 @@ const char *nbos_strerror(int32_t status) {
 
 int32_t nbos_sizeof_stats(void) { return (int32_t)sizeof(nbos_stats); }
 
-int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in, void *stream, nbos_replay **out) {
+int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, void *stream, nbos_replay **out) {
   if (out) *out = nullptr;
-  if (!cfg || !in || !out) return NBOS_E_ARG;
-  if (cfg->struct_size != sizeof(nbos_config)) return NBOS_E_ARG;
+  if (!cfg_in || !in || !out) return NBOS_E_ARG;
+  // the layout that ends at min_hosts is accepted as well: the later fields read as 0
+  constexpr uint32_t kShortConfig = offsetof(nbos_config, autoscale_f_milli);
+  if (cfg_in->struct_size != sizeof(nbos_config) && cfg_in->struct_size != kShortConfig) return NBOS_E_ARG;
+  nbos_config full;
+  memset(&full, 0, sizeof full);
+  memcpy(&full, cfg_in, cfg_in->struct_size);
+  full.struct_size = sizeof(nbos_config);
+  const nbos_config *cfg = &full;
   if (cfg->n_replays < 0 || cfg->n_traces < 0 || (cfg->n_replays > 0 && cfg->n_traces < 1)) return NBOS_E_ARG;
   if (cfg->replicas != 3) return NBOS_E_ARG;
   if (cfg->gpus_per_host < 1 || cfg->gpus_per_host > NBOS_MAX_GPUS) return NBOS_E_ARG;
@@ -115,12 +123,18 @@ int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in, void *
   if (cfg->hosts_max > NBOS_MAX_HOSTS) return NBOS_E_LIMIT;
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
-  if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS))
+  if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS |
+                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR))
     return NBOS_E_ARG;
+  if (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) {
+    if (cfg->scale_interval_ms < 1 || cfg->min_hosts < 0) return NBOS_E_ARG;
+  }
   if (cfg->flags & NBOS_F_SCALE_IN) {
-    if (cfg->scale_interval_ms < 1 || cfg->scale_in_idle_pct < 0 || cfg->scale_in_idle_pct > 100 ||
-        cfg->min_hosts < 0)
-      return NBOS_E_ARG;
+    if (cfg->scale_in_idle_pct < 0 || cfg->scale_in_idle_pct > 100) return NBOS_E_ARG;
+  }
+  if (cfg->flags & NBOS_F_AUTOSCALE) {
+    if (cfg->autoscale_f_milli < 0 || cfg->autoscale_f_milli > 100000) return NBOS_E_ARG;
+    if (cfg->scaling_buffer_hosts < 0 || cfg->scaling_buffer_hosts > NBOS_MAX_HOSTS) return NBOS_E_ARG;
   }
   if (cfg->n_replays > 0 &&
       (!in->ev_offset || !in->sess_offset || !in->trace_of_replay || !in->cap_milli)) return NBOS_E_ARG;
@@ -238,8 +252,9 @@ int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in, void *
     k.G = cfg->gpus_per_host; k.flags = cfg->flags;
     k.migr = cfg->migration_delay_ms; k.boot = cfg->boot_delay_ms; k.retry_iv = cfg->retry_interval_ms;
     k.max_retries = cfg->max_retries;
-    k.scale_iv = (cfg->flags & NBOS_F_SCALE_IN) ? cfg->scale_interval_ms : 1;
+    k.scale_iv = (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) ? cfg->scale_interval_ms : 1;
     k.idle_pct = cfg->scale_in_idle_pct; k.min_hosts = cfg->min_hosts;
+    k.f_milli = cfg->autoscale_f_milli; k.buffer = cfg->scaling_buffer_hosts;
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
     const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
     k.batch = (nb && nb[0] == '0') ? 0 : 1;

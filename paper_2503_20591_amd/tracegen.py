@@ -21,6 +21,7 @@ import numpy as np
 
 EV_START, EV_CELL, EV_END = 0, 1, 2
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
+F_AUTOSCALE, F_DYNAMIC_SR = 0x20, 0x40
 
 MAX_DUR_MS = 86_400_000          # a cell or an idle gap is at most 24 h
 MAX_TIME_MS = 1_900_000_000      # arrivals are clipped here so finish times stay in int32
@@ -254,9 +255,10 @@ def workload(name: str, n_replays: int | None = None, workers: int = 1) -> Trace
 
 # ---- small randomized cases for parity fuzzing -------------------------------------------------
 
-def random_case(seed: int, n_replays: int = 4) -> TraceBatch:
+def random_case(seed: int, n_replays: int = 4, policy_flags: bool = False) -> TraceBatch:
     """A small batch with randomly drawn cluster shape, flags, delays and load, including END
-    events, repeated START / END events, and replays that share a trace."""
+    events, repeated START / END events, and replays that share a trace. ``policy_flags`` adds
+    the periodic auto-scaler and / or the dynamic subscription-ratio limit with low caps."""
     rng = np.random.Generator(np.random.Philox(key=0x5EED0000 + seed))
     G = int(rng.choice([1, 2, 4, 8, 8, 8]))
     h0 = int(rng.integers(1, 20)) if rng.random() < 0.8 else int(rng.integers(60, 140))
@@ -293,4 +295,16 @@ def random_case(seed: int, n_replays: int = 4) -> TraceBatch:
         traces.append((t, d, sk, g))
     tor = rng.integers(0, n_traces, n_replays)
     caps = rng.choice([300, 333, 667, 1000, 1500, 2000, 3000, 4000, 100000], n_replays)
+    if policy_flags:
+        # the periodic auto-scaler and the dynamic limit, drawn from a stream of their own so that
+        # the case is otherwise the same as without them
+        r2 = np.random.Generator(np.random.Philox(key=0xA5CA1E00 + seed))
+        extra = int(r2.choice([F_AUTOSCALE, F_DYNAMIC_SR, F_AUTOSCALE | F_DYNAMIC_SR]))
+        cfg["flags"] |= extra
+        if extra & F_AUTOSCALE:
+            cfg["hosts_max"] = max(cfg["hosts_max"], h0 + int(r2.integers(0, 12)))
+            cfg["autoscale_f_milli"] = int(r2.choice([0, 1050, 1050, 2000, 8000]))
+            cfg["scaling_buffer_hosts"] = int(r2.choice([0, 0, 1, 3]))
+        if extra & F_DYNAMIC_SR:
+            caps = r2.choice([20, 50, 100, 200, 334, 1000], n_replays)
     return _pack(cfg, traces, tor, caps, f"random{seed}")

@@ -91,6 +91,32 @@ def test_random_cases_hosts_in_lds(rp, oracle, seed):
     assert_same(rp, oracle, b, st, logs)
 
 
+# ---- periodic auto-scaler (Section 3.4.2) and dynamic subscription-ratio limit (Section 3.4.1) -----
+
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
+@pytest.mark.parametrize("seed", range(60))
+def test_policy_flag_cases(rp, oracle, seed, in_lds):
+    b = tg.random_case(seed, policy_flags=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+    assert_same(rp, oracle, b, st, logs, check=not in_lds)
+
+
+@pytest.mark.parametrize("f_milli,buf,min_hosts", [(1050, 200, 100), (4000, 8, 300)])
+def test_autoscaler_on_a_large_cluster(rp, oracle, f_milli, buf, min_hosts):
+    # the diurnal 512-host workload under the periodic auto-scaler (the paper's f = 1.05 with a large
+    # buffer, and a more aggressive f with a small one), releases allowed, plus the dynamic limit:
+    # hosts come and go all day
+    b = tg.workload("c4", n_replays=2)
+    b.config.update(flags=tg.F_MIGRATE | tg.F_SCALE_OUT | tg.F_SCALE_IN | tg.F_AUTOSCALE | tg.F_DYNAMIC_SR,
+                    autoscale_f_milli=f_milli, scaling_buffer_hosts=buf, min_hosts=min_hosts)
+    b.cap_milli = np.asarray([2000, 700], np.int32)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+    assert st["scale_in_hosts"].min() > 0
+    auto = [sum(1 for c in lg if oracle.decode(c)["outcome"] == oracle.D_SCALE_AUTO) for lg in logs]
+    assert max(auto) > 0
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
