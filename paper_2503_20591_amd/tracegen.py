@@ -224,10 +224,19 @@ def _recipe(name: str):
                             dur=lambda r, s: lognormal_ms(r, 30.0, 1.0, s)),
                     cap=lambda i, n: 1000 + int(np.random.Generator(
                         np.random.Philox(key=0xCA9, counter=i)).integers(0, 3001)))
+    if name == "c4a":  # the c4 traces with the cluster sized by the periodic auto-scaler alone
+        # (Section 3.4.2: f = 1.05): 256 hosts at the start, a scaling buffer of 32 hosts, releases
+        # down to 128 hosts, no scale-out on failed placement, cap 4.0 plus the dynamic limit
+        rc = _recipe("c4")
+        rc["cfg"] = dict(rc["cfg"], hosts_initial=256, min_hosts=128,
+                         flags=F_MIGRATE | F_SCALE_IN | F_AUTOSCALE | F_DYNAMIC_SR,
+                         autoscale_f_milli=1050, scaling_buffer_hosts=32)
+        rc["cap"] = lambda i, n: 4000
+        return rc
     raise KeyError(name)
 
 
-WORKLOADS = ("c1", "c2", "c3", "c4", "c5")
+WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c4a")
 
 
 def _gen_range(args):

@@ -117,6 +117,14 @@ def test_autoscaler_on_a_large_cluster(rp, oracle, f_milli, buf, min_hosts):
     assert max(auto) > 0
 
 
+def test_named_workload_c4a_autoscaler_only(rp, oracle):
+    b = tg.workload("c4a", n_replays=2)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+    auto = [sum(1 for c in lg if oracle.decode(c)["outcome"] == oracle.D_SCALE_AUTO) for lg in logs]
+    assert min(auto) > 0 and st["scale_in_hosts"].min() > 0
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
