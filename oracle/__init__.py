@@ -38,13 +38,18 @@ _U32 = ("n_decisions", "sessions_placed", "sessions_rejected", "cells_total", "c
         "scale_in_hosts", "peak_hosts")
 _I32 = ("max_delay_ms", "t_end_ms")
 _I64 = ("sum_delay_ms", "sum_tct_ms", "gpu_ms_executed", "gpu_ms_committed",
-        "gpu_ms_provisioned", "reservation_gpu_ms", "sub_gpu_ms")
+        "gpu_ms_provisioned", "reservation_gpu_ms", "sub_gpu_ms", "replica_ms")
 
 
 class _Result(C.Structure):
     _fields_ = ([(n, C.c_uint32) for n in _U32] + [(n, C.c_int32) for n in _I32] +
                 [("delay_hist", C.c_uint32 * 32)] + [(n, C.c_int64) for n in _I64] +
                 [("digest", C.c_uint64)])
+
+
+class _Bill(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("provider_cost", "usage_revenue", "standby_revenue",
+                                         "reservation_revenue")]
 
 
 class _Final(C.Structure):
@@ -79,6 +84,8 @@ def _load(path: str | None = None):
         C.POINTER(_Params), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
         C.c_int32, C.c_void_p, C.POINTER(_Result), C.c_void_p, C.c_int64, C.POINTER(_Final)]
     lib.orc_sizeof_result.restype = C.c_int
+    lib.orc_billing.restype = None
+    lib.orc_billing.argtypes = [C.POINTER(_Result), C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(_Bill)]
     assert lib.orc_sizeof_result() == C.sizeof(_Result)
     if path is None:
         _lib = lib
@@ -156,6 +163,23 @@ def replay_batch(batch, replays=None, *, check: bool = False, threads: int = 1) 
     _load()
     with ThreadPoolExecutor(max_workers=threads) as ex:   # ctypes releases the GIL in the C call
         return list(ex.map(one, idx))
+
+
+def billing(result: dict, gpus_per_host: int, price_micro_per_host_hour: int, markup_pct: int = 115,
+            standby_permille: int = 125, lib_path: str | None = None) -> dict:
+    """Section 5.3.1 billing of one result dict (as returned by ``replay``), integer micro-dollars."""
+    lib = _load(lib_path)
+    res = _Result()
+    for name in RESULT_FIELDS:
+        if name == "delay_hist":
+            for i, v in enumerate(result[name]):
+                res.delay_hist[i] = v
+        else:
+            setattr(res, name, result[name])
+    out = _Bill()
+    lib.orc_billing(C.byref(res), int(gpus_per_host), int(price_micro_per_host_hour), int(markup_pct),
+                    int(standby_permille), C.byref(out))
+    return {n: int(getattr(out, n)) for n, _ in _Bill._fields_}
 
 
 def decode(code: int) -> dict:

@@ -16,6 +16,7 @@
  *   auto-scaler: expected capacity f * sum C, scaling buffer ....... 3.4.2
  *   dynamic cluster-wide limit on the subscription ratio ........... 3.4.1
  *   metric definitions (delay, TCT, immediate, reuse, GPU-hours) ... 5.2.2-5.2.4
+ *   billing model (provider cost, revenue, standby charge) ......... 5.3.1
  *
  * Readings taken where the paper leaves a choice open (all deterministic):
  *   - host preference key, smaller is better: (committed GPUs, subscribed GPUs,
@@ -88,6 +89,7 @@ typedef struct {
   int32_t clock;
   int n_on;                 /* hosts not off        */
   int64_t sum_S, sum_C;     /* cluster totals       */
+  int64_t n_replicas;       /* placed replicas      */
   orc_result r;
   uint64_t *log; int64_t log_cap;
   /* self-check accumulators */
@@ -151,6 +153,7 @@ static void advance(sim *m, int32_t t) {
   int64_t dt = (int64_t)t - m->clock;
   m->r.gpu_ms_provisioned += (int64_t)m->n_on * m->G * dt;
   m->r.sub_gpu_ms += m->sum_S * dt;
+  m->r.replica_ms += m->n_replicas * dt;
   m->chk_commit_integral += m->sum_C * dt;
   m->clock = t;
 }
@@ -171,8 +174,8 @@ static int host_better(const sim *m, int a, int b) {
   return a < b;
 }
 
-static void subscribe(sim *m, int h, int g) { m->hosts[h].S += g; m->hosts[h].nrep++; m->sum_S += g; }
-static void unsubscribe(sim *m, int h, int g) { m->hosts[h].S -= g; m->hosts[h].nrep--; m->sum_S -= g; }
+static void subscribe(sim *m, int h, int g) { m->hosts[h].S += g; m->hosts[h].nrep++; m->sum_S += g; m->n_replicas++; }
+static void unsubscribe(sim *m, int h, int g) { m->hosts[h].S -= g; m->hosts[h].nrep--; m->sum_S -= g; m->n_replicas--; }
 static void commit(sim *m, int h, int g) { m->hosts[h].C += g; m->sum_C += g; }
 static void release(sim *m, int h, int g) { m->hosts[h].C -= g; m->sum_C -= g; }
 
@@ -595,3 +598,21 @@ int orc_replay(const orc_params *p,
 }
 
 int orc_sizeof_result(void) { return (int)sizeof(orc_result); }
+
+/* ---- Section 5.3.1: billing ------------------------------------------------------ */
+static int64_t ratio(int64_t amount, int64_t num, int64_t den) {
+  return (int64_t)((unsigned __int128)amount * (unsigned __int128)num / (unsigned __int128)den);
+}
+
+void orc_billing(const orc_result *r, int G, int64_t price, int markup_pct, int standby_permille,
+                 orc_bill *out) {
+  const int64_t ms_per_hour = 3600000;
+  /* time replicas spent executing: every started cell runs for its duration */
+  int64_t exec_ms = r->sum_tct_ms - r->sum_delay_ms;
+  int64_t standby_ms = r->replica_ms - exec_ms;
+  /* host-hours = GPU-ms / (G * ms per hour) */
+  out->provider_cost = ratio(r->gpu_ms_provisioned, price, (int64_t)G * ms_per_hour);
+  out->usage_revenue = ratio(r->gpu_ms_executed, price * markup_pct, (int64_t)G * ms_per_hour * 100);
+  out->standby_revenue = ratio(standby_ms, price * markup_pct * standby_permille, ms_per_hour * 100 * 1000);
+  out->reservation_revenue = ratio(r->reservation_gpu_ms, price * markup_pct, (int64_t)G * ms_per_hour * 100);
+}

@@ -59,6 +59,7 @@ typedef struct {
   int64_t  sum_delay_ms, sum_tct_ms;
   int64_t  gpu_ms_executed, gpu_ms_committed, gpu_ms_provisioned;
   int64_t  reservation_gpu_ms, sub_gpu_ms;
+  int64_t  replica_ms;          /* integral over [0, t_end] of the number of placed replicas */
   uint64_t digest;
 } orc_result;
 
@@ -87,5 +88,22 @@ int orc_replay(const orc_params *p,
                orc_result *out, uint64_t *log, int64_t log_cap, orc_final *fin);
 
 int orc_sizeof_result(void);
+
+/*
+ * Billing model of Section 5.3.1 applied to one result, in integer micro-dollars (each amount
+ * rounded down): the provider pays `price` per host-hour provisioned; users pay markup_pct / 100
+ * times the provider's rate in proportion to the GPUs they use; a standby replica (placed, not
+ * executing) pays standby_permille / 1000 of the marked-up host rate. The Reservation baseline
+ * pays the marked-up rate for its reserved GPUs. The paper's values: markup 115, standby 125.
+ */
+typedef struct {
+  int64_t provider_cost;        /* price * provisioned host-hours                            */
+  int64_t usage_revenue;        /* executing replicas: g / G of the marked-up host rate      */
+  int64_t standby_revenue;      /* replica-hours not executing                               */
+  int64_t reservation_revenue;  /* what the Reservation baseline would bill                  */
+} orc_bill;
+
+void orc_billing(const orc_result *r, int gpus_per_host, int64_t price_micro_per_host_hour,
+                 int markup_pct, int standby_permille, orc_bill *out);
 
 #endif

@@ -59,6 +59,14 @@ MUTANTS = [
     ("dynamic limit: divides by hosts_max", "(h->S + g) * m->n_on <=", "(h->S + g) * m->H <="),
     ("dynamic limit replaces the cap", "if ((int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*",
      "if (!(m->p->flags & ORC_F_DYNAMIC_SR) && (int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*"),
+    ("billing: standby charge not reduced by the executing time", "int64_t standby_ms = r->replica_ms - exec_ms;", "int64_t standby_ms = r->replica_ms;"),
+    ("billing: markup dropped from the usage charge", "ratio(r->gpu_ms_executed, price * markup_pct, (int64_t)G * ms_per_hour * 100)", "ratio(r->gpu_ms_executed, price * 100, (int64_t)G * ms_per_hour * 100)"),
+    ("billing: standby share applied per GPU", "ratio(standby_ms, price * markup_pct * standby_permille, ms_per_hour * 100 * 1000)", "ratio(standby_ms, price * markup_pct * standby_permille, (int64_t)G * ms_per_hour * 100 * 1000)"),
+    ("billing: provider cost per GPU-hour", "ratio(r->gpu_ms_provisioned, price, (int64_t)G * ms_per_hour)", "ratio(r->gpu_ms_provisioned, price, ms_per_hour)"),
+    ("billing: Reservation billed without markup", "ratio(r->reservation_gpu_ms, price * markup_pct, (int64_t)G * ms_per_hour * 100)", "ratio(r->reservation_gpu_ms, price * 100, (int64_t)G * ms_per_hour * 100)"),
+    ("billing: 64-bit product", "(int64_t)((unsigned __int128)amount * (unsigned __int128)num / (unsigned __int128)den)", "(int64_t)((uint64_t)amount * (uint64_t)num / (uint64_t)den)"),
+    ("replica integral counts GPUs", "m->r.replica_ms += m->n_replicas * dt;", "m->r.replica_ms += m->sum_S * dt;"),
+    ("replicas of ended sessions keep counting", "m->sum_S -= g; m->n_replicas--; }", "m->sum_S -= g; }"),
     ("dynamic limit always on", "if (m->p->flags & ORC_F_DYNAMIC_SR)\n    return", "if (1)\n    return"),
     ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
     ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
@@ -80,6 +88,8 @@ MUTANTS = [
 def _shim(orc, lib_path):
     ns = types.SimpleNamespace(**{k: getattr(orc, k) for k in dir(orc) if k.startswith(("D_", "F_", "EV_"))})
     ns.decode = orc.decode
+    ns.RESULT_FIELDS = orc.RESULT_FIELDS
+    ns.billing = lambda *a, **kw: orc.billing(*a, lib_path=lib_path, **kw)
     ns.replay = lambda *a, **kw: orc.replay(*a, lib_path=lib_path, **kw)
 
     def replay_batch(batch, replays=None, check=False, threads=1):
@@ -113,6 +123,8 @@ def run_pins(lib_path):
     checks += [lambda s=s: pins.test_autoscale_with_f_zero_is_the_plain_policy(o, s) for s in range(6)]
     checks += [lambda s=s: pins.test_dynamic_limit_is_vacuous_on_large_clusters(o, s) for s in range(8)]
     checks.append(lambda: pins.test_dynamic_limit_brute_force(o))
+    checks += [lambda: pins.test_billing_printed_example(o), lambda: pins.test_billing_is_linear_and_exact_on_large_results(o)]
+    checks += [lambda s=s: pins.test_replica_integral_random(o, s) for s in range(3)]
     for c in checks:
         try:
             c()

@@ -410,6 +410,75 @@ def test_dynamic_limit_brute_force(oracle):
         assert [(d["session"], d["outcome"], d["slot"], d["host"]) for d in got] == expect
 
 
+# ---- Section 5.3.1: billing model, the printed $1.44 / $5.75 example ------------------------------
+
+HOUR = 3_600_000
+
+
+def _billing_example():
+    kv = {}
+    for line in open(os.path.join(GOLDEN, "billing_example.txt")):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=")
+            kv[k.strip()] = int(v)
+    return kv
+
+
+def test_billing_printed_example(oracle):
+    kv = _billing_example()
+    G, g = kv["gpus_per_host"], kv["training_gpus"]
+    price = kv["host_price_dollars_per_hour"] * 1_000_000          # micro-dollars per host-hour
+    # one session with g = 4 on three 8-GPU hosts: placed at 0, trains from 0 for one hour, ends at 2 h
+    cfg = dict(BASE, gpus_per_host=G)
+    r = run(oracle, cfg, [[0, S, 0, 0], [0, CELL, 0, HOUR], [2 * HOUR, END, 0, 0]], [g], 1000)
+    assert r["replica_ms"] == 3 * 2 * HOUR and r["gpu_ms_executed"] == g * HOUR
+    b = oracle.billing(r, G, price, kv["markup_pct"], kv["standby_permille"])
+    # the executing replica: $5.75 for its hour
+    assert b["usage_revenue"] == kv["training_cents_per_hour"] * 10_000
+    # 3 replicas x 2 h minus the executing hour = 5 standby replica-hours at $1.4375 (printed $1.44)
+    assert b["standby_revenue"] % 5 == 0
+    per_hour = b["standby_revenue"] // 5
+    assert round(per_hour / 10_000) == kv["standby_replica_cents_per_hour_rounded"]
+    assert per_hour == 1_437_500
+    assert b["provider_cost"] == 3 * 2 * price                      # three hosts for two hours
+    assert b["reservation_revenue"] == 2 * kv["training_cents_per_hour"] * 10_000   # 4 of 8 GPUs for 2 h
+
+
+def test_billing_is_linear_and_exact_on_large_results(oracle):
+    # amounts are floor(quantity * rate) in exact arithmetic, also where the product passes 2^64
+    from fractions import Fraction
+    rng = np.random.default_rng(5)
+    zero = {k: ([0] * 32 if k == "delay_hist" else 0) for k in oracle.RESULT_FIELDS}
+    for _ in range(200):
+        G = int(rng.integers(1, 9))
+        price = int(rng.integers(1, 10**9))
+        mk, sb = int(rng.integers(100, 400)), int(rng.integers(0, 1001))
+        r = dict(zero)
+        r["gpu_ms_provisioned"] = int(rng.integers(0, 2**44))
+        r["gpu_ms_executed"] = int(rng.integers(0, 2**44))
+        r["reservation_gpu_ms"] = int(rng.integers(0, 2**44))
+        r["sum_delay_ms"] = int(rng.integers(0, 2**40))
+        exec_ms = int(rng.integers(0, 2**44))
+        r["sum_tct_ms"] = r["sum_delay_ms"] + exec_ms
+        r["replica_ms"] = exec_ms + int(rng.integers(0, 2**46))
+        b = oracle.billing(r, G, price, mk, sb)
+        rate = Fraction(price, HOUR)                                 # micro-dollars per host-ms
+        assert b["provider_cost"] == int(Fraction(r["gpu_ms_provisioned"], G) * rate)
+        assert b["usage_revenue"] == int(Fraction(r["gpu_ms_executed"], G) * rate * Fraction(mk, 100))
+        assert b["standby_revenue"] == int((r["replica_ms"] - exec_ms) * rate * Fraction(mk, 100) * Fraction(sb, 1000))
+        assert b["reservation_revenue"] == int(Fraction(r["reservation_gpu_ms"], G) * rate * Fraction(mk, 100))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_replica_integral_random(oracle, seed):
+    # replica_ms is the subscribed-GPU integral with every request counted as 1: replay the same trace
+    # with all requests set to 1 GPU on 1-GPU-per-request terms and compare with sub_gpu_ms there
+    b = tg.random_case(600 + seed, n_replays=2)
+    b.sess_gpus = np.ones_like(b.sess_gpus)
+    for r in oracle.replay_batch(b, check=True):
+        assert r["replica_ms"] == r["sub_gpu_ms"]
+
+
 # ---- input validation -----------------------------------------------------------------------------
 
 def test_rejects_bad_input(oracle):
