@@ -152,6 +152,7 @@ typedef struct {
  *   reservation_gpu_ms sum over placed sessions g * (end - start): what the
  *                     Reservation baseline holds (end = END event time or t_end)
  *   sub_gpu_ms        integral over [0, t_end] of the cluster's subscribed GPUs
+ *   replica_ms        integral over [0, t_end] of the number of placed replicas
  *   digest            d = d * 0x100000001B3 + code over all decisions in order,
  *                     starting from 0xCBF29CE484222325 (wrapping uint64)
  * Decision code = host | slot << 10 | outcome << 12 | session << 16 | time << 32.
@@ -169,6 +170,7 @@ typedef struct {
   int64_t  sum_delay_ms, sum_tct_ms;
   int64_t  gpu_ms_executed, gpu_ms_committed, gpu_ms_provisioned;
   int64_t  reservation_gpu_ms, sub_gpu_ms;
+  int64_t  replica_ms;
   uint64_t digest;
 } nbos_stats;
 
@@ -237,6 +239,35 @@ int32_t nbos_replay_last_kernel_ms(nbos_replay *h, float *ms_out);
 /* Dynamic LDS bytes per workgroup and waves per workgroup chosen at create. */
 int32_t nbos_replay_launch_info(nbos_replay *h, int32_t *lds_bytes,
                                 int32_t *threads_per_group, int32_t *groups);
+
+/*
+ * Billing model of paper Section 5.3.1 as a post-pass over the results of the last run, in integer
+ * micro-dollars, every amount rounded down:
+ *   provider_cost        price * host-hours provisioned   (gpu_ms_provisioned / G)
+ *   usage_revenue        executing replicas pay markup_pct/100 of the provider's rate for the share
+ *                        g / G of a host they use         (gpu_ms_executed / G)
+ *   standby_revenue      a placed replica that is not executing pays standby_permille/1000 of the
+ *                        marked-up host rate              (replica_ms - executing time)
+ *   reservation_revenue  the Reservation baseline at the same markup (reservation_gpu_ms / G)
+ * The paper's example: $10 per host-hour (price 10,000,000), markup 115, standby 125.
+ */
+typedef struct {
+  int64_t price_micro_per_host_hour;  /* 0..1,000,000,000 */
+  int32_t markup_pct;                 /* 0..1000          */
+  int32_t standby_permille;           /* 0..1000          */
+} nbos_billing_params;
+
+typedef struct {
+  int64_t provider_cost, usage_revenue, standby_revenue, reservation_revenue;
+} nbos_bill;
+
+/*
+ * Compute the bills of replays [first, first+count) on the device from the stats of the last run and
+ * copy them to host_out (host memory, count * sizeof(nbos_bill) bytes). Synchronises the stream.
+ * Errors: NBOS_E_ARG (null, range, parameter out of range), NBOS_E_STATE (never run), NBOS_E_HIP.
+ */
+int32_t nbos_replay_billing(nbos_replay *h, const nbos_billing_params *params, int32_t first,
+                            int32_t count, nbos_bill *host_out);
 
 /* Free the handle and its device buffers (synchronises the stream). NULL is a no-op. */
 void nbos_replay_destroy(nbos_replay *h);

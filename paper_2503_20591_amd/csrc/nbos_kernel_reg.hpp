@@ -34,8 +34,8 @@ namespace regk {
 
 // cold counters kept in LDS (lane 0 adds with ds_add, no return value)
 enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
-       CS_NON, CS_SUMS, CS_OPENG, CS_N32 };
-enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_N64 };
+       CS_NON, CS_SUMS, CS_OPENG, CS_NREP, CS_N32 };
+enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_REPL, CL_N64 };
 
 // session record: x hosts word, y time word, z flags, w duration of the queued cell
 struct Lds {
@@ -342,6 +342,8 @@ __device__ __forceinline__ void session_start(Ctx<NJ> &c, Regs &r, uint32_t s, u
   c32_add(c.m, c.lane, CS_OPENG, (uint32_t)g);
   c64_add(c.m, c.lane, CL_SUB, -(int64_t)(3 * g) * now);
   c64_add(c.m, c.lane, CL_RESV, -(int64_t)g * now);
+  c32_add(c.m, c.lane, CS_NREP, 3u);
+  c64_add(c.m, c.lane, CL_REPL, -(int64_t)3 * now);
 }
 
 // the replicas of session s give their subscriptions back at time `now`
@@ -354,6 +356,8 @@ __device__ __forceinline__ void end_session(Ctx<NJ> &c, Regs &r, uint32_t s, uin
   sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
   c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(-3 * g));
   c64_add(c.m, c.lane, CL_SUB, (int64_t)(3 * g) * now);
+  c32_add(c.m, c.lane, CS_NREP, (uint32_t)-3);
+  c64_add(c.m, c.lane, CL_REPL, (int64_t)3 * now);
 }
 
 // ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
@@ -778,6 +782,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
     out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
     out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
     out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
+    out->replica_ms = (int64_t)m.c64[CL_REPL] + (int64_t)(int32_t)m.c32[CS_NREP] * t_end;
     out->digest = r.digest;
   }
 }

@@ -56,6 +56,38 @@ __global__ void nbos_validate_replays(const int32_t *trace_of_replay, const int3
   if (e) atomicOr(err, e);
 }
 
+// ---- billing post-pass (paper Section 5.3.1): one lane per replay ---------------------------------
+// floor(a * b / d) for a, b, d below 2^63 with a quotient below 2^64: 128-bit product, then binary
+// long division (the remainder stays below d, so it never overflows when doubled)
+__device__ uint64_t muldiv_floor(uint64_t a, uint64_t b, uint64_t d) {
+  const uint64_t hi = __umul64hi(a, b), lo = a * b;
+  uint64_t rem = 0, q = 0;
+  for (int i = 127; i >= 0; --i) {
+    const uint64_t bit = i >= 64 ? (hi >> (i - 64)) & 1u : (lo >> i) & 1u;
+    rem = (rem << 1) | bit;
+    q <<= 1;
+    if (rem >= d) { rem -= d; q |= 1u; }
+  }
+  return q;
+}
+
+__global__ void nbos_billing_kernel(const nbos_stats *stats, int first, int count, int G, int64_t price,
+                                    int32_t markup_pct, int32_t standby_permille, nbos_bill *out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  const nbos_stats &s = stats[first + i];
+  const uint64_t ms_per_hour = 3600000u;
+  const uint64_t exec_ms = (uint64_t)(s.sum_tct_ms - s.sum_delay_ms);      // every started cell runs its duration
+  const uint64_t standby_ms = (uint64_t)s.replica_ms - exec_ms;
+  const uint64_t marked = (uint64_t)price * (uint64_t)markup_pct;
+  nbos_bill b;
+  b.provider_cost = (int64_t)muldiv_floor((uint64_t)s.gpu_ms_provisioned, (uint64_t)price, (uint64_t)G * ms_per_hour);
+  b.usage_revenue = (int64_t)muldiv_floor((uint64_t)s.gpu_ms_executed, marked, (uint64_t)G * ms_per_hour * 100u);
+  b.standby_revenue = (int64_t)muldiv_floor(standby_ms, marked * (uint64_t)standby_permille, ms_per_hour * 100000u);
+  b.reservation_revenue = (int64_t)muldiv_floor((uint64_t)s.reservation_gpu_ms, marked, (uint64_t)G * ms_per_hour * 100u);
+  out[i] = b;
+}
+
 }  // namespace
 
 // ================================= host side: the C ABI ===========================================
@@ -69,6 +101,7 @@ struct nbos_replay {
   size_t lds_bytes;
   const void *kernel;      // the kernel instance chosen at create
   nbos_stats *d_stats;
+  nbos_bill *d_bill;
   uint64_t *d_log;
   std::vector<int64_t> ev_off;
   std::vector<int32_t> sess_off;
@@ -81,6 +114,7 @@ namespace {
 void free_handle(nbos_replay *h) {
   if (!h) return;
   if (h->d_stats) (void)hipFree(h->d_stats);
+  if (h->d_bill) (void)hipFree(h->d_bill);
   if (h->d_log) (void)hipFree(h->d_log);
   if (h->e0) (void)hipEventDestroy(h->e0);
   if (h->e1) (void)hipEventDestroy(h->e1);
@@ -146,7 +180,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   nbos_replay *h = new (std::nothrow) nbos_replay();
   if (!h) return NBOS_E_NOMEM;
   h->cfg = *cfg; h->in = *in; h->stream = (hipStream_t)stream;
-  h->d_stats = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
+  h->d_stats = nullptr; h->d_bill = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   int32_t rc = NBOS_OK;
 #define HIP_TRY(x) do { if ((x) != hipSuccess) { rc = NBOS_E_HIP; goto fail; } } while (0)
   {
@@ -227,6 +261,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
 
     if (cfg->n_replays > 0) {
       if (hipMalloc(&h->d_stats, sizeof(nbos_stats) * (size_t)cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
+      if (hipMalloc(&h->d_bill, sizeof(nbos_bill) * (size_t)cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
     }
     int64_t log_stride = 0;
     if ((cfg->flags & NBOS_F_DECISION_LOG) && cfg->n_replays > 0) {
@@ -288,6 +323,27 @@ int32_t nbos_replay_stats(nbos_replay *h, int32_t first, int32_t count, nbos_sta
       hipMemcpyAsync(host_out, h->d_stats + first, sizeof(nbos_stats) * (size_t)count, hipMemcpyDeviceToHost,
                      h->stream) != hipSuccess)
     return NBOS_E_HIP;
+  if (hipStreamSynchronize(h->stream) != hipSuccess) return NBOS_E_HIP;
+  return NBOS_OK;
+}
+
+int32_t nbos_replay_billing(nbos_replay *h, const nbos_billing_params *bp, int32_t first, int32_t count,
+                            nbos_bill *host_out) {
+  if (!h || !bp || first < 0 || count < 0 || (int64_t)first + count > h->cfg.n_replays) return NBOS_E_ARG;
+  if (count > 0 && !host_out) return NBOS_E_ARG;
+  if (bp->price_micro_per_host_hour < 0 || bp->price_micro_per_host_hour > 1000000000LL) return NBOS_E_ARG;
+  if (bp->markup_pct < 0 || bp->markup_pct > 1000 || bp->standby_permille < 0 || bp->standby_permille > 1000)
+    return NBOS_E_ARG;
+  if (!h->ran) return NBOS_E_STATE;
+  if (count > 0) {
+    hipLaunchKernelGGL(nbos_billing_kernel, dim3((count + 255) / 256), dim3(256), 0, h->stream, h->d_stats, first,
+                       count, h->cfg.gpus_per_host, bp->price_micro_per_host_hour, bp->markup_pct,
+                       bp->standby_permille, h->d_bill);
+    if (hipGetLastError() != hipSuccess) return NBOS_E_HIP;
+    if (hipMemcpyAsync(host_out, h->d_bill, sizeof(nbos_bill) * (size_t)count, hipMemcpyDeviceToHost, h->stream) !=
+        hipSuccess)
+      return NBOS_E_HIP;
+  }
   if (hipStreamSynchronize(h->stream) != hipSuccess) return NBOS_E_HIP;
   return NBOS_OK;
 }

@@ -21,7 +21,7 @@ F_AUTOSCALE, F_DYNAMIC_SR = 0x20, 0x40
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
-           "nbos_replay_last_kernel_ms", "nbos_replay_launch_info", "nbos_replay_destroy",
+           "nbos_replay_billing", "nbos_replay_last_kernel_ms", "nbos_replay_launch_info", "nbos_replay_destroy",
            "nbos_strerror", "nbos_sizeof_stats")
 
 
@@ -38,6 +38,14 @@ _INPUT_FIELDS = ("ev_offset", "ev_time_ms", "ev_dur_ms", "ev_sess_kind", "sess_o
                  "trace_of_replay", "cap_milli")
 
 
+class NbosBillingParams(C.Structure):
+    _fields_ = [("price_micro_per_host_hour", C.c_int64), ("markup_pct", C.c_int32), ("standby_permille", C.c_int32)]
+
+
+BILL_DTYPE = np.dtype([("provider_cost", "<i8"), ("usage_revenue", "<i8"), ("standby_revenue", "<i8"),
+                       ("reservation_revenue", "<i8")])
+
+
 class NbosInputs(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _INPUT_FIELDS]
 
@@ -49,7 +57,8 @@ STATS_DTYPE = np.dtype(
      ("executor_reused", "<u4"), ("migrations", "<u4"), ("scale_out_hosts", "<u4"), ("scale_in_hosts", "<u4"),
      ("peak_hosts", "<u4"), ("max_delay_ms", "<i4"), ("t_end_ms", "<i4"), ("delay_hist", "<u4", (32,)),
      ("sum_delay_ms", "<i8"), ("sum_tct_ms", "<i8"), ("gpu_ms_executed", "<i8"), ("gpu_ms_committed", "<i8"),
-     ("gpu_ms_provisioned", "<i8"), ("reservation_gpu_ms", "<i8"), ("sub_gpu_ms", "<i8"), ("digest", "<u8")],
+     ("gpu_ms_provisioned", "<i8"), ("reservation_gpu_ms", "<i8"), ("sub_gpu_ms", "<i8"), ("replica_ms", "<i8"),
+     ("digest", "<u8")],
     align=True)
 
 _lib = None
@@ -78,6 +87,8 @@ def load():
     lib.nbos_replay_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.nbos_replay_decisions.restype = C.c_int64
     lib.nbos_replay_decisions.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]
+    lib.nbos_replay_billing.restype = C.c_int32
+    lib.nbos_replay_billing.argtypes = [C.c_void_p, C.POINTER(NbosBillingParams), C.c_int32, C.c_int32, C.c_void_p]
     lib.nbos_replay_last_kernel_ms.restype = C.c_int32
     lib.nbos_replay_last_kernel_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
     lib.nbos_replay_launch_info.restype = C.c_int32
@@ -171,6 +182,17 @@ class Replay:
         if n < 0:
             raise NbosError(int(n), "nbos_replay_decisions")
         return buf[: min(n, cap)].copy()
+
+    def billing(self, price_micro_per_host_hour: int, markup_pct: int = 115, standby_permille: int = 125,
+                first: int = 0, count: int | None = None) -> np.ndarray:
+        """Bills (structured array of BILL_DTYPE) of the last run, computed on the device."""
+        count = self.n_replays - first if count is None else count
+        bp = NbosBillingParams(int(price_micro_per_host_hour), int(markup_pct), int(standby_permille))
+        out = np.zeros(max(count, 0), dtype=BILL_DTYPE)
+        rc = self._lib.nbos_replay_billing(self._h, C.byref(bp), first, count, out.ctypes.data)
+        if rc != 0:
+            raise NbosError(rc, "nbos_replay_billing")
+        return out
 
     def last_kernel_ms(self) -> float:
         ms = C.c_float()

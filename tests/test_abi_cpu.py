@@ -29,9 +29,10 @@ def test_exports_match_header(lib):
 
 
 def test_struct_sizes(lib):
-    assert lib.nbos_sizeof_stats() == replay.STATS_DTYPE.itemsize == 264
+    assert lib.nbos_sizeof_stats() == replay.STATS_DTYPE.itemsize == 272
     assert C.sizeof(replay.NbosConfig) == 17 * 4
     assert C.sizeof(replay.NbosInputs) == 8 * 8
+    assert C.sizeof(replay.NbosBillingParams) == 16 and replay.BILL_DTYPE.itemsize == 32
 
 
 def test_strerror(lib):

@@ -125,6 +125,64 @@ def test_named_workload_c4a_autoscaler_only(rp, oracle):
     assert min(auto) > 0 and st["scale_in_hosts"].min() > 0
 
 
+# ---- billing post-pass (Section 5.3.1) ---------------------------------------------------------------
+
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
+def test_billing_matches_oracle(rp, oracle, in_lds):
+    for seed, price, mk, sb in [(3, 10_000_000, 115, 125), (8, 1_000_000_000, 1000, 1000), (21, 1, 100, 0),
+                                (40, 32_770_000, 115, 125), (77, 0, 115, 125)]:
+        b = tg.random_case(seed, n_replays=5)
+        dev = rp.upload(b)
+        h = rp.Replay(b.config, dev, hosts_in_lds=in_lds)
+        h.run()
+        bills = h.billing(price, mk, sb)
+        part = h.billing(price, mk, sb, first=2, count=2)
+        h.close()
+        want = oracle.replay_batch(b)
+        for r in range(b.n_replays):
+            exp = oracle.billing(want[r], b.config["gpus_per_host"], price, mk, sb)
+            for k, v in exp.items():
+                assert int(bills[k][r]) == v, (seed, r, k)
+        assert (part == bills[2:4]).all()
+
+
+def test_billing_printed_example_gpu(rp):
+    # Section 5.3.1: $10 per 8-GPU host-hour, x1.15, standby 12.5 %: $5.75 for an hour on 4 GPUs,
+    # $1.4375 (printed $1.44) per standby replica-hour
+    HOUR = 3_600_000
+    t, d, sk = events_to_arrays([[0, 0, 0, 0], [0, 1, 0, HOUR], [2 * HOUR, 2, 0, 0]])
+    cfg = tg._base_config(hosts_initial=3, hosts_max=3, flags=0)
+    b = tg._pack(cfg, [(t, d, sk, np.asarray([4], np.uint8))], [0], [1000], "billing")
+    dev = rp.upload(b)
+    h = rp.Replay(b.config, dev)
+    h.run()
+    bill = h.billing(10_000_000)[0]
+    st = h.stats()[0]
+    h.close()
+    assert int(st["replica_ms"]) == 6 * HOUR
+    assert int(bill["usage_revenue"]) == 5_750_000
+    assert int(bill["standby_revenue"]) == 5 * 1_437_500
+    assert int(bill["provider_cost"]) == 60_000_000
+    assert int(bill["reservation_revenue"]) == 11_500_000
+
+
+def test_billing_rejects_bad_arguments(rp):
+    b = tg.random_case(1, n_replays=2)
+    dev = rp.upload(b)
+    h = rp.Replay(b.config, dev)
+    with pytest.raises(rp.NbosError) as e:
+        h.billing(10_000_000)                      # never run
+    assert e.value.code == rp.E_STATE
+    h.run()
+    for kw in (dict(price_micro_per_host_hour=-1), dict(price_micro_per_host_hour=10**9 + 1),
+               dict(price_micro_per_host_hour=1, markup_pct=1001), dict(price_micro_per_host_hour=1, standby_permille=-1),
+               dict(price_micro_per_host_hour=1, first=1, count=2)):
+        with pytest.raises(rp.NbosError) as e:
+            h.billing(**kw)
+        assert e.value.code == rp.E_ARG
+    h.close()
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
