@@ -516,6 +516,75 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
 }
 
+// ---- runs of retries that fail again ---------------------------------------------------------------
+// On a saturated cluster most timers are retries of queued cells (Section 3.2.3) that fail once more:
+// no replica's host can bind the GPUs, no migration target, no host to add. Such an attempt changes
+// nothing but the session's retry count and its place in the timer queue. This loop takes due
+// retries off the head of the sorted registers for as long as they are of that kind (same tests as
+// attempt(), same order), re-inserting each with one pass over the registers; the first timer that
+// needs anything else is left for the general path. t_limit = time of the next arrival (timers due
+// at or before it run first), tick_t = next auto-scaler period (a timer due at the same time runs
+// before it). Returns the time of the last retry handled, or -1.
+template <int NJ>
+__device__ __forceinline__ int32_t failing_retries(Ctx<NJ> &c, Regs &r, int32_t t_limit, int32_t tick_t) {
+  int32_t last = -1;
+  const int32_t due = t_limit < tick_t ? t_limit : tick_t;
+  const bool may_skip = !(c.p.flags & NBOS_F_AUTOSCALE) &&
+                        (c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT);
+  while (r.q_n > 0 && r.o_n == 0 && r.q_head_t <= due) {
+    const int32_t now = r.q_head_t;
+    const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
+    if ((key >> 16) != QK_RETRY) break;
+    const uint32_t s = key & 0xFFFFu;
+    wave_sync();
+    const int4 rec = c.m.sess[s];
+    const uint32_t hw = uni((uint32_t)rec.x), fl = uni((uint32_t)rec.z);
+    const int32_t t_submit = uni(rec.y);
+    int retries = (int)((fl >> 8) & 15u);
+    if (retries >= c.p.max_retries) break;                     // the abort is the general path's
+    const int g = (int)((fl >> 3) & 7u) + 1;
+    if (now >= lane_get(c.fu, g - 1)) {
+      const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+      const int C = committed(c, now);
+      const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);
+      if (idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2))) break;          // the election succeeds
+      if (idle_ok == 0) {
+        const int32_t bound = earliest_idle(c, g);
+        if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
+      } else if (c.p.flags & NBOS_F_MIGRATE) {
+        const int S = (int)(c.hs & 0xFFFFu);
+        if (idle_ok & wballot(S <= cap_room(c, g))) break;                        // a migration target
+      }
+    }
+    if (c.p.flags & NBOS_F_SCALE_OUT) {
+      wave_sync();
+      if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) break;                            // a host can be added
+    }
+    // it fails again: bump the retry count (skipping retries that are bound to fail as well) ...
+    retries++;
+    if (may_skip) {
+      const int32_t bound = lane_get(c.fu, g - 1);
+      while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
+    }
+    const uint32_t nfl = (fl & ~(15u << 8)) | ((uint32_t)retries << 8);
+    if (c.lane == 0) c.m.sess[s].z = (int)nfl;
+    r.dirty |= wballot(c.vsid == s);
+    // ... and move the entry from lane 0 to its new place: entries before it shift down one lane
+    const int32_t t_new = t_submit + retries * c.p.retry_iv;
+    const bool before = c.lane >= 1 && c.lane < r.q_n && (c.qt < t_new || (c.qt == t_new && c.qk < key));
+    const int pos = __builtin_popcountll(wballot(before));
+    const int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);          // wave_shl:1
+    const int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
+    const uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
+    const int32_t d_own = lane_get(c.qd, 0);
+    if (c.lane < pos) { c.qt = st; c.qd = sd; c.qk = sk; }
+    if (c.lane == pos) { c.qt = t_new; c.qd = d_own; c.qk = key; }
+    r.q_head_t = lane_get(c.qt, 0);
+    last = now;
+  }
+  return last;
+}
+
 // ---- auto-scaler period (Section 3.4.2) -----------------------------------------------------------
 // release the highest-numbered ready host without replicas
 template <int NJ>
@@ -725,6 +794,14 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
         }
       } else {
         // ---- a timer may be due (S2); always taken while draining ----
+        {
+          const int32_t last = failing_retries(c, r, t, tick_t);
+          if (last >= 0) {
+            r.t_end = r.t_end > last ? r.t_end : last;
+            due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+            if (t < due_t) continue;
+          }
+        }
         bool fire_q = r.q_n > 0, fire_t = ticking;
         if (final) {
           if (fire_t) fire_t = fire_q ? tick_t < r.q_head_t : tick_t < r.lazy_max;
