@@ -58,7 +58,12 @@ struct Regs {
   uint64_t dirty;                        // lanes of the current tile whose prefetched record is stale
 };
 
-template <int NJ>
+// F: the policy flags when they are known at compile time (the common sets get an instance of their
+// own, which drops the code of everything that is switched off), or kRuntimeFlags.
+constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
+constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
+
+template <int NJ, uint32_t F>
 struct Ctx {
   const KParams &p;
   Lds m;
@@ -74,6 +79,7 @@ struct Ctx {
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
   int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
+  __device__ __forceinline__ uint32_t flags() const { return F == kRuntimeFlags ? p.flags : F; }
 };
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
@@ -89,10 +95,10 @@ __device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
 // Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
 // replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
 // (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
-template <int NJ>
-__device__ __forceinline__ int32_t cap_room(const Ctx<NJ> &c, int g) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int32_t cap_room(const Ctx<NJ, F> &c, int g) {
   int32_t lim = c.slim;
-  if (c.p.flags & NBOS_F_DYNAMIC_SR) {
+  if (c.flags() & NBOS_F_DYNAMIC_SR) {
     wave_sync();
     const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
     if (n_on > 0) {
@@ -103,8 +109,8 @@ __device__ __forceinline__ int32_t cap_room(const Ctx<NJ> &c, int g) {
   return lim - g;
 }
 
-template <int NJ>
-__device__ __forceinline__ void decide(Ctx<NJ> &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void decide(Ctx<NJ, F> &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
                                        uint32_t slot, uint32_t host) {
   uint64_t code = (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) |
                   ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
@@ -116,13 +122,13 @@ __device__ __forceinline__ void decide(Ctx<NJ> &c, Regs &r, int32_t now, uint32_
 }
 
 // write a session record; lanes of the current tile that prefetched it go stale
-template <int NJ>
-__device__ __forceinline__ void sess_write(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void sess_write(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
   if (c.lane == 0) c.m.sess[s] = make_int4((int)hw, tm, (int)fl, 0);
   r.dirty |= wballot(c.vsid == s);
 }
-template <int NJ>
-__device__ __forceinline__ void sess_write_flag(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t fl) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void sess_write_flag(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t fl) {
   if (c.lane == 0) c.m.sess[s].z = (int)fl;
   r.dirty |= wballot(c.vsid == s);
 }
@@ -131,8 +137,8 @@ __device__ __forceinline__ void sess_write_flag(Ctx<NJ> &c, Regs &r, uint32_t s,
 // Such a session carries SF_OVF. Its timer is implied by its record: a queued session retries at
 // submit time + retries * interval (duration in w), a placed session that is ending ends at its
 // busy-until time. The earliest of them is tracked; finding the next one scans the session table.
-template <int NJ>
-__device__ __forceinline__ void ovf_rescan(Ctx<NJ> &c, Regs &r) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void ovf_rescan(Ctx<NJ, F> &c, Regs &r) {
   wave_sync();
   uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
   for (int s = c.lane; s < c.n_sess; s += WAVE) {
@@ -150,8 +156,8 @@ __device__ __forceinline__ void ovf_rescan(Ctx<NJ> &c, Regs &r) {
   r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
 }
 
-template <int NJ>
-__device__ __forceinline__ void ovf_push(Ctx<NJ> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void ovf_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
   const uint32_t s = k & 0xFFFFu;
   if (c.lane == 0) { atomicOr((unsigned int *)&c.m.sess[s].z, SF_OVF); c.m.sess[s].w = d; }
   r.dirty |= wballot(c.vsid == s);
@@ -162,8 +168,8 @@ __device__ __forceinline__ void ovf_push(Ctx<NJ> &c, Regs &r, int32_t t, uint32_
 // ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
 // Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
 // registers are empty only if the overflow array is.
-template <int NJ>
-__device__ __forceinline__ void timer_push(Ctx<NJ> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void timer_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
   uint32_t k = (kind << 16) | id;
   if (r.q_n == WAVE) {
     int32_t mt = lane_get(c.qt, WAVE - 1);
@@ -191,8 +197,8 @@ __device__ __forceinline__ void timer_push(Ctx<NJ> &c, Regs &r, int32_t t, uint3
 }
 
 // remove the earliest timer (lane 0); refill from the overflow array when the registers run empty
-template <int NJ>
-__device__ __forceinline__ void timer_pop(Ctx<NJ> &c, Regs &r) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void timer_pop(Ctx<NJ, F> &c, Regs &r) {
   c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                // wave_shl:1
   c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
   c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
@@ -212,8 +218,8 @@ __device__ __forceinline__ void timer_pop(Ctx<NJ> &c, Regs &r) {
 
 // ---- hosts ----------------------------------------------------------------------------------------
 // committed GPUs of host = lane at time `now`: byte (lane & 7) of the ballot of register (lane >> 3)
-template <int NJ>
-__device__ __forceinline__ int committed(const Ctx<NJ> &c, int32_t now) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int committed(const Ctx<NJ, F> &c, int32_t now) {
   const int sh = 8 * (c.lane & 7), grp = c.lane >> 3;
   uint32_t bits = 0;
 #pragma unroll
@@ -226,8 +232,8 @@ __device__ __forceinline__ int committed(const Ctx<NJ> &c, int32_t now) {
 }
 
 // bind g free GPUs of host h until `finish`
-template <int NJ>
-__device__ __forceinline__ void bind_gpus(Ctx<NJ> &c, int h, int g, int32_t now, int32_t finish) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void bind_gpus(Ctx<NJ, F> &c, int h, int g, int32_t now, int32_t finish) {
   const int j = h >> 3, hl = h & 7;
   const bool mine = (c.lane >> 3) == hl && (c.lane & 7) < c.p.G;
 #pragma unroll
@@ -240,8 +246,8 @@ __device__ __forceinline__ void bind_gpus(Ctx<NJ> &c, int h, int g, int32_t now,
   }
 }
 
-template <int NJ>
-__device__ __forceinline__ int boot_host(Ctx<NJ> &c, Regs &r, int32_t now, uint32_t hs_new) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int boot_host(Ctx<NJ, F> &c, Regs &r, int32_t now, uint32_t hs_new) {
   uint64_t off = wballot(c.lane < c.p.Hmax && c.hr == NEVER);
   int h = (int)__builtin_ctzll(off);                 // the caller has checked that one exists
   int32_t ra = now + c.p.boot;
@@ -260,8 +266,8 @@ __device__ __forceinline__ int boot_host(Ctx<NJ> &c, Regs &r, int32_t now, uint3
 // (as long as no host is added). Each lane counts, inside its host's group of 8 lanes, the GPUs that
 // are free no later than its own GPU (DPP quad rotations of the value and of its half-row mirror
 // reach all 8 lanes of the group).
-template <int NJ>
-__device__ __forceinline__ int32_t earliest_idle(const Ctx<NJ> &c, int g) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int32_t earliest_idle(const Ctx<NJ, F> &c, int g) {
   const bool used = (c.lane & 7) < c.p.G;
   int32_t best = NEVER;
 #pragma unroll
@@ -285,8 +291,8 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx<NJ> &c, int g) {
 }
 
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
-template <int NJ>
-__device__ __forceinline__ void session_start(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void session_start(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
   if ((fl & 7u) != SS_UNPLACED) return;
   const int g = (int)((fl >> 3) & 7u) + 1;
   const int C = committed(c, now);
@@ -311,7 +317,7 @@ __device__ __forceinline__ void session_start(Ctx<NJ> &c, Regs &r, uint32_t s, u
   if (missing > 0) {
     wave_sync();
     int n_on = (int)uni(c.m.c32[CS_NON]);
-    if (!((c.p.flags & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
+    if (!((c.flags() & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
       sess_write_flag(c, r, s, (fl & ~7u) | SS_REJECTED);
       c32_add(c.m, c.lane, CS_REJECTED, 1u);
       decide(c, r, now, NBOS_D_REJECT, s, 0, 0);
@@ -347,8 +353,8 @@ __device__ __forceinline__ void session_start(Ctx<NJ> &c, Regs &r, uint32_t s, u
 }
 
 // the replicas of session s give their subscriptions back at time `now`
-template <int NJ>
-__device__ __forceinline__ void end_session(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void end_session(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
   const int g = (int)((fl >> 3) & 7u) + 1;
   const uint32_t sub = (uint32_t)g | (1u << 16);
   const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
@@ -361,8 +367,8 @@ __device__ __forceinline__ void end_session(Ctx<NJ> &c, Regs &r, uint32_t s, uin
 }
 
 // ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
-template <int NJ>
-__device__ __forceinline__ void start_cell(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,
                                            uint32_t outcome) {
   const int g = (int)((fl >> 3) & 7u) + 1;
@@ -400,8 +406,8 @@ __device__ __forceinline__ void start_cell(Ctx<NJ> &c, Regs &r, uint32_t s, uint
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
-template <int NJ>
-__device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                         int32_t t_submit, int32_t dur) {
   const int g = (int)((fl >> 3) & 7u) + 1;
   const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
@@ -443,9 +449,9 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
   // ready host (ties: lowest host); replicas on booting hosts only if all three are.
   const int S = (int)(c.hs & 0xFFFFu);
   uint64_t target = 0;
-  if ((c.p.flags & NBOS_F_MIGRATE) && idle_ok != 0) target = idle_ok & wballot(S <= cap_room(c, g));
+  if ((c.flags() & NBOS_F_MIGRATE) && idle_ok != 0) target = idle_ok & wballot(S <= cap_room(c, g));
   bool grow = false;
-  if (target == 0 && (c.p.flags & NBOS_F_SCALE_OUT)) {
+  if (target == 0 && (c.flags() & NBOS_F_SCALE_OUT)) {
     wave_sync();
     grow = (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
   }
@@ -493,8 +499,8 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
     // A retry that is bound to fail only bumps the retry count: skip straight to the first retry
     // that could succeed (or to the last one, which aborts). Valid while no host can be added:
     // not with the periodic auto-scaler, and not when hosts can be both released and provisioned.
-    if (!(c.p.flags & NBOS_F_AUTOSCALE) &&
-        (c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
+    if (!(c.flags() & NBOS_F_AUTOSCALE) &&
+        (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) {
       const int32_t bound = lane_get(c.fu, g - 1);
       while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
     }
@@ -525,12 +531,12 @@ __device__ __forceinline__ void attempt(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_
 // needs anything else is left for the general path. t_limit = time of the next arrival (timers due
 // at or before it run first), tick_t = next auto-scaler period (a timer due at the same time runs
 // before it). Returns the time of the last retry handled, or -1.
-template <int NJ>
-__device__ __forceinline__ int32_t failing_retries(Ctx<NJ> &c, Regs &r, int32_t t_limit, int32_t tick_t) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32_t t_limit, int32_t tick_t) {
   int32_t last = -1;
   const int32_t due = t_limit < tick_t ? t_limit : tick_t;
-  const bool may_skip = !(c.p.flags & NBOS_F_AUTOSCALE) &&
-                        (c.p.flags & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT);
+  const bool may_skip = !(c.flags() & NBOS_F_AUTOSCALE) &&
+                        (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT);
   while (r.q_n > 0 && r.o_n == 0 && r.q_head_t <= due) {
     const int32_t now = r.q_head_t;
     const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
@@ -551,12 +557,12 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ> &c, Regs &r, int32_t 
       if (idle_ok == 0) {
         const int32_t bound = earliest_idle(c, g);
         if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
-      } else if (c.p.flags & NBOS_F_MIGRATE) {
+      } else if (c.flags() & NBOS_F_MIGRATE) {
         const int S = (int)(c.hs & 0xFFFFu);
         if (idle_ok & wballot(S <= cap_room(c, g))) break;                        // a migration target
       }
     }
-    if (c.p.flags & NBOS_F_SCALE_OUT) {
+    if (c.flags() & NBOS_F_SCALE_OUT) {
       wave_sync();
       if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) break;                            // a host can be added
     }
@@ -587,8 +593,8 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ> &c, Regs &r, int32_t 
 
 // ---- auto-scaler period (Section 3.4.2) -----------------------------------------------------------
 // release the highest-numbered ready host without replicas
-template <int NJ>
-__device__ __forceinline__ void release_host(Ctx<NJ> &c, Regs &r, int32_t now) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void release_host(Ctx<NJ, F> &c, Regs &r, int32_t now) {
   const uint64_t e = wballot(c.hr <= now && (c.hs >> 16) == 0);
   const int victim = 63 - (int)__builtin_clzll(e);
   if (c.lane == victim) c.hr = NEVER;
@@ -598,12 +604,12 @@ __device__ __forceinline__ void release_host(Ctx<NJ> &c, Regs &r, int32_t now) {
   decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
 }
 
-template <int NJ>
-__device__ __forceinline__ void tick(Ctx<NJ> &c, Regs &r, int32_t now) {
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void tick(Ctx<NJ, F> &c, Regs &r, int32_t now) {
   int A = __builtin_popcountll(wballot(c.hr <= now));
   int Z = __builtin_popcountll(wballot(c.hr <= now && (c.hs >> 16) == 0));
   int released = 0;
-  if (c.p.flags & NBOS_F_AUTOSCALE) {
+  if (c.flags() & NBOS_F_AUTOSCALE) {
     // expected capacity f * sum C in whole hosts plus the scaling buffer; hosts being provisioned
     // count as capacity
     uint32_t sum_c = 0;
@@ -620,7 +626,7 @@ __device__ __forceinline__ void tick(Ctx<NJ> &c, Regs &r, int32_t now) {
       decide(c, r, now, NBOS_D_SCALE_AUTO, 0, 0, (uint32_t)h);
     }
     if (n_on != before) c32_max(c.m, c.lane, CS_PEAK, (uint32_t)n_on);
-    if (c.p.flags & NBOS_F_SCALE_IN) {
+    if (c.flags() & NBOS_F_SCALE_IN) {
       while (n_on > want && Z > 0 && A > c.p.min_hosts && released < 2) {
         release_host(c, r, now);
         n_on--; A--; Z--; released++;
@@ -635,8 +641,8 @@ __device__ __forceinline__ void tick(Ctx<NJ> &c, Regs &r, int32_t now) {
   }
 }
 
-template <int NJ>
-__device__ __forceinline__ void on_session_end(Ctx<NJ> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl,
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void on_session_end(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl,
                                                int32_t now) {
   const uint32_t st = fl & 7u;
   if ((st != SS_PLACED && st != SS_QUEUED) || (fl & SF_ENDING)) return;
@@ -651,7 +657,7 @@ __device__ __forceinline__ void on_session_end(Ctx<NJ> &c, Regs &r, uint32_t s, 
   }
 }
 
-template <int NJ>
+template <int NJ, uint32_t F>
 __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;
@@ -681,7 +687,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   __syncthreads();
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
-  Ctx<NJ> c{p, m, lane, n_sess, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+  Ctx<NJ, F> c{p, m, lane, n_sess, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
 #pragma unroll
   for (int j = 0; j < NJ; j++) c.fin[j] = 0;
   c.hr = lane < p.H0 ? 0 : NEVER;
@@ -695,7 +701,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   r.q_head_t = NEVER;
   r.o_min_t = NEVER;
 
-  const bool ticking = (p.flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
+  const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   int32_t tick_t = ticking ? p.scale_iv : NEVER;
   int32_t due_t = tick_t;                   // earliest queued timer or auto-scaler period
 

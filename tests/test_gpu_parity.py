@@ -183,6 +183,27 @@ def test_billing_rejects_bad_arguments(rp):
     h.close()
 
 
+@pytest.mark.parametrize("generic", ["0", "1"])
+def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, generic):
+    # flag sets 0, MIGRATE and MIGRATE|SCALE_OUT have kernels of their own for small batches; large
+    # batches run the generic kernel. Both must give the oracle's results on the same cases.
+    monkeypatch.setenv("NBOS_REPLAY_GENERIC", generic)
+    done = set()
+    for seed in range(200):
+        b = tg.random_case(seed, n_replays=3)
+        f = b.config["flags"]
+        if f not in (0, 1, 3) or b.config["hosts_max"] > 64 or (f, (b.config["hosts_max"] + 7) // 8) in done:
+            continue
+        done.add((f, (b.config["hosts_max"] + 7) // 8))
+        st, logs = gpu_run(rp, b, log=True)
+        assert_same(rp, oracle, b, st, logs)
+    assert len(done) >= 6
+    for name, n in (("c2", 3), ("c5", 8)):
+        b = tg.workload(name, n_replays=n)
+        st, _ = gpu_run(rp, b)
+        assert_same(rp, oracle, b, st)
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
