@@ -72,6 +72,12 @@ struct Regs {
   uint64_t dirty;
 };
 
+// F: the policy flags when they are known at compile time (an instance of its own drops the code of
+// everything that is switched off), or kRuntimeFlags.
+constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
+constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
+
+template <uint32_t F>
 struct Ctx {
   const KParams &p;
   Lds m;
@@ -82,6 +88,7 @@ struct Ctx {
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
   int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
+  __device__ __forceinline__ uint32_t flags() const { return F == kRuntimeFlags ? p.flags : F; }
 };
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
@@ -97,9 +104,10 @@ __device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
 // Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
 // replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
 // (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
-__device__ __forceinline__ int32_t cap_room(const Ctx &c, int g) {
+template <uint32_t F>
+__device__ __forceinline__ int32_t cap_room(const Ctx<F> &c, int g) {
   int32_t lim = c.slim;
-  if (c.p.flags & NBOS_F_DYNAMIC_SR) {
+  if (c.flags() & NBOS_F_DYNAMIC_SR) {
     wave_sync();
     const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
     if (n_on > 0) {
@@ -116,7 +124,8 @@ __device__ __forceinline__ uint64_t decision_code(int32_t now, uint32_t outcome,
          ((uint64_t)(uint32_t)now << 32);
 }
 
-__device__ __forceinline__ void decide(Ctx &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
+template <uint32_t F>
+__device__ __forceinline__ void decide(Ctx<F> &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
                                        uint32_t slot, uint32_t host) {
   const uint64_t code = decision_code(now, outcome, s, slot, host);
   r.digest = r.digest * 0x100000001B3ULL + code;
@@ -126,17 +135,20 @@ __device__ __forceinline__ void decide(Ctx &c, Regs &r, int32_t now, uint32_t ou
   r.n_dec++;
 }
 
-__device__ __forceinline__ void sess_write(Ctx &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
+template <uint32_t F>
+__device__ __forceinline__ void sess_write(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
   if (c.lane == 0) { c.m.sess[s].x = (int)hw; c.m.sess[s].y = tm; c.m.sess[s].z = (int)fl; }
   r.dirty |= wballot(c.vsid == s);
 }
-__device__ __forceinline__ void sess_write_flag(Ctx &c, Regs &r, uint32_t s, uint32_t fl) {
+template <uint32_t F>
+__device__ __forceinline__ void sess_write_flag(Ctx<F> &c, Regs &r, uint32_t s, uint32_t fl) {
   if (c.lane == 0) c.m.sess[s].z = (int)fl;
   r.dirty |= wballot(c.vsid == s);
 }
 
 // ---- timers: overflow array in LDS (unsorted) ---------------------------------------------------
-__device__ __forceinline__ void ovf_rescan(Ctx &c, Regs &r) {
+template <uint32_t F>
+__device__ __forceinline__ void ovf_rescan(Ctx<F> &c, Regs &r) {
   wave_sync();
   uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
   int bi = 0;
@@ -153,7 +165,8 @@ __device__ __forceinline__ void ovf_rescan(Ctx &c, Regs &r) {
   r.o_min_k = ml;
 }
 
-__device__ __forceinline__ void ovf_push(Ctx &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
+template <uint32_t F>
+__device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
   if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
   if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
   if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) {
@@ -165,7 +178,8 @@ __device__ __forceinline__ void ovf_push(Ctx &c, Regs &r, int32_t t, uint32_t k,
 // ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
 // Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
 // registers are empty only if the overflow array is.
-__device__ __forceinline__ void timer_push(Ctx &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
+template <uint32_t F>
+__device__ __forceinline__ void timer_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
   uint32_t k = (kind << 16) | id;
   if (r.q_n == WAVE) {
     int32_t mt = lane_get(c.qt, WAVE - 1);
@@ -192,7 +206,8 @@ __device__ __forceinline__ void timer_push(Ctx &c, Regs &r, int32_t t, uint32_t 
   if (pos == 0) r.q_head_t = t;
 }
 
-__device__ __forceinline__ void timer_pop(Ctx &c, Regs &r) {
+template <uint32_t F>
+__device__ __forceinline__ void timer_pop(Ctx<F> &c, Regs &r) {
   c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                // wave_shl:1
   c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
   c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
@@ -215,13 +230,15 @@ __device__ __forceinline__ void timer_pop(Ctx &c, Regs &r) {
 
 // ---- host helpers -------------------------------------------------------------------------------
 // committed GPUs of host h at time `now` (GPUs beyond G keep fin = 0 and never count)
-__device__ __forceinline__ int committed(const Ctx &c, int h, int32_t now) {
+template <uint32_t F>
+__device__ __forceinline__ int committed(const Ctx<F> &c, int h, int32_t now) {
   const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
   return (a.x > now) + (a.y > now) + (a.z > now) + (a.w > now) + (b.x > now) + (b.y > now) + (b.z > now) + (b.w > now);
 }
 
 // bind g free GPUs of host h until `finish` (lanes 0..G-1 each look at one GPU)
-__device__ __forceinline__ void bind_gpus(Ctx &c, int h, int g, int32_t now, int32_t finish) {
+template <uint32_t F>
+__device__ __forceinline__ void bind_gpus(Ctx<F> &c, int h, int g, int32_t now, int32_t finish) {
   wave_sync();
   int32_t *row = (int32_t *)&c.m.fin[2 * h];
   const bool mine = c.lane < c.p.G;
@@ -232,7 +249,8 @@ __device__ __forceinline__ void bind_gpus(Ctx &c, int h, int g, int32_t now, int
 }
 
 // lowest host index that is off (the caller has checked that one exists)
-__device__ __forceinline__ int find_off_host(const Ctx &c) {
+template <uint32_t F>
+__device__ __forceinline__ int find_off_host(const Ctx<F> &c) {
   wave_sync();
   for (int base = 0; base < c.p.HP; base += WAVE) {
     const int h = base + c.lane;
@@ -242,7 +260,8 @@ __device__ __forceinline__ int find_off_host(const Ctx &c) {
   return 0;
 }
 
-__device__ __forceinline__ int boot_host(Ctx &c, Regs &r, int32_t now, uint32_t hs_new) {
+template <uint32_t F>
+__device__ __forceinline__ int boot_host(Ctx<F> &c, Regs &r, int32_t now, uint32_t hs_new) {
   const int h = find_off_host(c);
   const int32_t ra = now + c.p.boot;
   if (c.lane == 0) { c.m.ready_at[h] = ra; c.m.hsn[h] = hs_new; }
@@ -258,7 +277,8 @@ __device__ __forceinline__ int boot_host(Ctx &c, Regs &r, int32_t now, uint32_t 
 // Best host for one more replica with request g: ready, under the cap (S <= room), optionally with g
 // idle GPUs now; smallest (committed, subscribed, index). Hosts ex0 / ex1 are skipped. Returns the packed key
 // (host in the low 10 bits) or 0xFFFFFFFF. any_idle: some ready host has g idle GPUs, cap aside.
-__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, int32_t room, bool need_idle,
+template <uint32_t F>
+__device__ __forceinline__ uint32_t best_host(const Ctx<F> &c, int32_t now, int g, int32_t room, bool need_idle,
                                               int ex0, int ex1, bool &any_idle) {
   wave_sync();
   uint32_t best = 0xFFFFFFFFu;
@@ -282,7 +302,8 @@ __device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t now, int g, 
 }
 
 // least subscribed-GPU count among the hosts that are on (ready or being provisioned)
-__device__ __forceinline__ int32_t min_subscription(const Ctx &c) {
+template <uint32_t F>
+__device__ __forceinline__ int32_t min_subscription(const Ctx<F> &c) {
   wave_sync();
   uint32_t best = 0xFFFFu;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
@@ -302,7 +323,8 @@ __device__ __forceinline__ void order2(int32_t &a, int32_t &b) {
 // only push it back, so no election or migration for a request of g GPUs can succeed before it, as
 // long as no host is added (boot_host lowers the stored bound). One lane sorts one host's row with
 // the 19-comparator network for 8 inputs.
-__device__ __forceinline__ int32_t earliest_idle(const Ctx &c, int g) {
+template <uint32_t F>
+__device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g) {
   wave_sync();
   const int G = c.p.G;
   int32_t best = NEVER;
@@ -325,7 +347,8 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx &c, int g) {
 }
 
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
-__device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
+template <uint32_t F>
+__device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
   if ((fl & 7u) != SS_UNPLACED) return;
   const int g = (int)((fl >> 3) & 7u) + 1;
   // one pass computes every host's key (strided over the lanes), three minima pick the hosts
@@ -361,7 +384,7 @@ __device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint3
   if (missing > 0) {
     wave_sync();
     const int n_on = (int)uni(c.m.c32[CS_NON]);
-    if (!((c.p.flags & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
+    if (!((c.flags() & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
       sess_write_flag(c, r, s, (fl & ~7u) | SS_REJECTED);
       c32_add(c.m, c.lane, CS_REJECTED, 1u);
       decide(c, r, now, NBOS_D_REJECT, s, 0, 0);
@@ -398,7 +421,8 @@ __device__ __forceinline__ void session_start(Ctx &c, Regs &r, uint32_t s, uint3
 }
 
 // the replicas of session s give their subscriptions back at time `now`
-__device__ __forceinline__ void end_session(Ctx &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
+template <uint32_t F>
+__device__ __forceinline__ void end_session(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
   const int g = (int)((fl >> 3) & 7u) + 1;
   const uint32_t sub = (uint32_t)g | (1u << 16);
   if (c.lane < 3) {
@@ -414,7 +438,8 @@ __device__ __forceinline__ void end_session(Ctx &c, Regs &r, uint32_t s, uint32_
 }
 
 // ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
-__device__ __forceinline__ void start_cell(Ctx &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
+template <uint32_t F>
+__device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,
                                            uint32_t outcome) {
   const int g = (int)((fl >> 3) & 7u) + 1;
@@ -452,7 +477,8 @@ __device__ __forceinline__ void start_cell(Ctx &c, Regs &r, uint32_t s, uint32_t
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
-__device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
+template <uint32_t F>
+__device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                         int32_t t_submit, int32_t dur) {
   wave_sync();
   const int G = c.p.G;
@@ -491,7 +517,7 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
   }
   // (b), (c): a target exists? Only then is the replica to move worked out.
   uint32_t tkey = 0xFFFFFFFFu;
-  if (!hopeless && (c.p.flags & NBOS_F_MIGRATE)) {
+  if (!hopeless && (c.flags() & NBOS_F_MIGRATE)) {
     // the cap alone may rule every host out: S_h + g <= limit fails even for the least subscribed
     if (r.min_s < 0) r.min_s = min_subscription(c);
     const int32_t room = cap_room(c, g);
@@ -507,7 +533,7 @@ __device__ __forceinline__ void attempt(Ctx &c, Regs &r, uint32_t s, uint32_t hw
     }
   }
   bool grow = false;
-  if (tkey == 0xFFFFFFFFu && (c.p.flags & NBOS_F_SCALE_OUT)) {
+  if (tkey == 0xFFFFFFFFu && (c.flags() & NBOS_F_SCALE_OUT)) {
     wave_sync();
     grow = (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
   }
@@ -579,7 +605,8 @@ __device__ __forceinline__ uint64_t wave_sum(uint32_t v) {
 
 // ---- auto-scaler period (Section 3.4.2) -----------------------------------------------------------
 // release the highest-numbered ready host without replicas (the caller has checked that one exists)
-__device__ __forceinline__ void release_host(Ctx &c, Regs &r, int32_t now) {
+template <uint32_t F>
+__device__ __forceinline__ void release_host(Ctx<F> &c, Regs &r, int32_t now) {
   int victim = -1;
   wave_sync();
   for (int base = c.p.HP - WAVE; base >= 0 && victim < 0; base -= WAVE) {
@@ -595,9 +622,10 @@ __device__ __forceinline__ void release_host(Ctx &c, Regs &r, int32_t now) {
   decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
 }
 
-__device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
+template <uint32_t F>
+__device__ __forceinline__ void tick(Ctx<F> &c, Regs &r, int32_t now) {
   wave_sync();
-  const bool autoscale = (c.p.flags & NBOS_F_AUTOSCALE) != 0;
+  const bool autoscale = (c.flags() & NBOS_F_AUTOSCALE) != 0;
   int A = 0, Z = 0;
   uint32_t busy = 0;                       // this lane's share of sum C
   for (int base = 0; base < c.p.HP; base += WAVE) {
@@ -622,7 +650,7 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
       decide(c, r, now, NBOS_D_SCALE_AUTO, 0, 0, (uint32_t)h);
     }
     if (n_on != before) c32_max(c.m, c.lane, CS_PEAK, (uint32_t)n_on);
-    if (c.p.flags & NBOS_F_SCALE_IN) {
+    if (c.flags() & NBOS_F_SCALE_IN) {
       while (n_on > want && Z > 0 && A > c.p.min_hosts && released < 2) {
         release_host(c, r, now);
         n_on--; A--; Z--; released++;
@@ -637,7 +665,8 @@ __device__ __forceinline__ void tick(Ctx &c, Regs &r, int32_t now) {
   }
 }
 
-__device__ __forceinline__ void on_session_end(Ctx &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl,
+template <uint32_t F>
+__device__ __forceinline__ void on_session_end(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl,
                                                int32_t now) {
   const uint32_t st = fl & 7u;
   if ((st != SS_PLACED && st != SS_QUEUED) || (fl & SF_ENDING)) return;
@@ -654,7 +683,8 @@ __device__ __forceinline__ void on_session_end(Ctx &c, Regs &r, uint32_t s, uint
 
 // ---- one event-parallel round over the lanes in `run` (see the file header) -----------------------
 // Returns the mask of lanes whose cells were started. rec = the lane's prefetched session record.
-__device__ __forceinline__ uint64_t batch_round(Ctx &c, Regs &r, uint64_t run, int32_t vt, int32_t vd, uint32_t sid,
+template <uint32_t F>
+__device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run, int32_t vt, int32_t vd, uint32_t sid,
                                                 const SessRec &rec) {
   wave_sync();
   const int G = c.p.G;
@@ -733,6 +763,7 @@ __device__ __forceinline__ uint64_t batch_round(Ctx &c, Regs &r, uint64_t run, i
   return done;
 }
 
+template <uint32_t F>
 __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;
@@ -776,7 +807,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   __syncthreads();
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
-  Ctx c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
+  Ctx<F> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
         NEVER, 0, 0xFFFFFFFFu, 0xFFFFFFFFu, 0};
   Regs r;
   memset(&r, 0, sizeof r);
@@ -785,7 +816,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   r.o_min_t = NEVER;
   r.min_s = -1;
 
-  const bool ticking = (p.flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
+  const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   const bool batching = p.batch != 0;
   // hash buckets (power of two <= HP) for spotting two events of one session in a tile
   const uint32_t dup_mask = (1u << (31 - __builtin_clz((uint32_t)p.HP))) - 1u;

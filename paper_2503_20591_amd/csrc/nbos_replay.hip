@@ -256,7 +256,16 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (fixed + 12 * 64 > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       if (fixed + q_cap * 12 > (size_t)maxlds) q_cap = ((size_t)maxlds - fixed) / 12;
       h->lds_bytes = fixed + q_cap * 12;
-      h->kernel = (const void *)ldsk::nbos_replay_lds_kernel;
+      // same idea as for the register kernel; its batches are small (the LDS footprint allows few
+      // workgroups per compute unit), so the instance compiled for the flag set is used whenever
+      // there is one
+      const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
+      const char *ng = getenv("NBOS_REPLAY_GENERIC");
+      constexpr uint32_t kAllScaling = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN;
+      if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
+      else if (policy == kAllScaling) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAllScaling>;
+      else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<NBOS_F_MIGRATE>;
+      else h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
     }
     HIP_TRY(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
 

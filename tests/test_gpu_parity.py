@@ -198,6 +198,15 @@ def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, gener
         st, logs = gpu_run(rp, b, log=True)
         assert_same(rp, oracle, b, st, logs)
     assert len(done) >= 6
+    # the any-size kernel has instances for MIGRATE and MIGRATE|SCALE_OUT|SCALE_IN
+    seen = set()
+    for seed in range(200):
+        b = tg.random_case(seed, n_replays=3)
+        if b.config["flags"] in (1, 7) and b.config["flags"] not in seen:
+            seen.add(b.config["flags"])
+            st, logs = gpu_run(rp, b, log=True, in_lds=True)
+            assert_same(rp, oracle, b, st, logs)
+    assert seen == {1, 7}
     for name, n in (("c2", 3), ("c5", 8)):
         b = tg.workload(name, n_replays=n)
         st, _ = gpu_run(rp, b)
