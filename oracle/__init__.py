@@ -18,7 +18,7 @@ _SRC = os.path.join(_DIR, "nbos_oracle.c")
 _LIB = os.path.join(_DIR, "libnbos_oracle.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR = 0x20, 0x40
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY = 0x20, 0x40, 0x80
 EV_START, EV_CELL, EV_END = 0, 1, 2
 (D_PLACE, D_PLACE_NEW, D_REJECT, D_START, D_MIGRATE, D_SCALE_CELL, D_ABORT, D_SCALE_IN,
  D_SCALE_AUTO) = range(1, 10)

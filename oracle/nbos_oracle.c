@@ -44,6 +44,8 @@
  *     ratio after taking the replica is at most the cluster-wide ratio after
  *     taking it, (S_h + g) / (G R) <= (sum S + g) / (n G R), n = hosts not off;
  *     i.e. the limit in force is the larger of the configured cap and that mean.
+ *   - sticky executor (ORC_F_STICKY): when the replica that executed the session's
+ *     previous cell can lead (host ready, enough idle GPUs) it does; else the rule above.
  */
 #include "nbos_oracle.h"
 #include <stdlib.h>
@@ -279,6 +281,11 @@ static void attempt(sim *m, int s) {
     const host_rec *y = &m->hosts[q->host[lead]];
     if (x->C < y->C || (x->C == y->C && q->host[i] < q->host[lead])) lead = i;
   }
+  /* variant: the replica that ran the previous cell keeps leading while its host can bind */
+  if ((m->p->flags & ORC_F_STICKY) && lead >= 0 && q->last_exec >= 0) {
+    const host_rec *x = &m->hosts[q->host[q->last_exec]];
+    if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;
+  }
   if (lead >= 0) {
     commit(m, q->host[lead], g);
     if (m->clock == q->t_submit) m->r.cells_immediate++;
@@ -478,7 +485,7 @@ static int validate(const orc_params *p, int64_t n_events, const int32_t *ev_tim
   if (p->max_retries < 0 || p->max_retries > 15) return ORC_E_ARG;
   if (p->cap_milli < 1 || p->cap_milli > 100000) return ORC_E_ARG;
   if (p->flags & ~(uint32_t)(ORC_F_MIGRATE | ORC_F_SCALE_OUT | ORC_F_SCALE_IN | ORC_F_AUTOSCALE |
-                            ORC_F_DYNAMIC_SR)) return ORC_E_ARG;
+                            ORC_F_DYNAMIC_SR | ORC_F_STICKY)) return ORC_E_ARG;
   if (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) {
     if (p->scale_interval_ms < 1 || p->min_hosts < 0) return ORC_E_ARG;
   }

@@ -17,7 +17,8 @@ enum { ORC_EV_START = 0, ORC_EV_CELL = 1, ORC_EV_END = 2 };
 enum {
   ORC_F_MIGRATE = 1, ORC_F_SCALE_OUT = 2, ORC_F_SCALE_IN = 4,
   ORC_F_AUTOSCALE = 0x20,   /* Section 3.4.2: periodic expected-capacity test f * sum C    */
-  ORC_F_DYNAMIC_SR = 0x40   /* Section 3.4.1: cluster-wide subscription ratio as the limit */
+  ORC_F_DYNAMIC_SR = 0x40,  /* Section 3.4.1: cluster-wide subscription ratio as the limit */
+  ORC_F_STICKY = 0x80       /* election variant: the previous executor leads again if it can */
 };
 
 /* decision outcomes written to the log / folded into the digest */

@@ -67,6 +67,10 @@ MUTANTS = [
     ("billing: 64-bit product", "(int64_t)((unsigned __int128)amount * (unsigned __int128)num / (unsigned __int128)den)", "(int64_t)((uint64_t)amount * (uint64_t)num / (uint64_t)den)"),
     ("replica integral counts GPUs", "m->r.replica_ms += m->n_replicas * dt;", "m->r.replica_ms += m->sum_S * dt;"),
     ("replicas of ended sessions keep counting", "m->sum_S -= g; m->n_replicas--; }", "m->sum_S -= g; }"),
+    ("sticky executor leads although its host is full", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", "if (x->state == H_READY) lead = q->last_exec;"),
+    ("sticky executor always on", "if ((m->p->flags & ORC_F_STICKY) && lead >= 0 && q->last_exec >= 0) {", "if (lead >= 0 && q->last_exec >= 0) {"),
+    ("sticky executor never applied", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", ";"),
+    ("sticky executor off by one GPU", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", "if (x->state == H_READY && m->G - x->C > g) lead = q->last_exec;"),
     ("dynamic limit always on", "if (m->p->flags & ORC_F_DYNAMIC_SR)\n    return", "if (1)\n    return"),
     ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
     ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
@@ -123,6 +127,7 @@ def run_pins(lib_path):
     checks += [lambda s=s: pins.test_autoscale_with_f_zero_is_the_plain_policy(o, s) for s in range(6)]
     checks += [lambda s=s: pins.test_dynamic_limit_is_vacuous_on_large_clusters(o, s) for s in range(8)]
     checks.append(lambda: pins.test_dynamic_limit_brute_force(o))
+    checks.append(lambda: pins.test_sticky_election_brute_force(o))
     checks += [lambda: pins.test_billing_printed_example(o), lambda: pins.test_billing_is_linear_and_exact_on_large_results(o)]
     checks += [lambda s=s: pins.test_replica_integral_random(o, s) for s in range(3)]
     for c in checks:

@@ -147,6 +147,48 @@ def test_election_brute_force(oracle):
         assert list(r["final"]["host_committed"]) == [0] * H   # drained at the end
 
 
+def test_sticky_election_brute_force(oracle):
+    # Variant of Section 3.2.2: a session's previous executor leads again whenever its host can bind
+    # the GPUs; otherwise the plain rule. Two rounds of long-enough cells on 3-6 hosts: track C per
+    # host from the log (first-round cells end before the second round, then some are re-run while
+    # second-round cells are still on) and re-derive every election.
+    rng = np.random.default_rng(23)
+    differs = 0
+    for trial in range(60):
+        H, G = int(rng.integers(3, 7)), 8
+        n = int(rng.integers(3, 10))
+        gp = rng.choice([1, 2, 4, 8], n)
+        cfg = dict(BASE, hosts_initial=H, hosts_max=H, gpus_per_host=G, flags=0x80)
+        ev = [[0, S, s, 0] for s in range(n)]
+        first = rng.permutation(n)
+        ev += [[10 + i, CELL, int(s), 1000] for i, s in enumerate(first)]          # all over by 2000
+        second = rng.permutation(n)
+        ev += [[5000 + i, CELL, int(s), 10_000_000] for i, s in enumerate(second)]
+        r = run(oracle, cfg, ev, gp, 100000, want_log=True, want_final=True)
+        hosts = r["final"]["sess_hosts"].reshape(n, 3)
+        starts = [oracle.decode(c) for c in r["log"] if oracle.decode(c)["outcome"] == oracle.D_START]
+        got = {}
+        for d in starts:
+            got.setdefault(d["session"], []).append((d["slot"], d["host"]))
+        last = {}
+        for rnd, order in enumerate((first, second)):
+            Ch = [0] * H
+            for s in order:
+                s, g = int(s), int(gp[s])
+                feas = [(Ch[hosts[s, i]], hosts[s, i], i) for i in range(3) if G - Ch[hosts[s, i]] >= g]
+                if not feas:
+                    continue
+                c, h, i = min(feas)
+                if s in last and any(f[2] == last[s] for f in feas):
+                    differs += i != last[s]
+                    i = last[s]; h = hosts[s, i]
+                assert got[s].pop(0) == (i, h), (trial, rnd, s)
+                last[s] = i
+                Ch[h] += g
+        assert all(not v for v in got.values())
+    assert differs > 10          # the variant did change elections
+
+
 # ---- closed forms ---------------------------------------------------------------------------------
 
 def test_no_contention_closed_form(oracle):
