@@ -95,6 +95,12 @@ typedef enum {
                                       hosts not off, i.e. the limit in force is the larger of the
                                       replay's cap and the cluster-wide ratio after placing.  */
 
+#define NBOS_F_STICKY_EXECUTOR 0x80u /* election variant (Section 3.2.2; Section 5.2.3 reports that
+                                      consecutive cells ran on the same replica 89.45 % of the
+                                      time): the replica that executed the session's previous
+                                      cell leads again whenever its host can bind the GPUs;
+                                      otherwise the usual rule decides                        */
+
 /* ---- event encoding ------------------------------------------------------ */
 #define NBOS_EV_START  0
 #define NBOS_EV_CELL   1

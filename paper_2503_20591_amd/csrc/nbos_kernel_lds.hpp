@@ -75,7 +75,8 @@ struct Regs {
 // F: the policy flags when they are known at compile time (an instance of its own drops the code of
 // everything that is switched off), or kRuntimeFlags.
 constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
-constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
+constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
+                                  NBOS_F_STICKY_EXECUTOR;
 
 template <uint32_t F>
 struct Ctx {
@@ -504,7 +505,13 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
     const uint32_t k0 = (ok0 && C0 + g <= G) ? (((uint32_t)C0 << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
     const uint32_t k1 = (ok1 && C1 + g <= G) ? (((uint32_t)C1 << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
     const uint32_t k2 = (ok2 && C2 + g <= G) ? (((uint32_t)C2 << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
-    const uint32_t kb = umin(k0, umin(k1, k2));
+    uint32_t kb = umin(k0, umin(k1, k2));
+    if (c.flags() & NBOS_F_STICKY_EXECUTOR) {
+      // variant: the replica that ran the previous cell leads again if its host can bind
+      const uint32_t last = hw >> 30;
+      const uint32_t kp = last == 1u ? k0 : (last == 2u ? k1 : (last == 3u ? k2 : 0xFFFFFFFFu));
+      if (kp != 0xFFFFFFFFu) kb = kp;
+    }
     if (kb != 0xFFFFFFFFu) {
       const int lead = (int)(kb & 3u), hl = (int)((kb >> 2) & 1023u);
       const bool fr = act && (c.lane >> 3) == lead && k < G && f <= now;
@@ -703,7 +710,12 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   const uint32_t k0 = (r0 <= vt && C0 + g <= G) ? (((uint32_t)C0 << 12) | (h0 << 2) | 0u) : 0xFFFFFFFFu;
   const uint32_t k1 = (r1 <= vt && C1 + g <= G) ? (((uint32_t)C1 << 12) | (h1 << 2) | 1u) : 0xFFFFFFFFu;
   const uint32_t k2 = (r2 <= vt && C2 + g <= G) ? (((uint32_t)C2 << 12) | (h2 << 2) | 2u) : 0xFFFFFFFFu;
-  const uint32_t kb = umin(k0, umin(k1, k2));
+  uint32_t kb = umin(k0, umin(k1, k2));
+  if (c.flags() & NBOS_F_STICKY_EXECUTOR) {
+    const uint32_t last = hw >> 30;
+    const uint32_t kp = last == 1u ? k0 : (last == 2u ? k1 : (last == 3u ? k2 : 0xFFFFFFFFu));
+    if (kp != 0xFFFFFFFFu) kb = kp;
+  }
   const bool won = in_run && kb != 0xFFFFFFFFu;
   const int lead = (int)(kb & 3u);
   const int ch = won ? (int)((kb >> 2) & 1023u) : 0;

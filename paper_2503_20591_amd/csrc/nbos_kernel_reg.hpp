@@ -61,7 +61,8 @@ struct Regs {
 // F: the policy flags when they are known at compile time (the common sets get an instance of their
 // own, which drops the code of everything that is switched off), or kRuntimeFlags.
 constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
-constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
+constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
+                                  NBOS_F_STICKY_EXECUTOR;
 
 template <int NJ, uint32_t F>
 struct Ctx {
@@ -431,7 +432,15 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
       cand &= cand - 1;
       if (cand != 0) best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
     }
-    const int hl = (int)(best & 63u);
+    int hl = (int)(best & 63u);
+    if (c.flags() & NBOS_F_STICKY_EXECUTOR) {
+      // variant: the replica that ran the previous cell leads again if its host can bind
+      const uint32_t last = hw >> 30;
+      if (last != 0) {
+        const int hp = (int)((hw >> (10 * (last - 1u))) & 1023u);
+        if ((idle_ok >> hp) & 1u) hl = hp;
+      }
+    }
     const int lead = (uint32_t)hl == h0 ? 0 : ((uint32_t)hl == h1 ? 1 : 2);
     bind_gpus(c, hl, g, now, now + dur);
     if (now == t_submit) r.c_imm++;

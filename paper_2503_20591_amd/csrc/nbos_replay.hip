@@ -173,7 +173,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
   if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS |
-                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR))
+                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR))
     return NBOS_E_ARG;
   if (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) {
     if (cfg->scale_interval_ms < 1 || cfg->min_hosts < 0) return NBOS_E_ARG;

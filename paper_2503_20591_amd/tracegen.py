@@ -21,7 +21,7 @@ import numpy as np
 
 EV_START, EV_CELL, EV_END = 0, 1, 2
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR = 0x20, 0x40
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR = 0x20, 0x40, 0x80
 
 MAX_DUR_MS = 86_400_000          # a cell or an idle gap is at most 24 h
 MAX_TIME_MS = 1_900_000_000      # arrivals are clipped here so finish times stay in int32
@@ -267,7 +267,8 @@ def workload(name: str, n_replays: int | None = None, workers: int = 1) -> Trace
 def random_case(seed: int, n_replays: int = 4, policy_flags: bool = False) -> TraceBatch:
     """A small batch with randomly drawn cluster shape, flags, delays and load, including END
     events, repeated START / END events, and replays that share a trace. ``policy_flags`` adds
-    the periodic auto-scaler and / or the dynamic subscription-ratio limit with low caps."""
+    the periodic auto-scaler, the dynamic subscription-ratio limit with low caps and / or the sticky-executor
+    election."""
     rng = np.random.Generator(np.random.Philox(key=0x5EED0000 + seed))
     G = int(rng.choice([1, 2, 4, 8, 8, 8]))
     h0 = int(rng.integers(1, 20)) if rng.random() < 0.8 else int(rng.integers(60, 140))
@@ -308,7 +309,8 @@ def random_case(seed: int, n_replays: int = 4, policy_flags: bool = False) -> Tr
         # the periodic auto-scaler and the dynamic limit, drawn from a stream of their own so that
         # the case is otherwise the same as without them
         r2 = np.random.Generator(np.random.Philox(key=0xA5CA1E00 + seed))
-        extra = int(r2.choice([F_AUTOSCALE, F_DYNAMIC_SR, F_AUTOSCALE | F_DYNAMIC_SR]))
+        extra = int(r2.choice([F_AUTOSCALE, F_DYNAMIC_SR, F_AUTOSCALE | F_DYNAMIC_SR, F_STICKY_EXECUTOR,
+                               F_STICKY_EXECUTOR | F_AUTOSCALE | F_DYNAMIC_SR]))
         cfg["flags"] |= extra
         if extra & F_AUTOSCALE:
             cfg["hosts_max"] = max(cfg["hosts_max"], h0 + int(r2.integers(0, 12)))
