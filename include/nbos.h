@@ -200,6 +200,9 @@ typedef struct {
  *   out       receives the handle.
  * Validates parameters on the host and the trace contents with a device kernel
  * (synchronises the stream once). Allocates only its own result buffers.
+ * Two environment variables are read here, for comparison runs only; they change which kernel
+ * runs, never a result: NBOS_REPLAY_BATCH=0 (no event-parallel rounds in the any-size kernel),
+ * NBOS_REPLAY_GENERIC=0|1 (the kernel instance compiled for the flag set / the generic one).
  * Errors: NBOS_E_ARG, NBOS_E_RANGE, NBOS_E_LIMIT (hosts/sessions/LDS footprint
  * beyond what one workgroup can hold), NBOS_E_HIP, NBOS_E_NOMEM. *out is NULL
  * on error.
