@@ -15,13 +15,14 @@ import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "nbos_oracle.c")
+_SRC_BATCH = os.path.join(_DIR, "nbos_oracle_batch.c")
 _LIB = os.path.join(_DIR, "libnbos_oracle.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY = 0x20, 0x40, 0x80
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY, F_BATCH = 0x20, 0x40, 0x80, 0x100
 EV_START, EV_CELL, EV_END = 0, 1, 2
 (D_PLACE, D_PLACE_NEW, D_REJECT, D_START, D_MIGRATE, D_SCALE_CELL, D_ABORT, D_SCALE_IN,
- D_SCALE_AUTO) = range(1, 10)
+ D_SCALE_AUTO, D_BATCH_START, D_BATCH_HOST) = range(1, 12)
 
 
 class _Params(C.Structure):
@@ -29,7 +30,7 @@ class _Params(C.Structure):
         ("flags", C.c_uint32)] + [(n, C.c_int32) for n in (
             "migration_delay_ms", "boot_delay_ms", "retry_interval_ms", "max_retries",
             "scale_interval_ms", "scale_in_idle_pct", "min_hosts", "cap_milli", "check",
-            "autoscale_f_milli", "scaling_buffer_hosts")]
+            "autoscale_f_milli", "scaling_buffer_hosts", "batch_start_delay_ms")]
 
 
 _U32 = ("n_decisions", "sessions_placed", "sessions_rejected", "cells_total", "cells_immediate",
@@ -67,9 +68,9 @@ def build(force: bool = False, extra_cflags: tuple[str, ...] = (), out: str | No
     """Compile the oracle with gcc. Returns the path of the shared object."""
     out = out or _LIB
     if force or not os.path.exists(out) or os.path.getmtime(out) < max(
-            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_DIR, "nbos_oracle.h"))):
+            os.path.getmtime(_SRC), os.path.getmtime(_SRC_BATCH), os.path.getmtime(os.path.join(_DIR, "nbos_oracle.h"))):
         cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", *extra_cflags,
-               "-o", out, _SRC]
+               "-o", out, _SRC, _SRC_BATCH]
         subprocess.run(cmd, check=True, cwd=_DIR)
     return out
 
@@ -83,6 +84,8 @@ def _load(path: str | None = None):
     lib.orc_replay.argtypes = [
         C.POINTER(_Params), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
         C.c_int32, C.c_void_p, C.POINTER(_Result), C.c_void_p, C.c_int64, C.POINTER(_Final)]
+    lib.orc_replay_batch.restype = C.c_int
+    lib.orc_replay_batch.argtypes = lib.orc_replay.argtypes[:-1]
     lib.orc_sizeof_result.restype = C.c_int
     lib.orc_billing.restype = None
     lib.orc_billing.argtypes = [C.POINTER(_Result), C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(_Bill)]
@@ -129,10 +132,15 @@ def replay(cfg: dict, ev_time, ev_dur, ev_sk, sess_gpus, cap_milli: int, *, chec
                         ("host_nrep", hm), ("sess_state", max(n_s, 1)), ("sess_hosts", max(3 * n_s, 1))):
             keep[name] = np.zeros(n, dtype=np.int32)
             setattr(fin, name, keep[name].ctypes.data_as(C.POINTER(C.c_int32)))
-    rc = lib.orc_replay(C.byref(p), n_ev, ev_time.ctypes.data, ev_dur.ctypes.data, ev_sk.ctypes.data,
-                        n_s, sess_gpus.ctypes.data, C.byref(res),
-                        log.ctypes.data if log is not None else None, log_cap,
-                        C.byref(fin) if fin is not None else None)
+    if p.flags & F_BATCH:        # the Batch baseline has a replay loop of its own (no final-state dump)
+        rc = lib.orc_replay_batch(C.byref(p), n_ev, ev_time.ctypes.data, ev_dur.ctypes.data, ev_sk.ctypes.data,
+                                  n_s, sess_gpus.ctypes.data, C.byref(res),
+                                  log.ctypes.data if log is not None else None, log_cap)
+    else:
+        rc = lib.orc_replay(C.byref(p), n_ev, ev_time.ctypes.data, ev_dur.ctypes.data, ev_sk.ctypes.data,
+                            n_s, sess_gpus.ctypes.data, C.byref(res),
+                            log.ctypes.data if log is not None else None, log_cap,
+                            C.byref(fin) if fin is not None else None)
     if rc != 0:
         raise ValueError(f"orc_replay failed with code {rc}", rc)
     out = {}

@@ -18,14 +18,17 @@ enum {
   ORC_F_MIGRATE = 1, ORC_F_SCALE_OUT = 2, ORC_F_SCALE_IN = 4,
   ORC_F_AUTOSCALE = 0x20,   /* Section 3.4.2: periodic expected-capacity test f * sum C    */
   ORC_F_DYNAMIC_SR = 0x40,  /* Section 3.4.1: cluster-wide subscription ratio as the limit */
-  ORC_F_STICKY = 0x80       /* election variant: the previous executor leads again if it can */
+  ORC_F_STICKY = 0x80,      /* election variant: the previous executor leads again if it can */
+  ORC_F_BATCH = 0x100       /* replay the Batch baseline of Section 5.1.3 (orc_replay_batch)  */
 };
 
 /* decision outcomes written to the log / folded into the digest */
 enum {
   ORC_D_PLACE = 1, ORC_D_PLACE_NEW = 2, ORC_D_REJECT = 3, ORC_D_START = 4,
   ORC_D_MIGRATE = 5, ORC_D_SCALE_CELL = 6, ORC_D_ABORT = 7, ORC_D_SCALE_IN = 8,
-  ORC_D_SCALE_AUTO = 9   /* host added by the periodic auto-scaler (session field 0) */
+  ORC_D_SCALE_AUTO = 9,  /* host added by the periodic auto-scaler (session field 0) */
+  ORC_D_BATCH_START = 10,/* Batch baseline: GPUs allocated to the session's job on host */
+  ORC_D_BATCH_HOST = 11  /* Batch baseline: host provisioned for the job at the queue's head */
 };
 
 /* error returns of orc_replay (0 = ok) */
@@ -46,6 +49,7 @@ typedef struct {
   int32_t check;                /* != 0: verify the invariants after every item */
   int32_t autoscale_f_milli;    /* f x 1000 of the expected capacity f * sum C (paper: 1050) */
   int32_t scaling_buffer_hosts; /* extra hosts kept on top of the expected capacity          */
+  int32_t batch_start_delay_ms; /* Batch baseline: container start per job (GPUs already held) */
 } orc_params;
 
 typedef struct {
@@ -87,6 +91,19 @@ int orc_replay(const orc_params *p,
                const int32_t *ev_sk,
                int32_t n_sessions, const uint8_t *sess_gpus,
                orc_result *out, uint64_t *log, int64_t log_cap, orc_final *fin);
+
+/*
+ * Replay the same trace under the Batch baseline (paper Section 5.1.3): every cell is a job of its
+ * own, first come first served, a container per job. Same argument meaning as orc_replay; of the
+ * flags only ORC_F_BATCH and ORC_F_SCALE_OUT are accepted. Fields of the result that only exist
+ * with replicas (placement, migration, subscription, Reservation) stay 0; cells_queued counts the
+ * jobs that waited for GPUs.
+ */
+int orc_replay_batch(const orc_params *p,
+                     int64_t n_events, const int32_t *ev_time, const int32_t *ev_dur,
+                     const int32_t *ev_sk,
+                     int32_t n_sessions, const uint8_t *sess_gpus,
+                     orc_result *out, uint64_t *log, int64_t log_cap);
 
 int orc_sizeof_result(void);
 

@@ -71,6 +71,17 @@ MUTANTS = [
     ("sticky executor always on", "if ((m->p->flags & ORC_F_STICKY) && lead >= 0 && q->last_exec >= 0) {", "if (lead >= 0 && q->last_exec >= 0) {"),
     ("sticky executor never applied", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", ";"),
     ("sticky executor off by one GPU", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", "if (x->state == H_READY && m->G - x->C > g) lead = q->last_exec;"),
+    ("batch: a later job overtakes the head of the queue", "      return;\n    }\n    /* allocate", "      m->head = (m->head + 1) % (m->n_sess + 1); m->fifo[(m->head + m->count - 1) % (m->n_sess + 1)] = s;\n      if (++j->asked > m->count + 1) return;\n      continue;\n    }\n    /* allocate", "nbos_oracle_batch.c"),
+    ("batch: container start not part of the delay", "int32_t delay = start - j->t_submit;", "int32_t delay = m->clock - j->t_submit;", "nbos_oracle_batch.c"),
+    ("batch: GPUs not held during the container start", "(int64_t)j->g * ((int64_t)finish - m->clock)", "(int64_t)j->g * j->dur", "nbos_oracle_batch.c"),
+    ("batch: fullest feasible server", "if (best < 0 || x->C < m->hosts[best].C) best = h;", "if (best < 0 || x->C > m->hosts[best].C) best = h;", "nbos_oracle_batch.c"),
+    ("batch: tie to the highest index", "if (best < 0 || x->C < m->hosts[best].C) best = h;", "if (best < 0 || x->C <= m->hosts[best].C) best = h;", "nbos_oracle_batch.c"),
+    ("batch: GPUs never given back", "m->hosts[j->host].C -= j->g;", "", "nbos_oracle_batch.c"),
+    ("batch: feasibility off by one", "m->G - x->C < j->g) continue;", "m->G - x->C <= j->g) continue;", "nbos_oracle_batch.c"),
+    ("batch: busy session's cell is queued anyway", "if (j->state != J_IDLE) { m.r.cells_dropped_busy++; continue; }", "if (j->state == J_QUEUED) { m.r.cells_dropped_busy++; continue; }", "nbos_oracle_batch.c"),
+    ("batch: every queued job asks for a server", "j->asked = 1;", "", "nbos_oracle_batch.c"),
+    ("batch: timers due at an arrival run after it", "m.heap[0].time <= t && !m.err) run_instant(&m);", "m.heap[0].time < t && !m.err) run_instant(&m);", "nbos_oracle_batch.c"),
+    ("batch: queue looked at between two timers of one instant", "    }\n  }\n  dispatch(m);\n}", "    }\n    dispatch(m);\n  }\n  dispatch(m);\n}", "nbos_oracle_batch.c"),
     ("dynamic limit always on", "if (m->p->flags & ORC_F_DYNAMIC_SR)\n    return", "if (1)\n    return"),
     ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
     ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
@@ -128,6 +139,8 @@ def run_pins(lib_path):
     checks += [lambda s=s: pins.test_dynamic_limit_is_vacuous_on_large_clusters(o, s) for s in range(8)]
     checks.append(lambda: pins.test_dynamic_limit_brute_force(o))
     checks.append(lambda: pins.test_sticky_election_brute_force(o))
+    checks += [lambda: pins.test_batch_single_server_is_the_textbook_fifo_queue(o), lambda: pins.test_batch_without_contention(o)]
+    checks += [lambda s=s: pins.test_batch_order_and_capacity_random(o, s) for s in range(6)]
     checks += [lambda: pins.test_billing_printed_example(o), lambda: pins.test_billing_is_linear_and_exact_on_large_results(o)]
     checks += [lambda s=s: pins.test_replica_integral_random(o, s) for s in range(3)]
     for c in checks:
@@ -150,26 +163,33 @@ def _pins_fail(lib_path):
     return rc != 0
 
 
+SOURCES = ("nbos_oracle.c", "nbos_oracle_batch.c")
+
+
 def _build(oracle, tmp_path, name, edit):
+    """Copy the oracle's sources to tmp_path, passing the text of each through edit(file, text)."""
     odir = os.path.dirname(oracle.__file__)
-    src = open(os.path.join(odir, "nbos_oracle.c")).read()
-    (tmp_path / "nbos_oracle.c").write_text(edit(src))
+    for f in SOURCES:
+        (tmp_path / f).write_text(edit(f, open(os.path.join(odir, f)).read()))
     (tmp_path / "nbos_oracle.h").write_text(open(os.path.join(odir, "nbos_oracle.h")).read())
     out = str(tmp_path / name)
-    subprocess.run(["gcc", "-std=c99", "-O1", "-w", "-fPIC", "-shared", "-o", out, "nbos_oracle.c"],
+    subprocess.run(["gcc", "-std=c99", "-O1", "-w", "-fPIC", "-shared", "-o", out, *SOURCES],
                    check=True, cwd=tmp_path)
     return out
 
 
 def test_unmutated_copy_passes(oracle, tmp_path):
-    assert not _pins_fail(_build(oracle, tmp_path, "clean.so", lambda s: s))
+    assert not _pins_fail(_build(oracle, tmp_path, "clean.so", lambda f, s: s))
 
 
 @pytest.mark.parametrize("idx", range(len(MUTANTS)), ids=[m[0] for m in MUTANTS])
 def test_pins_catch_mutant(oracle, tmp_path, idx):
-    name, old, new = MUTANTS[idx]
+    name, old, new = MUTANTS[idx][:3]
+    target = MUTANTS[idx][3] if len(MUTANTS[idx]) > 3 else SOURCES[0]
 
-    def edit(src):
+    def edit(f, src):
+        if f != target:
+            return src
         assert src.count(old) >= 1, f"mutation site gone: {name}"
         return src.replace(old, new, 1)
     assert _pins_fail(_build(oracle, tmp_path, f"mutant{idx}.so", edit)), f"no pin notices: {name}"

@@ -521,6 +521,106 @@ def test_replica_integral_random(oracle, seed):
         assert r["replica_ms"] == r["sub_gpu_ms"]
 
 
+# ---- Section 5.1.3, Batch baseline: first come, first served, a container per job -----------------
+
+BATCH = 0x100
+BCFG = dict(BASE, flags=BATCH, batch_start_delay_ms=0)
+
+
+def test_batch_single_server_is_the_textbook_fifo_queue(oracle):
+    # one host whose G GPUs every job needs: a single-server FIFO queue. Lindley's recursion:
+    # begin_k = max(arrival_k, end_{k-1}), end_k = begin_k + start delay + duration.
+    rng = np.random.default_rng(3)
+    for trial in range(30):
+        n = int(rng.integers(1, 60))
+        Dc = int(rng.choice([0, 7, 300]))
+        t = np.sort(rng.integers(0, 5000, n))
+        d = rng.integers(1, 400, n)
+        cfg = dict(BCFG, hosts_initial=1, hosts_max=1, gpus_per_host=8, batch_start_delay_ms=Dc)
+        ev = [[int(t[i]), CELL, i, int(d[i])] for i in range(n)]          # one session per job: no drops
+        r = run(oracle, cfg, ev, [8] * n, 1000, want_log=True)
+        end, sum_delay, sum_tct, begins = 0, 0, 0, []
+        for i in range(n):
+            begin = max(int(t[i]), end)
+            end = begin + Dc + int(d[i])
+            begins.append(begin)
+            sum_delay += begin + Dc - int(t[i])
+            sum_tct += end - int(t[i])
+        assert (r["sum_delay_ms"], r["sum_tct_ms"], r["t_end_ms"]) == (sum_delay, sum_tct, max(end, int(t[-1])))
+        got = [oracle.decode(c) for c in r["log"]]
+        assert [(d_["time"], d_["session"], d_["host"], d_["outcome"]) for d_ in got] == \
+               [(b, i, 0, oracle.D_BATCH_START) for i, b in enumerate(begins)]
+        assert r["cells_immediate"] == sum(1 for i in range(n) if begins[i] == int(t[i]))
+        assert r["gpu_ms_committed"] == 8 * (n * Dc + int(d.sum())) and r["gpu_ms_executed"] == 8 * int(d.sum())
+
+
+def test_batch_without_contention(oracle):
+    # more hosts than jobs at any time: every job starts at once, delay = the container start
+    n, Dc = 40, 125
+    cfg = dict(BCFG, hosts_initial=64, hosts_max=64, batch_start_delay_ms=Dc)
+    gp = [1, 2, 4, 8] * 10
+    ev = [[10 * i, CELL, i, 50_000] for i in range(n)]
+    r = run(oracle, cfg, ev, gp, 1000)
+    assert (r["cells_started"], r["cells_immediate"], r["cells_queued"]) == (n, n, 0)
+    assert r["sum_delay_ms"] == n * Dc and r["max_delay_ms"] == Dc
+    assert r["sum_tct_ms"] == n * (Dc + 50_000)
+    assert r["gpu_ms_committed"] == sum(gp) * (Dc + 50_000)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_batch_order_and_capacity_random(oracle, seed):
+    # properties that define the policy, checked on the decision log of random traces: jobs get their
+    # GPUs in submission order, never before they were submitted, no host ever holds more than G, the
+    # chosen host is the least committed feasible one, and the head of the queue never waits while
+    # some ready host could take it.
+    b = tg.random_case(700 + seed, n_replays=1)
+    G = b.config["gpus_per_host"]
+    H = b.config["hosts_initial"]
+    Dc = 40
+    cfg = dict(b.config, flags=BATCH, hosts_max=H, batch_start_delay_ms=Dc)
+    r = oracle.replay(cfg, b.ev_time, b.ev_dur, b.ev_sk, b.sess_gpus, 1000, check=True, want_log=True)
+    kinds = b.ev_sk.view(np.uint32) >> 24
+    sess = b.ev_sk & 0xFFFFFF
+    log = [oracle.decode(c) for c in r["log"]]
+    # replay the log against the trace: accepted jobs in submission order
+    busy_until = {}
+    queue = []                      # (submit, session, dur) of accepted jobs, in order
+    li = 0
+    alloc = []                      # (time, host, g, finish)
+    pending = []
+    for i in range(len(b.ev_time)):
+        if kinds[i] != CELL:
+            continue
+        t, s, d = int(b.ev_time[i]), int(sess[i]), int(b.ev_dur[i])
+        # jobs whose log entry lies at or before t have been served by now
+        while li < len(log) and pending and log[li]["time"] <= t:
+            sub, ss, dd = pending.pop(0)
+            assert log[li]["session"] == ss and log[li]["time"] >= sub
+            fin = log[li]["time"] + Dc + dd
+            busy_until[ss] = fin
+            alloc.append((log[li]["time"], log[li]["host"], int(b.sess_gpus[ss]), fin))
+            li += 1
+        if busy_until.get(s, -1) > t or any(p[1] == s for p in pending):
+            continue                # dropped: previous job of the session not finished
+        pending.append((t, s, d))
+    while pending:
+        sub, ss, dd = pending.pop(0)
+        assert log[li]["session"] == ss and log[li]["time"] >= sub
+        alloc.append((log[li]["time"], log[li]["host"], int(b.sess_gpus[ss]), log[li]["time"] + Dc + dd))
+        li += 1
+    assert li == len(log) == r["cells_started"]
+    times = [a[0] for a in alloc]
+    assert times == sorted(times)
+    for k, (t, h, g, fin) in enumerate(alloc):
+        C = [0] * H
+        for (t2, h2, g2, f2) in alloc[:k]:
+            if f2 > t:
+                C[h2] += g2
+        assert C[h] + g <= G
+        feas = [(C[x], x) for x in range(H) if C[x] + g <= G]
+        assert min(feas) == (C[h], h)
+
+
 # ---- input validation -----------------------------------------------------------------------------
 
 def test_rejects_bad_input(oracle):
