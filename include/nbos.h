@@ -101,6 +101,22 @@ typedef enum {
                                       cell leads again whenever its host can bind the GPUs;
                                       otherwise the usual rule decides                        */
 
+#define NBOS_F_BATCH_MODE    0x100u /* replay the Batch baseline of Section 5.1.3 instead of the
+                                      NotebookOS policy: no replicas; every cell is a job of its
+                                      own, served first come first served (a job never overtakes
+                                      an earlier one) on the ready host with the fewest committed
+                                      GPUs that has g idle ones (ties: lowest index). The job holds
+                                      its GPUs for batch_start_delay_ms (container start) plus the
+                                      cell's duration. The queue is served after each arrival and
+                                      after all completions / hosts turning ready of one instant.
+                                      A cell whose session's previous job has not finished is
+                                      dropped. START / END events are ignored. Only
+                                      NBOS_F_SCALE_OUT (the job at the head of the queue that
+                                      finds no host asks for one more, once), NBOS_F_DECISION_LOG
+                                      and NBOS_F_HOSTS_IN_LDS may be combined with it. Of the
+                                      stats, the placement / migration / subscription fields stay
+                                      0; cells_queued counts the jobs that waited for GPUs.      */
+
 /* ---- event encoding ------------------------------------------------------ */
 #define NBOS_EV_START  0
 #define NBOS_EV_CELL   1
@@ -111,8 +127,9 @@ typedef struct nbos_replay nbos_replay;   /* opaque, owned by the library */
 
 /* Parameters common to all replays of one handle. */
 typedef struct {
-  uint32_t struct_size;         /* = sizeof(nbos_config); the 60-byte layout that ends at
-                                   min_hosts is accepted too, the missing fields read as 0      */
+  uint32_t struct_size;         /* = sizeof(nbos_config); the shorter layouts that end at
+                                   min_hosts (60 bytes) or scaling_buffer_hosts (68) are accepted
+                                   too, the missing fields read as 0      */
   int32_t  n_replays;           /* >= 0                                                         */
   int32_t  n_traces;            /* >= 1 when n_replays > 0                                      */
   int32_t  hosts_initial;       /* hosts 0..hosts_initial-1 are ready at time 0; >= 1           */
@@ -130,6 +147,7 @@ typedef struct {
   int32_t  autoscale_f_milli;   /* NBOS_F_AUTOSCALE: f * 1000 of the expected capacity f * sum C,
                                    0..100000 (Section 3.4.2 uses f = 1.05, i.e. 1050)           */
   int32_t  scaling_buffer_hosts;/* NBOS_F_AUTOSCALE: extra hosts kept on top of it, 0..1024     */
+  int32_t  batch_start_delay_ms;/* NBOS_F_BATCH_MODE: container start per job, 0..NBOS_MAX_DUR_MS */
 } nbos_config;
 
 /* The traces and per-replay parameters. All arrays are DEVICE pointers. */
@@ -164,7 +182,9 @@ typedef struct {
  * Decision code = host | slot << 10 | outcome << 12 | session << 16 | time << 32.
  */
 typedef struct {
-  int32_t  status;              /* NBOS_OK, or NBOS_E_LIMIT: retry queue overflowed, rest invalid */
+  int32_t  status;              /* NBOS_OK; NBOS_E_LIMIT: retry queue overflowed; NBOS_E_RANGE (Batch
+                                   baseline): the queue pushed a job beyond the int32 time range.
+                                   The other fields are invalid then.                              */
   uint32_t n_decisions;
   uint32_t sessions_placed, sessions_rejected;
   uint32_t cells_total, cells_immediate, cells_started, cells_queued, cells_aborted;
@@ -190,6 +210,8 @@ typedef struct {
 #define NBOS_D_ABORT       7   /* queued cell given up                               */
 #define NBOS_D_SCALE_IN    8   /* empty host released (session field 0)              */
 #define NBOS_D_SCALE_AUTO  9   /* host provisioned by the periodic auto-scaler       */
+#define NBOS_D_BATCH_START 10  /* Batch baseline: GPUs allocated to the job on host   */
+#define NBOS_D_BATCH_HOST  11  /* Batch baseline: host provisioned for the queue head */
 
 /*
  * Create a replay batch (paper Sections 3.2-3.4 define the simulated policy).

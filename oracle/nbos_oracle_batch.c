@@ -25,6 +25,8 @@
  *     session). SESSION_START / SESSION_END events carry no meaning here.
  *   - timers due at or before an arrival run before it; at one instant
  *     completions run before servers turn ready.
+ *   - times are int32 milliseconds: a replay whose queue pushes a job to 2^31 - 1 or
+ *     beyond ends with ORC_E_INPUT.
  */
 #include "nbos_oracle.h"
 #include <stdlib.h>
@@ -120,6 +122,7 @@ static void dispatch(sim *m) {
       if ((m->p->flags & ORC_F_SCALE_OUT) && !j->asked && m->n_on < m->H) {
         for (int h = 0; h < m->H; h++)
           if (m->hosts[h].state == H_OFF) {
+            if ((int64_t)m->clock + m->p->boot_delay_ms >= 2147483647LL) { m->err = ORC_E_INPUT; return; }
             m->hosts[h].state = H_BOOT;
             m->hosts[h].ready_at = m->clock + m->p->boot_delay_ms;
             heap_push(m, m->hosts[h].ready_at, T_HOST_READY, h);
@@ -133,6 +136,8 @@ static void dispatch(sim *m) {
       }
       return;
     }
+    /* a long queue can push a job beyond the int32 time range: the replay is invalid then */
+    if ((int64_t)m->clock + m->p->batch_start_delay_ms + j->dur >= 2147483647LL) { m->err = ORC_E_INPUT; return; }
     /* allocate: the container starts now, the cell runs after the start delay */
     int32_t start = m->clock + m->p->batch_start_delay_ms;
     int32_t finish = start + j->dur;

@@ -1,0 +1,300 @@
+// nbos_kernel_batch.hpp — replay of the Batch baseline (paper Section 5.1.3): every cell is a job of its
+// own, first come first served, a container per job. One workgroup (one wave64) per replay, any cluster
+// size up to NBOS_MAX_HOSTS.
+//
+// LDS per replay
+//   fin[h][8]    per-GPU "busy until" times, one 32-byte row per host: a GPU is held at time t iff
+//                fin > t. Completions need no timer (see below).
+//   ready_at[h]  0 for initial hosts, NEVER while off, boot completion time while provisioning.
+//   sess[s]      12 bytes: busy-until time of the session's job, or its submit time while it waits in the
+//                queue; its duration; g and a "waiting" bit.
+//   fifo         ring of waiting jobs (16-bit session ids); at most one per session.
+//
+// The CPU reference runs completions and "host ready" as timers and looks at the queue after each
+// instant. Here nothing is queued as a timer. The job at the head of the queue first meets the scheduler
+// at T0 = max(its submit time, the time the previous head got its GPUs). If some ready host has g idle
+// GPUs at T0 it starts there. Otherwise nothing is allocated until it starts (it blocks the queue), so
+// the busy-until times do not change while it waits and the instant it starts is known in closed form:
+// E = min over hosts of max(ready_at, g-th smallest busy-until time of the host), which is the time of a
+// completion or of a host turning ready, i.e. an instant at which the reference serves the queue.
+// A GPU with fin <= E is free at E exactly when the reference has applied every completion of that
+// instant. The queue is advanced up to the time of each arriving event before the event is looked at
+// (timers due at or before an arrival run before it), and to the end after the last one.
+#pragma once
+#include "nbos_common.hpp"
+
+namespace {
+namespace batchk {
+
+enum { CS_QUEUED, CS_SO, CS_PEAK, CS_NON, CS_MAXDELAY, CS_N32 };
+enum { CL_SUMDELAY, CL_PROV, CL_N64 };
+
+struct SessRec { int32_t time, dur, gq; };      // gq = g | waiting << 8
+constexpr int32_t WAITING = 1 << 8;
+
+struct Lds {
+  unsigned long long *c64;
+  uint32_t *c32, *hist;
+  int4 *fin;
+  int32_t *ready_at;
+  SessRec *sess;
+  uint16_t *fifo;
+};
+
+struct State {
+  uint32_t n_dec, c_total, c_started, c_imm, c_busy;
+  int64_t sum_dur, g_exec, g_hold;
+  uint64_t digest;
+  int32_t q_head, q_n;          // ring: index of the head, jobs waiting
+  int32_t last_T;               // when the previous head got its GPUs
+  int32_t head_E;               // start time worked out for a waiting head, or -1
+  bool head_asked;              // the waiting head has asked for a host
+  int32_t lazy_max, t_end;
+  int32_t status;               // NBOS_OK, or NBOS_E_RANGE once a time leaves the int32 range
+};
+
+struct Ctx {
+  const KParams &p;
+  Lds m;
+  int lane;
+  int ring;                     // ring capacity
+  uint64_t *dlog;
+};
+
+__device__ __forceinline__ void decide(Ctx &c, State &r, int32_t now, uint32_t outcome, uint32_t s, uint32_t host) {
+  const uint64_t code = (uint64_t)host | ((uint64_t)outcome << 12) | ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
+  r.digest = r.digest * 0x100000001B3ULL + code;
+  if (c.dlog) {
+    if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
+  }
+  r.n_dec++;
+}
+
+__device__ __forceinline__ int committed(const Ctx &c, int h, int32_t now) {
+  const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
+  return (a.x > now) + (a.y > now) + (a.z > now) + (a.w > now) + (b.x > now) + (b.y > now) + (b.z > now) + (b.w > now);
+}
+
+// ready host with the fewest GPUs held at time T that has g idle ones; ties to the lowest index.
+// Returns committed << 10 | host, or 0xFFFFFFFF.
+__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t T, int g) {
+  wave_sync();
+  uint32_t best = 0xFFFFFFFFu;
+  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+    const int C = committed(c, h, T);
+    if (c.m.ready_at[h] <= T && C + g <= c.p.G) best = umin(best, ((uint32_t)C << 10) | (uint32_t)h);
+  }
+  return wave_min(best);
+}
+
+__device__ __forceinline__ void order2(int32_t &a, int32_t &b) {
+  const int32_t lo = a < b ? a : b, hi = a < b ? b : a;
+  a = lo; b = hi;
+}
+
+// earliest time at which some host that is on has g idle GPUs if nothing new is allocated:
+// min over hosts of max(ready_at, g-th smallest busy-until time). One lane sorts one host's row with the
+// 19-comparator network for 8 inputs.
+__device__ __forceinline__ int32_t earliest_idle(const Ctx &c, int g) {
+  wave_sync();
+  const int G = c.p.G;
+  int32_t best = NEVER;
+  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+    const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
+    int32_t v0 = a.x, v1 = G > 1 ? a.y : NEVER, v2 = G > 2 ? a.z : NEVER, v3 = G > 3 ? a.w : NEVER;
+    int32_t v4 = G > 4 ? b.x : NEVER, v5 = G > 5 ? b.y : NEVER, v6 = G > 6 ? b.z : NEVER, v7 = G > 7 ? b.w : NEVER;
+    order2(v0, v1); order2(v2, v3); order2(v4, v5); order2(v6, v7);
+    order2(v0, v2); order2(v1, v3); order2(v4, v6); order2(v5, v7);
+    order2(v1, v2); order2(v5, v6);
+    order2(v0, v4); order2(v1, v5); order2(v2, v6); order2(v3, v7);
+    order2(v2, v4); order2(v3, v5);
+    order2(v1, v2); order2(v3, v4); order2(v5, v6);
+    int32_t y = g == 1 ? v0 : g == 2 ? v1 : g == 3 ? v2 : g == 4 ? v3 : g == 5 ? v4 : g == 6 ? v5 : g == 7 ? v6 : v7;
+    const int32_t ra = c.m.ready_at[h];
+    y = y > ra ? y : ra;
+    best = best < y ? best : y;
+  }
+  return (int32_t)wave_min((uint32_t)best);
+}
+
+// Serve the queue up to time `until`: the head gets its GPUs as soon as a host can give them.
+__device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
+  while (r.q_n > 0 && r.status == NBOS_OK) {
+    wave_sync();
+    const int32_t s = uni((int32_t)c.m.fifo[r.q_head]);
+    const SessRec j = c.m.sess[s];
+    const int32_t t_submit = uni(j.time), dur = uni(j.dur);
+    const int g = uni(j.gq) & 0xFF;
+    int32_t T = t_submit > r.last_T ? t_submit : r.last_T;          // the head meets the scheduler
+    if (T > until) break;
+    uint32_t key = 0xFFFFFFFFu;
+    if (r.head_E < 0) {
+      key = best_host(c, T, g);
+      if (key == 0xFFFFFFFFu) {
+        // nothing at T: ask for one more host (once), then the start time is a closed form
+        if ((c.p.flags & NBOS_F_SCALE_OUT) && !r.head_asked) {
+          wave_sync();
+          const int n_on = (int)uni(c.m.c32[CS_NON]);
+          if (n_on < c.p.Hmax) {
+            int h = 0;
+            for (int base = 0; base < c.p.HP; base += WAVE) {
+              const int hh = base + c.lane;
+              const uint64_t off = wballot(hh < c.p.Hmax && c.m.ready_at[hh] == NEVER);
+              if (off) { h = base + (int)__builtin_ctzll(off); break; }
+            }
+            if ((int64_t)T + c.p.boot >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; break; }
+            const int32_t ra = T + c.p.boot;
+            if (c.lane == 0) {
+              c.m.ready_at[h] = ra;
+              atomicAdd(&c.m.c32[CS_NON], 1u);
+              atomicAdd(&c.m.c32[CS_SO], 1u);
+              atomicMax(&c.m.c32[CS_PEAK], (uint32_t)(n_on + 1));
+              atomicAdd(&c.m.c64[CL_PROV], (unsigned long long)(-(int64_t)c.p.G * T));
+            }
+            r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
+            decide(c, r, T, NBOS_D_BATCH_HOST, (uint32_t)s, (uint32_t)h);
+          }
+          r.head_asked = true;
+        }
+        r.head_E = earliest_idle(c, g);
+      }
+    }
+    if (key == 0xFFFFFFFFu) {
+      if (r.head_E > until) break;                  // still waiting when the next event arrives
+      T = r.head_E;
+      key = best_host(c, T, g);
+    }
+    // a long queue can push a job beyond the int32 time range: the replay ends as invalid
+    if ((int64_t)T + c.p.batch_delay + dur >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; break; }
+    // the job gets its GPUs at T on host h: container start, then the cell
+    const int h = (int)(key & 1023u);
+    const int32_t start = T + c.p.batch_delay, finish = start + dur;
+    const int32_t delay = start - t_submit;
+    wave_sync();
+    {
+      int32_t *row = (int32_t *)&c.m.fin[2 * h];
+      const bool mine = c.lane < c.p.G;
+      const int32_t f = mine ? row[c.lane] : NEVER;
+      const bool fr = mine && f <= T;
+      const int rank = lane_rank(wballot(fr));
+      if (fr && rank < g) row[c.lane] = finish;
+    }
+    int b = delay == 0 ? 0 : 32 - __builtin_clz((uint32_t)delay);
+    b = b > 31 ? 31 : b;
+    if (c.lane == 0) {
+      c.m.sess[s].time = finish; c.m.sess[s].gq = g;
+      atomicAdd(&c.m.hist[b], 1u);
+      atomicAdd(&c.m.c64[CL_SUMDELAY], (unsigned long long)delay);
+      atomicMax(&c.m.c32[CS_MAXDELAY], (uint32_t)delay);
+      if (T != t_submit) atomicAdd(&c.m.c32[CS_QUEUED], 1u);
+    }
+    r.c_started++;
+    if (T == t_submit) r.c_imm++;
+    r.sum_dur += dur;
+    r.g_exec += (int64_t)g * dur;
+    r.g_hold += (int64_t)g * (finish - T);
+    r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
+    decide(c, r, T, NBOS_D_BATCH_START, (uint32_t)s, (uint32_t)h);
+    r.last_T = T;
+    r.head_E = -1;
+    r.head_asked = false;
+    r.q_head = r.q_head + 1 == c.ring ? 0 : r.q_head + 1;
+    r.q_n--;
+  }
+}
+
+__global__ void __launch_bounds__(WAVE) nbos_replay_batch_kernel(KParams p) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int rep = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (rep >= p.n_replays) return;
+
+  const int trace = p.trace_of_replay[rep];
+  const int64_t ev_lo = p.ev_offset[trace], ev_hi = p.ev_offset[trace + 1];
+  const int s_lo = p.sess_offset[trace];
+  const int n_sess = p.sess_offset[trace + 1] - s_lo;
+
+  Lds m;
+  unsigned char *q = lds_raw;
+  m.c64 = (unsigned long long *)q;  q += 8 * 8;
+  m.c32 = (uint32_t *)q;            q += 16 * 4;
+  m.hist = (uint32_t *)q;           q += 32 * 4;
+  m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
+  m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
+  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
+  m.fifo = (uint16_t *)q;
+
+  if (lane < 8) m.c64[lane] = 0;
+  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
+  if (lane < 32) m.hist[lane] = 0;
+  for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
+  for (int h = lane; h < p.HP; h += WAVE) m.ready_at[h] = h < p.H0 ? 0 : NEVER;
+  for (int s = lane; s < n_sess; s += WAVE) { m.sess[s].time = 0; m.sess[s].dur = 0; m.sess[s].gq = p.sess_gpus[s_lo + s]; }
+  __syncthreads();
+
+  Ctx c{p, m, lane, p.n_cap + 1, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+  State r;
+  memset(&r, 0, sizeof r);
+  r.digest = 0xCBF29CE484222325ULL;
+  r.head_E = -1;
+
+  // the events: one per lane per tile, next tile in flight
+  int64_t base = ev_lo;
+  int32_t vt = 0, vd = 0, vs = 0, nt = 0, nd = 0, ns = 0;
+  if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
+  while (base < ev_hi && r.status == NBOS_OK) {
+    vt = nt; vd = nd; vs = ns;
+    const int64_t cur = base;
+    base += WAVE;
+    if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
+    const bool valid = cur + lane < ev_hi;
+    const bool is_cell = valid && ((uint32_t)vs >> 24) == NBOS_EV_CELL;
+    uint64_t todo = wballot(is_cell);
+    r.c_total += (uint32_t)__builtin_popcountll(todo);
+    if (ev_hi - cur <= WAVE) {
+      const int32_t tl = lane_get(vt, (int)(ev_hi - cur - 1));
+      r.t_end = r.t_end > tl ? r.t_end : tl;
+    }
+    while (todo != 0 && r.status == NBOS_OK) {
+      const int i = (int)__builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int32_t t = lane_get(vt, i), dur = lane_get(vd, i);
+      const int32_t s = (int32_t)((uint32_t)lane_get(vs, i) & 0xFFFFFFu);
+      serve_queue(c, r, t);                       // everything due at or before the arrival comes first
+      wave_sync();
+      const SessRec rec = m.sess[s];
+      const int32_t gq = uni(rec.gq);
+      if ((gq & WAITING) || uni(rec.time) > t) { r.c_busy++; continue; }     // previous job not finished
+      int tail = r.q_head + r.q_n;
+      tail = tail >= c.ring ? tail - c.ring : tail;
+      if (lane == 0) { m.fifo[tail] = (uint16_t)s; m.sess[s].time = t; m.sess[s].dur = dur; m.sess[s].gq = gq | WAITING; }
+      r.q_n++;
+      serve_queue(c, r, t);
+    }
+  }
+  serve_queue(c, r, NEVER);
+
+  __syncthreads();
+  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
+  nbos_stats *out = p.stats + rep;
+  if (lane < 32) out->delay_hist[lane] = m.hist[lane];
+  if (lane == 0) {
+    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY];
+    out->status = r.status; out->n_decisions = r.n_dec;
+    out->sessions_placed = 0; out->sessions_rejected = 0;
+    out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
+    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = 0;
+    out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = 0;
+    out->executor_reused = 0; out->migrations = 0;
+    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = 0; out->peak_hosts = m.c32[CS_PEAK];
+    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
+    out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
+    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_hold;
+    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
+    out->reservation_gpu_ms = 0; out->sub_gpu_ms = 0; out->replica_ms = 0;
+    out->digest = r.digest;
+  }
+}
+
+}  // namespace batchk
+}  // namespace

@@ -2,6 +2,7 @@
 // and kernel dispatch. Two kernels implement the same replay (see their headers):
 //   nbos_kernel_reg.hpp   hosts_max <= 64: host state in registers, no LDS round trip per cell
 //   nbos_kernel_lds.hpp   any hosts_max up to 1024: host state in LDS
+// and a third replays the Batch baseline policy on the same traces (nbos_kernel_batch.hpp).
 // Everything is integer arithmetic; all control flow is wave-uniform.
 
 #include <hip/hip_runtime.h>
@@ -16,6 +17,7 @@
 #include "nbos_common.hpp"
 #include "nbos_kernel_lds.hpp"
 #include "nbos_kernel_reg.hpp"
+#include "nbos_kernel_batch.hpp"
 
 namespace {
 
@@ -157,9 +159,13 @@ int32_t nbos_sizeof_stats(void) { return (int32_t)sizeof(nbos_stats); }
 int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, void *stream, nbos_replay **out) {
   if (out) *out = nullptr;
   if (!cfg_in || !in || !out) return NBOS_E_ARG;
-  // the layout that ends at min_hosts is accepted as well: the later fields read as 0
+  // the layouts that end at min_hosts or at scaling_buffer_hosts are accepted as well: the later
+  // fields read as 0
   constexpr uint32_t kShortConfig = offsetof(nbos_config, autoscale_f_milli);
-  if (cfg_in->struct_size != sizeof(nbos_config) && cfg_in->struct_size != kShortConfig) return NBOS_E_ARG;
+  constexpr uint32_t kMidConfig = offsetof(nbos_config, batch_start_delay_ms);
+  if (cfg_in->struct_size != sizeof(nbos_config) && cfg_in->struct_size != kShortConfig &&
+      cfg_in->struct_size != kMidConfig)
+    return NBOS_E_ARG;
   nbos_config full;
   memset(&full, 0, sizeof full);
   memcpy(&full, cfg_in, cfg_in->struct_size);
@@ -173,8 +179,12 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
   if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS |
-                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR))
+                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE))
     return NBOS_E_ARG;
+  if (cfg->flags & NBOS_F_BATCH_MODE) {
+    if (cfg->flags & ~(NBOS_F_BATCH_MODE | NBOS_F_SCALE_OUT | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS)) return NBOS_E_ARG;
+    if (cfg->batch_start_delay_ms < 0 || cfg->batch_start_delay_ms > NBOS_MAX_DUR_MS) return NBOS_E_ARG;
+  }
   if (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) {
     if (cfg->scale_interval_ms < 1 || cfg->min_hosts < 0) return NBOS_E_ARG;
   }
@@ -190,6 +200,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   // the time a replay can reach beyond its last arrival
   int64_t slack = (int64_t)NBOS_MAX_DUR_MS + (int64_t)cfg->max_retries * cfg->retry_interval_ms +
                   cfg->boot_delay_ms + cfg->migration_delay_ms;
+  bool batch_mode = (cfg->flags & NBOS_F_BATCH_MODE) != 0;
   if (slack >= 0x7FFFFFFFLL) return NBOS_E_ARG;
 
   nbos_replay *h = new (std::nothrow) nbos_replay();
@@ -227,11 +238,15 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     // kernel choice and LDS footprint of one replay
     int maxlds = 0;
     HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    const bool in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS);
+    const bool in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode;
     const int HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
     const int n_cap = max_sess > 0 ? max_sess : 1;
     size_t q_cap = (size_t)n_cap + 1;               // at most one queued timer per session
-    if (in_regs) {
+    if (batch_mode) {
+      h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + (size_t)n_cap * 12 + ((size_t)n_cap + 2) * 2;
+      if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
+      h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
+    } else if (in_regs) {
       h->lds_bytes = 64 + 64 + 128 + (size_t)n_cap * 16;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       // The common policy flag sets have kernels compiled for them (everything that is switched off
@@ -321,6 +336,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     k.scale_iv = (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) ? cfg->scale_interval_ms : 1;
     k.idle_pct = cfg->scale_in_idle_pct; k.min_hosts = cfg->min_hosts;
     k.f_milli = cfg->autoscale_f_milli; k.buffer = cfg->scaling_buffer_hosts;
+    k.batch_delay = cfg->batch_start_delay_ms;
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
     const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
     k.batch = (nb && nb[0] == '0') ? 0 : 1;

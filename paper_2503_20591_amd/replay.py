@@ -17,7 +17,7 @@ import numpy as np
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG, F_HOSTS_IN_LDS = 1, 2, 4, 8, 16
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR = 0x20, 0x40, 0x80
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE = 0x20, 0x40, 0x80, 0x100
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
@@ -31,7 +31,8 @@ class NbosConfig(C.Structure):
                 ("replicas", C.c_int32), ("flags", C.c_uint32), ("migration_delay_ms", C.c_int32),
                 ("boot_delay_ms", C.c_int32), ("retry_interval_ms", C.c_int32), ("max_retries", C.c_int32),
                 ("scale_interval_ms", C.c_int32), ("scale_in_idle_pct", C.c_int32), ("min_hosts", C.c_int32),
-                ("autoscale_f_milli", C.c_int32), ("scaling_buffer_hosts", C.c_int32)]
+                ("autoscale_f_milli", C.c_int32), ("scaling_buffer_hosts", C.c_int32),
+                ("batch_start_delay_ms", C.c_int32)]
 
 
 _INPUT_FIELDS = ("ev_offset", "ev_time_ms", "ev_dur_ms", "ev_sess_kind", "sess_offset", "sess_gpus",
@@ -116,7 +117,7 @@ def make_config(cfg: dict, n_replays: int, n_traces: int, extra_flags: int = 0) 
     c.replicas = int(cfg.get("replicas", 3))
     for name in ("hosts_initial", "hosts_max", "gpus_per_host", "migration_delay_ms", "boot_delay_ms",
                  "retry_interval_ms", "max_retries", "scale_interval_ms", "scale_in_idle_pct", "min_hosts",
-                 "autoscale_f_milli", "scaling_buffer_hosts"):
+                 "autoscale_f_milli", "scaling_buffer_hosts", "batch_start_delay_ms"):
         setattr(c, name, int(cfg.get(name, 0)))
     c.flags = int(cfg.get("flags", 0)) | int(extra_flags)
     return c

@@ -21,7 +21,7 @@ import numpy as np
 
 EV_START, EV_CELL, EV_END = 0, 1, 2
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR = 0x20, 0x40, 0x80
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE = 0x20, 0x40, 0x80, 0x100
 
 MAX_DUR_MS = 86_400_000          # a cell or an idle gap is at most 24 h
 MAX_TIME_MS = 1_900_000_000      # arrivals are clipped here so finish times stay in int32
@@ -176,7 +176,7 @@ def _base_config(**kw) -> dict:
     cfg = dict(hosts_initial=8, hosts_max=8, gpus_per_host=8, flags=0, migration_delay_ms=15_000,
                boot_delay_ms=60_000, retry_interval_ms=10_000, max_retries=6,
                scale_interval_ms=60_000, scale_in_idle_pct=10, min_hosts=0,
-               autoscale_f_milli=0, scaling_buffer_hosts=0)
+               autoscale_f_milli=0, scaling_buffer_hosts=0, batch_start_delay_ms=0)
     cfg.update(kw)
     return cfg
 
@@ -233,10 +233,15 @@ def _recipe(name: str):
                          autoscale_f_milli=1050, scaling_buffer_hosts=32)
         rc["cap"] = lambda i, n: 4000
         return rc
+    if name in ("c2b", "c4b"):  # the c2 / c4 traces under the Batch baseline (Section 5.1.3): a container
+        # per cell (15 s to start, the GPUs already held), first come first served, fixed cluster
+        rc = _recipe(name[:2])
+        rc["cfg"] = dict(rc["cfg"], flags=F_BATCH_MODE, hosts_max=rc["cfg"]["hosts_initial"], batch_start_delay_ms=15_000)
+        return rc
     raise KeyError(name)
 
 
-WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c4a")
+WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b")
 
 
 def _gen_range(args):

@@ -213,6 +213,67 @@ def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, gener
         assert_same(rp, oracle, b, st)
 
 
+# ---- Batch baseline (Section 5.1.3) ------------------------------------------------------------------
+
+def as_batch(b, delay, scale_out):
+    b.config.update(flags=tg.F_BATCH_MODE | (tg.F_SCALE_OUT if scale_out else 0), batch_start_delay_ms=delay)
+    if not scale_out:
+        b.config["hosts_max"] = b.config["hosts_initial"]
+    return b
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_batch_mode_random_cases(rp, oracle, seed):
+    b = tg.random_case(seed)
+    as_batch(b, delay=[0, 1, 40, 15_000][seed % 4], scale_out=bool(b.config["flags"] & tg.F_SCALE_OUT))
+    if seed % 5 == 0:                      # room to grow
+        b.config["hosts_max"] = b.config["hosts_initial"] + 7
+        b.config["flags"] |= tg.F_SCALE_OUT
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+
+
+@pytest.mark.parametrize("name,n,hosts", [("c2", 4, 30), ("c2", 2, 6), ("c5", 8, 16), ("c4", 1, 512), ("c4", 1, 96)])
+def test_batch_mode_named_workloads(rp, oracle, name, n, hosts):
+    # the NotebookOS workloads replayed under the Batch baseline, also on far fewer hosts (long queues)
+    b = tg.workload(name, n_replays=n)
+    as_batch(b, delay=20_000, scale_out=False)
+    b.config["hosts_initial"] = b.config["hosts_max"] = hosts
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+    assert (st["cells_started"] + st["cells_dropped_busy"] == st["cells_total"]).all()
+
+
+def test_batch_mode_time_range(rp, oracle):
+    # 30 one-day jobs on a single host: the 25th would end beyond 2^31 - 1 ms. Both sides call the
+    # replay invalid (the oracle returns its input error, the kernel sets the replay's status).
+    n = 30
+    t, d, sk = events_to_arrays([[i, 1, i, 86_400_000] for i in range(n)])
+    cfg = tg._base_config(hosts_initial=1, hosts_max=1, flags=tg.F_BATCH_MODE)
+    b = tg._pack(cfg, [(t, d, sk, np.full(n, 8, np.uint8))], [0, 0], [1000, 1000], "overflow")
+    with pytest.raises(ValueError) as e:
+        oracle.replay_batch(b)
+    assert e.value.args[1] == -2
+    st, _ = gpu_run(rp, b)
+    assert (st["status"] == rp.E_RANGE).all()
+    # one job fewer than the limit allows is fine
+    n = 24
+    t, d, sk = events_to_arrays([[i, 1, i, 86_400_000] for i in range(n)])
+    b = tg._pack(cfg, [(t, d, sk, np.full(n, 8, np.uint8))], [0], [1000], "no-overflow")
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
+def test_batch_mode_rejects_other_policy_flags(rp):
+    b = tg.random_case(2)
+    dev = rp.upload(b)
+    for f in (tg.F_BATCH_MODE | tg.F_MIGRATE, tg.F_BATCH_MODE | tg.F_SCALE_IN, tg.F_BATCH_MODE | tg.F_AUTOSCALE):
+        cfg = dict(b.config, flags=f)
+        with pytest.raises(rp.NbosError) as e:
+            rp.Replay(cfg, dev)
+        assert e.value.code == rp.E_ARG
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
