@@ -19,10 +19,10 @@ _SRC_BATCH = os.path.join(_DIR, "nbos_oracle_batch.c")
 _LIB = os.path.join(_DIR, "libnbos_oracle.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY, F_BATCH = 0x20, 0x40, 0x80, 0x100
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY, F_BATCH, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
 EV_START, EV_CELL, EV_END = 0, 1, 2
 (D_PLACE, D_PLACE_NEW, D_REJECT, D_START, D_MIGRATE, D_SCALE_CELL, D_ABORT, D_SCALE_IN,
- D_SCALE_AUTO, D_BATCH_START, D_BATCH_HOST) = range(1, 12)
+ D_SCALE_AUTO, D_BATCH_START, D_BATCH_HOST, D_MIGRATE_WARM) = range(1, 13)
 
 
 class _Params(C.Structure):
@@ -30,13 +30,14 @@ class _Params(C.Structure):
         ("flags", C.c_uint32)] + [(n, C.c_int32) for n in (
             "migration_delay_ms", "boot_delay_ms", "retry_interval_ms", "max_retries",
             "scale_interval_ms", "scale_in_idle_pct", "min_hosts", "cap_milli", "check",
-            "autoscale_f_milli", "scaling_buffer_hosts", "batch_start_delay_ms")]
+            "autoscale_f_milli", "scaling_buffer_hosts", "batch_start_delay_ms",
+            "warm_pool_per_host", "warm_migration_delay_ms", "prewarm_delay_ms")]
 
 
 _U32 = ("n_decisions", "sessions_placed", "sessions_rejected", "cells_total", "cells_immediate",
         "cells_started", "cells_queued", "cells_aborted", "cells_dropped_busy",
         "cells_dropped_unplaced", "executor_reused", "migrations", "scale_out_hosts",
-        "scale_in_hosts", "peak_hosts")
+        "scale_in_hosts", "peak_hosts", "migrations_warm")
 _I32 = ("max_delay_ms", "t_end_ms")
 _I64 = ("sum_delay_ms", "sum_tct_ms", "gpu_ms_executed", "gpu_ms_committed",
         "gpu_ms_provisioned", "reservation_gpu_ms", "sub_gpu_ms", "replica_ms")

@@ -17,6 +17,7 @@
  *   dynamic cluster-wide limit on the subscription ratio ........... 3.4.1
  *   metric definitions (delay, TCT, immediate, reuse, GPU-hours) ... 5.2.2-5.2.4
  *   billing model (provider cost, revenue, standby charge) ......... 5.3.1
+ *   pre-warmed container pool for migrations ........................ 3.2.3
  *
  * Readings taken where the paper leaves a choice open (all deterministic):
  *   - host preference key, smaller is better: (committed GPUs, subscribed GPUs,
@@ -44,6 +45,12 @@
  *     ratio after taking the replica is at most the cluster-wide ratio after
  *     taking it, (S_h + g) / (G R) <= (sum S + g) / (n G R), n = hosts not off;
  *     i.e. the limit in force is the larger of the configured cap and that mean.
+ *   - pre-warmed containers (ORC_F_WARM_POOL): every host keeps warm_pool_per_host of
+ *     them; an initial host has them from time 0, a provisioned host prewarm_delay_ms
+ *     after it is ready. A migration takes the target's container that has been
+ *     available longest, if one is available now: the cell then starts after
+ *     warm_migration_delay_ms instead of migration_delay_ms, and a replacement is
+ *     available prewarm_delay_ms later. A host added for the cell has none yet.
  *   - sticky executor (ORC_F_STICKY): when the replica that executed the session's
  *     previous cell can lead (host ready, enough idle GPUs) it does; else the rule above.
  */
@@ -64,6 +71,7 @@ typedef struct {
   int state;
   int32_t ready_at;
   int C, S, nrep;
+  int32_t warm[4];    /* when each pre-warmed container is (again) available */
 } host_rec;
 
 typedef struct {
@@ -187,6 +195,8 @@ static int boot_host(sim *m) {
     if (m->hosts[h].state == H_OFF) {
       m->hosts[h].state = H_BOOT;
       m->hosts[h].ready_at = m->clock + m->p->boot_delay_ms;
+      for (int i = 0; i < 4; i++)          /* its pool is filled once it is up */
+        m->hosts[h].warm[i] = m->hosts[h].ready_at + m->p->prewarm_delay_ms;
       m->n_on++;
       if ((uint32_t)m->n_on > m->r.peak_hosts) m->r.peak_hosts = (uint32_t)m->n_on;
       heap_push(m, m->hosts[h].ready_at, T_HOST_READY, h);
@@ -319,6 +329,18 @@ static void attempt(sim *m, int s) {
       commit(m, dst, g);
       q->host[victim] = dst;
       m->r.migrations++;
+      /* Section 3.2.3, pre-warmed container pool: a warm container on the target cuts the delay */
+      if (m->p->flags & ORC_F_WARM_POOL) {
+        host_rec *d = &m->hosts[dst];
+        int w = 0;
+        for (int i = 1; i < m->p->warm_pool_per_host; i++) if (d->warm[i] < d->warm[w]) w = i;
+        if (d->warm[w] <= m->clock) {
+          d->warm[w] = m->clock + m->p->prewarm_delay_ms;
+          m->r.migrations_warm++;
+          start_cell(m, s, victim, m->clock + m->p->warm_migration_delay_ms, ORC_D_MIGRATE_WARM);
+          return;
+        }
+      }
       start_cell(m, s, victim, m->clock + m->p->migration_delay_ms, ORC_D_MIGRATE);
       return;
     }
@@ -485,7 +507,11 @@ static int validate(const orc_params *p, int64_t n_events, const int32_t *ev_tim
   if (p->max_retries < 0 || p->max_retries > 15) return ORC_E_ARG;
   if (p->cap_milli < 1 || p->cap_milli > 100000) return ORC_E_ARG;
   if (p->flags & ~(uint32_t)(ORC_F_MIGRATE | ORC_F_SCALE_OUT | ORC_F_SCALE_IN | ORC_F_AUTOSCALE |
-                            ORC_F_DYNAMIC_SR | ORC_F_STICKY)) return ORC_E_ARG;
+                            ORC_F_DYNAMIC_SR | ORC_F_STICKY | ORC_F_WARM_POOL)) return ORC_E_ARG;
+  if (p->flags & ORC_F_WARM_POOL) {
+    if (p->warm_pool_per_host < 1 || p->warm_pool_per_host > 4) return ORC_E_ARG;
+    if (p->warm_migration_delay_ms < 0 || p->prewarm_delay_ms < 0) return ORC_E_ARG;
+  }
   if (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) {
     if (p->scale_interval_ms < 1 || p->min_hosts < 0) return ORC_E_ARG;
   }
@@ -507,8 +533,10 @@ static int validate(const orc_params *p, int64_t n_events, const int32_t *ev_tim
     if (kind > ORC_EV_END || s >= n_sessions) return ORC_E_INPUT;
     if (kind == ORC_EV_CELL && (ev_dur[i] < 1 || ev_dur[i] > MAX_DUR)) return ORC_E_INPUT;
   }
+  int64_t slowest = p->migration_delay_ms;
+  if ((p->flags & ORC_F_WARM_POOL) && p->warm_migration_delay_ms > slowest) slowest = p->warm_migration_delay_ms;
   int64_t horizon = (int64_t)prev + MAX_DUR + (int64_t)p->max_retries * p->retry_interval_ms +
-                    p->boot_delay_ms + p->migration_delay_ms;
+                    p->boot_delay_ms + slowest + ((p->flags & ORC_F_WARM_POOL) ? p->prewarm_delay_ms : 0);
   if (horizon >= 2147483647LL) return ORC_E_INPUT;
   return 0;
 }

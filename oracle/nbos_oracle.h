@@ -19,7 +19,8 @@ enum {
   ORC_F_AUTOSCALE = 0x20,   /* Section 3.4.2: periodic expected-capacity test f * sum C    */
   ORC_F_DYNAMIC_SR = 0x40,  /* Section 3.4.1: cluster-wide subscription ratio as the limit */
   ORC_F_STICKY = 0x80,      /* election variant: the previous executor leads again if it can */
-  ORC_F_BATCH = 0x100       /* replay the Batch baseline of Section 5.1.3 (orc_replay_batch)  */
+  ORC_F_BATCH = 0x100,      /* replay the Batch baseline of Section 5.1.3 (orc_replay_batch)  */
+  ORC_F_WARM_POOL = 0x200   /* Section 3.2.3: pre-warmed containers shorten a migration        */
 };
 
 /* decision outcomes written to the log / folded into the digest */
@@ -28,7 +29,8 @@ enum {
   ORC_D_MIGRATE = 5, ORC_D_SCALE_CELL = 6, ORC_D_ABORT = 7, ORC_D_SCALE_IN = 8,
   ORC_D_SCALE_AUTO = 9,  /* host added by the periodic auto-scaler (session field 0) */
   ORC_D_BATCH_START = 10,/* Batch baseline: GPUs allocated to the session's job on host */
-  ORC_D_BATCH_HOST = 11  /* Batch baseline: host provisioned for the job at the queue's head */
+  ORC_D_BATCH_HOST = 11, /* Batch baseline: host provisioned for the job at the queue's head */
+  ORC_D_MIGRATE_WARM = 12/* migration into a pre-warmed container on the target host          */
 };
 
 /* error returns of orc_replay (0 = ok) */
@@ -50,6 +52,9 @@ typedef struct {
   int32_t autoscale_f_milli;    /* f x 1000 of the expected capacity f * sum C (paper: 1050) */
   int32_t scaling_buffer_hosts; /* extra hosts kept on top of the expected capacity          */
   int32_t batch_start_delay_ms; /* Batch baseline: container start per job (GPUs already held) */
+  int32_t warm_pool_per_host;   /* pre-warmed containers kept per host, 1..4 (ORC_F_WARM_POOL)  */
+  int32_t warm_migration_delay_ms; /* migration delay into a pre-warmed container            */
+  int32_t prewarm_delay_ms;     /* time to provision one pre-warmed container                */
 } orc_params;
 
 typedef struct {
@@ -59,6 +64,7 @@ typedef struct {
   uint32_t cells_dropped_busy, cells_dropped_unplaced;
   uint32_t executor_reused, migrations;
   uint32_t scale_out_hosts, scale_in_hosts, peak_hosts;
+  uint32_t migrations_warm;     /* migrations that found a pre-warmed container                */
   int32_t  max_delay_ms, t_end_ms;
   uint32_t delay_hist[32];
   int64_t  sum_delay_ms, sum_tct_ms;

@@ -71,7 +71,7 @@ MUTANTS = [
     ("sticky executor always on", "if ((m->p->flags & ORC_F_STICKY) && lead >= 0 && q->last_exec >= 0) {", "if (lead >= 0 && q->last_exec >= 0) {"),
     ("sticky executor never applied", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", ";"),
     ("sticky executor off by one GPU", "if (x->state == H_READY && m->G - x->C >= g) lead = q->last_exec;", "if (x->state == H_READY && m->G - x->C > g) lead = q->last_exec;"),
-    ("batch: a later job overtakes the head of the queue", "      return;\n    }\n    /* allocate", "      m->head = (m->head + 1) % (m->n_sess + 1); m->fifo[(m->head + m->count - 1) % (m->n_sess + 1)] = s;\n      if (++j->asked > m->count + 1) return;\n      continue;\n    }\n    /* allocate", "nbos_oracle_batch.c"),
+    ("batch: a later job overtakes the head of the queue", "      return;\n    }\n    /* a long queue", "      m->head = (m->head + 1) % (m->n_sess + 1); m->fifo[(m->head + m->count - 1) % (m->n_sess + 1)] = s;\n      if (++j->asked > m->count + 1) return;\n      continue;\n    }\n    /* a long queue", "nbos_oracle_batch.c"),
     ("batch: container start not part of the delay", "int32_t delay = start - j->t_submit;", "int32_t delay = m->clock - j->t_submit;", "nbos_oracle_batch.c"),
     ("batch: GPUs not held during the container start", "(int64_t)j->g * ((int64_t)finish - m->clock)", "(int64_t)j->g * j->dur", "nbos_oracle_batch.c"),
     ("batch: fullest feasible server", "if (best < 0 || x->C < m->hosts[best].C) best = h;", "if (best < 0 || x->C > m->hosts[best].C) best = h;", "nbos_oracle_batch.c"),
@@ -82,6 +82,13 @@ MUTANTS = [
     ("batch: every queued job asks for a server", "j->asked = 1;", "", "nbos_oracle_batch.c"),
     ("batch: timers due at an arrival run after it", "m.heap[0].time <= t && !m.err) run_instant(&m);", "m.heap[0].time < t && !m.err) run_instant(&m);", "nbos_oracle_batch.c"),
     ("batch: queue looked at between two timers of one instant", "    }\n  }\n  dispatch(m);\n}", "    }\n    dispatch(m);\n  }\n  dispatch(m);\n}", "nbos_oracle_batch.c"),
+    ("warm pool: takes the newest container", "if (d->warm[i] < d->warm[w]) w = i;", "if (d->warm[i] > d->warm[w]) w = i;"),
+    ("warm pool: never refilled", "d->warm[w] = m->clock + m->p->prewarm_delay_ms;", "d->warm[w] = 2147483647;"),
+    ("warm pool: refilled at once", "d->warm[w] = m->clock + m->p->prewarm_delay_ms;", ""),
+    ("warm pool: an added host is warm from the start", "m->hosts[h].warm[i] = m->hosts[h].ready_at + m->p->prewarm_delay_ms;", "m->hosts[h].warm[i] = 0;"),
+    ("warm pool: container available exactly now is not taken", "if (d->warm[w] <= m->clock) {", "if (d->warm[w] < m->clock) {"),
+    ("warm pool: warm start pays the cold delay", "m->clock + m->p->warm_migration_delay_ms, ORC_D_MIGRATE_WARM", "m->clock + m->p->migration_delay_ms, ORC_D_MIGRATE_WARM"),
+    ("warm pool: only one container per host", "for (int i = 1; i < m->p->warm_pool_per_host; i++)", "for (int i = 1; i < 1; i++)"),
     ("dynamic limit always on", "if (m->p->flags & ORC_F_DYNAMIC_SR)\n    return", "if (1)\n    return"),
     ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
     ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
@@ -139,6 +146,8 @@ def run_pins(lib_path):
     checks += [lambda s=s: pins.test_dynamic_limit_is_vacuous_on_large_clusters(o, s) for s in range(8)]
     checks.append(lambda: pins.test_dynamic_limit_brute_force(o))
     checks.append(lambda: pins.test_sticky_election_brute_force(o))
+    checks += [lambda: pins.test_warm_pool_pin_sees_many_migrations(o)]
+    checks += [lambda s=s: pins.test_warm_pool_that_refills_at_once_is_a_shorter_delay(o, s) for s in range(3)]
     checks += [lambda: pins.test_batch_single_server_is_the_textbook_fifo_queue(o), lambda: pins.test_batch_without_contention(o)]
     checks += [lambda s=s: pins.test_batch_order_and_capacity_random(o, s) for s in range(6)]
     checks += [lambda: pins.test_billing_printed_example(o), lambda: pins.test_billing_is_linear_and_exact_on_large_results(o)]

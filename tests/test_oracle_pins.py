@@ -621,6 +621,97 @@ def test_batch_order_and_capacity_random(oracle, seed):
         assert min(feas) == (C[h], h)
 
 
+# ---- Section 3.2.3, pre-warmed container pool ------------------------------------------------------
+
+WARM = 0x200
+
+
+def _warm_case(seed):
+    b = tg.random_case(800 + seed, n_replays=2)
+    b.config["flags"] |= tg.F_MIGRATE
+    b.config["migration_delay_ms"] = 15_000
+    return b
+
+
+def _warm_pool_replayed_from_the_log(oracle, seed):
+    # re-derive warm / cold for every migration from the decision log alone: per target host a pool of W
+    # availability times (0 for initial hosts, ready + pre-warm for added ones); the longest-available
+    # container is taken if it is available, and is back pre-warm later
+    W, prewarm = int(1 + seed % 4), int([0, 3_000, 40_000, 10**8][seed % 4])
+    n_mig = 0
+    for b in (_warm_case(3 * seed), _warm_case(3 * seed + 1), _warm_case(3 * seed + 2)):
+      cfg = dict(b.config, flags=b.config["flags"] | WARM, warm_pool_per_host=W, warm_migration_delay_ms=700,
+                 prewarm_delay_ms=prewarm)
+      for r in range(b.n_replays):
+          t = int(b.trace_of_replay[r])
+          a, e = int(b.ev_offset[t]), int(b.ev_offset[t + 1])
+          sa, se = int(b.sess_offset[t]), int(b.sess_offset[t + 1])
+          res = oracle.replay(cfg, b.ev_time[a:e], b.ev_dur[a:e], b.ev_sk[a:e], b.sess_gpus[sa:se],
+                              int(b.cap_milli[r]), check=True, want_log=True)
+          pool = {h: [0] * W for h in range(cfg["hosts_initial"])}
+          warm = 0
+          for code in res["log"]:
+              d = oracle.decode(code)
+              if d["outcome"] in (oracle.D_PLACE_NEW, oracle.D_SCALE_CELL):
+                  pool[d["host"]] = [d["time"] + cfg["boot_delay_ms"] + prewarm] * W
+              elif d["outcome"] == oracle.D_SCALE_IN:
+                  pool.pop(d["host"], None)
+              elif d["outcome"] in (oracle.D_MIGRATE, oracle.D_MIGRATE_WARM):
+                  n_mig += 1
+                  p = pool[d["host"]]
+                  i = p.index(min(p))
+                  if p[i] <= d["time"]:
+                      assert d["outcome"] == oracle.D_MIGRATE_WARM, (seed, r, d)
+                      p[i] = d["time"] + prewarm
+                      warm += 1
+                  else:
+                      assert d["outcome"] == oracle.D_MIGRATE, (seed, r, d)
+          assert res["migrations_warm"] == warm
+    return n_mig
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_warm_pool_replayed_from_the_log(oracle, seed):
+    _warm_pool_replayed_from_the_log(oracle, seed)
+
+
+def test_warm_pool_pin_sees_many_migrations(oracle):
+    assert sum(_warm_pool_replayed_from_the_log(oracle, s) for s in range(10)) > 200
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_warm_pool_with_equal_delays_changes_nothing_else(oracle, seed):
+    # same delay warm or cold: only the outcome code of warm migrations (and their count) may differ
+    b = _warm_case(20 + seed)
+    x = oracle.replay_batch(b, check=True)
+    b.config.update(flags=b.config["flags"] | WARM, warm_pool_per_host=2,
+                    warm_migration_delay_ms=b.config["migration_delay_ms"], prewarm_delay_ms=5_000)
+    y = oracle.replay_batch(b, check=True)
+    for u, v in zip(x, y):
+        for k in u:
+            if k not in ("digest", "migrations_warm"):
+                assert u[k] == v[k], k
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_warm_pool_that_refills_at_once_is_a_shorter_delay(oracle, seed):
+    # pre-warm time 0 on initial hosts only (no scale-out): every migration is warm, i.e. the replay
+    # equals one without the pool whose migration delay is the warm one
+    b = _warm_case(40 + seed)
+    b.config["flags"] &= ~(tg.F_SCALE_OUT | tg.F_SCALE_IN)
+    b.config["hosts_max"] = b.config["hosts_initial"]
+    b.config["migration_delay_ms"] = 700
+    x = oracle.replay_batch(b, check=True)
+    b.config.update(flags=b.config["flags"] | WARM, warm_pool_per_host=1, warm_migration_delay_ms=700,
+                    prewarm_delay_ms=0, migration_delay_ms=15_000)
+    y = oracle.replay_batch(b, check=True)
+    for u, v in zip(x, y):
+        assert v["migrations_warm"] == v["migrations"]
+        for k in u:
+            if k not in ("digest", "migrations_warm"):
+                assert u[k] == v[k], k
+
+
 # ---- input validation -----------------------------------------------------------------------------
 
 def test_rejects_bad_input(oracle):
