@@ -117,6 +117,15 @@ typedef enum {
                                       stats, the placement / migration / subscription fields stay
                                       0; cells_queued counts the jobs that waited for GPUs.      */
 
+#define NBOS_F_WARM_POOL     0x200u /* pre-warmed container pool (Section 3.2.3): every host keeps
+                                      warm_pool_per_host pre-warmed containers (initial hosts from
+                                      time 0, added hosts prewarm_delay_ms after they are ready).
+                                      A migration takes the target's container that has been
+                                      available longest, if one is available: the cell then starts
+                                      after warm_migration_delay_ms instead of migration_delay_ms
+                                      (decision NBOS_D_MIGRATE_WARM) and a replacement is available
+                                      prewarm_delay_ms later. Not with NBOS_F_BATCH_MODE.        */
+
 /* ---- event encoding ------------------------------------------------------ */
 #define NBOS_EV_START  0
 #define NBOS_EV_CELL   1
@@ -128,7 +137,8 @@ typedef struct nbos_replay nbos_replay;   /* opaque, owned by the library */
 /* Parameters common to all replays of one handle. */
 typedef struct {
   uint32_t struct_size;         /* = sizeof(nbos_config); the shorter layouts that end at
-                                   min_hosts (60 bytes) or scaling_buffer_hosts (68) are accepted
+                                   min_hosts (60 bytes), scaling_buffer_hosts (68) or
+                                   batch_start_delay_ms (72) are accepted
                                    too, the missing fields read as 0      */
   int32_t  n_replays;           /* >= 0                                                         */
   int32_t  n_traces;            /* >= 1 when n_replays > 0                                      */
@@ -148,6 +158,9 @@ typedef struct {
                                    0..100000 (Section 3.4.2 uses f = 1.05, i.e. 1050)           */
   int32_t  scaling_buffer_hosts;/* NBOS_F_AUTOSCALE: extra hosts kept on top of it, 0..1024     */
   int32_t  batch_start_delay_ms;/* NBOS_F_BATCH_MODE: container start per job, 0..NBOS_MAX_DUR_MS */
+  int32_t  warm_pool_per_host;  /* NBOS_F_WARM_POOL: pre-warmed containers per host, 1..4        */
+  int32_t  warm_migration_delay_ms; /* NBOS_F_WARM_POOL: migration delay into one of them, >= 0  */
+  int32_t  prewarm_delay_ms;    /* NBOS_F_WARM_POOL: time to pre-warm a container, 0..NBOS_MAX_DUR_MS */
 } nbos_config;
 
 /* The traces and per-replay parameters. All arrays are DEVICE pointers. */
@@ -191,6 +204,7 @@ typedef struct {
   uint32_t cells_dropped_busy, cells_dropped_unplaced;
   uint32_t executor_reused, migrations;
   uint32_t scale_out_hosts, scale_in_hosts, peak_hosts;
+  uint32_t migrations_warm;     /* migrations that found a pre-warmed container (NBOS_F_WARM_POOL) */
   int32_t  max_delay_ms, t_end_ms;
   uint32_t delay_hist[32];
   int64_t  sum_delay_ms, sum_tct_ms;
@@ -212,6 +226,7 @@ typedef struct {
 #define NBOS_D_SCALE_AUTO  9   /* host provisioned by the periodic auto-scaler       */
 #define NBOS_D_BATCH_START 10  /* Batch baseline: GPUs allocated to the job on host   */
 #define NBOS_D_BATCH_HOST  11  /* Batch baseline: host provisioned for the queue head */
+#define NBOS_D_MIGRATE_WARM 12 /* as NBOS_D_MIGRATE, into a pre-warmed container      */
 
 /*
  * Create a replay batch (paper Sections 3.2-3.4 define the simulated policy).

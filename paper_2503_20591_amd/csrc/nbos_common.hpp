@@ -34,6 +34,7 @@ struct KParams {
   int32_t migr, boot, retry_iv, max_retries, scale_iv, idle_pct, min_hosts;
   int32_t f_milli, buffer; // auto-scaler: f * 1000 of the expected capacity, extra hosts
   int32_t batch_delay;     // Batch baseline: container start per job
+  int32_t warm_n, warm_migr, prewarm;   // pre-warmed containers per host, warm migration delay, pre-warm time
   int32_t n_cap, q_cap;    // LDS capacity: sessions, queue entries
   int32_t batch;           // event-parallel rounds on (LDS kernel)
 };

@@ -287,6 +287,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_batch_kernel(KParams p) {
     out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = 0;
     out->executor_reused = 0; out->migrations = 0;
     out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = 0; out->peak_hosts = m.c32[CS_PEAK];
+    out->migrations_warm = 0;
     out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
     out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
     out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_hold;

@@ -40,7 +40,7 @@ namespace {
 namespace ldsk {
 
 enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
-       CS_NON, CS_SUMS, CS_OPENG, CS_BLAZY, CS_NREP, CS_N32 };
+       CS_NON, CS_SUMS, CS_OPENG, CS_BLAZY, CS_NREP, CS_MIGRWARM, CS_N32 };
 enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_BDUR, CL_BGEXEC, CL_REPL, CL_N64 };   // B*: added by the rounds
 
 constexpr int32_t MARK_FREE = 0x7FFFFFFF;
@@ -53,6 +53,7 @@ struct Lds {
   unsigned long long *ppow;    // P^0 .. P^64 of the digest multiplier
   int4 *fin;                   // two int4 per host
   int32_t *ready_at, *mark;
+  int32_t *warm;               // [HP][4] when each pre-warmed container of a host is available (only with the pool)
   uint32_t *hsn;
   SessRec *sess;
   int32_t *o_t, *o_d;
@@ -76,7 +77,7 @@ struct Regs {
 // everything that is switched off), or kRuntimeFlags.
 constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
 constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
-                                  NBOS_F_STICKY_EXECUTOR;
+                                  NBOS_F_STICKY_EXECUTOR | NBOS_F_WARM_POOL;
 
 template <uint32_t F>
 struct Ctx {
@@ -266,6 +267,9 @@ __device__ __forceinline__ int boot_host(Ctx<F> &c, Regs &r, int32_t now, uint32
   const int h = find_off_host(c);
   const int32_t ra = now + c.p.boot;
   if (c.lane == 0) { c.m.ready_at[h] = ra; c.m.hsn[h] = hs_new; }
+  if (c.flags() & NBOS_F_WARM_POOL) {         // its pre-warmed containers are there once it is up
+    if (c.lane < 4) c.m.warm[4 * h + c.lane] = ra + c.p.prewarm;
+  }
   c.fu = c.fu < ra ? c.fu : ra;               // a new host may have idle GPUs from then on
   r.min_s = -1;
   c32_add(c.m, c.lane, CS_NON, 1u);
@@ -557,12 +561,27 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       // (b) migration, Section 3.2.3: the target binds the GPUs at once. A ready host of this session
       // with g idle GPUs would have won the election, so none of its hosts can show up as a target.
       const int dst = (int)(tkey & 1023u);
-      const int32_t start = now + c.p.migr;
+      int32_t start = now + c.p.migr;
+      uint32_t outcome = NBOS_D_MIGRATE;
+      if (c.flags() & NBOS_F_WARM_POOL) {
+        // Section 3.2.3: the target's pre-warmed container that has been available longest, if any
+        // is available now, shortens the start; its replacement is there one pre-warm time later
+        wave_sync();
+        const uint32_t av = c.lane < c.p.warm_n ? (uint32_t)c.m.warm[4 * dst + c.lane] : 0xFFFFFFFFu;
+        const uint32_t first = wave_min(av);
+        if ((int32_t)first <= now) {
+          const int w = (int)__builtin_ctzll(wballot(av == first));
+          if (c.lane == w) c.m.warm[4 * dst + w] = now + c.p.prewarm;
+          start = now + c.p.warm_migr;
+          outcome = NBOS_D_MIGRATE_WARM;
+          c32_add(c.m, c.lane, CS_MIGRWARM, 1u);
+        }
+      }
       if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[dst] += moved; }
       r.min_s = -1;
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
-      start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
+      start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, outcome);
     } else {
       // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
@@ -797,6 +816,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
   m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
   m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
+  m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
   m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
   m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
   m.o_k = (uint32_t *)q;            q += (size_t)p.q_cap * 4;
@@ -812,6 +832,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   }
   for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
   for (int h = lane; h < p.HP; h += WAVE) { m.ready_at[h] = h < p.H0 ? 0 : NEVER; m.mark[h] = MARK_FREE; m.hsn[h] = 0; }
+  if (p.warm_n > 0) {
+    for (int i = lane; i < 4 * p.HP; i += WAVE) m.warm[i] = 0;     // initial hosts: warm from time 0
+  }
   for (int s = lane; s < n_sess; s += WAVE) {
     const uint32_t g = p.sess_gpus[s_lo + s];
     m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
@@ -1004,6 +1027,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
     out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
     out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
     out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
+    out->migrations_warm = m.c32[CS_MIGRWARM];
     out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
     const int64_t sum_dur = r.sum_dur + (int64_t)m.c64[CL_BDUR], g_exec = r.g_exec + (int64_t)m.c64[CL_BGEXEC];
     out->sum_delay_ms = sum_delay; out->sum_tct_ms = sum_dur + sum_delay;

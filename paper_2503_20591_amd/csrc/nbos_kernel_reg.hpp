@@ -34,11 +34,12 @@ namespace regk {
 
 // cold counters kept in LDS (lane 0 adds with ds_add, no return value)
 enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
-       CS_NON, CS_SUMS, CS_OPENG, CS_NREP, CS_N32 };
+       CS_NON, CS_SUMS, CS_OPENG, CS_NREP, CS_MIGRWARM, CS_N32 };
 enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_REPL, CL_N64 };
 
 // session record: x hosts word, y time word, z flags, w duration of the queued cell
 struct Lds {
+  int32_t *warm;     // [64][4] when each pre-warmed container of a host is available (only with the pool)
   int4 *sess;
   uint32_t *hist;
   uint32_t *c32;
@@ -62,7 +63,7 @@ struct Regs {
 // own, which drops the code of everything that is switched off), or kRuntimeFlags.
 constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
 constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
-                                  NBOS_F_STICKY_EXECUTOR;
+                                  NBOS_F_STICKY_EXECUTOR | NBOS_F_WARM_POOL;
 
 template <int NJ, uint32_t F>
 struct Ctx {
@@ -253,6 +254,9 @@ __device__ __forceinline__ int boot_host(Ctx<NJ, F> &c, Regs &r, int32_t now, ui
   int h = (int)__builtin_ctzll(off);                 // the caller has checked that one exists
   int32_t ra = now + c.p.boot;
   if (c.lane == h) { c.hr = ra; c.hs = hs_new; }
+  if (c.flags() & NBOS_F_WARM_POOL) {         // its pre-warmed containers are there once it is up
+    if (c.lane < 4) c.m.warm[4 * h + c.lane] = ra + c.p.prewarm;
+  }
   c.fu = c.fu < ra ? c.fu : ra;               // a new host may have idle GPUs from then on
   c32_add(c.m, c.lane, CS_NON, 1u);
   c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
@@ -482,12 +486,27 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
       const uint32_t key = ((target >> c.lane) & 1u) ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane)
                                                       : 0xFFFFFFFFu;
       const int dst = (int)(wave_min(key) & 1023u);
-      const int32_t start = now + c.p.migr;
+      int32_t start = now + c.p.migr;
+      uint32_t outcome = NBOS_D_MIGRATE;
+      if (c.flags() & NBOS_F_WARM_POOL) {
+        // Section 3.2.3: the target's pre-warmed container that has been available longest, if any
+        // is available now, shortens the start; its replacement is there one pre-warm time later
+        wave_sync();
+        const uint32_t av = c.lane < c.p.warm_n ? (uint32_t)c.m.warm[4 * dst + c.lane] : 0xFFFFFFFFu;
+        const uint32_t first = wave_min(av);
+        if ((int32_t)first <= now) {
+          const int w = (int)__builtin_ctzll(wballot(av == first));
+          if (c.lane == w) c.m.warm[4 * dst + w] = now + c.p.prewarm;
+          start = now + c.p.warm_migr;
+          outcome = NBOS_D_MIGRATE_WARM;
+          c32_add(c.m, c.lane, CS_MIGRWARM, 1u);
+        }
+      }
       if (c.lane == hv) c.hs -= moved;
       if (c.lane == dst) c.hs += moved;
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
-      start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
+      start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, outcome);
     } else {
       // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
@@ -683,12 +702,16 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   m.c64 = (unsigned long long *)q; q += 8 * 8;
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
+  m.warm = (int32_t *)q;       q += p.warm_n > 0 ? WAVE * 16 : 0;
   m.sess = (int4 *)q;          q += (size_t)p.n_cap * 16;
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
   if (lane < 8) m.c64[lane] = 0;
   if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
   if (lane < 32) m.hist[lane] = 0;
+  if (p.warm_n > 0) {
+    for (int i = lane; i < WAVE * 4; i += WAVE) m.warm[i] = 0;     // initial hosts: warm from time 0
+  }
   for (int s = lane; s < n_sess; s += WAVE) {
     uint32_t g = p.sess_gpus[s_lo + s];
     m.sess[s] = make_int4(0, 0, (int)(SS_UNPLACED | ((g - 1u) << 3)), 0);
@@ -868,6 +891,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
     out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
     out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
     out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
+    out->migrations_warm = m.c32[CS_MIGRWARM];
     out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
     out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
     out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_exec + g_wait;

@@ -159,12 +159,12 @@ int32_t nbos_sizeof_stats(void) { return (int32_t)sizeof(nbos_stats); }
 int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, void *stream, nbos_replay **out) {
   if (out) *out = nullptr;
   if (!cfg_in || !in || !out) return NBOS_E_ARG;
-  // the layouts that end at min_hosts or at scaling_buffer_hosts are accepted as well: the later
-  // fields read as 0
+  // earlier, shorter layouts are accepted as well: the later fields read as 0
   constexpr uint32_t kShortConfig = offsetof(nbos_config, autoscale_f_milli);
   constexpr uint32_t kMidConfig = offsetof(nbos_config, batch_start_delay_ms);
+  constexpr uint32_t kBatchConfig = offsetof(nbos_config, warm_pool_per_host);
   if (cfg_in->struct_size != sizeof(nbos_config) && cfg_in->struct_size != kShortConfig &&
-      cfg_in->struct_size != kMidConfig)
+      cfg_in->struct_size != kMidConfig && cfg_in->struct_size != kBatchConfig)
     return NBOS_E_ARG;
   nbos_config full;
   memset(&full, 0, sizeof full);
@@ -179,10 +179,15 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
   if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS |
-                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE))
+                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE | NBOS_F_WARM_POOL))
     return NBOS_E_ARG;
+  if (cfg->flags & NBOS_F_WARM_POOL) {
+    if (cfg->warm_pool_per_host < 1 || cfg->warm_pool_per_host > 4 || cfg->warm_migration_delay_ms < 0 ||
+        cfg->prewarm_delay_ms < 0 || cfg->prewarm_delay_ms > NBOS_MAX_DUR_MS)
+      return NBOS_E_ARG;
+  }
   if (cfg->flags & NBOS_F_BATCH_MODE) {
-    if (cfg->flags & ~(NBOS_F_BATCH_MODE | NBOS_F_SCALE_OUT | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS)) return NBOS_E_ARG;
+    if (cfg->flags & ~(NBOS_F_BATCH_MODE | NBOS_F_SCALE_OUT | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS)) return NBOS_E_ARG;   // no pool either
     if (cfg->batch_start_delay_ms < 0 || cfg->batch_start_delay_ms > NBOS_MAX_DUR_MS) return NBOS_E_ARG;
   }
   if (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) {
@@ -198,9 +203,12 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (cfg->n_replays > 0 &&
       (!in->ev_offset || !in->sess_offset || !in->trace_of_replay || !in->cap_milli)) return NBOS_E_ARG;
   // the time a replay can reach beyond its last arrival
+  int64_t slowest = cfg->migration_delay_ms;
+  if ((cfg->flags & NBOS_F_WARM_POOL) && cfg->warm_migration_delay_ms > slowest) slowest = cfg->warm_migration_delay_ms;
   int64_t slack = (int64_t)NBOS_MAX_DUR_MS + (int64_t)cfg->max_retries * cfg->retry_interval_ms +
-                  cfg->boot_delay_ms + cfg->migration_delay_ms;
+                  cfg->boot_delay_ms + slowest + ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0);
   bool batch_mode = (cfg->flags & NBOS_F_BATCH_MODE) != 0;
+  bool warm_pool = (cfg->flags & NBOS_F_WARM_POOL) != 0;
   if (slack >= 0x7FFFFFFFLL) return NBOS_E_ARG;
 
   nbos_replay *h = new (std::nothrow) nbos_replay();
@@ -247,7 +255,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
     } else if (in_regs) {
-      h->lds_bytes = 64 + 64 + 128 + (size_t)n_cap * 16;
+      h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + (size_t)n_cap * 16;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       // The common policy flag sets have kernels compiled for them (everything that is switched off
       // is gone from the code). They have the shorter path per item, which is what counts while a
@@ -267,7 +275,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) h->kernel = reg_kernel_for<NBOS_F_MIGRATE | NBOS_F_SCALE_OUT>(nj);
       else h->kernel = reg_kernel_for<regk::kRuntimeFlags>(nj);
     } else {
-      size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12) + (size_t)n_cap * 12;
+      size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 12;
       if (fixed + 12 * 64 > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       if (fixed + q_cap * 12 > (size_t)maxlds) q_cap = ((size_t)maxlds - fixed) / 12;
       h->lds_bytes = fixed + q_cap * 12;
@@ -337,6 +345,8 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     k.idle_pct = cfg->scale_in_idle_pct; k.min_hosts = cfg->min_hosts;
     k.f_milli = cfg->autoscale_f_milli; k.buffer = cfg->scaling_buffer_hosts;
     k.batch_delay = cfg->batch_start_delay_ms;
+    k.warm_n = (cfg->flags & NBOS_F_WARM_POOL) ? cfg->warm_pool_per_host : 0;
+    k.warm_migr = cfg->warm_migration_delay_ms; k.prewarm = cfg->prewarm_delay_ms;
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
     const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
     k.batch = (nb && nb[0] == '0') ? 0 : 1;

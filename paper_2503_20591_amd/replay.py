@@ -17,7 +17,7 @@ import numpy as np
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG, F_HOSTS_IN_LDS = 1, 2, 4, 8, 16
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE = 0x20, 0x40, 0x80, 0x100
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
@@ -32,7 +32,8 @@ class NbosConfig(C.Structure):
                 ("boot_delay_ms", C.c_int32), ("retry_interval_ms", C.c_int32), ("max_retries", C.c_int32),
                 ("scale_interval_ms", C.c_int32), ("scale_in_idle_pct", C.c_int32), ("min_hosts", C.c_int32),
                 ("autoscale_f_milli", C.c_int32), ("scaling_buffer_hosts", C.c_int32),
-                ("batch_start_delay_ms", C.c_int32)]
+                ("batch_start_delay_ms", C.c_int32), ("warm_pool_per_host", C.c_int32),
+                ("warm_migration_delay_ms", C.c_int32), ("prewarm_delay_ms", C.c_int32)]
 
 
 _INPUT_FIELDS = ("ev_offset", "ev_time_ms", "ev_dur_ms", "ev_sess_kind", "sess_offset", "sess_gpus",
@@ -56,7 +57,7 @@ STATS_DTYPE = np.dtype(
      ("cells_total", "<u4"), ("cells_immediate", "<u4"), ("cells_started", "<u4"), ("cells_queued", "<u4"),
      ("cells_aborted", "<u4"), ("cells_dropped_busy", "<u4"), ("cells_dropped_unplaced", "<u4"),
      ("executor_reused", "<u4"), ("migrations", "<u4"), ("scale_out_hosts", "<u4"), ("scale_in_hosts", "<u4"),
-     ("peak_hosts", "<u4"), ("max_delay_ms", "<i4"), ("t_end_ms", "<i4"), ("delay_hist", "<u4", (32,)),
+     ("peak_hosts", "<u4"), ("migrations_warm", "<u4"), ("max_delay_ms", "<i4"), ("t_end_ms", "<i4"), ("delay_hist", "<u4", (32,)),
      ("sum_delay_ms", "<i8"), ("sum_tct_ms", "<i8"), ("gpu_ms_executed", "<i8"), ("gpu_ms_committed", "<i8"),
      ("gpu_ms_provisioned", "<i8"), ("reservation_gpu_ms", "<i8"), ("sub_gpu_ms", "<i8"), ("replica_ms", "<i8"),
      ("digest", "<u8")],
@@ -117,7 +118,8 @@ def make_config(cfg: dict, n_replays: int, n_traces: int, extra_flags: int = 0) 
     c.replicas = int(cfg.get("replicas", 3))
     for name in ("hosts_initial", "hosts_max", "gpus_per_host", "migration_delay_ms", "boot_delay_ms",
                  "retry_interval_ms", "max_retries", "scale_interval_ms", "scale_in_idle_pct", "min_hosts",
-                 "autoscale_f_milli", "scaling_buffer_hosts", "batch_start_delay_ms"):
+                 "autoscale_f_milli", "scaling_buffer_hosts", "batch_start_delay_ms", "warm_pool_per_host",
+                 "warm_migration_delay_ms", "prewarm_delay_ms"):
         setattr(c, name, int(cfg.get(name, 0)))
     c.flags = int(cfg.get("flags", 0)) | int(extra_flags)
     return c

@@ -21,7 +21,7 @@ import numpy as np
 
 EV_START, EV_CELL, EV_END = 0, 1, 2
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE = 0x20, 0x40, 0x80, 0x100
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
 
 MAX_DUR_MS = 86_400_000          # a cell or an idle gap is at most 24 h
 MAX_TIME_MS = 1_900_000_000      # arrivals are clipped here so finish times stay in int32
@@ -176,7 +176,8 @@ def _base_config(**kw) -> dict:
     cfg = dict(hosts_initial=8, hosts_max=8, gpus_per_host=8, flags=0, migration_delay_ms=15_000,
                boot_delay_ms=60_000, retry_interval_ms=10_000, max_retries=6,
                scale_interval_ms=60_000, scale_in_idle_pct=10, min_hosts=0,
-               autoscale_f_milli=0, scaling_buffer_hosts=0, batch_start_delay_ms=0)
+               autoscale_f_milli=0, scaling_buffer_hosts=0, batch_start_delay_ms=0,
+               warm_pool_per_host=0, warm_migration_delay_ms=0, prewarm_delay_ms=0)
     cfg.update(kw)
     return cfg
 
@@ -323,4 +324,9 @@ def random_case(seed: int, n_replays: int = 4, policy_flags: bool = False) -> Tr
             cfg["scaling_buffer_hosts"] = int(r2.choice([0, 0, 1, 3]))
         if extra & F_DYNAMIC_SR:
             caps = r2.choice([20, 50, 100, 200, 334, 1000], n_replays)
+        if r2.random() < 0.5:          # pre-warmed containers for migrations
+            cfg["flags"] |= F_WARM_POOL | F_MIGRATE
+            cfg["warm_pool_per_host"] = int(r2.integers(1, 5))
+            cfg["warm_migration_delay_ms"] = int(r2.choice([0, 100, 2_000]))
+            cfg["prewarm_delay_ms"] = int(r2.choice([0, 5_000, 60_000, 10_000_000]))
     return _pack(cfg, traces, tor, caps, f"random{seed}")

@@ -29,8 +29,8 @@ def test_exports_match_header(lib):
 
 
 def test_struct_sizes(lib):
-    assert lib.nbos_sizeof_stats() == replay.STATS_DTYPE.itemsize == 272
-    assert C.sizeof(replay.NbosConfig) == 18 * 4
+    assert lib.nbos_sizeof_stats() == replay.STATS_DTYPE.itemsize == 280
+    assert C.sizeof(replay.NbosConfig) == 21 * 4
     assert C.sizeof(replay.NbosInputs) == 8 * 8
     assert C.sizeof(replay.NbosBillingParams) == 16 and replay.BILL_DTYPE.itemsize == 32
 
@@ -60,7 +60,8 @@ def _create(lib, cfg, n_replays=1, n_traces=1, inputs=True, struct_size=None, ou
 @pytest.mark.parametrize("bad", [
     dict(replicas=2), dict(gpus_per_host=0), dict(gpus_per_host=9), dict(hosts_initial=0),
     dict(hosts_max=3), dict(migration_delay_ms=-1), dict(boot_delay_ms=-1), dict(retry_interval_ms=0),
-    dict(max_retries=16), dict(max_retries=-1), dict(flags=512), dict(flags=0x101), dict(flags=0x120), dict(flags=0x100, batch_start_delay_ms=-1), dict(flags=4, scale_interval_ms=0),
+    dict(max_retries=16), dict(max_retries=-1), dict(flags=1024), dict(flags=0x200), dict(flags=0x200, warm_pool_per_host=5), dict(flags=0x300, warm_pool_per_host=1),
+    dict(flags=0x200, warm_pool_per_host=1, prewarm_delay_ms=-1), dict(flags=0x101), dict(flags=0x120), dict(flags=0x100, batch_start_delay_ms=-1), dict(flags=4, scale_interval_ms=0),
     dict(flags=0x20, scale_interval_ms=0), dict(flags=0x20, autoscale_f_milli=-1), dict(flags=0x20, autoscale_f_milli=100_001),
     dict(flags=0x20, scaling_buffer_hosts=-1), dict(flags=0x20, scaling_buffer_hosts=1025), dict(flags=0x24, min_hosts=-1),
     dict(flags=4, scale_in_idle_pct=101), dict(retry_interval_ms=2_000_000_000, max_retries=15)])
