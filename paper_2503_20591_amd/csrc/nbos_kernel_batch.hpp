@@ -3,8 +3,11 @@
 // size up to NBOS_MAX_HOSTS.
 //
 // LDS per replay
-//   fin[h][8]    per-GPU "busy until" times, one 32-byte row per host: a GPU is held at time t iff
-//                fin > t. Completions need no timer (see below).
+//   fin[h][8]    per-GPU "busy until" times, one 32-byte row per host, kept sorted ascending (slots
+//                beyond G hold NEVER): a GPU is held at time t iff fin > t, the host has g idle GPUs
+//                from fin[g-1] on, and an allocation rewrites the row in one step (the g smallest
+//                entries leave, g copies of the finish time enter at their sorted place).
+//                Completions need no timer (see below).
 //   ready_at[h]  0 for initial hosts, NEVER while off, boot completion time while provisioning.
 //   sess[s]      12 bytes: busy-until time of the session's job, or its submit time while it waits in the
 //                queue; its duration; g and a "waiting" bit.
@@ -70,9 +73,11 @@ __device__ __forceinline__ void decide(Ctx &c, State &r, int32_t now, uint32_t o
   r.n_dec++;
 }
 
+// GPUs of host h held at time `now` (the slots beyond G hold NEVER and are taken off again)
 __device__ __forceinline__ int committed(const Ctx &c, int h, int32_t now) {
   const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
-  return (a.x > now) + (a.y > now) + (a.z > now) + (a.w > now) + (b.x > now) + (b.y > now) + (b.z > now) + (b.w > now);
+  return (a.x > now) + (a.y > now) + (a.z > now) + (a.w > now) + (b.x > now) + (b.y > now) + (b.z > now) + (b.w > now) -
+         (NGPU - c.p.G);
 }
 
 // ready host with the fewest GPUs held at time T that has g idle ones; ties to the lowest index.
@@ -81,36 +86,25 @@ __device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t T, int g) {
   wave_sync();
   uint32_t best = 0xFFFFFFFFu;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
+    const int32_t *row = (const int32_t *)&c.m.fin[2 * h];
+    const int32_t ra = c.m.ready_at[h];
+    const bool ok = ra <= T && row[g - 1] <= T;
+    if (wballot(ok) == 0) continue;              // nobody in this chunk of hosts: leave the rows alone
     const int C = committed(c, h, T);
-    if (c.m.ready_at[h] <= T && C + g <= c.p.G) best = umin(best, ((uint32_t)C << 10) | (uint32_t)h);
+    if (ok) best = umin(best, ((uint32_t)C << 10) | (uint32_t)h);
   }
   return wave_min(best);
 }
 
-__device__ __forceinline__ void order2(int32_t &a, int32_t &b) {
-  const int32_t lo = a < b ? a : b, hi = a < b ? b : a;
-  a = lo; b = hi;
-}
-
 // earliest time at which some host that is on has g idle GPUs if nothing new is allocated:
-// min over hosts of max(ready_at, g-th smallest busy-until time). One lane sorts one host's row with the
-// 19-comparator network for 8 inputs.
+// min over hosts of max(ready_at, g-th smallest busy-until time) = max(ready_at, fin[g-1]).
 __device__ __forceinline__ int32_t earliest_idle(const Ctx &c, int g) {
   wave_sync();
-  const int G = c.p.G;
   int32_t best = NEVER;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
-    const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
-    int32_t v0 = a.x, v1 = G > 1 ? a.y : NEVER, v2 = G > 2 ? a.z : NEVER, v3 = G > 3 ? a.w : NEVER;
-    int32_t v4 = G > 4 ? b.x : NEVER, v5 = G > 5 ? b.y : NEVER, v6 = G > 6 ? b.z : NEVER, v7 = G > 7 ? b.w : NEVER;
-    order2(v0, v1); order2(v2, v3); order2(v4, v5); order2(v6, v7);
-    order2(v0, v2); order2(v1, v3); order2(v4, v6); order2(v5, v7);
-    order2(v1, v2); order2(v5, v6);
-    order2(v0, v4); order2(v1, v5); order2(v2, v6); order2(v3, v7);
-    order2(v2, v4); order2(v3, v5);
-    order2(v1, v2); order2(v3, v4); order2(v5, v6);
-    int32_t y = g == 1 ? v0 : g == 2 ? v1 : g == 3 ? v2 : g == 4 ? v3 : g == 5 ? v4 : g == 6 ? v5 : g == 7 ? v6 : v7;
+    const int32_t *row = (const int32_t *)&c.m.fin[2 * h];
     const int32_t ra = c.m.ready_at[h];
+    int32_t y = row[g - 1];
     y = y > ra ? y : ra;
     best = best < y ? best : y;
   }
@@ -172,12 +166,16 @@ __device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
     const int32_t delay = start - t_submit;
     wave_sync();
     {
+      // the g GPUs that have been free longest (entries 0..g-1, all <= T) are taken until `finish`:
+      // entries g.. that are <= finish move down g places, then g copies of finish, the rest stays
       int32_t *row = (int32_t *)&c.m.fin[2 * h];
-      const bool mine = c.lane < c.p.G;
-      const int32_t f = mine ? row[c.lane] : NEVER;
-      const bool fr = mine && f <= T;
-      const int rank = lane_rank(wballot(fr));
-      if (fr && rank < g) row[c.lane] = finish;
+      const int k = c.lane & 7;
+      const int32_t own = row[k];
+      const int32_t up = row[(k + g) & 7];
+      const int m = __builtin_popcountll(wballot(c.lane < 8 && k >= g && own <= finish));
+      const int32_t nv = k < m ? up : (k < m + g ? finish : own);
+      wave_sync();
+      if (c.lane < 8) row[k] = nv;
     }
     int b = delay == 0 ? 0 : 32 - __builtin_clz((uint32_t)delay);
     b = b > 31 ? 31 : b;
@@ -227,7 +225,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_batch_kernel(KParams p) {
   if (lane < 8) m.c64[lane] = 0;
   if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
   if (lane < 32) m.hist[lane] = 0;
-  for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
+  for (int i = lane; i < 8 * p.HP; i += WAVE) ((int32_t *)m.fin)[i] = (i & 7) < p.G ? 0 : NEVER;
   for (int h = lane; h < p.HP; h += WAVE) m.ready_at[h] = h < p.H0 ? 0 : NEVER;
   for (int s = lane; s < n_sess; s += WAVE) { m.sess[s].time = 0; m.sess[s].dur = 0; m.sess[s].gq = p.sess_gpus[s_lo + s]; }
   __syncthreads();
