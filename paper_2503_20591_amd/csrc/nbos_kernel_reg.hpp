@@ -486,8 +486,7 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
       const uint32_t key = ((target >> c.lane) & 1u) ? (((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)c.lane)
                                                       : 0xFFFFFFFFu;
       const int dst = (int)(wave_min(key) & 1023u);
-      int32_t start = now + c.p.migr;
-      uint32_t outcome = NBOS_D_MIGRATE;
+      bool warm = false;
       if (c.flags() & NBOS_F_WARM_POOL) {
         // Section 3.2.3: the target's pre-warmed container that has been available longest, if any
         // is available now, shortens the start; its replacement is there one pre-warm time later
@@ -497,16 +496,22 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
         if ((int32_t)first <= now) {
           const int w = (int)__builtin_ctzll(wballot(av == first));
           if (c.lane == w) c.m.warm[4 * dst + w] = now + c.p.prewarm;
-          start = now + c.p.warm_migr;
-          outcome = NBOS_D_MIGRATE_WARM;
           c32_add(c.m, c.lane, CS_MIGRWARM, 1u);
+          warm = true;
         }
       }
       if (c.lane == hv) c.hs -= moved;
       if (c.lane == dst) c.hs += moved;
-      bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
-      start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, outcome);
+      if (warm) {
+        const int32_t start = now + c.p.warm_migr;
+        bind_gpus(c, dst, g, now, start + dur);
+        start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE_WARM);
+      } else {
+        const int32_t start = now + c.p.migr;
+        bind_gpus(c, dst, g, now, start + dur);
+        start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, NBOS_D_MIGRATE);
+      }
     } else {
       // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
@@ -702,8 +707,8 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   m.c64 = (unsigned long long *)q; q += 8 * 8;
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
-  m.warm = (int32_t *)q;       q += p.warm_n > 0 ? WAVE * 16 : 0;
-  m.sess = (int4 *)q;          q += (size_t)p.n_cap * 16;
+  m.sess = (int4 *)q;          q += (size_t)p.n_cap * 16;    // at a fixed offset: its accesses fold it in
+  m.warm = (int32_t *)q;                                     // only there with the pool
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
   if (lane < 8) m.c64[lane] = 0;
