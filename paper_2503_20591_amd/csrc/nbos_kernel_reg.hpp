@@ -24,8 +24,9 @@
 //         arrived are the only timers that change decisions. The 64 earliest live sorted in
 //         registers (insert = ballot + DPP wave shift, pop = DPP wave shift); later ones wait in an
 //         unsorted LDS array that is only touched when the registers run empty or full.
-// Sessions in LDS: hosts word (3 x 10 bits + last executor slot), time word (busy-until, or submit
-//         time while queued), flags, duration of the queued cell.
+// Sessions in LDS, 8 bytes each: one word with the state, g, the retry count, the three replica hosts
+//         (6 bits each) and the last executor slot; one time word (busy-until, or the submit time while
+//         queued). The duration of a queued cell travels with its timer.
 #pragma once
 #include "nbos_common.hpp"
 
@@ -37,10 +38,17 @@ enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_
        CS_NON, CS_SUMS, CS_OPENG, CS_NREP, CS_MIGRWARM, CS_N32 };
 enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_REPL, CL_N64 };
 
-// session record: x hosts word, y time word, z flags, w duration of the queued cell
+// Session record: x = state (bits 0-2) | g - 1 (3-5) | ENDING (6) | RK_OVF (7) | retries (8-11) |
+// host of slot 0, 1, 2 (6 bits each from bit 12) | last executor slot + 1 (30-31); y = time word.
+// The code below calls the word `hw` where it looks at the hosts and `fl` where it looks at the low
+// bits; both names hold the whole word.
+constexpr uint32_t RK_OVF = 1u << 7;
+constexpr uint32_t RK_FLAGS = 0xFFFu;        // the bits below the hosts
+__device__ __forceinline__ uint32_t slot_host(uint32_t hw, uint32_t slot) { return (hw >> (12u + 6u * slot)) & 63u; }
+
 struct Lds {
   int32_t *warm;     // [64][4] when each pre-warmed container of a host is available (only with the pool)
-  int4 *sess;
+  int2 *sess;
   uint32_t *hist;
   uint32_t *c32;
   unsigned long long *c64;
@@ -73,6 +81,7 @@ struct Ctx {
   int n_sess;
   int32_t slim;              // floor(cap_milli * G * 3 / 1000): S + g <= slim is the cap test
   uint64_t *dlog;
+  int32_t *ovf_dur;          // [n_sess] durations of queued cells whose timer is outside the registers
   // per-lane state
   int32_t fin[NJ];
   int32_t hr;                // ready_at of host = lane
@@ -126,27 +135,27 @@ __device__ __forceinline__ void decide(Ctx<NJ, F> &c, Regs &r, int32_t now, uint
 // write a session record; lanes of the current tile that prefetched it go stale
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void sess_write(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, int32_t tm, uint32_t fl) {
-  if (c.lane == 0) c.m.sess[s] = make_int4((int)hw, tm, (int)fl, 0);
+  if (c.lane == 0) c.m.sess[s] = make_int2((int)((hw & ~RK_FLAGS) | (fl & RK_FLAGS)), tm);
   r.dirty |= wballot(c.vsid == s);
 }
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void sess_write_flag(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t fl) {
-  if (c.lane == 0) c.m.sess[s].z = (int)fl;
+  if (c.lane == 0) c.m.sess[s].x = (int)fl;
   r.dirty |= wballot(c.vsid == s);
 }
 
 // ---- timers beyond the 64 sorted ones stay with their session -------------------------------------
-// Such a session carries SF_OVF. Its timer is implied by its record: a queued session retries at
-// submit time + retries * interval (duration in w), a placed session that is ending ends at its
-// busy-until time. The earliest of them is tracked; finding the next one scans the session table.
+// Such a session carries RK_OVF. Its timer is implied by its record: a queued session retries at
+// submit time + retries * interval (the duration of its cell waits in a per-replay array in device
+// memory), a placed session that is ending ends at its busy-until time. The earliest of them is tracked; finding the next one scans the session table.
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void ovf_rescan(Ctx<NJ, F> &c, Regs &r) {
   wave_sync();
   uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
   for (int s = c.lane; s < c.n_sess; s += WAVE) {
-    const int4 rec = c.m.sess[s];
-    const uint32_t fl = (uint32_t)rec.z;
-    if (fl & SF_OVF) {
+    const int2 rec = c.m.sess[s];
+    const uint32_t fl = (uint32_t)rec.x;
+    if (fl & RK_OVF) {
       const bool retry = (fl & 7u) == SS_QUEUED;
       const uint32_t t = (uint32_t)(retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y);
       const uint32_t l = ((retry ? QK_RETRY : QK_END) << 16) | (uint32_t)s;
@@ -161,7 +170,7 @@ __device__ __forceinline__ void ovf_rescan(Ctx<NJ, F> &c, Regs &r) {
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void ovf_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
   const uint32_t s = k & 0xFFFFu;
-  if (c.lane == 0) { atomicOr((unsigned int *)&c.m.sess[s].z, SF_OVF); c.m.sess[s].w = d; }
+  if (c.lane == 0) { atomicOr((unsigned int *)&c.m.sess[s].x, RK_OVF); c.ovf_dur[s] = d; }
   r.dirty |= wballot(c.vsid == s);
   if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) { r.o_min_t = t; r.o_min_k = k; }
   r.o_n++;
@@ -208,8 +217,8 @@ __device__ __forceinline__ void timer_pop(Ctx<NJ, F> &c, Regs &r) {
   if (r.q_n == 0 && r.o_n > 0) {
     wave_sync();
     const uint32_t s = r.o_min_k & 0xFFFFu;
-    const int32_t d = uni(c.m.sess[s].w);
-    if (c.lane == 0) { atomicAnd((unsigned int *)&c.m.sess[s].z, ~SF_OVF); c.qt = r.o_min_t; c.qd = d; c.qk = r.o_min_k; }
+    const int32_t d = uni(c.ovf_dur[s]);
+    if (c.lane == 0) { atomicAnd((unsigned int *)&c.m.sess[s].x, ~RK_OVF); c.qt = r.o_min_t; c.qd = d; c.qk = r.o_min_k; }
     r.dirty |= wballot(c.vsid == s);
     r.o_n--;
     r.q_n = 1;
@@ -341,7 +350,7 @@ __device__ __forceinline__ void session_start(Ctx<NJ, F> &c, Regs &r, uint32_t s
       h = boot_host(c, r, now, add);
       decide(c, r, now, NBOS_D_PLACE_NEW, s, (uint32_t)i, (uint32_t)h);
     }
-    hw |= (uint32_t)h << (10 * i);
+    hw |= (uint32_t)h << (12 + 6 * i);
   }
   if (missing > 0) {
     wave_sync();
@@ -362,7 +371,7 @@ template <int NJ, uint32_t F>
 __device__ __forceinline__ void end_session(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now) {
   const int g = (int)((fl >> 3) & 7u) + 1;
   const uint32_t sub = (uint32_t)g | (1u << 16);
-  const int h0 = (int)(hw & 1023u), h1 = (int)((hw >> 10) & 1023u), h2 = (int)((hw >> 20) & 1023u);
+  const int h0 = (int)slot_host(hw, 0), h1 = (int)slot_host(hw, 1), h2 = (int)slot_host(hw, 2);
   if (c.lane == h0 || c.lane == h1 || c.lane == h2) c.hs -= sub;
   sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
   c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(-3 * g));
@@ -385,19 +394,17 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
   const uint32_t last = hw >> 30;               // 0 none, else slot + 1
   if (last == (uint32_t)slot + 1u) r.reused++;
   hw = (hw & 0x3FFFFFFFu) | ((uint32_t)(slot + 1) << 30);
-  hw = (hw & ~(1023u << (10 * slot))) | ((uint32_t)host << (10 * slot));
-  const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
+  hw = (hw & ~(63u << (12 + 6 * slot))) | ((uint32_t)host << (12 + 6 * slot));
+  // the record's word: hosts and last executor from hw, state back to "placed", retry count cleared
+  const uint32_t nw = (hw & ~RK_FLAGS) | (((fl & ~(7u | (15u << 8))) | SS_PLACED) & RK_FLAGS);
   if (delay == 0) {
     r.h0++;                                     // histogram bin 0 lives in a register
-    if (c.lane == 0) {
-      c.m.sess[s].x = (int)hw; c.m.sess[s].y = finish;
-      if (nfl != fl) c.m.sess[s].z = (int)nfl;
-    }
+    if (c.lane == 0) c.m.sess[s] = make_int2((int)nw, finish);
   } else {
     int b = 32 - __builtin_clz((uint32_t)delay);
     b = b > 31 ? 31 : b;
     if (c.lane == 0) {
-      c.m.sess[s] = make_int4((int)hw, finish, (int)nfl, 0);
+      c.m.sess[s] = make_int2((int)nw, finish);
       atomicAdd(&c.m.hist[b], 1u);
       atomicAdd(&c.m.c64[CL_SUMDELAY], (unsigned long long)delay);
       atomicMax(&c.m.c32[CS_MAXDELAY], (uint32_t)delay);
@@ -415,7 +422,7 @@ template <int NJ, uint32_t F>
 __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                         int32_t t_submit, int32_t dur) {
   const int g = (int)((fl >> 3) & 7u) + 1;
-  const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+  const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
   // Known in advance that no host has g idle GPUs yet? Then neither election nor migration can work.
   const bool hopeless = now < lane_get(c.fu, g - 1);
   int C = 0;
@@ -441,7 +448,7 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
       // variant: the replica that ran the previous cell leads again if its host can bind
       const uint32_t last = hw >> 30;
       if (last != 0) {
-        const int hp = (int)((hw >> (10 * (last - 1u))) & 1023u);
+        const int hp = (int)slot_host(hw, last - 1u);
         if ((idle_ok >> hp) & 1u) hl = hp;
       }
     }
@@ -528,6 +535,7 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
   // (d) queue and retry periodically, then give up, Section 3.2.3
   int retries = (int)((fl >> 8) & 15u);
   if (retries < c.p.max_retries) {
+    const bool first = retries == 0;             // an arrival comes in with the count at 0, a retry never
     retries++;
     // A retry that is bound to fail only bumps the retry count: skip straight to the first retry
     // that could succeed (or to the last one, which aborts). Valid while no host can be added:
@@ -537,12 +545,12 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
       const int32_t bound = lane_get(c.fu, g - 1);
       while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
     }
-    const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | SF_QONCE | ((uint32_t)retries << 8);
-    if (!(fl & SF_QONCE)) {                      // first time in the queue: the submit time goes in
+    const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_QUEUED | ((uint32_t)retries << 8);
+    if (first) {                                 // first time in the queue: the submit time goes in
       c32_add(c.m, c.lane, CS_QUEUED, 1u);
-      if (c.lane == 0) { c.m.sess[s].y = t_submit; c.m.sess[s].z = (int)nfl; }
+      if (c.lane == 0) c.m.sess[s] = make_int2((int)nfl, t_submit);
     } else {
-      if (c.lane == 0) c.m.sess[s].z = (int)nfl;
+      if (c.lane == 0) c.m.sess[s].x = (int)nfl;
     }
     r.dirty |= wballot(c.vsid == s);
     timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
@@ -550,7 +558,7 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
   }
   c32_add(c.m, c.lane, CS_ABORTED, 1u);
   decide(c, r, now, NBOS_D_ABORT, s, 0, 0);
-  const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
+  const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_PLACED;
   sess_write(c, r, s, hw, 0, nfl);
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
 }
@@ -576,14 +584,14 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
     if ((key >> 16) != QK_RETRY) break;
     const uint32_t s = key & 0xFFFFu;
     wave_sync();
-    const int4 rec = c.m.sess[s];
-    const uint32_t hw = uni((uint32_t)rec.x), fl = uni((uint32_t)rec.z);
+    const int2 rec = c.m.sess[s];
+    const uint32_t hw = uni((uint32_t)rec.x), fl = hw;
     const int32_t t_submit = uni(rec.y);
     int retries = (int)((fl >> 8) & 15u);
     if (retries >= c.p.max_retries) break;                     // the abort is the general path's
     const int g = (int)((fl >> 3) & 7u) + 1;
     if (now >= lane_get(c.fu, g - 1)) {
-      const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+      const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
       const int C = committed(c, now);
       const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);
       if (idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2))) break;          // the election succeeds
@@ -606,7 +614,7 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
       while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
     }
     const uint32_t nfl = (fl & ~(15u << 8)) | ((uint32_t)retries << 8);
-    if (c.lane == 0) c.m.sess[s].z = (int)nfl;
+    if (c.lane == 0) c.m.sess[s].x = (int)nfl;
     r.dirty |= wballot(c.vsid == s);
     // ... and move the entry from lane 0 to its new place: entries before it shift down one lane
     const int32_t t_new = t_submit + retries * c.p.retry_iv;
@@ -690,8 +698,10 @@ __device__ __forceinline__ void on_session_end(Ctx<NJ, F> &c, Regs &r, uint32_t 
   }
 }
 
+// At most 128 vector registers (4 waves per SIMD): with 8-byte session records a compute unit then holds
+// 16 replays of 1,000 sessions at once.
 template <int NJ, uint32_t F>
-__global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
+__global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;
   const int lane = threadIdx.x;
@@ -707,7 +717,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   m.c64 = (unsigned long long *)q; q += 8 * 8;
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
-  m.sess = (int4 *)q;          q += (size_t)p.n_cap * 16;    // at a fixed offset: its accesses fold it in
+  m.sess = (int2 *)q;          q += (size_t)p.n_cap * 8;     // at a fixed offset: its accesses fold it in
   m.warm = (int32_t *)q;                                     // only there with the pool
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
@@ -719,12 +729,13 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   }
   for (int s = lane; s < n_sess; s += WAVE) {
     uint32_t g = p.sess_gpus[s_lo + s];
-    m.sess[s] = make_int4(0, 0, (int)(SS_UNPLACED | ((g - 1u) << 3)), 0);
+    m.sess[s] = make_int2((int)(SS_UNPLACED | ((g - 1u) << 3)), 0);
   }
   __syncthreads();
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
-  Ctx<NJ, F> c{p, m, lane, n_sess, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+  Ctx<NJ, F> c{p, m, lane, n_sess, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
+               p.ovf_dur + (int64_t)rep * p.n_cap};
 #pragma unroll
   for (int j = 0; j < NJ; j++) c.fin[j] = 0;
   c.hr = lane < p.H0 ? 0 : NEVER;
@@ -752,7 +763,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
   // never touches the registers of the tile in flight.
   bool final = false;
   while (r.status == NBOS_OK) {
-    int4 rec = make_int4(0, 0, 0, 0);       // prefetched session record of this lane's event
+    int2 rec = make_int2(0, 0);             // prefetched session record of this lane's event
     uint32_t fast = 0;                      // this lane's event is a cell of an idle placed session
     uint64_t todo = 0;
     if (base < ev_hi) {
@@ -772,14 +783,14 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
       // session's running cell lasts beyond them change nothing: count them, skip them. Neither
       // condition can be undone before the event's time. The last event of the trace is never
       // skipped, so timers due before it still run first.
-      const uint32_t st = (uint32_t)rec.z & 7u;
+      const uint32_t st = (uint32_t)rec.x & 7u;
       const bool dead = st == SS_REJECTED || st == SS_ENDED;
       const bool running = st == SS_PLACED && rec.y > vt;
       const bool skip = valid && !is_last && (dead || (is_cell && running));
       r.c_total += (uint32_t)__builtin_popcountll(wballot(valid && is_cell));
       r.c_unplaced += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && dead));
       r.c_busy += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && !dead));
-      fast = (valid && is_cell && st == SS_PLACED && !running && !((uint32_t)rec.z & SF_ENDING)) ? 1u : 0u;
+      fast = (valid && is_cell && st == SS_PLACED && !running && !((uint32_t)rec.x & SF_ENDING)) ? 1u : 0u;
       todo = wballot(valid && !skip);
       r.dirty = 0;
       if (ev_hi - cur <= WAVE) {
@@ -808,22 +819,22 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
         if (__builtin_expect((fastmask & ~r.dirty & bit) != 0, 1)) {
           // a cell of an idle placed session whose record nobody touched since the prefetch
           a_s = s; a_hw = (uint32_t)lane_get(rec.x, i);
-          a_fl = (uint32_t)lane_get(rec.z, i);
+          a_fl = a_hw;
           a_now = t; a_sub = t; a_dur = lane_get(vd, i);
         } else {
           const uint32_t kind = sk >> 24;
           uint32_t hw, fl;
           int32_t tm;
           if ((r.dirty >> i) & 1u) {
-            int4 cur = m.sess[s];
-            hw = uni((uint32_t)cur.x); tm = uni(cur.y); fl = uni((uint32_t)cur.z);
+            int2 cur = m.sess[s];
+            hw = uni((uint32_t)cur.x); tm = uni(cur.y); fl = hw;
           } else {
-            hw = (uint32_t)lane_get(rec.x, i); tm = lane_get(rec.y, i); fl = (uint32_t)lane_get(rec.z, i);
+            hw = (uint32_t)lane_get(rec.x, i); tm = lane_get(rec.y, i); fl = hw;
           }
           if (kind == NBOS_EV_CELL) {           // S4-S8 (counted in c_total at tile load)
             const uint32_t st = fl & 7u;
             if (st == SS_PLACED && tm <= t) {
-              a_s = s; a_hw = hw; a_fl = fl & ~(SF_QONCE | (15u << 8)); a_now = t; a_sub = t; a_dur = lane_get(vd, i);
+              a_s = s; a_hw = hw; a_fl = fl & ~(15u << 8); a_now = t; a_sub = t; a_dur = lane_get(vd, i);
             } else {
               if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++; else r.c_unplaced++;
               continue;
@@ -867,8 +878,8 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_reg_kernel(KParams p) {
         timer_pop(c, r);
         r.t_end = r.t_end > now ? r.t_end : now;
         const uint32_t s = key & 0xFFFFu;
-        const int4 cur = m.sess[s];
-        const uint32_t hw = uni((uint32_t)cur.x), fl = uni((uint32_t)cur.z);
+        const int2 cur = m.sess[s];
+        const uint32_t hw = uni((uint32_t)cur.x), fl = hw;
         if ((key >> 16) != QK_RETRY) {
           end_session(c, r, s, hw, fl, now);
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;

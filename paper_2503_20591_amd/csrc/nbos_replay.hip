@@ -119,6 +119,7 @@ struct nbos_replay {
   const void *kernel;      // the kernel instance chosen at create
   nbos_stats *d_stats;
   nbos_bill *d_bill;
+  int32_t *d_ovf;          // register kernel only
   uint64_t *d_log;
   std::vector<int64_t> ev_off;
   std::vector<int32_t> sess_off;
@@ -132,6 +133,7 @@ void free_handle(nbos_replay *h) {
   if (!h) return;
   if (h->d_stats) (void)hipFree(h->d_stats);
   if (h->d_bill) (void)hipFree(h->d_bill);
+  if (h->d_ovf) (void)hipFree(h->d_ovf);
   if (h->d_log) (void)hipFree(h->d_log);
   if (h->e0) (void)hipEventDestroy(h->e0);
   if (h->e1) (void)hipEventDestroy(h->e1);
@@ -214,7 +216,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   nbos_replay *h = new (std::nothrow) nbos_replay();
   if (!h) return NBOS_E_NOMEM;
   h->cfg = *cfg; h->in = *in; h->stream = (hipStream_t)stream;
-  h->d_stats = nullptr; h->d_bill = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
+  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   int32_t rc = NBOS_OK;
 #define HIP_TRY(x) do { if ((x) != hipSuccess) { rc = NBOS_E_HIP; goto fail; } } while (0)
   {
@@ -255,25 +257,52 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
     } else if (in_regs) {
-      h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + (size_t)n_cap * 16;
+      h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + (size_t)n_cap * 8;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       // The common policy flag sets have kernels compiled for them (everything that is switched off
-      // is gone from the code). They have the shorter path per item, which is what counts while a
-      // replay has a SIMD to itself (up to 4 workgroups per compute unit): 10 % faster there. They
-      // also execute about 9 % more scalar instructions (measured with SQ_INSTS_SALU; the generic
-      // kernel keeps its flag tests in spilled registers), and a batch that fills every SIMD many
-      // times over is bound by instruction issue: there the generic kernel is 5 % faster.
+      // is gone from the code). They have the shorter path per item and need fewer registers; the
+      // generic kernel executes about 9 % fewer scalar instructions (it keeps hoisted flag tests in
+      // spilled registers). Which one is faster depends on what bounds the batch (all measured):
+      //  - a replay has a SIMD to itself (at most 4 workgroups per compute unit): the length of the
+      //    path counts, the instance for the flag set is 10 % faster;
+      //  - 5 or more waves per SIMD resident: instruction issue counts, the generic kernel is 5 %
+      //    faster;
+      //  - in between, waves hide little of each other's latency and a batch that does not fit at
+      //    once runs in rounds: the kernel that needs fewer rounds wins, the generic one on a tie
+      //    (64 hosts, 4,096 replays: 297 ms with 16 workgroups per compute unit resident, 436 ms
+      //    with 12; the kernels are compiled for at most 128 registers so that 16 fit).
       const int nj = (cfg->hosts_max + 7) / 8;
       const uint32_t policy = cfg->flags & regk::kPolicyFlags;
+      const void *generic = reg_kernel_for<regk::kRuntimeFlags>(nj);
+      const void *special = policy == 0u ? reg_kernel_for<0u>(nj)
+                          : policy == NBOS_F_MIGRATE ? reg_kernel_for<NBOS_F_MIGRATE>(nj)
+                          : policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT) ? reg_kernel_for<NBOS_F_MIGRATE | NBOS_F_SCALE_OUT>(nj)
+                          : generic;
       int cus = 0;
       HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
       const char *ng = getenv("NBOS_REPLAY_GENERIC");         // "0" / "1" force the choice (comparison runs)
-      const bool generic = ng && (ng[0] == '0' || ng[0] == '1') ? ng[0] == '1' : cfg->n_replays > 4 * cus;
-      if (generic) h->kernel = reg_kernel_for<regk::kRuntimeFlags>(nj);
-      else if (policy == 0u) h->kernel = reg_kernel_for<0u>(nj);
-      else if (policy == NBOS_F_MIGRATE) h->kernel = reg_kernel_for<NBOS_F_MIGRATE>(nj);
-      else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) h->kernel = reg_kernel_for<NBOS_F_MIGRATE | NBOS_F_SCALE_OUT>(nj);
-      else h->kernel = reg_kernel_for<regk::kRuntimeFlags>(nj);
+      bool use_generic;
+      if (ng && (ng[0] == '0' || ng[0] == '1')) {
+        use_generic = ng[0] == '1';
+      } else {
+        const int per_cu = cus > 0 ? (cfg->n_replays + cus - 1) / cus : cfg->n_replays;
+        hipFuncAttributes fa_g, fa_s;
+        HIP_TRY(hipFuncGetAttributes(&fa_g, generic));
+        HIP_TRY(hipFuncGetAttributes(&fa_s, special));
+        const int by_lds = (int)((size_t)maxlds / ((h->lds_bytes + 511) / 512 * 512));
+        auto resident = [&](const hipFuncAttributes &fa) {      // workgroups (= waves) per compute unit
+          const int regs = (fa.numRegs + 7) / 8 * 8;
+          int per_simd = regs > 0 ? 512 / regs : 8;
+          per_simd = per_simd > 8 ? 8 : per_simd;
+          const int by_regs = 4 * per_simd;
+          return by_lds < by_regs ? by_lds : by_regs;
+        };
+        const int res_g = resident(fa_g) > 0 ? resident(fa_g) : 1, res_s = resident(fa_s) > 0 ? resident(fa_s) : 1;
+        if (per_cu <= 4) use_generic = false;
+        else if ((per_cu < res_g ? per_cu : res_g) >= 20) use_generic = true;
+        else use_generic = (per_cu + res_s - 1) / res_s >= (per_cu + res_g - 1) / res_g;
+      }
+      h->kernel = use_generic ? generic : special;
     } else {
       size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 12;
       if (fixed + 12 * 64 > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
@@ -316,6 +345,8 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     if (cfg->n_replays > 0) {
       if (hipMalloc(&h->d_stats, sizeof(nbos_stats) * (size_t)cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
       if (hipMalloc(&h->d_bill, sizeof(nbos_bill) * (size_t)cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
+      if (in_regs &&
+          hipMalloc(&h->d_ovf, sizeof(int32_t) * (size_t)cfg->n_replays * (size_t)n_cap) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
     }
     int64_t log_stride = 0;
     if ((cfg->flags & NBOS_F_DECISION_LOG) && cfg->n_replays > 0) {
@@ -336,7 +367,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     k.ev_offset = in->ev_offset; k.ev_time = in->ev_time_ms; k.ev_dur = in->ev_dur_ms; k.ev_sk = in->ev_sess_kind;
     k.sess_offset = in->sess_offset; k.sess_gpus = in->sess_gpus;
     k.trace_of_replay = in->trace_of_replay; k.cap_milli = in->cap_milli;
-    k.stats = h->d_stats; k.dlog = h->d_log; k.dlog_stride = log_stride;
+    k.stats = h->d_stats; k.dlog = h->d_log; k.dlog_stride = log_stride; k.ovf_dur = h->d_ovf;
     k.n_replays = cfg->n_replays; k.H0 = cfg->hosts_initial; k.Hmax = cfg->hosts_max; k.HP = HP;
     k.G = cfg->gpus_per_host; k.flags = cfg->flags;
     k.migr = cfg->migration_delay_ms; k.boot = cfg->boot_delay_ms; k.retry_iv = cfg->retry_interval_ms;
