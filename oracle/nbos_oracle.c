@@ -645,6 +645,7 @@ void orc_billing(const orc_result *r, int G, int64_t price, int markup_pct, int 
   /* time replicas spent executing: every started cell runs for its duration */
   int64_t exec_ms = r->sum_tct_ms - r->sum_delay_ms;
   int64_t standby_ms = r->replica_ms - exec_ms;
+  if (standby_ms < 0) standby_ms = 0;             /* no replicas (Batch baseline): nothing stands by */
   /* host-hours = GPU-ms / (G * ms per hour) */
   out->provider_cost = ratio(r->gpu_ms_provisioned, price, (int64_t)G * ms_per_hour);
   out->usage_revenue = ratio(r->gpu_ms_executed, price * markup_pct, (int64_t)G * ms_per_hour * 100);

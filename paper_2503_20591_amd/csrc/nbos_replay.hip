@@ -95,7 +95,8 @@ __global__ void nbos_billing_kernel(const nbos_stats *stats, int first, int coun
   const nbos_stats &s = stats[first + i];
   const uint64_t ms_per_hour = 3600000u;
   const uint64_t exec_ms = (uint64_t)(s.sum_tct_ms - s.sum_delay_ms);      // every started cell runs its duration
-  const uint64_t standby_ms = (uint64_t)s.replica_ms - exec_ms;
+  // no replicas (Batch baseline): nothing stands by
+  const uint64_t standby_ms = (uint64_t)s.replica_ms > exec_ms ? (uint64_t)s.replica_ms - exec_ms : 0u;
   const uint64_t marked = (uint64_t)price * (uint64_t)markup_pct;
   nbos_bill b;
   b.provider_cost = (int64_t)muldiv_floor((uint64_t)s.gpu_ms_provisioned, (uint64_t)price, (uint64_t)G * ms_per_hour);

@@ -34,6 +34,13 @@ def gpu_run(rp, batch, log=False, in_lds=False):
     return st, logs
 
 
+def as_batch(b, delay, scale_out):
+    b.config.update(flags=tg.F_BATCH_MODE | (tg.F_SCALE_OUT if scale_out else 0), batch_start_delay_ms=delay)
+    if not scale_out:
+        b.config["hosts_max"] = b.config["hosts_initial"]
+    return b
+
+
 def first_diff(a, b, orc):
     for i, (x, y) in enumerate(zip(a, b)):
         if int(x) != int(y):
@@ -166,6 +173,22 @@ def test_billing_printed_example_gpu(rp):
     assert int(bill["reservation_revenue"]) == 11_500_000
 
 
+def test_billing_of_the_batch_baseline(rp, oracle):
+    # no replicas there: no standby charge, usage and provider cost as usual
+    b = as_batch(tg.random_case(5, n_replays=3), delay=500, scale_out=False)
+    dev = rp.upload(b)
+    h = rp.Replay(b.config, dev)
+    h.run()
+    bills = h.billing(10_000_000)
+    h.close()
+    want = oracle.replay_batch(b)
+    for r in range(b.n_replays):
+        exp = oracle.billing(want[r], b.config["gpus_per_host"], 10_000_000)
+        assert exp["standby_revenue"] == 0
+        for k, v in exp.items():
+            assert int(bills[k][r]) == v, (r, k)
+
+
 def test_billing_rejects_bad_arguments(rp):
     b = tg.random_case(1, n_replays=2)
     dev = rp.upload(b)
@@ -214,13 +237,6 @@ def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, gener
 
 
 # ---- Batch baseline (Section 5.1.3) ------------------------------------------------------------------
-
-def as_batch(b, delay, scale_out):
-    b.config.update(flags=tg.F_BATCH_MODE | (tg.F_SCALE_OUT if scale_out else 0), batch_start_delay_ms=delay)
-    if not scale_out:
-        b.config["hosts_max"] = b.config["hosts_initial"]
-    return b
-
 
 @pytest.mark.parametrize("seed", range(60))
 def test_batch_mode_random_cases(rp, oracle, seed):

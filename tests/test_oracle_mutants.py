@@ -59,7 +59,7 @@ MUTANTS = [
     ("dynamic limit: divides by hosts_max", "(h->S + g) * m->n_on <=", "(h->S + g) * m->H <="),
     ("dynamic limit replaces the cap", "if ((int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*",
      "if (!(m->p->flags & ORC_F_DYNAMIC_SR) && (int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*"),
-    ("billing: standby charge not reduced by the executing time", "int64_t standby_ms = r->replica_ms - exec_ms;", "int64_t standby_ms = r->replica_ms;"),
+    ("billing: standby charge not reduced by the executing time", "int64_t standby_ms = r->replica_ms - exec_ms;\n", "int64_t standby_ms = r->replica_ms;\n"),
     ("billing: markup dropped from the usage charge", "ratio(r->gpu_ms_executed, price * markup_pct, (int64_t)G * ms_per_hour * 100)", "ratio(r->gpu_ms_executed, price * 100, (int64_t)G * ms_per_hour * 100)"),
     ("billing: standby share applied per GPU", "ratio(standby_ms, price * markup_pct * standby_permille, ms_per_hour * 100 * 1000)", "ratio(standby_ms, price * markup_pct * standby_permille, (int64_t)G * ms_per_hour * 100 * 1000)"),
     ("billing: provider cost per GPU-hour", "ratio(r->gpu_ms_provisioned, price, (int64_t)G * ms_per_hour)", "ratio(r->gpu_ms_provisioned, price, ms_per_hour)"),
