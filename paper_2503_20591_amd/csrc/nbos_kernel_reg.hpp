@@ -126,7 +126,7 @@ __device__ __forceinline__ void decide(Ctx<NJ, F> &c, Regs &r, int32_t now, uint
   uint64_t code = (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) |
                   ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
   r.digest = r.digest * 0x100000001B3ULL + code;
-  if (c.dlog) {
+  if (__builtin_expect(c.dlog != nullptr, 0)) {
     if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
   }
   r.n_dec++;
@@ -397,7 +397,7 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
   hw = (hw & ~(63u << (12 + 6 * slot))) | ((uint32_t)host << (12 + 6 * slot));
   // the record's word: hosts and last executor from hw, state back to "placed", retry count cleared
   const uint32_t nw = (hw & ~RK_FLAGS) | (((fl & ~(7u | (15u << 8))) | SS_PLACED) & RK_FLAGS);
-  if (delay == 0) {
+  if (__builtin_expect(delay == 0, 1)) {
     r.h0++;                                     // histogram bin 0 lives in a register
     if (c.lane == 0) c.m.sess[s] = make_int2((int)nw, finish);
   } else {
@@ -414,7 +414,7 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
   r.dirty |= wballot(c.vsid == s);
   r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
   decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
-  if (fl & SF_ENDING) timer_push(c, r, finish, QK_END, s, 0);
+  if (__builtin_expect((fl & SF_ENDING) != 0, 0)) timer_push(c, r, finish, QK_END, s, 0);
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
@@ -569,7 +569,8 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
 // nothing but the session's retry count and its place in the timer queue. This loop takes due
 // retries off the head of the sorted registers for as long as they are of that kind (same tests as
 // attempt(), same order), re-inserting each with one pass over the registers; the first timer that
-// needs anything else is left for the general path. t_limit = time of the next arrival (timers due
+// needs anything else is left for the general path. A retry that fails with no retries left gives its
+// cell up right here. t_limit = time of the next arrival (timers due
 // at or before it run first), tick_t = next auto-scaler period (a timer due at the same time runs
 // before it). Returns the time of the last retry handled, or -1.
 template <int NJ, uint32_t F>
@@ -588,7 +589,8 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
     const uint32_t hw = uni((uint32_t)rec.x), fl = hw;
     const int32_t t_submit = uni(rec.y);
     int retries = (int)((fl >> 8) & 15u);
-    if (retries >= c.p.max_retries) break;                     // the abort is the general path's
+    const bool give_up = retries >= c.p.max_retries;           // no retry left: the cell is aborted
+    if (give_up && (fl & SF_ENDING)) break;                    // ... and the session ends: general path
     const int g = (int)((fl >> 3) & 7u) + 1;
     if (now >= lane_get(c.fu, g - 1)) {
       const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
@@ -606,6 +608,20 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
     if (c.flags() & NBOS_F_SCALE_OUT) {
       wave_sync();
       if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) break;                            // a host can be added
+    }
+    last = now;
+    if (give_up) {
+      // it fails for the last time: the cell is given up, the session is idle again, the timer goes
+      c32_add(c.m, c.lane, CS_ABORTED, 1u);
+      decide(c, r, now, NBOS_D_ABORT, s, 0, 0);
+      if (c.lane == 0) c.m.sess[s] = make_int2((int)((fl & ~(7u | (15u << 8))) | SS_PLACED), 0);
+      r.dirty |= wballot(c.vsid == s);
+      c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                      // wave_shl:1
+      c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
+      c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
+      r.q_n--;
+      r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
+      continue;
     }
     // it fails again: bump the retry count (skipping retries that are bound to fail as well) ...
     retries++;
@@ -627,7 +643,6 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
     if (c.lane < pos) { c.qt = st; c.qd = sd; c.qk = sk; }
     if (c.lane == pos) { c.qt = t_new; c.qd = d_own; c.qk = key; }
     r.q_head_t = lane_get(c.qt, 0);
-    last = now;
   }
   return last;
 }
