@@ -610,7 +610,7 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
       if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) break;                            // a host can be added
     }
     last = now;
-    if (give_up) {
+    if (__builtin_expect(give_up, 0)) {
       // it fails for the last time: the cell is given up, the session is idle again, the timer goes
       c32_add(c.m, c.lane, CS_ABORTED, 1u);
       decide(c, r, now, NBOS_D_ABORT, s, 0, 0);
