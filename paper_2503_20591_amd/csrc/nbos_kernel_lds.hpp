@@ -936,7 +936,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
           const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
           if ((run & (run - 1)) != 0) {          // at least two lanes
             const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec);
-            cooldown = done == 0 ? 4 : ((done & (done - 1)) == 0 ? 2 : 0);   // poor yield: go serial for a bit
+            cooldown = (done & (done - 1)) == 0 ? 1 : 0;    // none or one started: the next arrival goes alone
             if (done != 0) { todo &= ~done; continue; }
           }
         }
