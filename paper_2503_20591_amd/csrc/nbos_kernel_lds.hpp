@@ -23,10 +23,11 @@
 // Event-parallel rounds: lane = event. A run of consecutive cell arrivals of idle placed sessions
 // with no timer due before them is evaluated at once: every lane gathers the rows of its session's
 // three hosts, counts committed GPUs at its own time and elects. A lane's result equals the serial
-// one iff no earlier lane of the run binds GPUs on one of its three hosts (its inputs are then
-// untouched) and no earlier lane failed its election (a failed election may migrate anywhere). The
-// longest prefix with that property is committed at once - the chosen hosts are pairwise distinct
-// by construction - and the rest is evaluated again. Counters are reduced over the prefix; the
+// one if no earlier lane of the run binds GPUs on the host it chose (an earlier lane that binds on
+// one of its other two hosts only makes that host a worse candidate: the choice stands) and no
+// earlier lane failed its election (a failed election may migrate anywhere). The longest prefix
+// with that property is committed at once - the chosen hosts are pairwise distinct by
+// construction - and the rest is evaluated again. Counters are reduced over the prefix; the
 // decision digest d*P + code is folded as d*P^n + sum(code_i * P^(n-1-i)) with a table of powers.
 //
 // Events: coalesced dword loads, one event per lane, next tile in flight while the current tile is
@@ -741,8 +742,7 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   // who binds where: the lowest lane that chose a host marks it
   if (won) atomicMin(&c.m.mark[ch], c.lane);
   wave_sync();
-  const int32_t m0 = c.m.mark[h0], m1 = c.m.mark[h1], m2 = c.m.mark[h2];
-  const int32_t first = m0 < m1 ? (m0 < m2 ? m0 : m2) : (m1 < m2 ? m1 : m2);
+  const int32_t first = c.m.mark[ch];        // the lowest lane that binds on the host this lane chose
   wave_sync();
   if (won) c.m.mark[ch] = MARK_FREE;
   const uint64_t bad = run & wballot(in_run && (!won || first < c.lane));
