@@ -19,7 +19,7 @@ _SRC_BATCH = os.path.join(_DIR, "nbos_oracle_batch.c")
 _LIB = os.path.join(_DIR, "libnbos_oracle.so")
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
-F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY, F_BATCH, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
+F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY, F_BATCH, F_WARM_POOL, F_CLOSED_LOOP = 0x20, 0x40, 0x80, 0x100, 0x200, 0x400
 EV_START, EV_CELL, EV_END = 0, 1, 2
 (D_PLACE, D_PLACE_NEW, D_REJECT, D_START, D_MIGRATE, D_SCALE_CELL, D_ABORT, D_SCALE_IN,
  D_SCALE_AUTO, D_BATCH_START, D_BATCH_HOST, D_MIGRATE_WARM) = range(1, 13)

@@ -51,6 +51,16 @@
  *     available longest, if one is available now: the cell then starts after
  *     warm_migration_delay_ms instead of migration_delay_ms, and a replacement is
  *     available prewarm_delay_ms later. A host added for the cell has none yet.
+ *   - closed loop (ORC_F_CLOSED_LOOP; Section 2.2 describes users who think, edit and
+ *     re-submit between cells): only a session's first START keeps its time. Every
+ *     later CELL / END of the session is due one think time after the session's
+ *     previous cell is over (finished or given up; for the first one: after the
+ *     placement), where the think time is what the trace leaves between the
+ *     previous event's nominal end (its time, plus its duration for a CELL) and the
+ *     event's own time, at least 0. Events before the first START, repeated STARTs
+ *     and everything after the first END are ignored. Due events run as timers
+ *     after RETRY timers of the same instant, by ascending session id. No cell
+ *     ever meets a busy session. Not combined with the periodic auto-scaler.
  *   - sticky executor (ORC_F_STICKY): when the replica that executed the session's
  *     previous cell can lead (host ready, enough idle GPUs) it does; else the rule above.
  */
@@ -63,7 +73,7 @@
 
 enum { H_OFF = 0, H_BOOT = 1, H_READY = 2 };
 enum { S_UNPLACED = 0, S_IDLE = 1, S_BUSY = 2, S_REJECTED = 3, S_ENDED = 4 };
-enum { T_COMPLETE = 0, T_HOST_READY = 1, T_RETRY = 2, T_TICK = 3 };
+enum { T_COMPLETE = 0, T_HOST_READY = 1, T_RETRY = 2, T_NEXT = 3, T_TICK = 4 };
 
 typedef struct { int32_t time; int32_t prio; int32_t id; } tmr;
 
@@ -107,6 +117,11 @@ typedef struct {
   uint32_t chk_starts_seen;
   tmr last_popped; int have_last;
   int err;
+  /* closed loop: the trace, each session's chain of events and where it stands */
+  const int32_t *ev_dur, *ev_sk;
+  int32_t *think;           /* [n_events] think time before the event       */
+  int64_t *next_ev;         /* [n_events] next event of the same session, -1 */
+  int64_t *cursor;          /* [n_sess] the session's next event, -1 = none  */
 } sim;
 
 /* ---- pending timers: textbook binary min-heap on (time, prio, id) ---------- */
@@ -206,6 +221,15 @@ static int boot_host(sim *m) {
   return -1;
 }
 
+/* closed loop: the session's next event is due one think time after `base` */
+static void schedule_next(sim *m, int s, int32_t base) {
+  int64_t e = m->cursor[s];
+  if (e < 0) return;
+  int64_t t = (int64_t)base + m->think[e];
+  if (t >= 2147483647LL) { m->err = ORC_E_INPUT; return; }     /* beyond the int32 time range */
+  heap_push(m, (int32_t)t, T_NEXT, s);
+}
+
 /* ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 ---------------------------- */
 static void on_session_start(sim *m, int s) {
   sess_rec *q = &m->sess[s];
@@ -246,12 +270,14 @@ static void on_session_start(sim *m, int s) {
   q->state = S_IDLE;
   q->t_placed = m->clock;
   m->r.sessions_placed++;
+  if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, m->clock);
 }
 
 /* ---- a cell starts: Section 3.3 (bind GPUs), metrics of Sections 5.2.2-5.2.4 - */
 static void start_cell(sim *m, int s, int slot, int32_t start, int outcome) {
   sess_rec *q = &m->sess[s];
   int32_t commit_t = m->clock;
+  if ((int64_t)start + q->dur >= 2147483647LL) { m->err = ORC_E_INPUT; return; }   /* closed loop only */
   int32_t finish = start + q->dur;
   int32_t delay = start - q->t_submit;
   q->exec_slot = slot;
@@ -270,6 +296,7 @@ static void start_cell(sim *m, int s, int slot, int32_t start, int outcome) {
   if (q->last_exec == slot) m->r.executor_reused++;
   q->last_exec = slot;
   decide(m, outcome, s, slot, q->host[slot]);
+  if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, finish);
 }
 
 static void end_session(sim *m, int s) {
@@ -362,6 +389,7 @@ static void attempt(sim *m, int s) {
   if (q->retries < m->p->max_retries) {
     q->retries++;
     if (!q->queued_once) { q->queued_once = 1; m->r.cells_queued++; }
+    if ((int64_t)q->t_submit + (int64_t)q->retries * m->p->retry_interval_ms >= 2147483647LL) { m->err = ORC_E_INPUT; return; }
     heap_push(m, q->t_submit + q->retries * m->p->retry_interval_ms, T_RETRY, s);
     return;
   }
@@ -369,6 +397,7 @@ static void attempt(sim *m, int s) {
   m->r.cells_aborted++;
   decide(m, ORC_D_ABORT, s, 0, 0);
   if (q->ending) end_session(m, s);
+  if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, m->clock);
 }
 
 static void on_cell(sim *m, int s, int32_t dur) {
@@ -490,6 +519,13 @@ static void run_timer(sim *m, tmr t) {
     case T_COMPLETE:   on_complete(m, t.id); break;
     case T_HOST_READY: m->hosts[t.id].state = H_READY; break;
     case T_RETRY:      attempt(m, t.id); break;
+    case T_NEXT: {                                   /* closed loop: the session's next event is due */
+      int64_t e = m->cursor[t.id];
+      m->cursor[t.id] = m->next_ev[e];
+      if ((int)((uint32_t)m->ev_sk[e] >> 24) == ORC_EV_CELL) on_cell(m, t.id, m->ev_dur[e]);
+      else { on_session_end(m, t.id); m->cursor[t.id] = -1; }
+      break;
+    }
     case T_TICK:
       on_tick(m);
       heap_push(m, t.time + m->p->scale_interval_ms, T_TICK, 0);
@@ -507,7 +543,8 @@ static int validate(const orc_params *p, int64_t n_events, const int32_t *ev_tim
   if (p->max_retries < 0 || p->max_retries > 15) return ORC_E_ARG;
   if (p->cap_milli < 1 || p->cap_milli > 100000) return ORC_E_ARG;
   if (p->flags & ~(uint32_t)(ORC_F_MIGRATE | ORC_F_SCALE_OUT | ORC_F_SCALE_IN | ORC_F_AUTOSCALE |
-                            ORC_F_DYNAMIC_SR | ORC_F_STICKY | ORC_F_WARM_POOL)) return ORC_E_ARG;
+                            ORC_F_DYNAMIC_SR | ORC_F_STICKY | ORC_F_WARM_POOL | ORC_F_CLOSED_LOOP)) return ORC_E_ARG;
+  if ((p->flags & ORC_F_CLOSED_LOOP) && (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE))) return ORC_E_ARG;
   if (p->flags & ORC_F_WARM_POOL) {
     if (p->warm_pool_per_host < 1 || p->warm_pool_per_host > 4) return ORC_E_ARG;
     if (p->warm_migration_delay_ms < 0 || p->prewarm_delay_ms < 0) return ORC_E_ARG;
@@ -571,10 +608,42 @@ int orc_replay(const orc_params *p,
   }
   m.r.digest = 0xCBF29CE484222325ULL;
   if (p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) heap_push(&m, p->scale_interval_ms, T_TICK, 0);
+  const int closed = (p->flags & ORC_F_CLOSED_LOOP) != 0;
+  char *first_start = NULL;
+  if (closed) {
+    /* chain every session's events: first START, then its CELLs up to and including its first END */
+    size_t ne = (size_t)(n_events > 0 ? n_events : 1), ns = (size_t)(n_sessions > 0 ? n_sessions : 1);
+    m.ev_dur = ev_dur; m.ev_sk = ev_sk;
+    m.think = (int32_t *)calloc(ne, sizeof(int32_t));
+    m.next_ev = (int64_t *)malloc(ne * sizeof(int64_t));
+    m.cursor = (int64_t *)malloc(ns * sizeof(int64_t));
+    first_start = (char *)calloc(ne, 1);
+    int64_t *last = (int64_t *)malloc(ns * sizeof(int64_t));       /* last chained event of the session */
+    int32_t *anchor = (int32_t *)calloc(ns, sizeof(int32_t));      /* its nominal end                   */
+    char *closed_s = (char *)calloc(ns, 1);                        /* the session's END has been seen   */
+    if (!m.think || !m.next_ev || !m.cursor || !first_start || !last || !anchor || !closed_s) m.err = ORC_E_NOMEM;
+    for (int s = 0; s < n_sessions && !m.err; s++) { m.cursor[s] = -1; last[s] = -1; }
+    for (int64_t i = 0; i < n_events && !m.err; i++) {
+      int kind = (int)((uint32_t)ev_sk[i] >> 24), s = ev_sk[i] & 0xFFFFFF;
+      m.next_ev[i] = -1;
+      if (kind == ORC_EV_START) {
+        if (last[s] < 0) { first_start[i] = 1; last[s] = i; anchor[s] = ev_time[i]; }
+        continue;
+      }
+      if (last[s] < 0 || closed_s[s]) continue;
+      m.think[i] = ev_time[i] > anchor[s] ? ev_time[i] - anchor[s] : 0;
+      if (first_start[last[s]]) m.cursor[s] = i; else m.next_ev[last[s]] = i;
+      last[s] = i;
+      anchor[s] = kind == ORC_EV_CELL ? ev_time[i] + ev_dur[i] : ev_time[i];
+      if (kind == ORC_EV_END) closed_s[s] = 1;
+    }
+    free(last); free(anchor); free(closed_s);
+  }
 
   /* arrivals in input order; every timer due at or before an arrival runs first */
   for (int64_t i = 0; i < n_events && !m.err; i++) {
     int32_t t = ev_time[i];
+    if (closed && !first_start[i]) continue;        /* everything else comes by its session's chain */
     while (m.n_heap > 0 && m.heap[0].time <= t && !m.err) run_timer(&m, heap_pop(&m));
     if (m.err) break;
     advance(&m, t);
@@ -629,6 +698,7 @@ int orc_replay(const orc_params *p,
   *out = m.r;
   int err = m.err;
   free(m.hosts); free(m.sess); free(m.heap);
+  free(m.think); free(m.next_ev); free(m.cursor); free(first_start);
   return err;
 }
 

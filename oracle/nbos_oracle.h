@@ -20,7 +20,9 @@ enum {
   ORC_F_DYNAMIC_SR = 0x40,  /* Section 3.4.1: cluster-wide subscription ratio as the limit */
   ORC_F_STICKY = 0x80,      /* election variant: the previous executor leads again if it can */
   ORC_F_BATCH = 0x100,      /* replay the Batch baseline of Section 5.1.3 (orc_replay_batch)  */
-  ORC_F_WARM_POOL = 0x200   /* Section 3.2.3: pre-warmed containers shorten a migration        */
+  ORC_F_WARM_POOL = 0x200,  /* Section 3.2.3: pre-warmed containers shorten a migration        */
+  ORC_F_CLOSED_LOOP = 0x400 /* a session's next event comes a think time after its previous
+                               cell is over (not at its time in the trace)                    */
 };
 
 /* decision outcomes written to the log / folded into the digest */

@@ -89,6 +89,13 @@ MUTANTS = [
     ("warm pool: container available exactly now is not taken", "if (d->warm[w] <= m->clock) {", "if (d->warm[w] < m->clock) {"),
     ("warm pool: warm start pays the cold delay", "m->clock + m->p->warm_migration_delay_ms, ORC_D_MIGRATE_WARM", "m->clock + m->p->migration_delay_ms, ORC_D_MIGRATE_WARM"),
     ("warm pool: only one container per host", "for (int i = 1; i < m->p->warm_pool_per_host; i++)", "for (int i = 1; i < 1; i++)"),
+    ("closed loop: think measured from the previous event's start", "anchor[s] = kind == ORC_EV_CELL ? ev_time[i] + ev_dur[i] : ev_time[i];", "anchor[s] = ev_time[i];"),
+    ("closed loop: next event counted from the start of the cell", "if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, finish);", "if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, start);"),
+    ("closed loop: a cell that is given up ends the chain", "  if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, m->clock);\n}\n\nstatic void on_cell", "}\n\nstatic void on_cell"),
+    ("closed loop: first cell counted from time 0", "  m->r.sessions_placed++;\n  if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, m->clock);", "  m->r.sessions_placed++;\n  if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, 0);"),
+    ("closed loop: think time of the END ignored", "      m.think[i] = ev_time[i] > anchor[s] ? ev_time[i] - anchor[s] : 0;", "      m.think[i] = (kind == ORC_EV_END) ? 0 : (ev_time[i] > anchor[s] ? ev_time[i] - anchor[s] : 0);"),
+    ("closed loop: due events run before retries of the same instant", "enum { T_COMPLETE = 0, T_HOST_READY = 1, T_RETRY = 2, T_NEXT = 3, T_TICK = 4 };", "enum { T_COMPLETE = 0, T_HOST_READY = 1, T_RETRY = 3, T_NEXT = 2, T_TICK = 4 };"),
+    ("closed loop: cells keep their time in the trace", "    if (closed && !first_start[i]) continue;", "    if (0) continue;"),
     ("dynamic limit always on", "if (m->p->flags & ORC_F_DYNAMIC_SR)\n    return", "if (1)\n    return"),
     ("Reservation ignores END", "q->has_end ? q->end_time : m.clock", "m.clock"),
     ("executor reuse inverted", "if (q->last_exec == slot)", "if (q->last_exec != slot)"),
@@ -147,6 +154,9 @@ def run_pins(lib_path):
     checks.append(lambda: pins.test_dynamic_limit_brute_force(o))
     checks.append(lambda: pins.test_sticky_election_brute_force(o))
     checks += [lambda: pins.test_warm_pool_pin_sees_many_migrations(o)]
+    checks += [lambda s=s: pins.test_closed_loop_without_waiting_is_the_open_loop(o, s) for s in range(3)]
+    checks += [lambda s=s: pins.test_closed_loop_schedule_from_the_log(o, s) for s in range(5)]
+    checks += [lambda s=s: pins.test_closed_loop_never_meets_a_busy_session(o, s) for s in range(4)]
     checks += [lambda s=s: pins.test_warm_pool_that_refills_at_once_is_a_shorter_delay(o, s) for s in range(3)]
     checks += [lambda: pins.test_batch_single_server_is_the_textbook_fifo_queue(o), lambda: pins.test_batch_without_contention(o)]
     checks += [lambda s=s: pins.test_batch_order_and_capacity_random(o, s) for s in range(6)]

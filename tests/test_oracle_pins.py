@@ -712,6 +712,97 @@ def test_warm_pool_that_refills_at_once_is_a_shorter_delay(oracle, seed):
                 assert u[k] == v[k], k
 
 
+# ---- closed loop: a session's next event is due a think time after its previous cell is over -------
+
+CLOSED = 0x400
+
+
+def _nominal_trace(seed, n_sess, cells, with_end=True):
+    """START, then repeat {think; CELL; run}: the times a session would see if nothing ever waited."""
+    rng = np.random.default_rng(seed)
+    ev = []
+    for s_ in range(n_sess):
+        t = int(rng.integers(0, 50_000))
+        ev.append([t, S, s_, 0])
+        for _ in range(cells):
+            t += int(rng.integers(0, 4_000))
+            d = int(rng.integers(1, 3_000))
+            ev.append([t, CELL, s_, d])
+            t += d
+        if with_end:
+            ev.append([t + int(rng.integers(0, 2_000)), END, s_, 0])
+    ev.sort(key=lambda e: (e[0], e[2], e[1]))
+    return ev
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_closed_loop_without_waiting_is_the_open_loop(oracle, seed):
+    # plenty of hosts: no cell ever waits, so every event falls on its time in the trace and the two
+    # readings of the trace agree (the order of decisions at one instant may differ: compare as sets)
+    n = 12
+    ev = _nominal_trace(seed, n, 15)
+    gp = np.random.default_rng(seed).choice([1, 2, 4, 8], n)
+    cfg = dict(BASE, hosts_initial=40, hosts_max=40, flags=tg.F_MIGRATE)
+    x = run(oracle, cfg, ev, gp, 100000, want_log=True)
+    y = run(oracle, dict(cfg, flags=tg.F_MIGRATE | CLOSED), ev, gp, 100000, want_log=True)
+    assert x["cells_immediate"] == x["cells_total"] == 15 * n
+    for k in x:
+        if k not in ("digest", "log"):
+            assert x[k] == y[k], k
+    assert sorted(int(c) for c in x["log"]) == sorted(int(c) for c in y["log"])
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_closed_loop_schedule_from_the_log(oracle, seed):
+    # a crowded cluster without migration: re-derive every cell's submit time from the decision log
+    # (previous cell over + think) and check that its first decision falls on submit + k * retry
+    n, cells, I, R = 30, 12, 700, 3
+    ev = _nominal_trace(100 + seed, n, cells)
+    gp = np.random.default_rng(seed).choice([4, 8], n)
+    cfg = dict(BASE, hosts_initial=5, hosts_max=5, flags=CLOSED, retry_interval_ms=I, max_retries=R)
+    r = run(oracle, cfg, ev, gp, 100000, want_log=True)
+    assert r["cells_dropped_busy"] == 0 and r["cells_queued"] > 0 and r["cells_aborted"] > 0
+    per = {}
+    for code in r["log"]:
+        d = oracle.decode(code)
+        if d["outcome"] in (oracle.D_START, oracle.D_ABORT):
+            per.setdefault(d["session"], []).append(d)
+    placed = {oracle.decode(c)["session"] for c in r["log"] if oracle.decode(c)["outcome"] == oracle.D_PLACE}
+    total = 0
+    for s_ in sorted(placed):
+        mine = [e for e in ev if e[2] == s_]
+        anchor_nominal = mine[0][0]          # START
+        over = mine[0][0]                    # placement time
+        k = 0
+        for e in mine[1:]:
+            think = max(0, e[0] - anchor_nominal)
+            if e[1] == END:
+                break
+            submit = over + think
+            d = per[s_][k]; k += 1; total += 1
+            waited = d["time"] - submit
+            assert waited >= 0 and waited % I == 0 and waited // I <= R, (s_, k, d, submit)
+            if d["outcome"] == oracle.D_START:
+                over = d["time"] + e[3]
+            else:
+                assert waited == R * I
+                over = d["time"]
+            anchor_nominal = e[0] + e[3]
+        assert k == len(per.get(s_, []))
+    assert total == r["cells_total"]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_closed_loop_never_meets_a_busy_session(oracle, seed):
+    b = tg.random_case(900 + seed, n_replays=2)          # with repeated START / END and early cells
+    b.config["flags"] = (b.config["flags"] & ~(tg.F_SCALE_IN)) | CLOSED
+    n_cells = int(((b.ev_sk.view(np.uint32) >> 24) == CELL).sum())
+    for r in oracle.replay_batch(b, check=True):
+        assert r["cells_dropped_busy"] == 0
+        assert r["cells_total"] == r["cells_started"] + r["cells_aborted"] + r["cells_dropped_unplaced"]
+        assert r["cells_total"] <= n_cells
+
+
 # ---- input validation -----------------------------------------------------------------------------
 
 def test_rejects_bad_input(oracle):
