@@ -66,7 +66,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b", "c2l", "c4l"])
     ap.add_argument("--replays", type=int, default=None, help="truncate the batch (for quick looks)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 = skip")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = all host cores (at most 16)")

@@ -126,6 +126,22 @@ typedef enum {
                                       (decision NBOS_D_MIGRATE_WARM) and a replacement is available
                                       prewarm_delay_ms later. Not with NBOS_F_BATCH_MODE.        */
 
+#define NBOS_F_CLOSED_LOOP   0x400u /* closed-loop reading of the traces (Section 2.2 describes
+                                      users who think and edit between cells): only a session's
+                                      first START keeps its time. Every later CELL / END of the
+                                      session is due one think time after the session's previous
+                                      cell is over (finished or given up; the first one: after the
+                                      placement); the think time is what the trace leaves between
+                                      the previous event's nominal end (its time, plus its duration
+                                      for a CELL) and the event's own time, at least 0. Events
+                                      before the first START, repeated STARTs and everything after
+                                      the first END are ignored; cells of sessions that were not
+                                      placed never arrive (cells_total counts arrivals). Due events
+                                      run after retries of the same instant, by ascending session.
+                                      Runs on the any-size kernel; not with NBOS_F_SCALE_IN,
+                                      NBOS_F_AUTOSCALE or NBOS_F_BATCH_MODE. A replay whose lag
+                                      pushes a time to 2^31 - 1 ends with status NBOS_E_RANGE.    */
+
 /* ---- event encoding ------------------------------------------------------ */
 #define NBOS_EV_START  0
 #define NBOS_EV_CELL   1
@@ -196,7 +212,7 @@ typedef struct {
  */
 typedef struct {
   int32_t  status;              /* NBOS_OK; NBOS_E_LIMIT: retry queue overflowed; NBOS_E_RANGE (Batch
-                                   baseline): the queue pushed a job beyond the int32 time range.
+                                   baseline, closed loop): a time left the int32 range.
                                    The other fields are invalid then.                              */
   uint32_t n_decisions;
   uint32_t sessions_placed, sessions_rejected;

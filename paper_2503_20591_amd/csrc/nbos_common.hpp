@@ -18,7 +18,7 @@ constexpr uint32_t SS_UNPLACED = 0, SS_PLACED = 1, SS_QUEUED = 2, SS_REJECTED = 
 constexpr uint32_t SF_ENDING = 1u << 6, SF_QONCE = 1u << 7;
 constexpr uint32_t SF_OVF = 1u << 12;     // the session's pending timer waits outside the sorted registers
 // queue entry kinds, in the order they run when due at the same time
-constexpr uint32_t QK_END = 0, QK_RETRY = 2;
+constexpr uint32_t QK_END = 0, QK_RETRY = 2, QK_NEXT = 3;   // QK_NEXT: closed loop, the session's next event is due
 
 struct KParams {
   const int64_t *ev_offset;
@@ -39,6 +39,11 @@ struct KParams {
   int32_t warm_n, warm_migr, prewarm;   // pre-warmed containers per host, warm migration delay, pre-warm time
   int32_t n_cap, q_cap;    // LDS capacity: sessions, queue entries
   int32_t batch;           // event-parallel rounds on (LDS kernel)
+  // closed loop only: per event the think time before it (-1: the event is ignored) and the next event
+  // of its session (index within the trace, -1: none); per session of a trace its first chained event;
+  // per replay and session the event that is due next or under way
+  const int32_t *cl_think, *cl_next, *cl_first;
+  int32_t *cl_cursor;
 };
 
 __device__ __forceinline__ int32_t uni(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }

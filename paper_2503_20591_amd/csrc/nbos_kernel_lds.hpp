@@ -59,6 +59,7 @@ struct Lds {
   SessRec *sess;
   int32_t *o_t, *o_d;
   uint32_t *o_k;
+  int32_t *due;                // closed loop: [n_cap] time of a session's timer while it waits outside the registers
 };
 
 struct Regs {
@@ -77,6 +78,7 @@ struct Regs {
 // F: the policy flags when they are known at compile time (an instance of its own drops the code of
 // everything that is switched off), or kRuntimeFlags.
 constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
+constexpr uint32_t kRuntimeClosed = 0xFFFFFFFEu;     // policy flags at run time, closed-loop reading of the trace
 constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
                                   NBOS_F_STICKY_EXECUTOR | NBOS_F_WARM_POOL;
 
@@ -91,8 +93,21 @@ struct Ctx {
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
   int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
-  __device__ __forceinline__ uint32_t flags() const { return F == kRuntimeFlags ? p.flags : F; }
+  // closed loop: sessions of the trace, the replay's cursors, and the trace's per-session first event,
+  // per-event think time, next event, duration and kind word
+  int32_t n_sess;
+  int32_t *cl_cur;
+  const int32_t *cl_first, *cl_th, *cl_nx, *cl_dur, *cl_sk;
+  static constexpr bool closed = F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
+  __device__ __forceinline__ uint32_t flags() const {
+    return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
+  }
 };
+
+// closed loop: a session has at most one timer (its next event, or the retry or deferred end of the
+// cell under way), so a timer that does not fit into the sorted registers waits in the session's own
+// record: SF_OVF and the kind in the flags word, the time in due[s]
+constexpr uint32_t CL_KIND_SHIFT = 13, CL_TIMER_BITS = SF_OVF | (3u << CL_KIND_SHIFT);
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
   if (lane == 0) atomicAdd(&m.c32[idx], v);
@@ -170,12 +185,64 @@ __device__ __forceinline__ void ovf_rescan(Ctx<F> &c, Regs &r) {
 
 template <uint32_t F>
 __device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
-  if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
-  if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
+  if constexpr (Ctx<F>::closed) {
+    const uint32_t s = k & 0xFFFFu;
+    if (c.lane == 0) {
+      const uint32_t z = (uint32_t)c.m.sess[s].z;
+      c.m.sess[s].z = (int)((z & ~CL_TIMER_BITS) | SF_OVF | ((k >> 16) << CL_KIND_SHIFT));
+      c.m.due[s] = t;
+    }
+  } else {
+    if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
+    if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
+  }
   if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) {
     r.o_min_t = t; r.o_min_k = k; r.o_min_i = r.o_n;
   }
   r.o_n++;
+}
+
+// closed loop, registers empty: every lane finds the earliest and second earliest waiting timer of the
+// sessions s = lane, lane + 64, ...; B = the earliest of the second ones is the earliest timer that
+// stays behind if every lane hands over its earliest, so all of those before B move into the
+// registers at once (at least the overall earliest does), sorted by their rank among themselves.
+template <uint32_t F>
+__device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
+  wave_sync();
+  uint64_t m1 = ~0ull, m2 = ~0ull;
+  for (int s = c.lane; s < c.n_sess; s += WAVE) {
+    const uint32_t z = (uint32_t)c.m.sess[s].z;
+    const uint64_t k = ((uint64_t)(uint32_t)c.m.due[s] << 32) | (uint64_t)((((z >> CL_KIND_SHIFT) & 3u) << 16) | (uint32_t)s);
+    const uint64_t kk = (z & SF_OVF) ? k : ~0ull;
+    if (kk < m1) { m2 = m1; m1 = kk; }
+    else if (kk < m2) m2 = kk;
+  }
+  const uint32_t bh = wave_min((uint32_t)(m2 >> 32));
+  const uint32_t bl = wave_min((uint32_t)(m2 >> 32) == bh ? (uint32_t)m2 : 0xFFFFFFFFu);
+  const uint64_t B = ((uint64_t)bh << 32) | bl;
+  const bool take = m1 < B;
+  const uint64_t tk = wballot(take);
+  const int n = __builtin_popcountll(tk);
+  int rank = 0;
+  for (uint64_t w = tk; w != 0; w &= w - 1) {
+    const int j = (int)__builtin_ctzll(w);
+    const uint64_t kj = ((uint64_t)(uint32_t)lane_get((int)(m1 >> 32), j) << 32) | (uint32_t)lane_get((int)(uint32_t)m1, j);
+    rank += kj < m1 ? 1 : 0;
+  }
+  if (take) {
+    const uint32_t s = (uint32_t)m1 & 0xFFFFu;
+    c.m.sess[s].z = (int)((uint32_t)c.m.sess[s].z & ~CL_TIMER_BITS);
+  }
+  wave_sync();
+  // a permutation of the lanes: the timers taken go to lanes 0..n-1 in order, the rest behind them
+  const int dst = take ? rank : n + lane_rank(~tk);
+  c.qt = __builtin_amdgcn_ds_permute(dst << 2, (int)(m1 >> 32));
+  c.qk = (uint32_t)__builtin_amdgcn_ds_permute(dst << 2, (int)(uint32_t)m1);
+  c.qd = 0;
+  r.q_n = n;
+  r.o_n -= n;
+  r.o_min_t = r.o_n > 0 ? (int32_t)bh : NEVER;
+  r.o_min_k = bl;
 }
 
 // ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
@@ -215,7 +282,9 @@ __device__ __forceinline__ void timer_pop(Ctx<F> &c, Regs &r) {
   c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
   c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
   r.q_n--;
-  if (r.q_n == 0 && r.o_n > 0) {
+  if constexpr (Ctx<F>::closed) {
+    if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
+  } else if (r.q_n == 0 && r.o_n > 0) {
     wave_sync();
     int i = r.o_min_i, last = r.o_n - 1;
     int32_t t = uni(c.m.o_t[i]), d = uni(c.m.o_d[i]);
@@ -352,6 +421,29 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g) {
   return (int32_t)wave_min((uint32_t)best);
 }
 
+// ---- closed loop: the session's next event is due one think time after `base` --------------------
+// first: the session was placed just now and its first chained event comes up; otherwise the event
+// under way is over and the one after it comes up. Lane 0 alone touches the cursors.
+template <uint32_t F>
+__device__ __forceinline__ void cl_schedule(Ctx<F> &c, Regs &r, uint32_t s, int32_t base, bool first) {
+  int32_t e = -1, th = 0;
+  if (c.lane == 0) {
+    if (first) {
+      e = c.cl_first[s];
+      c.cl_cur[s] = e;
+    } else {
+      e = c.cl_cur[s];
+      if (e >= 0) { e = c.cl_nx[e]; c.cl_cur[s] = e; }
+    }
+    if (e >= 0) th = c.cl_th[e];
+  }
+  e = uni(e); th = uni(th);
+  if (e < 0) return;
+  const int64_t t = (int64_t)base + th;
+  if (t >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+  timer_push(c, r, (int32_t)t, QK_NEXT, s, 0);
+}
+
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
 template <uint32_t F>
 __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
@@ -424,6 +516,7 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
   c64_add(c.m, c.lane, CL_RESV, -(int64_t)g * now);
   c32_add(c.m, c.lane, CS_NREP, 3u);
   c64_add(c.m, c.lane, CL_REPL, -(int64_t)3 * now);
+  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now, true);
 }
 
 // the replicas of session s give their subscriptions back at time `now`
@@ -449,6 +542,9 @@ __device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint3
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,
                                            uint32_t outcome) {
   const int g = (int)((fl >> 3) & 7u) + 1;
+  if constexpr (Ctx<F>::closed) {             // the lag of a closed loop is not bounded in advance
+    if ((int64_t)start + dur >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+  }
   const int32_t finish = start + dur;
   const int32_t delay = start - t_submit;
   r.c_started++;
@@ -480,6 +576,7 @@ __device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint3
   r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
   decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
   if (fl & SF_ENDING) timer_push(c, r, finish, QK_END, s, 0);
+  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, finish, false);
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
@@ -609,6 +706,9 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       if (c.lane == 0) c.m.sess[s].z = (int)nfl;
     }
     r.dirty |= wballot(c.vsid == s);
+    if constexpr (Ctx<F>::closed) {
+      if ((int64_t)t_submit + (int64_t)retries * c.p.retry_iv >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+    }
     timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
     return;
   }
@@ -617,6 +717,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
   const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
   sess_write(c, r, s, hw, 0, nfl);
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
+  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now, false);
 }
 
 // Sum of a per-lane value below 2^26 over the wave as a 64-bit uniform value: exact 32-bit sums per
@@ -794,6 +895,87 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   return done;
 }
 
+// ---- LDS layout of one replay and its initial state (S0) -------------------------------------------
+// CL: closed loop (no scratch for the rounds, no overflow array; due[] instead)
+template <bool CL>
+__device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
+  Lds m;
+  m.c64 = (unsigned long long *)q;  q += 8 * 8;
+  m.c32 = (uint32_t *)q;            q += 16 * 4;
+  m.hist = (uint32_t *)q;           q += 32 * 4;
+  m.ppow = (unsigned long long *)q; q += 66 * 8;
+  m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
+  m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
+  m.mark = (int32_t *)q;            q += CL ? 0 : (size_t)p.HP * 4;
+  m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
+  m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
+  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
+  if (CL) {
+    m.due = (int32_t *)q;
+    m.o_t = nullptr; m.o_k = nullptr; m.o_d = nullptr;
+  } else {
+    m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
+    m.o_k = (uint32_t *)q;            q += (size_t)p.q_cap * 4;
+    m.o_d = (int32_t *)q;
+    m.due = nullptr;
+  }
+  return m;
+}
+
+// hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
+template <bool CL>
+__device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int lane, int s_lo, int n_sess) {
+  if (lane < 8) m.c64[lane] = 0;
+  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
+  if (lane < 32) m.hist[lane] = 0;
+  if (lane == 0) {
+    unsigned long long pw = 1;
+    for (int i = 0; i <= 64; i++) { m.ppow[i] = pw; pw *= 0x100000001B3ULL; }
+  }
+  for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
+  for (int h = lane; h < p.HP; h += WAVE) {
+    m.ready_at[h] = h < p.H0 ? 0 : NEVER;
+    if (!CL) m.mark[h] = MARK_FREE;
+    m.hsn[h] = 0;
+  }
+  if (p.warm_n > 0) {
+    for (int i = lane; i < 4 * p.HP; i += WAVE) m.warm[i] = 0;     // initial hosts: warm from time 0
+  }
+  for (int s = lane; s < n_sess; s += WAVE) {
+    const uint32_t g = p.sess_gpus[s_lo + s];
+    m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
+  }
+  __syncthreads();
+}
+
+// ---- S10: close the integrals at t_end and write the result record ---------------------------------
+__device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, const Regs &r, int rep, int lane) {
+  __syncthreads();
+  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
+  nbos_stats *out = p.stats + rep;
+  if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
+  if (lane == 0) {
+    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
+    out->status = r.status; out->n_decisions = r.n_dec;
+    out->sessions_placed = m.c32[CS_PLACED]; out->sessions_rejected = m.c32[CS_REJECTED];
+    out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
+    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = m.c32[CS_ABORTED];
+    out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
+    out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
+    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
+    out->migrations_warm = m.c32[CS_MIGRWARM];
+    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
+    const int64_t sum_dur = r.sum_dur + (int64_t)m.c64[CL_BDUR], g_exec = r.g_exec + (int64_t)m.c64[CL_BGEXEC];
+    out->sum_delay_ms = sum_delay; out->sum_tct_ms = sum_dur + sum_delay;
+    out->gpu_ms_executed = g_exec; out->gpu_ms_committed = g_exec + g_wait;
+    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
+    out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
+    out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
+    out->replica_ms = (int64_t)m.c64[CL_REPL] + (int64_t)(int32_t)m.c32[CS_NREP] * t_end;
+    out->digest = r.digest;
+  }
+}
+
 template <uint32_t F>
 __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -806,40 +988,8 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   const int s_lo = p.sess_offset[trace];
   const int n_sess = p.sess_offset[trace + 1] - s_lo;
 
-  Lds m;
-  unsigned char *q = lds_raw;
-  m.c64 = (unsigned long long *)q;  q += 8 * 8;
-  m.c32 = (uint32_t *)q;            q += 16 * 4;
-  m.hist = (uint32_t *)q;           q += 32 * 4;
-  m.ppow = (unsigned long long *)q; q += 66 * 8;
-  m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
-  m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
-  m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
-  m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
-  m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
-  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
-  m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
-  m.o_k = (uint32_t *)q;            q += (size_t)p.q_cap * 4;
-  m.o_d = (int32_t *)q;
-
-  // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
-  if (lane < 8) m.c64[lane] = 0;
-  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
-  if (lane < 32) m.hist[lane] = 0;
-  if (lane == 0) {
-    unsigned long long pw = 1;
-    for (int i = 0; i <= 64; i++) { m.ppow[i] = pw; pw *= 0x100000001B3ULL; }
-  }
-  for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
-  for (int h = lane; h < p.HP; h += WAVE) { m.ready_at[h] = h < p.H0 ? 0 : NEVER; m.mark[h] = MARK_FREE; m.hsn[h] = 0; }
-  if (p.warm_n > 0) {
-    for (int i = lane; i < 4 * p.HP; i += WAVE) m.warm[i] = 0;     // initial hosts: warm from time 0
-  }
-  for (int s = lane; s < n_sess; s += WAVE) {
-    const uint32_t g = p.sess_gpus[s_lo + s];
-    m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
-  }
-  __syncthreads();
+  const Lds m = lds_carve<false>(p, lds_raw);
+  lds_init<false>(p, m, lane, s_lo, n_sess);
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
   Ctx<F> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
@@ -1013,31 +1163,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
     if (final) break;
   }
 
-  // S10: close the integrals at t_end and write the result record
-  __syncthreads();
-  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
-  nbos_stats *out = p.stats + rep;
-  if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
-  if (lane == 0) {
-    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
-    out->status = r.status; out->n_decisions = r.n_dec;
-    out->sessions_placed = m.c32[CS_PLACED]; out->sessions_rejected = m.c32[CS_REJECTED];
-    out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
-    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = m.c32[CS_ABORTED];
-    out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
-    out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
-    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
-    out->migrations_warm = m.c32[CS_MIGRWARM];
-    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
-    const int64_t sum_dur = r.sum_dur + (int64_t)m.c64[CL_BDUR], g_exec = r.g_exec + (int64_t)m.c64[CL_BGEXEC];
-    out->sum_delay_ms = sum_delay; out->sum_tct_ms = sum_dur + sum_delay;
-    out->gpu_ms_executed = g_exec; out->gpu_ms_committed = g_exec + g_wait;
-    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
-    out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
-    out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
-    out->replica_ms = (int64_t)m.c64[CL_REPL] + (int64_t)(int32_t)m.c32[CS_NREP] * t_end;
-    out->digest = r.digest;
-  }
+  write_stats(p, m, r, rep, lane);
 }
 
 }  // namespace ldsk

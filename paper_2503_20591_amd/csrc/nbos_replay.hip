@@ -2,7 +2,8 @@
 // and kernel dispatch. Two kernels implement the same replay (see their headers):
 //   nbos_kernel_reg.hpp   hosts_max <= 64: host state in registers, no LDS round trip per cell
 //   nbos_kernel_lds.hpp   any hosts_max up to 1024: host state in LDS
-// and a third replays the Batch baseline policy on the same traces (nbos_kernel_batch.hpp).
+// A third replays the Batch baseline policy on the same traces (nbos_kernel_batch.hpp), a fourth reads
+// the traces as closed loops on the any-size kernel's code (nbos_kernel_closed.hpp).
 // Everything is integer arithmetic; all control flow is wave-uniform.
 
 #include <hip/hip_runtime.h>
@@ -16,6 +17,7 @@
 #include "../../include/nbos.h"
 #include "nbos_common.hpp"
 #include "nbos_kernel_lds.hpp"
+#include "nbos_kernel_closed.hpp"
 #include "nbos_kernel_reg.hpp"
 #include "nbos_kernel_batch.hpp"
 
@@ -121,6 +123,7 @@ struct nbos_replay {
   nbos_stats *d_stats;
   nbos_bill *d_bill;
   int32_t *d_ovf;          // register kernel only
+  int32_t *d_chain;        // closed loop only: think times, next events, first events, cursors
   uint64_t *d_log;
   std::vector<int64_t> ev_off;
   std::vector<int32_t> sess_off;
@@ -135,6 +138,7 @@ void free_handle(nbos_replay *h) {
   if (h->d_stats) (void)hipFree(h->d_stats);
   if (h->d_bill) (void)hipFree(h->d_bill);
   if (h->d_ovf) (void)hipFree(h->d_ovf);
+  if (h->d_chain) (void)hipFree(h->d_chain);
   if (h->d_log) (void)hipFree(h->d_log);
   if (h->e0) (void)hipEventDestroy(h->e0);
   if (h->e1) (void)hipEventDestroy(h->e1);
@@ -182,7 +186,10 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
   if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS |
-                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE | NBOS_F_WARM_POOL))
+                     NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE | NBOS_F_WARM_POOL |
+                     NBOS_F_CLOSED_LOOP))
+    return NBOS_E_ARG;
+  if ((cfg->flags & NBOS_F_CLOSED_LOOP) && (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_BATCH_MODE)))
     return NBOS_E_ARG;
   if (cfg->flags & NBOS_F_WARM_POOL) {
     if (cfg->warm_pool_per_host < 1 || cfg->warm_pool_per_host > 4 || cfg->warm_migration_delay_ms < 0 ||
@@ -212,12 +219,13 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
                   cfg->boot_delay_ms + slowest + ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0);
   bool batch_mode = (cfg->flags & NBOS_F_BATCH_MODE) != 0;
   bool warm_pool = (cfg->flags & NBOS_F_WARM_POOL) != 0;
+  bool closed_loop = (cfg->flags & NBOS_F_CLOSED_LOOP) != 0;
   if (slack >= 0x7FFFFFFFLL) return NBOS_E_ARG;
 
   nbos_replay *h = new (std::nothrow) nbos_replay();
   if (!h) return NBOS_E_NOMEM;
   h->cfg = *cfg; h->in = *in; h->stream = (hipStream_t)stream;
-  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
+  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_chain = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   int32_t rc = NBOS_OK;
 #define HIP_TRY(x) do { if ((x) != hipSuccess) { rc = NBOS_E_HIP; goto fail; } } while (0)
   {
@@ -239,6 +247,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
         int64_t ns = (int64_t)h->sess_off[t + 1] - h->sess_off[t];
         if (ne < 0 || ns < 0) { rc = NBOS_E_RANGE; goto fail; }
         if (ns > NBOS_MAX_SESSIONS) { rc = NBOS_E_LIMIT; goto fail; }
+        if (closed_loop && ne >= 0x40000000LL) { rc = NBOS_E_LIMIT; goto fail; }    // event indices within a trace
         if (ns > max_sess) max_sess = (int32_t)ns;
       }
       total_ev = h->ev_off[nt];
@@ -249,7 +258,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     // kernel choice and LDS footprint of one replay
     int maxlds = 0;
     HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    const bool in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode;
+    const bool in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
     const int HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
     const int n_cap = max_sess > 0 ? max_sess : 1;
     size_t q_cap = (size_t)n_cap + 1;               // at most one queued timer per session
@@ -257,6 +266,12 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + (size_t)n_cap * 12 + ((size_t)n_cap + 2) * 2;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
+    } else if (closed_loop) {
+      // hosts without the scratch of the rounds; 12 bytes of record and 4 of timer per session
+      h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 8 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16;
+      if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
+      q_cap = 0;
+      h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
     } else if (in_regs) {
       h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + (size_t)n_cap * 8;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
@@ -349,6 +364,21 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (in_regs &&
           hipMalloc(&h->d_ovf, sizeof(int32_t) * (size_t)cfg->n_replays * (size_t)n_cap) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
     }
+    int32_t *d_think = nullptr, *d_next = nullptr, *d_first = nullptr, *d_cursor = nullptr;
+    if (closed_loop && cfg->n_replays > 0) {
+      // one allocation: think[total_ev], next[total_ev], first[sessions of all traces], cursor[n_replays][n_cap]
+      const size_t n_first = (size_t)h->sess_off[nt];
+      const size_t words = 2 * (size_t)total_ev + n_first + (size_t)cfg->n_replays * (size_t)n_cap;
+      if (hipMalloc(&h->d_chain, sizeof(int32_t) * (words > 0 ? words : 1)) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
+      d_think = h->d_chain; d_next = d_think + total_ev; d_first = d_next + total_ev; d_cursor = d_first + n_first;
+      const size_t chain_lds = (size_t)n_cap * 8;
+      HIP_TRY(hipFuncSetAttribute((const void *)ldsk::nbos_closed_chain_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)chain_lds));
+      hipLaunchKernelGGL(ldsk::nbos_closed_chain_kernel, dim3(nt), dim3(WAVE), chain_lds, h->stream, in->ev_offset,
+                         in->ev_time_ms, in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, d_think, d_next, d_first);
+      HIP_TRY(hipGetLastError());
+      HIP_TRY(hipStreamSynchronize(h->stream));
+    }
     int64_t log_stride = 0;
     if ((cfg->flags & NBOS_F_DECISION_LOG) && cfg->n_replays > 0) {
       h->trace_of_replay.resize((size_t)cfg->n_replays);
@@ -382,6 +412,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
     const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
     k.batch = (nb && nb[0] == '0') ? 0 : 1;
+    k.cl_think = d_think; k.cl_next = d_next; k.cl_first = d_first; k.cl_cursor = d_cursor;
   }
   *out = h;
   return NBOS_OK;

@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so
 
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG, F_HOSTS_IN_LDS = 1, 2, 4, 8, 16
 F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
+F_CLOSED_LOOP = 0x400
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",

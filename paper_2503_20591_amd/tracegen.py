@@ -22,6 +22,7 @@ import numpy as np
 EV_START, EV_CELL, EV_END = 0, 1, 2
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN = 1, 2, 4
 F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
+F_CLOSED_LOOP = 0x400
 
 MAX_DUR_MS = 86_400_000          # a cell or an idle gap is at most 24 h
 MAX_TIME_MS = 1_900_000_000      # arrivals are clipped here so finish times stay in int32
@@ -239,10 +240,15 @@ def _recipe(name: str):
         rc = _recipe(name[:2])
         rc["cfg"] = dict(rc["cfg"], flags=F_BATCH_MODE, hosts_max=rc["cfg"]["hosts_initial"], batch_start_delay_ms=15_000)
         return rc
+    if name in ("c2l", "c4l"):  # the c2 / c4 traces read as closed loops (Section 2.2: a user submits the
+        # next cell a think time after the previous one is over); c4l without the periodic scale-in
+        rc = _recipe(name[:2])
+        rc["cfg"] = dict(rc["cfg"], flags=(rc["cfg"]["flags"] & ~F_SCALE_IN) | F_CLOSED_LOOP)
+        return rc
     raise KeyError(name)
 
 
-WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b")
+WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b", "c2l", "c4l")
 
 
 def _gen_range(args):

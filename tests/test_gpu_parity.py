@@ -290,6 +290,95 @@ def test_batch_mode_rejects_other_policy_flags(rp):
         assert e.value.code == rp.E_ARG
 
 
+# ---- closed-loop reading of the traces (Section 2.2: users think between the cells they submit) ------
+
+def as_closed(b):
+    b.config["flags"] = (b.config["flags"] & ~(tg.F_SCALE_IN | tg.F_AUTOSCALE)) | tg.F_CLOSED_LOOP
+    return b
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_closed_loop_random_cases(rp, oracle, seed):
+    b = as_closed(tg.random_case(seed))
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_closed_loop_policy_flag_cases(rp, oracle, seed):
+    # with the dynamic limit, the sticky executor and the pre-warmed containers
+    b = as_closed(tg.random_case(seed, policy_flags=True))
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+
+
+@pytest.mark.parametrize("name,n", [("c2l", 6), ("c4l", 2)])
+def test_closed_loop_named_workloads(rp, oracle, name, n):
+    b = tg.workload(name, n_replays=n)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+    assert (st["cells_dropped_busy"] == 0).all()          # a session never submits while its cell runs
+    assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"]).all()
+
+
+@pytest.mark.parametrize("name,n", [("c3", 4), ("c5", 16), ("c1", 1)])
+def test_closed_loop_on_the_other_traces(rp, oracle, name, n):
+    # 1,000 sessions on 64 hosts: nearly every session's timer waits in its record, not in the
+    # 64 sorted slots (refill takes several at once, pushes evict the latest)
+    b = as_closed(tg.workload(name, n_replays=n))
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=name != "c3")
+
+
+def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
+    # the whole c2l batch in the launch shape the benchmark uses; a sample of replays against the oracle
+    b = tg.workload("c2l", workers=8)
+    st, _ = gpu_run(rp, b)
+    assert (st["status"] == 0).all()
+    assert_same(rp, oracle, b, st, replays=list(range(0, b.n_replays, 37)) + [b.n_replays - 1])
+    assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"]).all()
+
+
+def test_closed_loop_time_range(rp, oracle):
+    # Three sessions keep all three hosts busy for a day, twice; the fourth session's first two cells
+    # are given up after a minute each, so its third cell, nominally at the latest time a trace may
+    # hold, comes two minutes late: with a one-day duration it would end beyond 2^31 - 1 ms. Both
+    # sides call the replay invalid; 59,998 ms less and it ends at 2^31 - 2 and is fine.
+    day = 86_400_000
+    cfg = tg._base_config(hosts_initial=3, hosts_max=3, gpus_per_host=8, flags=tg.F_CLOSED_LOOP,
+                          migration_delay_ms=0, boot_delay_ms=0, retry_interval_ms=10_000, max_retries=6)
+    t_limit = 2**31 - 2 - (day + 6 * 10_000)
+
+    def batch(d3):
+        ev = [[0, 0, s, 0] for s in range(4)]
+        ev += [[10, 1, s, day] for s in range(3)] + [[20, 1, 3, 1]]
+        ev += [[10 + day + 5, 1, s, day] for s in range(3)] + [[10 + day + 100, 1, 3, 1]]
+        ev += [[t_limit, 1, 3, d3]]
+        return _tiny(cfg, ev, [8, 8, 8, 8], [100000])
+
+    for d3 in (day, day - 59_997):
+        b = batch(d3)
+        with pytest.raises(ValueError) as e:
+            oracle.replay(b.config, b.ev_time, b.ev_dur, b.ev_sk, b.sess_gpus, 100000)
+        assert e.value.args[1] == -2
+        st, _ = gpu_run(rp, b)
+        assert (st["status"] == rp.E_RANGE).all()
+    b = batch(day - 59_998)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+    assert st["t_end_ms"][0] == 2**31 - 2
+
+
+def test_closed_loop_rejects_periodic_scaling_and_batch(rp):
+    b = tg.random_case(2)
+    dev = rp.upload(b)
+    for f in (tg.F_SCALE_IN, tg.F_AUTOSCALE | tg.F_SCALE_IN, tg.F_BATCH_MODE):
+        cfg = dict(b.config, flags=tg.F_CLOSED_LOOP | f)
+        with pytest.raises(rp.NbosError) as e:
+            rp.Replay(cfg, dev)
+        assert e.value.code == rp.E_ARG
+
+
 def test_random_cases_without_log(rp, oracle):
     for seed in range(120, 150):
         b = tg.random_case(seed, n_replays=6)
