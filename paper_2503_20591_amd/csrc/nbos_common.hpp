@@ -39,10 +39,10 @@ struct KParams {
   int32_t warm_n, warm_migr, prewarm;   // pre-warmed containers per host, warm migration delay, pre-warm time
   int32_t n_cap, q_cap;    // LDS capacity: sessions, queue entries
   int32_t batch;           // event-parallel rounds on (LDS kernel)
-  // closed loop only: per event the think time before it (-1: the event is ignored) and the next event
-  // of its session (index within the trace, -1: none); per session of a trace its first chained event;
-  // per replay and session the event that is due next or under way
-  const int32_t *cl_think, *cl_next, *cl_first;
+  // closed loop only. cl_chain: per event of the traces {the next event of its session (index within
+  // the trace, -1: none), the think time before that event}; the second word is -1 for an event no
+  // chain holds. cl_cursor: per replay and session the event that is due next or under way.
+  const int2 *cl_chain;
   int32_t *cl_cursor;
 };
 

@@ -59,7 +59,8 @@ struct Lds {
   SessRec *sess;
   int32_t *o_t, *o_d;
   uint32_t *o_k;
-  int32_t *due;                // closed loop: [n_cap] time of a session's timer while it waits outside the registers
+  int32_t *due;                // closed loop: [n_cap] time of a session's timer while it waits outside the registers, else NEVER
+  int32_t *stage;              // closed loop: [64] sessions whose timers move into the registers
 };
 
 struct Regs {
@@ -73,6 +74,9 @@ struct Regs {
   int32_t status;
   int32_t min_s;             // least subscription among hosts that are on, or -1 when stale
   uint64_t dirty;
+  // closed loop: the event being handled, its duration and kind (packed as in Ctx::qx), its session's next
+  // event and the think time before that; the time window the next refill takes
+  int32_t cl_e, cl_x, cl_nx, cl_nth, cl_win;
 };
 
 // F: the policy flags when they are known at compile time (an instance of its own drops the code of
@@ -93,11 +97,14 @@ struct Ctx {
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
   int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
-  // closed loop: sessions of the trace, the replay's cursors, and the trace's per-session first event,
-  // per-event think time, next event, duration and kind word
+  // closed loop: sessions of the trace, the replay's cursors, the events of the trace; and with every
+  // sorted timer what firing it needs: qd = the event's index, qx = its duration | kind << 28 |
+  // CLX_LOADED (0: not loaded yet), qnx / qnth = its chain record
   int32_t n_sess;
   int32_t *cl_cur;
-  const int32_t *cl_first, *cl_th, *cl_nx, *cl_dur, *cl_sk;
+  const int32_t *cl_dur, *cl_sk;
+  const int2 *cl_chain;
+  int32_t qx, qnx, qnth;
   static constexpr bool closed = F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
   __device__ __forceinline__ uint32_t flags() const {
     return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
@@ -106,8 +113,10 @@ struct Ctx {
 
 // closed loop: a session has at most one timer (its next event, or the retry or deferred end of the
 // cell under way), so a timer that does not fit into the sorted registers waits in the session's own
-// record: SF_OVF and the kind in the flags word, the time in due[s]
-constexpr uint32_t CL_KIND_SHIFT = 13, CL_TIMER_BITS = SF_OVF | (3u << CL_KIND_SHIFT);
+// record: the kind in the flags word, the time in due[s] (NEVER: no timer waits there)
+constexpr uint32_t CL_KIND_SHIFT = 13;
+constexpr int32_t CLX_LOADED = (int32_t)0x80000000;
+constexpr int32_t CL_WIN_MAX = 1 << 24;
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
   if (lane == 0) atomicAdd(&m.c32[idx], v);
@@ -189,7 +198,7 @@ __device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t
     const uint32_t s = k & 0xFFFFu;
     if (c.lane == 0) {
       const uint32_t z = (uint32_t)c.m.sess[s].z;
-      c.m.sess[s].z = (int)((z & ~CL_TIMER_BITS) | SF_OVF | ((k >> 16) << CL_KIND_SHIFT));
+      c.m.sess[s].z = (int)((z & ~(3u << CL_KIND_SHIFT)) | ((k >> 16) << CL_KIND_SHIFT));
       c.m.due[s] = t;
     }
   } else {
@@ -202,54 +211,111 @@ __device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t
   r.o_n++;
 }
 
-// closed loop, registers empty: every lane finds the earliest and second earliest waiting timer of the
-// sessions s = lane, lane + 64, ...; B = the earliest of the second ones is the earliest timer that
-// stays behind if every lane hands over its earliest, so all of those before B move into the
-// registers at once (at least the overall earliest does), sorted by their rank among themselves.
+// closed loop, registers empty: all timers that are due within a window after the earliest one move
+// from the session records into the registers at once, at most 64. A window takes whole instants, so
+// everything taken is earlier than everything left behind whatever the kinds. The window adapts to
+// the density of the timers (half of the registers filled is the aim); if more than 64 timers wait
+// for one and the same instant, the single earliest (time, kind, session) is taken. What firing the
+// timers will need - their events' duration, kind and chain record - is gathered here, one lane per
+// timer, in two round trips to device memory for the lot.
 template <uint32_t F>
 __device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
   wave_sync();
-  uint64_t m1 = ~0ull, m2 = ~0ull;
-  for (int s = c.lane; s < c.n_sess; s += WAVE) {
-    const uint32_t z = (uint32_t)c.m.sess[s].z;
-    const uint64_t k = ((uint64_t)(uint32_t)c.m.due[s] << 32) | (uint64_t)((((z >> CL_KIND_SHIFT) & 3u) << 16) | (uint32_t)s);
-    const uint64_t kk = (z & SF_OVF) ? k : ~0ull;
-    if (kk < m1) { m2 = m1; m1 = kk; }
-    else if (kk < m2) m2 = kk;
+  int cnt;
+  int32_t left;                                  // earliest time left behind
+  int32_t win = r.cl_win;
+  for (;;) {
+    const int64_t lim = (int64_t)r.o_min_t + win;
+    const int32_t T = lim < NEVER - 1 ? (int32_t)lim : NEVER - 1;
+    cnt = 0;
+    int32_t mn = NEVER, all = NEVER;
+    for (int s0 = 0; s0 < c.n_sess; s0 += WAVE) {
+      const int s = s0 + c.lane;
+      const int32_t d = s < c.n_sess ? c.m.due[s] : NEVER;
+      const bool hit = d <= T;
+      const uint64_t b = wballot(hit);
+      if (b != 0) {
+        const int pos = cnt + lane_rank(b);
+        if (hit && pos < WAVE) c.m.stage[pos] = s;
+        cnt += __builtin_popcountll(b);
+      }
+      mn = hit ? mn : (d < mn ? d : mn);
+      all = d < all ? d : all;
+    }
+    left = (int32_t)wave_min((uint32_t)mn);
+    if (cnt == 0) {                              // the stored bound was below the earliest time: use that
+      const int32_t first = (int32_t)wave_min((uint32_t)all);
+      if (first == NEVER) { r.o_n = 0; r.o_min_t = NEVER; return; }     // nothing waits (not reached: o_n counts them)
+      r.o_min_t = first;
+      continue;
+    }
+    if (cnt <= WAVE) break;
+    if (win == 0) {
+      // more than 64 timers at the instant o_min_t: the earliest by kind and session alone
+      wave_sync();
+      uint32_t best = 0xFFFFFFFFu;
+      for (int s = c.lane; s < c.n_sess; s += WAVE) {
+        if (c.m.due[s] == T) best = umin(best, ((((uint32_t)c.m.sess[s].z >> CL_KIND_SHIFT) & 3u) << 16) | (uint32_t)s);
+      }
+      best = wave_min(best);
+      if (c.lane == 0) c.m.stage[0] = (int32_t)(best & 0xFFFFu);
+      cnt = 1;
+      left = T;
+      break;
+    }
+    win = win * 32 / cnt;                        // aim at half of the registers
+    wave_sync();
   }
-  const uint32_t bh = wave_min((uint32_t)(m2 >> 32));
-  const uint32_t bl = wave_min((uint32_t)(m2 >> 32) == bh ? (uint32_t)m2 : 0xFFFFFFFFu);
-  const uint64_t B = ((uint64_t)bh << 32) | bl;
-  const bool take = m1 < B;
-  const uint64_t tk = wballot(take);
-  const int n = __builtin_popcountll(tk);
-  int rank = 0;
-  for (uint64_t w = tk; w != 0; w &= w - 1) {
-    const int j = (int)__builtin_ctzll(w);
-    const uint64_t kj = ((uint64_t)(uint32_t)lane_get((int)(m1 >> 32), j) << 32) | (uint32_t)lane_get((int)(uint32_t)m1, j);
-    rank += kj < m1 ? 1 : 0;
-  }
-  if (take) {
-    const uint32_t s = (uint32_t)m1 & 0xFFFFu;
-    c.m.sess[s].z = (int)((uint32_t)c.m.sess[s].z & ~CL_TIMER_BITS);
-  }
+  if (cnt < WAVE / 4 && win < CL_WIN_MAX) r.cl_win = win == 0 ? 1 : win * 2;
+  else if (cnt > 3 * WAVE / 4) r.cl_win = win / 2;
+  else r.cl_win = win;
   wave_sync();
-  // a permutation of the lanes: the timers taken go to lanes 0..n-1 in order, the rest behind them
-  const int dst = take ? rank : n + lane_rank(~tk);
-  c.qt = __builtin_amdgcn_ds_permute(dst << 2, (int)(m1 >> 32));
-  c.qk = (uint32_t)__builtin_amdgcn_ds_permute(dst << 2, (int)(uint32_t)m1);
-  c.qd = 0;
-  r.q_n = n;
-  r.o_n -= n;
-  r.o_min_t = r.o_n > 0 ? (int32_t)bh : NEVER;
-  r.o_min_k = bl;
+  // lane i < cnt takes the timer of session stage[i]
+  const bool take = c.lane < cnt;
+  uint32_t key = 0xFFFFFFFFu;
+  int32_t t = NEVER, e = 0;
+  if (take) {
+    const int s = c.m.stage[c.lane];
+    t = c.m.due[s];
+    c.m.due[s] = NEVER;
+    key = ((((uint32_t)c.m.sess[s].z >> CL_KIND_SHIFT) & 3u) << 16) | (uint32_t)s;
+  }
+  // the cursors were written by lane 0 when the timers were scheduled: the fence makes this wave's own
+  // stores visible to its other lanes
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  if (take) e = c.cl_cur[key & 0xFFFFu];
+  int32_t x = 0, nx = -1, nth = 0;
+  if (take && (key >> 16) != QK_END) {
+    const int2 ch = c.cl_chain[e];
+    x = c.cl_dur[e] | (int32_t)(((uint32_t)c.cl_sk[e] >> 24) << 28) | CLX_LOADED;
+    nx = ch.x; nth = ch.y;
+  }
+  int rank = 0;
+  for (int j = 0; j < cnt; j++) {
+    const int32_t tj = lane_get(t, j);
+    const uint32_t kj = (uint32_t)lane_get((int)key, j);
+    rank += (tj < t || (tj == t && kj < key)) ? 1 : 0;
+  }
+  // lanes beyond cnt hold the largest key: their rank is cnt, any order among them will do
+  const int dst = take ? rank : c.lane;
+  c.qt = __builtin_amdgcn_ds_permute(dst << 2, t);
+  c.qk = (uint32_t)__builtin_amdgcn_ds_permute(dst << 2, (int)key);
+  c.qd = __builtin_amdgcn_ds_permute(dst << 2, e);
+  c.qx = __builtin_amdgcn_ds_permute(dst << 2, x);
+  c.qnx = __builtin_amdgcn_ds_permute(dst << 2, nx);
+  c.qnth = __builtin_amdgcn_ds_permute(dst << 2, nth);
+  r.q_n = cnt;
+  r.o_n -= cnt;
+  r.o_min_t = r.o_n > 0 ? left : NEVER;
+  r.o_min_k = 0;                                 // a lower bound: pushes for that very instant wait in the records
 }
 
 // ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
 // Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
 // registers are empty only if the overflow array is.
 template <uint32_t F>
-__device__ __forceinline__ void timer_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
+__device__ __forceinline__ void timer_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d,
+                                           int32_t x = 0, int32_t nx = -1, int32_t nth = 0) {
   uint32_t k = (kind << 16) | id;
   if (r.q_n == WAVE) {
     int32_t mt = lane_get(c.qt, WAVE - 1);
@@ -272,6 +338,13 @@ __device__ __forceinline__ void timer_push(Ctx<F> &c, Regs &r, int32_t t, uint32
   uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
   if (c.lane > pos) { c.qt = st; c.qd = sd; c.qk = sk; }
   if (c.lane == pos) { c.qt = t; c.qd = d; c.qk = k; }
+  if constexpr (Ctx<F>::closed) {
+    const int32_t sx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x138, 0xF, 0xF, false);
+    const int32_t sn = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x138, 0xF, 0xF, false);
+    const int32_t sh = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x138, 0xF, 0xF, false);
+    if (c.lane > pos) { c.qx = sx; c.qnx = sn; c.qnth = sh; }
+    if (c.lane == pos) { c.qx = x; c.qnx = nx; c.qnth = nth; }
+  }
   r.q_n++;
   if (pos == 0) r.q_head_t = t;
 }
@@ -283,6 +356,9 @@ __device__ __forceinline__ void timer_pop(Ctx<F> &c, Regs &r) {
   c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
   r.q_n--;
   if constexpr (Ctx<F>::closed) {
+    c.qx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
+    c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
+    c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
     if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
   } else if (r.q_n == 0 && r.o_n > 0) {
     wave_sync();
@@ -422,26 +498,16 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g) {
 }
 
 // ---- closed loop: the session's next event is due one think time after `base` --------------------
-// first: the session was placed just now and its first chained event comes up; otherwise the event
-// under way is over and the one after it comes up. Lane 0 alone touches the cursors.
+// r.cl_nx / r.cl_nth: the event after the one being handled and the think time before it. The timer
+// carries the event's index; the cursor keeps it for the time the timer waits outside the registers.
 template <uint32_t F>
-__device__ __forceinline__ void cl_schedule(Ctx<F> &c, Regs &r, uint32_t s, int32_t base, bool first) {
-  int32_t e = -1, th = 0;
-  if (c.lane == 0) {
-    if (first) {
-      e = c.cl_first[s];
-      c.cl_cur[s] = e;
-    } else {
-      e = c.cl_cur[s];
-      if (e >= 0) { e = c.cl_nx[e]; c.cl_cur[s] = e; }
-    }
-    if (e >= 0) th = c.cl_th[e];
-  }
-  e = uni(e); th = uni(th);
+__device__ __forceinline__ void cl_schedule(Ctx<F> &c, Regs &r, uint32_t s, int32_t base) {
+  const int32_t e = r.cl_nx;
   if (e < 0) return;
-  const int64_t t = (int64_t)base + th;
+  const int64_t t = (int64_t)base + r.cl_nth;
   if (t >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
-  timer_push(c, r, (int32_t)t, QK_NEXT, s, 0);
+  if (c.lane == 0) c.cl_cur[s] = e;
+  timer_push(c, r, (int32_t)t, QK_NEXT, s, e);
 }
 
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
@@ -516,7 +582,7 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
   c64_add(c.m, c.lane, CL_RESV, -(int64_t)g * now);
   c32_add(c.m, c.lane, CS_NREP, 3u);
   c64_add(c.m, c.lane, CL_REPL, -(int64_t)3 * now);
-  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now, true);
+  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now);
 }
 
 // the replicas of session s give their subscriptions back at time `now`
@@ -576,7 +642,7 @@ __device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint3
   r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
   decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
   if (fl & SF_ENDING) timer_push(c, r, finish, QK_END, s, 0);
-  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, finish, false);
+  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, finish);
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
@@ -709,7 +775,9 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
     if constexpr (Ctx<F>::closed) {
       if ((int64_t)t_submit + (int64_t)retries * c.p.retry_iv >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
     }
-    timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
+    // closed loop: every timer carries its event (the cursor still points at the cell under way)
+    if constexpr (Ctx<F>::closed) timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, r.cl_e, r.cl_x, r.cl_nx, r.cl_nth);
+    else timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
     return;
   }
   c32_add(c.m, c.lane, CS_ABORTED, 1u);
@@ -717,7 +785,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
   const uint32_t nfl = (fl & ~(7u | SF_QONCE | (15u << 8))) | SS_PLACED;
   sess_write(c, r, s, hw, 0, nfl);
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
-  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now, false);
+  if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now);
 }
 
 // Sum of a per-lane value below 2^26 over the wave as a 64-bit uniform value: exact 32-bit sums per
@@ -910,8 +978,10 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
   m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
   m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
+  m.stage = nullptr;
   if (CL) {
-    m.due = (int32_t *)q;
+    m.due = (int32_t *)q;             q += (size_t)p.n_cap * 4;
+    m.stage = (int32_t *)q;
     m.o_t = nullptr; m.o_k = nullptr; m.o_d = nullptr;
   } else {
     m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
@@ -944,6 +1014,7 @@ __device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int lan
   for (int s = lane; s < n_sess; s += WAVE) {
     const uint32_t g = p.sess_gpus[s_lo + s];
     m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
+    if (CL) m.due[s] = NEVER;
   }
   __syncthreads();
 }

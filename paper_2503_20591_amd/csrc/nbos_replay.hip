@@ -123,7 +123,7 @@ struct nbos_replay {
   nbos_stats *d_stats;
   nbos_bill *d_bill;
   int32_t *d_ovf;          // register kernel only
-  int32_t *d_chain;        // closed loop only: think times, next events, first events, cursors
+  int32_t *d_chain;        // closed loop only: the chain records of all events, then the cursors
   uint64_t *d_log;
   std::vector<int64_t> ev_off;
   std::vector<int32_t> sess_off;
@@ -267,8 +267,8 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
     } else if (closed_loop) {
-      // hosts without the scratch of the rounds; 12 bytes of record and 4 of timer per session
-      h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 8 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16;
+      // hosts without the scratch of the rounds; 12 bytes of record and 4 of timer per session; 64 staged sessions
+      h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 8 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16 + WAVE * 4;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       q_cap = 0;
       h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
@@ -364,18 +364,18 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (in_regs &&
           hipMalloc(&h->d_ovf, sizeof(int32_t) * (size_t)cfg->n_replays * (size_t)n_cap) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
     }
-    int32_t *d_think = nullptr, *d_next = nullptr, *d_first = nullptr, *d_cursor = nullptr;
+    int2 *d_chain = nullptr;
+    int32_t *d_cursor = nullptr;
     if (closed_loop && cfg->n_replays > 0) {
-      // one allocation: think[total_ev], next[total_ev], first[sessions of all traces], cursor[n_replays][n_cap]
-      const size_t n_first = (size_t)h->sess_off[nt];
-      const size_t words = 2 * (size_t)total_ev + n_first + (size_t)cfg->n_replays * (size_t)n_cap;
+      // one allocation: chain[total_ev] (two words each), cursor[n_replays][n_cap]
+      const size_t words = 2 * (size_t)total_ev + (size_t)cfg->n_replays * (size_t)n_cap;
       if (hipMalloc(&h->d_chain, sizeof(int32_t) * (words > 0 ? words : 1)) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-      d_think = h->d_chain; d_next = d_think + total_ev; d_first = d_next + total_ev; d_cursor = d_first + n_first;
+      d_chain = (int2 *)h->d_chain; d_cursor = h->d_chain + 2 * (size_t)total_ev;
       const size_t chain_lds = (size_t)n_cap * 8;
       HIP_TRY(hipFuncSetAttribute((const void *)ldsk::nbos_closed_chain_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)chain_lds));
       hipLaunchKernelGGL(ldsk::nbos_closed_chain_kernel, dim3(nt), dim3(WAVE), chain_lds, h->stream, in->ev_offset,
-                         in->ev_time_ms, in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, d_think, d_next, d_first);
+                         in->ev_time_ms, in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, d_chain);
       HIP_TRY(hipGetLastError());
       HIP_TRY(hipStreamSynchronize(h->stream));
     }
@@ -412,7 +412,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
     const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
     k.batch = (nb && nb[0] == '0') ? 0 : 1;
-    k.cl_think = d_think; k.cl_next = d_next; k.cl_first = d_first; k.cl_cursor = d_cursor;
+    k.cl_chain = d_chain; k.cl_cursor = d_cursor;
   }
   *out = h;
   return NBOS_OK;

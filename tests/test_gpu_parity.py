@@ -339,6 +339,25 @@ def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
     assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"]).all()
 
 
+def test_closed_loop_many_timers_at_one_instant(rp, oracle):
+    # 300 sessions placed at time 0 whose first cells are all due at the same millisecond, and again
+    # later: far more than 64 timers for one instant wait outside the sorted slots, so they are
+    # taken one by one in (kind, session) order; mixed with retries of queued cells
+    n = 300
+    rng = np.random.default_rng(4)
+    ev = [[0, 0, s, 0] for s in range(n)]
+    ev += [[5000, 1, s, 2000] for s in range(n)]                 # think 5000 after the placement
+    ev += [[9000, 1, s, 1000 + 1000 * (s % 3)] for s in range(n)]   # think 2000 after the first cell
+    ev += [[20000 + s, 2, s, 0] for s in range(0, n, 2)]
+    cfg = dict(BASE, hosts_initial=6, hosts_max=6, flags=tg.F_MIGRATE | tg.F_CLOSED_LOOP, migration_delay_ms=300,
+               retry_interval_ms=1000, max_retries=3)
+    gp = rng.choice([1, 2, 4], n)
+    b = _tiny(cfg, ev, gp, [100000, 6000])
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+    assert st["cells_queued"].max() > 64
+
+
 def test_closed_loop_time_range(rp, oracle):
     # Three sessions keep all three hosts busy for a day, twice; the fourth session's first two cells
     # are given up after a minute each, so its third cell, nominally at the latest time a trace may
