@@ -271,7 +271,14 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 8 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16 + WAVE * 4;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       q_cap = 0;
-      h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
+      // instances for the common flag sets, as for the other kernels
+      const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
+      const char *ng = getenv("NBOS_REPLAY_GENERIC");
+      constexpr uint32_t kMigr = NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP, kMigrOut = kMigr | NBOS_F_SCALE_OUT;
+      if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
+      else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigr>;
+      else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigrOut>;
+      else h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
     } else if (in_regs) {
       h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + (size_t)n_cap * 8;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
