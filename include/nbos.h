@@ -254,8 +254,11 @@ typedef struct {
  * Validates parameters on the host and the trace contents with a device kernel
  * (synchronises the stream once). Allocates only its own result buffers.
  * Two environment variables are read here, for comparison runs only; they change which kernel
- * runs, never a result: NBOS_REPLAY_BATCH=0 (no event-parallel rounds in the any-size kernel),
+ * runs, never a result: NBOS_REPLAY_BATCH=0|1 (event-parallel rounds in the any-size and the
+ * closed-loop kernel off / on; by default on, except for closed loops on at most 64 hosts),
  * NBOS_REPLAY_GENERIC=0|1 (the kernel instance compiled for the flag set / the generic one).
+ * With NBOS_F_CLOSED_LOOP a device kernel links every session's events here (8 bytes per event
+ * and 4 per replay and session of device memory are held until destroy).
  * Errors: NBOS_E_ARG, NBOS_E_RANGE, NBOS_E_LIMIT (hosts/sessions/LDS footprint
  * beyond what one workgroup can hold), NBOS_E_HIP, NBOS_E_NOMEM. *out is NULL
  * on error.

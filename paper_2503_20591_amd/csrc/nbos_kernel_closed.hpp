@@ -18,10 +18,12 @@
 //                            records (see cl_refill), and no queue can overflow. A timer in the
 //                            registers carries the index of its event and, once loaded, the event's
 //                            duration, kind and chain record: timers that come in by a refill have
-//                            them gathered for all of them at once, a timer scheduled straight into
-//                            the registers loads them when it fires (one round trip to device
-//                            memory). While a timer waits outside the registers the index is kept in
-//                            a cursor array in device memory.
+//                            them gathered for all of them at once, timers scheduled straight into
+//                            the registers load them together when the first of them gets to the
+//                            head (one round trip to device memory). While a timer waits outside the registers the index is kept in
+//                            a cursor array in device memory. The due cells at the head of the sorted
+//                            timers are started by the any-size kernel's event-parallel rounds, lane =
+//                            timer; their sessions' next events are scheduled all at once.
 #pragma once
 #include "nbos_kernel_lds.hpp"
 
@@ -77,6 +79,46 @@ __global__ void __launch_bounds__(WAVE) nbos_closed_chain_kernel(const int64_t *
   }
 }
 
+// The first n sorted timers were cells that an event-parallel round has started (lane i = timer i):
+// they leave the registers, and the next event of each of their sessions is scheduled one think time
+// after the cell's finish. Those that are not before the earliest timer waiting in the session
+// records go there, all at once; the others are inserted into the registers one by one.
+template <uint32_t F>
+__device__ __forceinline__ void cl_after_round(Ctx<F> &c, Regs &r, int n) {
+  const bool succ = c.lane < n && c.qnx >= 0;
+  const int32_t ts = succ ? c.qt + (c.qx & 0x0FFFFFFF) + c.qnth : 0;       // in range: checked before the round
+  const int32_t es = c.qnx;
+  const uint32_t ss = c.qk & 0xFFFFu;
+  if (succ) c.cl_cur[ss] = es;
+  // drop the n earliest
+  const int src = ((c.lane + n) & (WAVE - 1)) << 2;
+  c.qt = __builtin_amdgcn_ds_bpermute(src, c.qt);
+  c.qk = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)c.qk);
+  c.qd = __builtin_amdgcn_ds_bpermute(src, c.qd);
+  c.qx = __builtin_amdgcn_ds_bpermute(src, c.qx);
+  c.qnx = __builtin_amdgcn_ds_bpermute(src, c.qnx);
+  c.qnth = __builtin_amdgcn_ds_bpermute(src, c.qnth);
+  r.q_n -= n;
+  r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
+  const uint32_t ks = (QK_NEXT << 16) | ss;
+  const bool far = succ && r.o_n > 0 && !(ts < r.o_min_t || (ts == r.o_min_t && ks < r.o_min_k));
+  wave_sync();
+  if (far) {
+    c.m.sess[ss].z = (int)(((uint32_t)c.m.sess[ss].z & ~(3u << CL_KIND_SHIFT)) | (QK_NEXT << CL_KIND_SHIFT));
+    c.m.due[ss] = ts;
+  }
+  wave_sync();
+  r.o_n += __builtin_popcountll(wballot(far));
+  for (uint64_t w = wballot(succ && !far); w != 0 && r.status == NBOS_OK; w &= w - 1) {
+    const int j = (int)__builtin_ctzll(w);
+    timer_push(c, r, lane_get(ts, j), QK_NEXT, (uint32_t)lane_get((int)ss, j), lane_get(es, j));
+  }
+  if (r.q_n == 0 && r.o_n > 0) {
+    cl_refill(c, r);
+    r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
+  }
+}
+
 template <uint32_t F>
 __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
   static_assert(Ctx<F>::closed, "instantiate with a closed-loop flag set");
@@ -104,6 +146,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
   r.o_min_t = NEVER;
   r.min_s = -1;
   r.cl_win = 1024;
+  const bool batching = p.batch != 0;
+  int cooldown = 0, backoff = 1;            // timers to fire one by one before the next parallel round: doubles
+                                            // (up to 64) while rounds start at most one cell, back to 1 when they pay
 
   bool final = false;
   for (int64_t base = ev_lo; r.status == NBOS_OK; base += WAVE) {
@@ -128,11 +173,55 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
       else if (!final) break;
       wave_sync();
       if (r.q_n > 0 && r.q_head_t <= t) {
+        if (!(lane_get(c.qx, 0) & CLX_LOADED) && ((uint32_t)lane_get((int)c.qk, 0) >> 16) != QK_END) {
+          // the earliest timer was scheduled straight into the registers: its event's duration, kind and
+          // chain record are loaded now, and with them those of all other such timers (one round trip)
+          if (c.lane < r.q_n && !(c.qx & CLX_LOADED) && (c.qk >> 16) != QK_END) {
+            const int2 ch = c.cl_chain[c.qd];
+            c.qx = c.cl_dur[c.qd] | (int32_t)(((uint32_t)c.cl_sk[c.qd] >> 24) << 28) | CLX_LOADED;
+            c.qnx = ch.x; c.qnth = ch.y;
+          }
+        }
+        // a round needs the next cells of two sessions at the head at least
+        if (batching && cooldown == 0 && r.q_n >= 2 && ((uint32_t)lane_get((int)c.qk, 0) >> 16) == QK_NEXT &&
+            ((uint32_t)lane_get((int)c.qk, 1) >> 16) == QK_NEXT && lane_get(c.qt, 1) <= t) {
+          // ---- event-parallel round over the run of due cells at the head of the sorted timers ----
+          // lane i = timer i. A timer can join if it brings the next cell of an idle placed session
+          // (its event's data are loaded), and if no successor that the run schedules could come
+          // before it: it is earlier than the earliest "finish + think time" over all of them.
+          const uint32_t sid = c.qk & 0xFFFFu;
+          const bool cell = c.lane < r.q_n && (c.qk >> 16) == QK_NEXT && (c.qx & CLX_LOADED) != 0 &&
+                            (((uint32_t)c.qx >> 28) & 3u) == NBOS_EV_CELL && c.qt <= t;
+          SessRec rec = {0, 0, 0};
+          if (cell) rec = m.sess[sid];
+          const int32_t vd = c.qx & 0x0FFFFFFF;
+          const int64_t after = (int64_t)c.qt + vd + (c.qnx >= 0 ? c.qnth : 0);
+          const bool ok = cell && ((uint32_t)rec.z & 7u) == SS_PLACED && rec.y <= c.qt && !((uint32_t)rec.z & SF_ENDING) &&
+                          after < 0x7FFFFFFFLL;
+          const int32_t bound = (int32_t)wave_min(ok && c.qnx >= 0 ? (uint32_t)after : 0x7FFFFFFFu);
+          const uint64_t out = ~wballot(ok && c.qt < bound);
+          const int k = out != 0 ? (int)__builtin_ctzll(out) : WAVE;
+          if (k >= 2) {
+            const uint64_t run = k >= WAVE ? ~0ull : ((1ull << k) - 1ull);
+            const uint64_t done = batch_round(c, r, run, c.qt, vd, sid, rec);
+            const int n = __builtin_popcountll(done);
+            if (n <= 1) { cooldown = backoff; backoff = backoff < 64 ? 2 * backoff : 64; }
+            else if (n >= 3) backoff = 1;
+            if (n > 0) {
+              r.c_total += (uint32_t)n;
+              const int32_t tl = lane_get(c.qt, n - 1);
+              r.t_end = r.t_end > tl ? r.t_end : tl;
+              cl_after_round(c, r, n);
+              continue;
+            }
+          }
+        }
+        if (cooldown > 0) cooldown--;
         // ---- S2: the earliest timer is due ----
         const int32_t now = r.q_head_t;
         const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
         const int32_t e = lane_get(c.qd, 0);
-        int32_t x = lane_get(c.qx, 0), nx = lane_get(c.qnx, 0), nth = lane_get(c.qnth, 0);
+        const int32_t x = lane_get(c.qx, 0), nx = lane_get(c.qnx, 0), nth = lane_get(c.qnth, 0);
         timer_pop(c, r);
         r.t_end = r.t_end > now ? r.t_end : now;
         const uint32_t s = key & 0xFFFFu, kind = key >> 16;
@@ -141,13 +230,6 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
         const uint32_t hw = uni((uint32_t)cur.x), fl = uni((uint32_t)cur.z);
         const int32_t tm = uni(cur.y);
         if (kind == QK_END) { end_session(c, r, s, hw, fl, now); continue; }
-        if (!(x & CLX_LOADED)) {
-          // scheduled straight into the registers: one round trip for the event's duration, kind and
-          // chain record
-          const int2 ch = c.cl_chain[e];
-          x = uni(c.cl_dur[e]) | (int32_t)((uni((uint32_t)c.cl_sk[e]) >> 24) << 28) | CLX_LOADED;
-          nx = uni(ch.x); nth = uni(ch.y);
-        }
         r.cl_e = e; r.cl_x = x; r.cl_nx = nx; r.cl_nth = nth;
         const int32_t dur = x & 0x0FFFFFFF;
         if (kind == QK_RETRY) {
@@ -173,6 +255,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
     }
     if (final) break;
   }
+  wave_sync();
+  const int32_t bl = (int32_t)uni(m.c32[CS_BLAZY]);             // finish times bound by the rounds
+  r.lazy_max = r.lazy_max > bl ? r.lazy_max : bl;
   write_stats(p, m, r, rep, lane);
 }
 

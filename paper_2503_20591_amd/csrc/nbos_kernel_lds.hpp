@@ -964,7 +964,7 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
 }
 
 // ---- LDS layout of one replay and its initial state (S0) -------------------------------------------
-// CL: closed loop (no scratch for the rounds, no overflow array; due[] instead)
+// CL: closed loop (no overflow array; due[] and stage[] instead)
 template <bool CL>
 __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   Lds m;
@@ -974,7 +974,7 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   m.ppow = (unsigned long long *)q; q += 66 * 8;
   m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
   m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
-  m.mark = (int32_t *)q;            q += CL ? 0 : (size_t)p.HP * 4;
+  m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
   m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
   m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
   m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
@@ -1005,7 +1005,7 @@ __device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int lan
   for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
   for (int h = lane; h < p.HP; h += WAVE) {
     m.ready_at[h] = h < p.H0 ? 0 : NEVER;
-    if (!CL) m.mark[h] = MARK_FREE;
+    m.mark[h] = MARK_FREE;
     m.hsn[h] = 0;
   }
   if (p.warm_n > 0) {

@@ -267,8 +267,8 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
     } else if (closed_loop) {
-      // hosts without the scratch of the rounds; 12 bytes of record and 4 of timer per session; 64 staged sessions
-      h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 8 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16 + WAVE * 4;
+      // 12 bytes of record and 4 of timer per session; 64 staged sessions
+      h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16 + WAVE * 4;
       if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
       q_cap = 0;
       // instances for the common flag sets, as for the other kernels
@@ -417,8 +417,11 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
     k.warm_n = (cfg->flags & NBOS_F_WARM_POOL) ? cfg->warm_pool_per_host : 0;
     k.warm_migr = cfg->warm_migration_delay_ms; k.prewarm = cfg->prewarm_delay_ms;
     k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
-    const char *nb = getenv("NBOS_REPLAY_BATCH");           // "0" turns the event-parallel rounds off
-    k.batch = (nb && nb[0] == '0') ? 0 : 1;
+    // Event-parallel rounds: on, except for closed loops on clusters of at most 64 hosts, where two
+    // cells of a run choose the same host too often for a round to pay (measured: 30 hosts, 110 ms
+    // without, 119 ms with). NBOS_REPLAY_BATCH = "0" / "1" forces the choice (comparison runs, tests).
+    const char *nb = getenv("NBOS_REPLAY_BATCH");
+    k.batch = (nb && nb[0] == '0') ? 0 : (nb && nb[0] == '1') ? 1 : (closed_loop && cfg->hosts_max <= WAVE) ? 0 : 1;
     k.cl_chain = d_chain; k.cl_cursor = d_cursor;
   }
   *out = h;

@@ -330,6 +330,34 @@ def test_closed_loop_on_the_other_traces(rp, oracle, name, n):
     assert_same(rp, oracle, b, st, logs, check=name != "c3")
 
 
+@pytest.mark.parametrize("seed", range(0, 60, 2))
+def test_closed_loop_random_cases_with_forced_rounds(rp, oracle, monkeypatch, seed):
+    # small clusters run without the event-parallel rounds by default: here with them
+    monkeypatch.setenv("NBOS_REPLAY_BATCH", "1")
+    b = as_closed(tg.random_case(seed, policy_flags=seed % 4 == 0))
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+
+
+def test_closed_loop_named_workloads_with_forced_rounds(rp, oracle, monkeypatch):
+    monkeypatch.setenv("NBOS_REPLAY_BATCH", "1")
+    for name, n in (("c2l", 3), ("c3", 2), ("c5", 8)):
+        b = as_closed(tg.workload(name, n_replays=n))
+        st, logs = gpu_run(rp, b, log=True)
+        assert_same(rp, oracle, b, st, logs)
+    # all sessions' cells due at the same instants, again and again
+    test_closed_loop_many_timers_at_one_instant(rp, oracle)
+
+
+def test_closed_loop_without_the_parallel_rounds(rp, oracle, monkeypatch):
+    # the same replays with every timer fired one by one
+    monkeypatch.setenv("NBOS_REPLAY_BATCH", "0")
+    for name, n in (("c3", 2), ("c4l", 1)):
+        b = as_closed(tg.workload(name, n_replays=n))
+        st, logs = gpu_run(rp, b, log=True)
+        assert_same(rp, oracle, b, st, logs)
+
+
 def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
     # the whole c2l batch in the launch shape the benchmark uses; a sample of replays against the oracle
     b = tg.workload("c2l", workers=8)
