@@ -63,10 +63,14 @@ class TraceBatch:
         return int(per_trace[self.trace_of_replay].sum())
 
     def algorithmic_bytes(self, stats_bytes: int) -> int:
-        """12 B per event + 1 B per session + 8 B per replay read, one stats record written."""
+        """12 B per event + 1 B per session + 8 B per replay read, one stats record written.
+        Closed loop: 32 B per event (time, kind word and 8-byte chain record from the stream; duration,
+        kind word and chain record again when the event's timer fires) + 8 B per event for the cursor
+        (written when the timer is scheduled, read when it moves into the sorted registers)."""
         ev = np.diff(self.ev_offset)[self.trace_of_replay].sum()
         ss = np.diff(self.sess_offset)[self.trace_of_replay].sum()
-        return int(12 * ev + ss + (8 + stats_bytes) * self.n_replays)
+        per_event = 40 if self.config.get("flags", 0) & F_CLOSED_LOOP else 12
+        return int(per_event * ev + ss + (8 + stats_bytes) * self.n_replays)
 
 
 # ---- samplers: float64 seconds -> integer milliseconds ---------------------------------------
