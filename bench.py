@@ -61,6 +61,23 @@ def cpu_baseline(batch, budget_s: float, threads: int):
                       f"{threads} thread(s), {dt:.1f} s"}
 
 
+def measured_copy_gbs(torch):
+    """What a plain device-to-device copy reaches on this GPU (bytes read + written per second): the
+    achievable HBM rate the 8 TB/s vendor peak is put beside."""
+    n = 512 * 1024 * 1024
+    src = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +136,7 @@ def main():
     st = h.stats()
     assert (st["status"] == 0).all()
     h.close()
+    copy_gbs = measured_copy_gbs(torch)
 
     ms_per_step = wall * 1e3 / args.steps
     cells = batch.n_cells()
@@ -144,6 +162,7 @@ def main():
                    "gen_s": round(t_gen, 2), "upload_s": round(t_up, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
+                     "copy_gbs": copy_gbs, "frac_of_copy": achieved / copy_gbs,
                      "traffic": None if (args.replays or args.hosts_in_lds) else measured_traffic(args.workload),
                      "kernel": "nbos_replay_kernel", "kernel_ms": avg_kernel_ms, "algorithmic_bytes": alg_bytes,
                      "ns_per_event_per_replay": avg_kernel_ms * 1e6 / (batch.n_events() / max(batch.n_replays, 1))},
