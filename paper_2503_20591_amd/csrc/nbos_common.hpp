@@ -16,7 +16,6 @@ constexpr int NGPU = NBOS_MAX_GPUS;
 constexpr uint32_t SS_UNPLACED = 0, SS_PLACED = 1, SS_QUEUED = 2, SS_REJECTED = 3, SS_ENDED = 4;
 // session flag word: state[0..2] g-1[3..5] ending[6] queued_once[7] retries[8..11]
 constexpr uint32_t SF_ENDING = 1u << 6, SF_QONCE = 1u << 7;
-constexpr uint32_t SF_OVF = 1u << 12;     // the session's pending timer waits outside the sorted registers
 // queue entry kinds, in the order they run when due at the same time
 constexpr uint32_t QK_END = 0, QK_RETRY = 2, QK_NEXT = 3;   // QK_NEXT: closed loop, the session's next event is due
 

@@ -144,40 +144,26 @@ void free_handle(nbos_replay *h) {
   if (h->e1) (void)hipEventDestroy(h->e1);
   delete h;
 }
-}  // namespace
 
-extern "C" {
+// ---- steps of nbos_replay_create -------------------------------------------------------------------
+#define HIP_TRY(x) do { if ((x) != hipSuccess) return NBOS_E_HIP; } while (0)
 
-const char *nbos_strerror(int32_t status) {
-  switch (status) {
-    case NBOS_OK: return "ok";
-    case NBOS_E_ARG: return "invalid argument";
-    case NBOS_E_RANGE: return "invalid trace content";
-    case NBOS_E_LIMIT: return "beyond a compiled or device limit";
-    case NBOS_E_HIP: return "HIP runtime error";
-    case NBOS_E_NOMEM: return "out of memory";
-    case NBOS_E_STATE: return "call not valid in this state";
-    default: return "unknown status";
-  }
-}
-
-int32_t nbos_sizeof_stats(void) { return (int32_t)sizeof(nbos_stats); }
-
-int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, void *stream, nbos_replay **out) {
-  if (out) *out = nullptr;
-  if (!cfg_in || !in || !out) return NBOS_E_ARG;
-  // earlier, shorter layouts are accepted as well: the later fields read as 0
+// the configuration in the current layout (earlier, shorter layouts are accepted: later fields read as 0)
+int32_t read_config(const nbos_config *cfg_in, nbos_config *full) {
   constexpr uint32_t kShortConfig = offsetof(nbos_config, autoscale_f_milli);
   constexpr uint32_t kMidConfig = offsetof(nbos_config, batch_start_delay_ms);
   constexpr uint32_t kBatchConfig = offsetof(nbos_config, warm_pool_per_host);
   if (cfg_in->struct_size != sizeof(nbos_config) && cfg_in->struct_size != kShortConfig &&
       cfg_in->struct_size != kMidConfig && cfg_in->struct_size != kBatchConfig)
     return NBOS_E_ARG;
-  nbos_config full;
-  memset(&full, 0, sizeof full);
-  memcpy(&full, cfg_in, cfg_in->struct_size);
-  full.struct_size = sizeof(nbos_config);
-  const nbos_config *cfg = &full;
+  memset(full, 0, sizeof *full);
+  memcpy(full, cfg_in, cfg_in->struct_size);
+  full->struct_size = sizeof(nbos_config);
+  return NBOS_OK;
+}
+
+// host-side checks of the parameters
+int32_t check_config(const nbos_config *cfg, const nbos_inputs *in) {
   if (cfg->n_replays < 0 || cfg->n_traces < 0 || (cfg->n_replays > 0 && cfg->n_traces < 1)) return NBOS_E_ARG;
   if (cfg->replicas != 3) return NBOS_E_ARG;
   if (cfg->gpus_per_host < 1 || cfg->gpus_per_host > NBOS_MAX_GPUS) return NBOS_E_ARG;
@@ -212,224 +198,292 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   }
   if (cfg->n_replays > 0 &&
       (!in->ev_offset || !in->sess_offset || !in->trace_of_replay || !in->cap_milli)) return NBOS_E_ARG;
-  // the time a replay can reach beyond its last arrival
+  return NBOS_OK;
+}
+
+// the time a replay can reach beyond its last arrival
+int64_t time_slack(const nbos_config *cfg) {
   int64_t slowest = cfg->migration_delay_ms;
   if ((cfg->flags & NBOS_F_WARM_POOL) && cfg->warm_migration_delay_ms > slowest) slowest = cfg->warm_migration_delay_ms;
-  int64_t slack = (int64_t)NBOS_MAX_DUR_MS + (int64_t)cfg->max_retries * cfg->retry_interval_ms +
-                  cfg->boot_delay_ms + slowest + ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0);
-  bool batch_mode = (cfg->flags & NBOS_F_BATCH_MODE) != 0;
-  bool warm_pool = (cfg->flags & NBOS_F_WARM_POOL) != 0;
-  bool closed_loop = (cfg->flags & NBOS_F_CLOSED_LOOP) != 0;
+  return (int64_t)NBOS_MAX_DUR_MS + (int64_t)cfg->max_retries * cfg->retry_interval_ms + cfg->boot_delay_ms + slowest +
+         ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0);
+}
+
+// what create works out about the batch before it chooses a kernel
+struct Shape {
+  int32_t max_sess = 0;     // most sessions in one trace
+  int64_t max_ev = 0;       // most events in one trace
+  int64_t total_ev = 0;
+  int HP = 0;               // hosts_max rounded up to whole waves
+  int n_cap = 1;            // session capacity of a replay's LDS
+  size_t q_cap = 0;         // any-size kernel: timers that fit beside the 64 sorted ones
+  bool in_regs = false;     // the register kernel runs
+};
+
+// the offsets of the traces, copied to the host
+int32_t read_offsets(nbos_replay *h, Shape *sh) {
+  const nbos_config *cfg = &h->cfg;
+  const nbos_inputs *in = &h->in;
+  const int nt = cfg->n_traces;
+  if (cfg->n_replays == 0) return NBOS_OK;
+  h->ev_off.resize((size_t)nt + 1);
+  h->sess_off.resize((size_t)nt + 1);
+  HIP_TRY(hipMemcpyAsync(h->ev_off.data(), in->ev_offset, sizeof(int64_t) * (nt + 1), hipMemcpyDeviceToHost, h->stream));
+  HIP_TRY(hipMemcpyAsync(h->sess_off.data(), in->sess_offset, sizeof(int32_t) * (nt + 1), hipMemcpyDeviceToHost, h->stream));
+  HIP_TRY(hipStreamSynchronize(h->stream));
+  if (h->ev_off[0] != 0 || h->sess_off[0] != 0) return NBOS_E_RANGE;
+  for (int t = 0; t < nt; t++) {
+    const int64_t ne = h->ev_off[t + 1] - h->ev_off[t];
+    const int64_t ns = (int64_t)h->sess_off[t + 1] - h->sess_off[t];
+    if (ne < 0 || ns < 0) return NBOS_E_RANGE;
+    if (ns > NBOS_MAX_SESSIONS) return NBOS_E_LIMIT;
+    if ((cfg->flags & NBOS_F_CLOSED_LOOP) && ne >= 0x40000000LL) return NBOS_E_LIMIT;    // event indices within a trace
+    if (ns > sh->max_sess) sh->max_sess = (int32_t)ns;
+    if (ne > sh->max_ev) sh->max_ev = ne;
+  }
+  sh->total_ev = h->ev_off[nt];
+  if ((sh->total_ev > 0 && (!in->ev_time_ms || !in->ev_dur_ms || !in->ev_sess_kind)) ||
+      (h->sess_off[nt] > 0 && !in->sess_gpus))
+    return NBOS_E_ARG;
+  return NBOS_OK;
+}
+
+// which flavour of the register kernel: see the comment inside
+int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
+  const nbos_config *cfg = &h->cfg;
+  // The common policy flag sets have kernels compiled for them (everything that is switched off
+  // is gone from the code). They have the shorter path per item and need fewer registers; the
+  // generic kernel executes about 9 % fewer scalar instructions (it keeps hoisted flag tests in
+  // spilled registers). Which one is faster depends on what bounds the batch (all measured):
+  //  - a replay has a SIMD to itself (at most 4 workgroups per compute unit): the length of the
+  //    path counts, the instance for the flag set is 10 % faster;
+  //  - 5 or more waves per SIMD resident: instruction issue counts, the generic kernel is 5 %
+  //    faster;
+  //  - in between, waves hide little of each other's latency and a batch that does not fit at
+  //    once runs in rounds: the kernel that needs fewer rounds wins, the generic one on a tie
+  //    (64 hosts, 4,096 replays: 297 ms with 16 workgroups per compute unit resident, 436 ms
+  //    with 12; the kernels are compiled for at most 128 registers so that 16 fit).
+  const int nj = (cfg->hosts_max + 7) / 8;
+  const uint32_t policy = cfg->flags & regk::kPolicyFlags;
+  const void *generic = reg_kernel_for<regk::kRuntimeFlags>(nj);
+  const void *special = policy == 0u ? reg_kernel_for<0u>(nj)
+                      : policy == NBOS_F_MIGRATE ? reg_kernel_for<NBOS_F_MIGRATE>(nj)
+                      : policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT) ? reg_kernel_for<NBOS_F_MIGRATE | NBOS_F_SCALE_OUT>(nj)
+                      : generic;
+  int cus = 0;
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
+  const char *ng = getenv("NBOS_REPLAY_GENERIC");         // "0" / "1" force the choice (comparison runs)
+  bool use_generic;
+  if (ng && (ng[0] == '0' || ng[0] == '1')) {
+    use_generic = ng[0] == '1';
+  } else {
+    const int per_cu = cus > 0 ? (cfg->n_replays + cus - 1) / cus : cfg->n_replays;
+    hipFuncAttributes fa_g, fa_s;
+    HIP_TRY(hipFuncGetAttributes(&fa_g, generic));
+    HIP_TRY(hipFuncGetAttributes(&fa_s, special));
+    const int by_lds = (int)((size_t)maxlds / ((h->lds_bytes + 511) / 512 * 512));
+    auto resident = [&](const hipFuncAttributes &fa) {      // workgroups (= waves) per compute unit
+      const int regs = (fa.numRegs + 7) / 8 * 8;
+      int per_simd = regs > 0 ? 512 / regs : 8;
+      per_simd = per_simd > 8 ? 8 : per_simd;
+      const int by_regs = 4 * per_simd;
+      return by_lds < by_regs ? by_lds : by_regs;
+    };
+    const int res_g = resident(fa_g) > 0 ? resident(fa_g) : 1, res_s = resident(fa_s) > 0 ? resident(fa_s) : 1;
+    if (per_cu <= 4) use_generic = false;
+    else if ((per_cu < res_g ? per_cu : res_g) >= 20) use_generic = true;
+    else use_generic = (per_cu + res_s - 1) / res_s >= (per_cu + res_g - 1) / res_g;
+  }
+  h->kernel = use_generic ? generic : special;
+  return NBOS_OK;
+}
+
+// kernel choice and LDS footprint of one replay
+int32_t choose_kernel(nbos_replay *h, Shape *sh) {
+  const nbos_config *cfg = &h->cfg;
+  const bool batch_mode = (cfg->flags & NBOS_F_BATCH_MODE) != 0, warm_pool = (cfg->flags & NBOS_F_WARM_POOL) != 0;
+  const bool closed_loop = (cfg->flags & NBOS_F_CLOSED_LOOP) != 0;
+  int maxlds = 0;
+  HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
+  sh->in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
+  sh->HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
+  sh->n_cap = sh->max_sess > 0 ? sh->max_sess : 1;
+  sh->q_cap = (size_t)sh->n_cap + 1;               // at most one queued timer per session
+  const int HP = sh->HP;
+  const size_t n_cap = (size_t)sh->n_cap;
+  const char *ng = getenv("NBOS_REPLAY_GENERIC");
+  if (batch_mode) {
+    h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + n_cap * 12 + (n_cap + 2) * 2;
+    if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
+    h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
+  } else if (closed_loop) {
+    // 12 bytes of record and 4 of timer per session; 64 staged sessions
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 16 + WAVE * 4;
+    if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
+    sh->q_cap = 0;
+    // instances for the common flag sets, as for the other kernels
+    const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
+    constexpr uint32_t kMigr = NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP, kMigrOut = kMigr | NBOS_F_SCALE_OUT;
+    if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
+    else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigr>;
+    else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigrOut>;
+    else h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
+  } else if (sh->in_regs) {
+    h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8;
+    if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
+    const int32_t rc = choose_reg_kernel(h, maxlds);
+    if (rc != NBOS_OK) return rc;
+  } else {
+    const size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12;
+    if (fixed + 12 * 64 > (size_t)maxlds) return NBOS_E_LIMIT;
+    if (fixed + sh->q_cap * 12 > (size_t)maxlds) sh->q_cap = ((size_t)maxlds - fixed) / 12;
+    h->lds_bytes = fixed + sh->q_cap * 12;
+    // same idea as for the register kernel; its batches are small (the LDS footprint allows few
+    // workgroups per compute unit), so the instance compiled for the flag set is used whenever
+    // there is one
+    const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
+    constexpr uint32_t kAllScaling = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN;
+    if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
+    else if (policy == kAllScaling) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAllScaling>;
+    else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<NBOS_F_MIGRATE>;
+    else h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
+  }
+  HIP_TRY(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
+  return NBOS_OK;
+}
+
+// device-side validation of the trace contents
+int32_t validate_on_device(nbos_replay *h, int64_t slack) {
+  const nbos_config *cfg = &h->cfg;
+  const nbos_inputs *in = &h->in;
+  if (cfg->n_replays == 0) return NBOS_OK;
+  uint32_t *d_err = nullptr, h_err = 0;
+  if (hipMalloc(&d_err, sizeof(uint32_t)) != hipSuccess) return NBOS_E_NOMEM;
+  hipError_t e = hipMemsetAsync(d_err, 0, sizeof(uint32_t), h->stream);
+  if (e == hipSuccess) {
+    const int32_t t_limit = (int32_t)(0x7FFFFFFELL - slack);
+    hipLaunchKernelGGL(nbos_validate_traces, dim3(cfg->n_traces), dim3(256), 0, h->stream, in->ev_offset, in->ev_time_ms,
+                       in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, in->sess_gpus, cfg->gpus_per_host,
+                       t_limit, d_err);
+    hipLaunchKernelGGL(nbos_validate_replays, dim3((cfg->n_replays + 255) / 256), dim3(256), 0, h->stream,
+                       in->trace_of_replay, in->cap_milli, cfg->n_replays, cfg->n_traces, d_err);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, h->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+  (void)hipFree(d_err);
+  if (e != hipSuccess) return NBOS_E_HIP;
+  return h_err ? NBOS_E_RANGE : NBOS_OK;
+}
+
+// result buffers, and what single kernels need beside them
+int32_t allocate_buffers(nbos_replay *h, const Shape &sh) {
+  const nbos_config *cfg = &h->cfg;
+  const nbos_inputs *in = &h->in;
+  const size_t n = (size_t)cfg->n_replays;
+  if (n == 0) return NBOS_OK;
+  if (hipMalloc(&h->d_stats, sizeof(nbos_stats) * n) != hipSuccess) return NBOS_E_NOMEM;
+  if (hipMalloc(&h->d_bill, sizeof(nbos_bill) * n) != hipSuccess) return NBOS_E_NOMEM;
+  if (sh.in_regs && hipMalloc(&h->d_ovf, sizeof(int32_t) * n * (size_t)sh.n_cap) != hipSuccess) return NBOS_E_NOMEM;
+  if (cfg->flags & NBOS_F_CLOSED_LOOP) {
+    // one allocation: chain[total_ev] (two words each), cursor[n_replays][n_cap]; the chains are linked here
+    const size_t words = 2 * (size_t)sh.total_ev + n * (size_t)sh.n_cap;
+    if (hipMalloc(&h->d_chain, sizeof(int32_t) * (words > 0 ? words : 1)) != hipSuccess) return NBOS_E_NOMEM;
+    const size_t chain_lds = (size_t)sh.n_cap * 8;
+    HIP_TRY(hipFuncSetAttribute((const void *)ldsk::nbos_closed_chain_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)chain_lds));
+    hipLaunchKernelGGL(ldsk::nbos_closed_chain_kernel, dim3(cfg->n_traces), dim3(WAVE), chain_lds, h->stream, in->ev_offset,
+                       in->ev_time_ms, in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, (int2 *)h->d_chain);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(h->stream));
+  }
+  if (cfg->flags & NBOS_F_DECISION_LOG) {
+    h->trace_of_replay.resize(n);
+    HIP_TRY(hipMemcpyAsync(h->trace_of_replay.data(), in->trace_of_replay, sizeof(int32_t) * n, hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    h->kp.dlog_stride = 3 * (int64_t)sh.max_sess + sh.max_ev + 4096;
+    if (hipMalloc(&h->d_log, sizeof(uint64_t) * (size_t)h->kp.dlog_stride * n) != hipSuccess) return NBOS_E_NOMEM;
+  }
+  return NBOS_OK;
+}
+
+// the kernels' parameter block
+void fill_params(nbos_replay *h, const Shape &sh) {
+  const nbos_config *cfg = &h->cfg;
+  const nbos_inputs *in = &h->in;
+  KParams &k = h->kp;
+  k.ev_offset = in->ev_offset; k.ev_time = in->ev_time_ms; k.ev_dur = in->ev_dur_ms; k.ev_sk = in->ev_sess_kind;
+  k.sess_offset = in->sess_offset; k.sess_gpus = in->sess_gpus;
+  k.trace_of_replay = in->trace_of_replay; k.cap_milli = in->cap_milli;
+  k.stats = h->d_stats; k.dlog = h->d_log; k.ovf_dur = h->d_ovf;       // dlog_stride: set with the log's allocation
+  k.n_replays = cfg->n_replays; k.H0 = cfg->hosts_initial; k.Hmax = cfg->hosts_max; k.HP = sh.HP;
+  k.G = cfg->gpus_per_host; k.flags = cfg->flags;
+  k.migr = cfg->migration_delay_ms; k.boot = cfg->boot_delay_ms; k.retry_iv = cfg->retry_interval_ms;
+  k.max_retries = cfg->max_retries;
+  k.scale_iv = (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) ? cfg->scale_interval_ms : 1;
+  k.idle_pct = cfg->scale_in_idle_pct; k.min_hosts = cfg->min_hosts;
+  k.f_milli = cfg->autoscale_f_milli; k.buffer = cfg->scaling_buffer_hosts;
+  k.batch_delay = cfg->batch_start_delay_ms;
+  k.warm_n = (cfg->flags & NBOS_F_WARM_POOL) ? cfg->warm_pool_per_host : 0;
+  k.warm_migr = cfg->warm_migration_delay_ms; k.prewarm = cfg->prewarm_delay_ms;
+  k.n_cap = sh.n_cap; k.q_cap = (int32_t)sh.q_cap;
+  // Event-parallel rounds: on, except for closed loops on clusters of at most 64 hosts, where two
+  // cells of a run choose the same host too often for a round to pay (measured: 30 hosts, 110 ms
+  // without, 119 ms with). NBOS_REPLAY_BATCH = "0" / "1" forces the choice (comparison runs, tests).
+  const char *nb = getenv("NBOS_REPLAY_BATCH");
+  const bool closed_loop = (cfg->flags & NBOS_F_CLOSED_LOOP) != 0;
+  k.batch = (nb && nb[0] == '0') ? 0 : (nb && nb[0] == '1') ? 1 : (closed_loop && cfg->hosts_max <= WAVE) ? 0 : 1;
+  k.cl_chain = (const int2 *)h->d_chain;
+  k.cl_cursor = h->d_chain ? h->d_chain + 2 * (size_t)sh.total_ev : nullptr;
+}
+#undef HIP_TRY
+}  // namespace
+
+extern "C" {
+
+const char *nbos_strerror(int32_t status) {
+  switch (status) {
+    case NBOS_OK: return "ok";
+    case NBOS_E_ARG: return "invalid argument";
+    case NBOS_E_RANGE: return "invalid trace content";
+    case NBOS_E_LIMIT: return "beyond a compiled or device limit";
+    case NBOS_E_HIP: return "HIP runtime error";
+    case NBOS_E_NOMEM: return "out of memory";
+    case NBOS_E_STATE: return "call not valid in this state";
+    default: return "unknown status";
+  }
+}
+
+int32_t nbos_sizeof_stats(void) { return (int32_t)sizeof(nbos_stats); }
+
+int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, void *stream, nbos_replay **out) {
+  if (out) *out = nullptr;
+  if (!cfg_in || !in || !out) return NBOS_E_ARG;
+  nbos_config cfg;
+  int32_t rc = read_config(cfg_in, &cfg);
+  if (rc == NBOS_OK) rc = check_config(&cfg, in);
+  if (rc != NBOS_OK) return rc;
+  const int64_t slack = time_slack(&cfg);
   if (slack >= 0x7FFFFFFFLL) return NBOS_E_ARG;
 
   nbos_replay *h = new (std::nothrow) nbos_replay();
   if (!h) return NBOS_E_NOMEM;
-  h->cfg = *cfg; h->in = *in; h->stream = (hipStream_t)stream;
-  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_chain = nullptr; h->d_log = nullptr; h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
-  int32_t rc = NBOS_OK;
-#define HIP_TRY(x) do { if ((x) != hipSuccess) { rc = NBOS_E_HIP; goto fail; } } while (0)
-  {
-    HIP_TRY(hipGetDevice(&h->device));
-    HIP_TRY(hipEventCreate(&h->e0));
-    HIP_TRY(hipEventCreate(&h->e1));
-    const int nt = cfg->n_traces;
-    int32_t max_sess = 0;
-    int64_t total_ev = 0;
-    if (cfg->n_replays > 0) {
-      h->ev_off.resize((size_t)nt + 1);
-      h->sess_off.resize((size_t)nt + 1);
-      HIP_TRY(hipMemcpyAsync(h->ev_off.data(), in->ev_offset, sizeof(int64_t) * (nt + 1), hipMemcpyDeviceToHost, h->stream));
-      HIP_TRY(hipMemcpyAsync(h->sess_off.data(), in->sess_offset, sizeof(int32_t) * (nt + 1), hipMemcpyDeviceToHost, h->stream));
-      HIP_TRY(hipStreamSynchronize(h->stream));
-      if (h->ev_off[0] != 0 || h->sess_off[0] != 0) { rc = NBOS_E_RANGE; goto fail; }
-      for (int t = 0; t < nt; t++) {
-        int64_t ne = h->ev_off[t + 1] - h->ev_off[t];
-        int64_t ns = (int64_t)h->sess_off[t + 1] - h->sess_off[t];
-        if (ne < 0 || ns < 0) { rc = NBOS_E_RANGE; goto fail; }
-        if (ns > NBOS_MAX_SESSIONS) { rc = NBOS_E_LIMIT; goto fail; }
-        if (closed_loop && ne >= 0x40000000LL) { rc = NBOS_E_LIMIT; goto fail; }    // event indices within a trace
-        if (ns > max_sess) max_sess = (int32_t)ns;
-      }
-      total_ev = h->ev_off[nt];
-      if ((total_ev > 0 && (!in->ev_time_ms || !in->ev_dur_ms || !in->ev_sess_kind)) ||
-          (h->sess_off[nt] > 0 && !in->sess_gpus)) { rc = NBOS_E_ARG; goto fail; }
-    }
-
-    // kernel choice and LDS footprint of one replay
-    int maxlds = 0;
-    HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    const bool in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
-    const int HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
-    const int n_cap = max_sess > 0 ? max_sess : 1;
-    size_t q_cap = (size_t)n_cap + 1;               // at most one queued timer per session
-    if (batch_mode) {
-      h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + (size_t)n_cap * 12 + ((size_t)n_cap + 2) * 2;
-      if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
-      h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
-    } else if (closed_loop) {
-      // 12 bytes of record and 4 of timer per session; 64 staged sessions
-      h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 16 + WAVE * 4;
-      if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
-      q_cap = 0;
-      // instances for the common flag sets, as for the other kernels
-      const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
-      const char *ng = getenv("NBOS_REPLAY_GENERIC");
-      constexpr uint32_t kMigr = NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP, kMigrOut = kMigr | NBOS_F_SCALE_OUT;
-      if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
-      else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigr>;
-      else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigrOut>;
-      else h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
-    } else if (in_regs) {
-      h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + (size_t)n_cap * 8;
-      if (h->lds_bytes > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
-      // The common policy flag sets have kernels compiled for them (everything that is switched off
-      // is gone from the code). They have the shorter path per item and need fewer registers; the
-      // generic kernel executes about 9 % fewer scalar instructions (it keeps hoisted flag tests in
-      // spilled registers). Which one is faster depends on what bounds the batch (all measured):
-      //  - a replay has a SIMD to itself (at most 4 workgroups per compute unit): the length of the
-      //    path counts, the instance for the flag set is 10 % faster;
-      //  - 5 or more waves per SIMD resident: instruction issue counts, the generic kernel is 5 %
-      //    faster;
-      //  - in between, waves hide little of each other's latency and a batch that does not fit at
-      //    once runs in rounds: the kernel that needs fewer rounds wins, the generic one on a tie
-      //    (64 hosts, 4,096 replays: 297 ms with 16 workgroups per compute unit resident, 436 ms
-      //    with 12; the kernels are compiled for at most 128 registers so that 16 fit).
-      const int nj = (cfg->hosts_max + 7) / 8;
-      const uint32_t policy = cfg->flags & regk::kPolicyFlags;
-      const void *generic = reg_kernel_for<regk::kRuntimeFlags>(nj);
-      const void *special = policy == 0u ? reg_kernel_for<0u>(nj)
-                          : policy == NBOS_F_MIGRATE ? reg_kernel_for<NBOS_F_MIGRATE>(nj)
-                          : policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT) ? reg_kernel_for<NBOS_F_MIGRATE | NBOS_F_SCALE_OUT>(nj)
-                          : generic;
-      int cus = 0;
-      HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
-      const char *ng = getenv("NBOS_REPLAY_GENERIC");         // "0" / "1" force the choice (comparison runs)
-      bool use_generic;
-      if (ng && (ng[0] == '0' || ng[0] == '1')) {
-        use_generic = ng[0] == '1';
-      } else {
-        const int per_cu = cus > 0 ? (cfg->n_replays + cus - 1) / cus : cfg->n_replays;
-        hipFuncAttributes fa_g, fa_s;
-        HIP_TRY(hipFuncGetAttributes(&fa_g, generic));
-        HIP_TRY(hipFuncGetAttributes(&fa_s, special));
-        const int by_lds = (int)((size_t)maxlds / ((h->lds_bytes + 511) / 512 * 512));
-        auto resident = [&](const hipFuncAttributes &fa) {      // workgroups (= waves) per compute unit
-          const int regs = (fa.numRegs + 7) / 8 * 8;
-          int per_simd = regs > 0 ? 512 / regs : 8;
-          per_simd = per_simd > 8 ? 8 : per_simd;
-          const int by_regs = 4 * per_simd;
-          return by_lds < by_regs ? by_lds : by_regs;
-        };
-        const int res_g = resident(fa_g) > 0 ? resident(fa_g) : 1, res_s = resident(fa_s) > 0 ? resident(fa_s) : 1;
-        if (per_cu <= 4) use_generic = false;
-        else if ((per_cu < res_g ? per_cu : res_g) >= 20) use_generic = true;
-        else use_generic = (per_cu + res_s - 1) / res_s >= (per_cu + res_g - 1) / res_g;
-      }
-      h->kernel = use_generic ? generic : special;
-    } else {
-      size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + (size_t)n_cap * 12;
-      if (fixed + 12 * 64 > (size_t)maxlds) { rc = NBOS_E_LIMIT; goto fail; }
-      if (fixed + q_cap * 12 > (size_t)maxlds) q_cap = ((size_t)maxlds - fixed) / 12;
-      h->lds_bytes = fixed + q_cap * 12;
-      // same idea as for the register kernel; its batches are small (the LDS footprint allows few
-      // workgroups per compute unit), so the instance compiled for the flag set is used whenever
-      // there is one
-      const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
-      const char *ng = getenv("NBOS_REPLAY_GENERIC");
-      constexpr uint32_t kAllScaling = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN;
-      if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
-      else if (policy == kAllScaling) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAllScaling>;
-      else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<NBOS_F_MIGRATE>;
-      else h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
-    }
-    HIP_TRY(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
-
-    // device-side validation of the trace contents
-    if (cfg->n_replays > 0) {
-      uint32_t *d_err = nullptr, h_err = 0;
-      if (hipMalloc(&d_err, sizeof(uint32_t)) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-      hipError_t e = hipMemsetAsync(d_err, 0, sizeof(uint32_t), h->stream);
-      if (e == hipSuccess) {
-        int32_t t_limit = (int32_t)(0x7FFFFFFELL - slack);
-        hipLaunchKernelGGL(nbos_validate_traces, dim3(nt), dim3(256), 0, h->stream, in->ev_offset, in->ev_time_ms,
-                           in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, in->sess_gpus, cfg->gpus_per_host,
-                           t_limit, d_err);
-        hipLaunchKernelGGL(nbos_validate_replays, dim3((cfg->n_replays + 255) / 256), dim3(256), 0, h->stream,
-                           in->trace_of_replay, in->cap_milli, cfg->n_replays, nt, d_err);
-        e = hipGetLastError();
-      }
-      if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, h->stream);
-      if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
-      (void)hipFree(d_err);
-      if (e != hipSuccess) { rc = NBOS_E_HIP; goto fail; }
-      if (h_err) { rc = NBOS_E_RANGE; goto fail; }
-    }
-
-    if (cfg->n_replays > 0) {
-      if (hipMalloc(&h->d_stats, sizeof(nbos_stats) * (size_t)cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-      if (hipMalloc(&h->d_bill, sizeof(nbos_bill) * (size_t)cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-      if (in_regs &&
-          hipMalloc(&h->d_ovf, sizeof(int32_t) * (size_t)cfg->n_replays * (size_t)n_cap) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-    }
-    int2 *d_chain = nullptr;
-    int32_t *d_cursor = nullptr;
-    if (closed_loop && cfg->n_replays > 0) {
-      // one allocation: chain[total_ev] (two words each), cursor[n_replays][n_cap]
-      const size_t words = 2 * (size_t)total_ev + (size_t)cfg->n_replays * (size_t)n_cap;
-      if (hipMalloc(&h->d_chain, sizeof(int32_t) * (words > 0 ? words : 1)) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-      d_chain = (int2 *)h->d_chain; d_cursor = h->d_chain + 2 * (size_t)total_ev;
-      const size_t chain_lds = (size_t)n_cap * 8;
-      HIP_TRY(hipFuncSetAttribute((const void *)ldsk::nbos_closed_chain_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)chain_lds));
-      hipLaunchKernelGGL(ldsk::nbos_closed_chain_kernel, dim3(nt), dim3(WAVE), chain_lds, h->stream, in->ev_offset,
-                         in->ev_time_ms, in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, d_chain);
-      HIP_TRY(hipGetLastError());
-      HIP_TRY(hipStreamSynchronize(h->stream));
-    }
-    int64_t log_stride = 0;
-    if ((cfg->flags & NBOS_F_DECISION_LOG) && cfg->n_replays > 0) {
-      h->trace_of_replay.resize((size_t)cfg->n_replays);
-      HIP_TRY(hipMemcpyAsync(h->trace_of_replay.data(), in->trace_of_replay, sizeof(int32_t) * cfg->n_replays,
-                             hipMemcpyDeviceToHost, h->stream));
-      HIP_TRY(hipStreamSynchronize(h->stream));
-      int64_t max_ev = 0;
-      for (int t = 0; t < nt; t++) {
-        int64_t ne = h->ev_off[t + 1] - h->ev_off[t];
-        if (ne > max_ev) max_ev = ne;
-      }
-      log_stride = 3 * (int64_t)max_sess + max_ev + 4096;
-      if (hipMalloc(&h->d_log, sizeof(uint64_t) * (size_t)log_stride * cfg->n_replays) != hipSuccess) { rc = NBOS_E_NOMEM; goto fail; }
-    }
-
-    KParams &k = h->kp;
-    k.ev_offset = in->ev_offset; k.ev_time = in->ev_time_ms; k.ev_dur = in->ev_dur_ms; k.ev_sk = in->ev_sess_kind;
-    k.sess_offset = in->sess_offset; k.sess_gpus = in->sess_gpus;
-    k.trace_of_replay = in->trace_of_replay; k.cap_milli = in->cap_milli;
-    k.stats = h->d_stats; k.dlog = h->d_log; k.dlog_stride = log_stride; k.ovf_dur = h->d_ovf;
-    k.n_replays = cfg->n_replays; k.H0 = cfg->hosts_initial; k.Hmax = cfg->hosts_max; k.HP = HP;
-    k.G = cfg->gpus_per_host; k.flags = cfg->flags;
-    k.migr = cfg->migration_delay_ms; k.boot = cfg->boot_delay_ms; k.retry_iv = cfg->retry_interval_ms;
-    k.max_retries = cfg->max_retries;
-    k.scale_iv = (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) ? cfg->scale_interval_ms : 1;
-    k.idle_pct = cfg->scale_in_idle_pct; k.min_hosts = cfg->min_hosts;
-    k.f_milli = cfg->autoscale_f_milli; k.buffer = cfg->scaling_buffer_hosts;
-    k.batch_delay = cfg->batch_start_delay_ms;
-    k.warm_n = (cfg->flags & NBOS_F_WARM_POOL) ? cfg->warm_pool_per_host : 0;
-    k.warm_migr = cfg->warm_migration_delay_ms; k.prewarm = cfg->prewarm_delay_ms;
-    k.n_cap = n_cap; k.q_cap = (int32_t)q_cap;
-    // Event-parallel rounds: on, except for closed loops on clusters of at most 64 hosts, where two
-    // cells of a run choose the same host too often for a round to pay (measured: 30 hosts, 110 ms
-    // without, 119 ms with). NBOS_REPLAY_BATCH = "0" / "1" forces the choice (comparison runs, tests).
-    const char *nb = getenv("NBOS_REPLAY_BATCH");
-    k.batch = (nb && nb[0] == '0') ? 0 : (nb && nb[0] == '1') ? 1 : (closed_loop && cfg->hosts_max <= WAVE) ? 0 : 1;
-    k.cl_chain = d_chain; k.cl_cursor = d_cursor;
-  }
+  h->cfg = cfg; h->in = *in; h->stream = (hipStream_t)stream;
+  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_chain = nullptr; h->d_log = nullptr;
+  h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
+  memset(&h->kp, 0, sizeof h->kp);
+  Shape sh;
+  if (hipGetDevice(&h->device) != hipSuccess || hipEventCreate(&h->e0) != hipSuccess ||
+      hipEventCreate(&h->e1) != hipSuccess)
+    rc = NBOS_E_HIP;
+  if (rc == NBOS_OK) rc = read_offsets(h, &sh);
+  if (rc == NBOS_OK) rc = choose_kernel(h, &sh);
+  if (rc == NBOS_OK) rc = validate_on_device(h, slack);
+  if (rc == NBOS_OK) rc = allocate_buffers(h, sh);
+  if (rc != NBOS_OK) { free_handle(h); return rc; }
+  fill_params(h, sh);
   *out = h;
   return NBOS_OK;
-fail:
-  free_handle(h);
-  return rc;
-#undef HIP_TRY
 }
 
 int32_t nbos_replay_run(nbos_replay *h) {
