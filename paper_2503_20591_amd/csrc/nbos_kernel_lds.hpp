@@ -214,7 +214,7 @@ __device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t
 // closed loop, registers empty: all timers that are due within a window after the earliest one move
 // from the session records into the registers at once, at most 64. A window takes whole instants, so
 // everything taken is earlier than everything left behind whatever the kinds. The window adapts to
-// the density of the timers (half of the registers filled is the aim); if more than 64 timers wait
+// the density of the timers (32 to 56 of the registers filled is the aim); if more than 64 timers wait
 // for one and the same instant, the single earliest (time, kind, session) is taken. What firing the
 // timers will need - their events' duration, kind and chain record - is gathered here, one lane per
 // timer, in two round trips to device memory for the lot.
@@ -228,25 +228,31 @@ __device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
     const int64_t lim = (int64_t)r.o_min_t + win;
     const int32_t T = lim < NEVER - 1 ? (int32_t)lim : NEVER - 1;
     cnt = 0;
-    int32_t mn = NEVER, all = NEVER;
-    for (int s0 = 0; s0 < c.n_sess; s0 += WAVE) {
-      const int s = s0 + c.lane;
-      const int32_t d = s < c.n_sess ? c.m.due[s] : NEVER;
-      const bool hit = d <= T;
-      const uint64_t b = wballot(hit);
-      if (b != 0) {
-        const int pos = cnt + lane_rank(b);
-        if (hit && pos < WAVE) c.m.stage[pos] = s;
-        cnt += __builtin_popcountll(b);
+    int32_t mn = NEVER;                          // earliest time beyond the window, per lane
+    // four sessions per lane and step (due[] is padded with NEVER to a multiple of four)
+    const int4 *due4 = (const int4 *)c.m.due;
+    for (int s0 = 4 * c.lane; s0 - 4 * c.lane < c.n_sess; s0 += 4 * WAVE) {
+      const int4 d = s0 < c.n_sess ? due4[s0 >> 2] : make_int4(NEVER, NEVER, NEVER, NEVER);
+      const int32_t lo = min(min(d.x, d.y), min(d.z, d.w));
+      if (wballot(lo <= T) != 0) {               // rare: some of these timers are inside the window
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const int32_t dj = j == 0 ? d.x : j == 1 ? d.y : j == 2 ? d.z : d.w;
+          const bool hit = dj <= T;
+          const uint64_t b = wballot(hit);
+          const int pos = cnt + lane_rank(b);
+          if (hit && pos < WAVE) c.m.stage[pos] = s0 + j;
+          cnt += __builtin_popcountll(b);
+          mn = hit ? mn : (dj < mn ? dj : mn);
+        }
+      } else {
+        mn = lo < mn ? lo : mn;
       }
-      mn = hit ? mn : (d < mn ? d : mn);
-      all = d < all ? d : all;
     }
     left = (int32_t)wave_min((uint32_t)mn);
     if (cnt == 0) {                              // the stored bound was below the earliest time: use that
-      const int32_t first = (int32_t)wave_min((uint32_t)all);
-      if (first == NEVER) { r.o_n = 0; r.o_min_t = NEVER; return; }     // nothing waits (not reached: o_n counts them)
-      r.o_min_t = first;
+      if (left == NEVER) { r.o_n = 0; r.o_min_t = NEVER; return; }      // nothing waits (not reached: o_n counts them)
+      r.o_min_t = left;
       continue;
     }
     if (cnt <= WAVE) break;
@@ -263,11 +269,11 @@ __device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
       left = T;
       break;
     }
-    win = win * 32 / cnt;                        // aim at half of the registers
+    win = (int32_t)((int64_t)win * 40 / cnt);    // aim at 40 of the 64 registers
     wave_sync();
   }
-  if (cnt < WAVE / 4 && win < CL_WIN_MAX) r.cl_win = win == 0 ? 1 : win * 2;
-  else if (cnt > 3 * WAVE / 4) r.cl_win = win / 2;
+  if (cnt < WAVE / 2 && win < CL_WIN_MAX) r.cl_win = win == 0 ? 1 : win + (win + 1) / 2;
+  else if (cnt > 7 * WAVE / 8) r.cl_win = win - win / 4;
   else r.cl_win = win;
   wave_sync();
   // lane i < cnt takes the timer of session stage[i]
@@ -977,11 +983,13 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
   m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
   m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
-  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
   m.stage = nullptr;
+  if (CL) {                         // 16-byte aligned: the refill reads four times at once
+    m.due = (int32_t *)q;             q += (size_t)((p.n_cap + 3) / 4 * 4) * 4;
+    m.stage = (int32_t *)q;           q += WAVE * 4;
+  }
+  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
   if (CL) {
-    m.due = (int32_t *)q;             q += (size_t)p.n_cap * 4;
-    m.stage = (int32_t *)q;
     m.o_t = nullptr; m.o_k = nullptr; m.o_d = nullptr;
   } else {
     m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
@@ -1014,7 +1022,9 @@ __device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int lan
   for (int s = lane; s < n_sess; s += WAVE) {
     const uint32_t g = p.sess_gpus[s_lo + s];
     m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
-    if (CL) m.due[s] = NEVER;
+  }
+  if (CL) {
+    for (int s = lane; s < (p.n_cap + 3) / 4 * 4; s += WAVE) m.due[s] = NEVER;
   }
   __syncthreads();
 }

@@ -318,7 +318,8 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
   } else if (closed_loop) {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
-    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 16 + WAVE * 4;
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
+                   (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     sh->q_cap = 0;
     // instances for the common flag sets, as for the other kernels
