@@ -340,6 +340,10 @@ void nbos_replay_destroy(nbos_replay *h);
 /* Static, NUL-terminated description of a status code. */
 const char *nbos_strerror(int32_t status);
 
+/* After nbos_replay_create returned NBOS_E_HIP on this thread: the runtime call that failed and the
+ * runtime's message for it, NUL-terminated, valid until the thread's next create. "" otherwise. */
+const char *nbos_last_error_detail(void);
+
 /* sizeof(nbos_stats) as compiled, for binding self-checks. */
 int32_t nbos_sizeof_stats(void);
 

@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #include <new>
@@ -146,7 +147,12 @@ void free_handle(nbos_replay *h) {
 }
 
 // ---- steps of nbos_replay_create -------------------------------------------------------------------
-#define HIP_TRY(x) do { if ((x) != hipSuccess) return NBOS_E_HIP; } while (0)
+// what nbos_last_error_detail() returns on this thread: the runtime call that failed and the runtime's word for it
+thread_local char g_detail[256] = "";
+void note_hip_failure(const char *call, hipError_t e) {
+  snprintf(g_detail, sizeof g_detail, "%s: %s", call, hipGetErrorString(e));
+}
+#define HIP_TRY(x) do { const hipError_t e_ = (x); if (e_ != hipSuccess) { note_hip_failure(#x, e_); return NBOS_E_HIP; } } while (0)
 
 // the configuration in the current layout (earlier, shorter layouts are accepted: later fields read as 0)
 int32_t read_config(const nbos_config *cfg_in, nbos_config *full) {
@@ -207,6 +213,13 @@ int64_t time_slack(const nbos_config *cfg) {
   if ((cfg->flags & NBOS_F_WARM_POOL) && cfg->warm_migration_delay_ms > slowest) slowest = cfg->warm_migration_delay_ms;
   return (int64_t)NBOS_MAX_DUR_MS + (int64_t)cfg->max_retries * cfg->retry_interval_ms + cfg->boot_delay_ms + slowest +
          ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0);
+}
+
+int32_t open_device(nbos_replay *h) {
+  HIP_TRY(hipGetDevice(&h->device));
+  HIP_TRY(hipEventCreate(&h->e0));
+  HIP_TRY(hipEventCreate(&h->e1));
+  return NBOS_OK;
 }
 
 // what create works out about the batch before it chooses a kernel
@@ -373,7 +386,7 @@ int32_t validate_on_device(nbos_replay *h, int64_t slack) {
   if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, h->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
   (void)hipFree(d_err);
-  if (e != hipSuccess) return NBOS_E_HIP;
+  if (e != hipSuccess) { note_hip_failure("trace validation", e); return NBOS_E_HIP; }
   return h_err ? NBOS_E_RANGE : NBOS_OK;
 }
 
@@ -457,6 +470,8 @@ const char *nbos_strerror(int32_t status) {
 
 int32_t nbos_sizeof_stats(void) { return (int32_t)sizeof(nbos_stats); }
 
+const char *nbos_last_error_detail(void) { return g_detail; }
+
 int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, void *stream, nbos_replay **out) {
   if (out) *out = nullptr;
   if (!cfg_in || !in || !out) return NBOS_E_ARG;
@@ -474,9 +489,8 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   memset(&h->kp, 0, sizeof h->kp);
   Shape sh;
-  if (hipGetDevice(&h->device) != hipSuccess || hipEventCreate(&h->e0) != hipSuccess ||
-      hipEventCreate(&h->e1) != hipSuccess)
-    rc = NBOS_E_HIP;
+  g_detail[0] = 0;
+  rc = open_device(h);
   if (rc == NBOS_OK) rc = read_offsets(h, &sh);
   if (rc == NBOS_OK) rc = choose_kernel(h, &sh);
   if (rc == NBOS_OK) rc = validate_on_device(h, slack);

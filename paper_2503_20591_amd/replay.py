@@ -23,7 +23,7 @@ E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
            "nbos_replay_billing", "nbos_replay_last_kernel_ms", "nbos_replay_launch_info", "nbos_replay_destroy",
-           "nbos_strerror", "nbos_sizeof_stats")
+           "nbos_strerror", "nbos_last_error_detail", "nbos_sizeof_stats")
 
 
 class NbosConfig(C.Structure):
@@ -69,7 +69,8 @@ _lib = None
 
 class NbosError(RuntimeError):
     def __init__(self, code: int, what: str):
-        super().__init__(f"{what}: {strerror(code)} ({code})")
+        detail = load().nbos_last_error_detail().decode() if code == E_HIP else ""
+        super().__init__(f"{what}: {strerror(code)} ({code})" + (f": {detail}" if detail else ""))
         self.code = code
 
 
@@ -80,6 +81,9 @@ def load():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError(f"{_LIB_PATH} is missing: build it with paper_2503_20591_amd.build.build_library()")
+    # torch first: the library has to share the HIP runtime that owns torch's device memory and streams
+    # (loaded the other way round, the process holds two runtimes and this one finds no device)
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     lib.nbos_replay_create.restype = C.c_int32
     lib.nbos_replay_create.argtypes = [C.POINTER(NbosConfig), C.POINTER(NbosInputs), C.c_void_p,
@@ -101,6 +105,8 @@ def load():
     lib.nbos_replay_destroy.argtypes = [C.c_void_p]
     lib.nbos_strerror.restype = C.c_char_p
     lib.nbos_strerror.argtypes = [C.c_int32]
+    lib.nbos_last_error_detail.restype = C.c_char_p
+    lib.nbos_last_error_detail.argtypes = []
     lib.nbos_sizeof_stats.restype = C.c_int32
     if lib.nbos_sizeof_stats() != STATS_DTYPE.itemsize:
         raise RuntimeError("nbos_stats layout mismatch between the binding and libnbos.so")
