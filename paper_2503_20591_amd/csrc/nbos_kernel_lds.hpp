@@ -1135,7 +1135,13 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
         const bool dup = valid && m.mark[b] < lane;
         wave_sync();
         if (valid) m.mark[b] = MARK_FREE;
-        r.dirty = wballot(dup);
+        // the buckets are few (a lane in eight shares one with an earlier lane by chance): keep only the
+        // lanes that really have their session in an earlier lane
+        for (uint64_t w = wballot(dup); w != 0; w &= w - 1) {
+          const int j = (int)__builtin_ctzll(w);
+          const uint32_t sj = (uint32_t)lane_get((int)sid, j);
+          if (wballot(valid && sid == sj && lane < j) != 0) r.dirty |= 1ull << j;
+        }
       }
       if (ev_hi - cur <= WAVE) {
         int32_t tl = lane_get(vt, (int)(ev_hi - cur - 1));
