@@ -228,6 +228,19 @@ class Replay:
             pass
 
 
+DECISION_NAMES = {1: "PLACE", 2: "PLACE_NEW", 3: "REJECT", 4: "START", 5: "MIGRATE", 6: "SCALE_CELL", 7: "ABORT",
+                  8: "SCALE_IN", 9: "SCALE_AUTO", 10: "BATCH_START", 11: "BATCH_HOST", 12: "MIGRATE_WARM"}
+
+
+def decode_decision(code: int) -> dict:
+    """The fields of one decision code (layout of nbos.h: host | slot << 10 | outcome << 12 |
+    session << 16 | time << 32)."""
+    code = int(code)
+    outcome = (code >> 12) & 0xF
+    return {"time_ms": code >> 32, "session": (code >> 16) & 0xFFFF, "outcome": outcome,
+            "name": DECISION_NAMES.get(outcome, "?"), "slot": (code >> 10) & 3, "host": code & 0x3FF}
+
+
 def stats_to_dict(row) -> dict:
     """One stats record as plain Python ints (delay_hist as a list)."""
     return {n: ([int(x) for x in row[n]] if n == "delay_hist" else int(row[n])) for n in STATS_DTYPE.names}

@@ -86,3 +86,13 @@ def test_null_handle_calls(lib):
     assert lib.nbos_replay_last_kernel_ms(None, None) == replay.E_ARG
     assert lib.nbos_replay_launch_info(None, None, None, None) == replay.E_ARG
     lib.nbos_replay_destroy(None)
+
+
+def test_decision_codes_decode_to_their_fields():
+    from helpers import code_of
+    from paper_2503_20591_amd import replay
+    # code_of(time, outcome, session, slot, host) builds codes the way the hand-worked traces list them
+    d = replay.decode_decision(code_of(123456, 5, 4321, 2, 777))
+    assert d == {"time_ms": 123456, "session": 4321, "outcome": 5, "name": "MIGRATE", "slot": 2, "host": 777}
+    names = {int(m.group(2)): m.group(1) for m in re.finditer(r"#define NBOS_D_(\w+)\s+(\d+)", header_text())}
+    assert names == replay.DECISION_NAMES
