@@ -94,5 +94,5 @@ def test_decision_codes_decode_to_their_fields():
     # code_of(time, outcome, session, slot, host) builds codes the way the hand-worked traces list them
     d = replay.decode_decision(code_of(123456, 5, 4321, 2, 777))
     assert d == {"time_ms": 123456, "session": 4321, "outcome": 5, "name": "MIGRATE", "slot": 2, "host": 777}
-    names = {int(m.group(2)): m.group(1) for m in re.finditer(r"#define NBOS_D_(\w+)\s+(\d+)", header_text())}
+    names = {int(m.group(2)): m.group(1) for m in re.finditer(r"#define NBOS_D_(\w+)\s+(\d+)", open(os.path.join(ROOT, "include", "nbos.h")).read())}
     assert names == replay.DECISION_NAMES
