@@ -477,6 +477,23 @@ def test_full_size_bench_config(rp, oracle):
     assert st2.tobytes() == st.tobytes()
 
 
+@pytest.mark.parametrize("name,n_sample", [("c3", 16), ("c4", 6), ("c5", 32)])
+def test_full_size_other_configs(rp, oracle, name, n_sample):
+    # the other named workloads with all their replays, in the launch shape the benchmark times (c3: 16
+    # workgroups per compute unit resident, c5: 64 per compute unit in several rounds, the kernel flavour
+    # chosen for that shape); identities on every replay, a spread of replays against the oracle
+    b = tg.workload(name, workers=16)
+    st, _ = gpu_run(rp, b)
+    assert (st["status"] == 0).all()
+    assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"] + st["cells_dropped_busy"]
+            + st["cells_dropped_unplaced"]).all()
+    assert (st["delay_hist"].sum(axis=1) == st["cells_started"]).all()
+    assert (st["gpu_ms_committed"] >= st["gpu_ms_executed"]).all()
+    n = b.n_replays
+    sample = sorted(set(list(range(0, n, max(n // n_sample, 1))) + [1, n // 2 + 1, n - 1]))
+    assert_same(rp, oracle, b, st, replays=sample)
+
+
 # ---- edge cases ---------------------------------------------------------------------------------------
 
 def _tiny(cfg, events, gpus, caps, tor=None):
