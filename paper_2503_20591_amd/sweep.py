@@ -27,12 +27,12 @@ def study_batch(n_traces: int = 4, caps=(1000, 1500, 2000, 3000, 4000), sessions
                 **config) -> tg.TraceBatch:
     """``n_traces`` diurnal traces (the recipe of workload c4 at the given size, seeds 0..n-1), each
     replayed under every cap: replay ``t * len(caps) + j`` is trace ``t`` under ``caps[j]``."""
-    kw = tg._recipe("c4")["kw"]
+    kw = tg.recipe("c4")["kw"]
     traces = [tg.make_trace(seed, sessions, cells, **kw) for seed in range(n_traces)]
-    cfg = tg._base_config(hosts_initial=hosts_initial, hosts_max=hosts_max, flags=flags, min_hosts=hosts_initial)
+    cfg = tg.base_config(hosts_initial=hosts_initial, hosts_max=hosts_max, flags=flags, min_hosts=hosts_initial)
     cfg.update(config)
     tor = [t for t in range(n_traces) for _ in caps]
-    return tg._pack(cfg, traces, tor, [int(c) for _ in range(n_traces) for c in caps], "study")
+    return tg.pack(cfg, traces, tor, [int(c) for _ in range(n_traces) for c in caps], "study")
 
 
 def _run(batch: tg.TraceBatch, dev: dict, price: int):

@@ -252,6 +252,9 @@ def _recipe(name: str):
     raise KeyError(name)
 
 
+# public names for building batches of one's own (policy studies, tests)
+pack, base_config, recipe = _pack, _base_config, _recipe
+
 WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b", "c2l", "c4l")
 
 
