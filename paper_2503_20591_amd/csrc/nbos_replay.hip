@@ -265,17 +265,12 @@ int32_t read_offsets(nbos_replay *h, Shape *sh) {
 int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
   const nbos_config *cfg = &h->cfg;
   // The common policy flag sets have kernels compiled for them (everything that is switched off
-  // is gone from the code). They have the shorter path per item and need fewer registers; the
-  // generic kernel executes about 9 % fewer scalar instructions (it keeps hoisted flag tests in
-  // spilled registers). Which one is faster depends on what bounds the batch (all measured):
-  //  - a replay has a SIMD to itself (at most 4 workgroups per compute unit): the length of the
-  //    path counts, the instance for the flag set is 10 % faster;
-  //  - 5 or more waves per SIMD resident: instruction issue counts, the generic kernel is 5 %
-  //    faster;
-  //  - in between, waves hide little of each other's latency and a batch that does not fit at
-  //    once runs in rounds: the kernel that needs fewer rounds wins, the generic one on a tie
-  //    (64 hosts, 4,096 replays: 297 ms with 16 workgroups per compute unit resident, 436 ms
-  //    with 12; the kernels are compiled for at most 128 registers so that 16 fit).
+  // is gone from the code): the shorter path per item makes them faster at every occupancy the
+  // kernels reach (both are compiled for at most 128 registers, i.e. up to 16 workgroups per
+  // compute unit; measured: 30 hosts, 4 per compute unit, -10 %; 64 hosts, 16 per compute unit,
+  // 288 against 307 ms; 24 hosts, 64 per compute unit in four rounds, 100 against 115 ms). The
+  // generic kernel runs for the other flag sets, and if it ever needs fewer rounds for the batch
+  // (a batch that does not fit at once runs in rounds; waves hide little of each other's latency).
   const int nj = (cfg->hosts_max + 7) / 8;
   const uint32_t policy = cfg->flags & regk::kPolicyFlags;
   const void *generic = reg_kernel_for<regk::kRuntimeFlags>(nj);
@@ -303,9 +298,7 @@ int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
       return by_lds < by_regs ? by_lds : by_regs;
     };
     const int res_g = resident(fa_g) > 0 ? resident(fa_g) : 1, res_s = resident(fa_s) > 0 ? resident(fa_s) : 1;
-    if (per_cu <= 4) use_generic = false;
-    else if ((per_cu < res_g ? per_cu : res_g) >= 20) use_generic = true;
-    else use_generic = (per_cu + res_s - 1) / res_s >= (per_cu + res_g - 1) / res_g;
+    use_generic = (per_cu + res_g - 1) / res_g < (per_cu + res_s - 1) / res_s;
   }
   h->kernel = use_generic ? generic : special;
   return NBOS_OK;
