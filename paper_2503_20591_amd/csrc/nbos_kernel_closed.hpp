@@ -39,20 +39,29 @@ __global__ void __launch_bounds__(WAVE) nbos_closed_chain_kernel(const int64_t *
   const int trace = blockIdx.x, lane = threadIdx.x;
   const int64_t lo = ev_offset[trace], hi = ev_offset[trace + 1];
   const int n_sess = sess_offset[trace + 1] - sess_offset[trace];
-  int32_t *last = (int32_t *)lds_raw, *anchor = last + n_sess;    // last chained event, its nominal end
-  for (int s = lane; s < n_sess; s += WAVE) { last[s] = CH_NONE; anchor[s] = 0; }
+  // per session: last chained event, its nominal end, the first lane of the current tile that holds it
+  int32_t *last = (int32_t *)lds_raw, *anchor = last + n_sess, *mark = anchor + n_sess;
+  for (int s = lane; s < n_sess; s += WAVE) { last[s] = CH_NONE; anchor[s] = 0; mark[s] = MARK_FREE; }
   __syncthreads();
+  int32_t nt = 0, nd = 0, nsk = 0;              // the next tile, in flight while the current one is linked
+  if (lo + lane < hi) { nt = ev_time[lo + lane]; nd = ev_dur[lo + lane]; nsk = ev_sk[lo + lane]; }
   for (int64_t base = lo; base < hi; base += WAVE) {
     const int cnt = hi - base < WAVE ? (int)(hi - base) : WAVE;
     const int32_t idx0 = (int32_t)(base - lo);
-    int32_t t = 0, d = 0;
-    uint32_t sk = 0;
-    if (lane < cnt) { t = ev_time[base + lane]; d = ev_dur[base + lane]; sk = (uint32_t)ev_sk[base + lane]; }
+    const bool valid = lane < cnt;
+    const int32_t t = nt, d = nd;
+    const uint32_t sk = (uint32_t)nsk;
+    if (base + WAVE + lane < hi) { nt = ev_time[base + WAVE + lane]; nd = ev_dur[base + WAVE + lane]; nsk = ev_sk[base + WAVE + lane]; }
+    const uint32_t kind = sk >> 24, s = sk & 0xFFFFFFu;
     int32_t nx = -1, ny = -1;                   // this lane's record; ny = -1: in no chain
-    for (int i = 0; i < cnt; i++) {             // in trace order: events of a tile may share a session
-      const uint32_t ski = (uint32_t)lane_get((int)sk, i);
-      const uint32_t kind = ski >> 24, s = ski & 0xFFFFFFu;
-      const int32_t ti = lane_get(t, i), di = lane_get(d, i);
+    // Sessions are independent, and a tile rarely holds two events of one session: the lanes that are the
+    // first of their session in the tile go all at once (their predecessors are in earlier tiles) ...
+    if (valid) atomicMin(&mark[s], lane);
+    wave_sync();
+    const bool first = valid && mark[s] == lane;
+    wave_sync();
+    if (valid) mark[s] = MARK_FREE;
+    if (first) {
       const int32_t L = last[s];
       bool chained = false;
       if (kind == NBOS_EV_START) {
@@ -60,6 +69,28 @@ __global__ void __launch_bounds__(WAVE) nbos_closed_chain_kernel(const int64_t *
       } else if (L >= 0) {
         chained = true;
         const int32_t a = anchor[s];
+        chain[lo + L] = make_int2(idx0 + lane, t > a ? t - a : 0);
+      }
+      if (chained) {
+        ny = 0;
+        last[s] = kind == NBOS_EV_END ? CH_CLOSED : idx0 + lane;
+        anchor[s] = kind == NBOS_EV_CELL ? t + d : t;
+      }
+    }
+    wave_sync();
+    // ... the others follow one by one, in trace order
+    for (uint64_t w = wballot(valid && !first); w != 0; w &= w - 1) {
+      const int i = (int)__builtin_ctzll(w);
+      const uint32_t ski = (uint32_t)lane_get((int)sk, i);
+      const uint32_t ki = ski >> 24, si = ski & 0xFFFFFFu;
+      const int32_t ti = lane_get(t, i), di = lane_get(d, i);
+      const int32_t L = last[si];
+      bool chained = false;
+      if (ki == NBOS_EV_START) {
+        chained = L == CH_NONE;
+      } else if (L >= 0) {
+        chained = true;
+        const int32_t a = anchor[si];
         const int32_t th = ti > a ? ti - a : 0;
         if (L >= idx0) { if (lane == L - idx0) { nx = idx0 + i; ny = th; } }     // the predecessor is in this tile
         else if (lane == 0) chain[lo + L] = make_int2(idx0 + i, th);
@@ -68,14 +99,15 @@ __global__ void __launch_bounds__(WAVE) nbos_closed_chain_kernel(const int64_t *
       if (chained) {
         if (lane == i) ny = 0;
         if (lane == 0) {
-          last[s] = kind == NBOS_EV_END ? CH_CLOSED : idx0 + i;
-          anchor[s] = kind == NBOS_EV_CELL ? ti + di : ti;
+          last[si] = ki == NBOS_EV_END ? CH_CLOSED : idx0 + i;
+          anchor[si] = ki == NBOS_EV_CELL ? ti + di : ti;
         }
       }
       wave_sync();
     }
-    if (lane < cnt) chain[base + lane] = make_int2(nx, ny);
-    __threadfence();                            // a later tile may overwrite one of these records
+    if (valid) chain[base + lane] = make_int2(nx, ny);
+    // a later tile may overwrite one of these records: wait until the stores have been taken
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   }
 }
 

@@ -396,7 +396,7 @@ int32_t allocate_buffers(nbos_replay *h, const Shape &sh) {
     // one allocation: chain[total_ev] (two words each), cursor[n_replays][n_cap]; the chains are linked here
     const size_t words = 2 * (size_t)sh.total_ev + n * (size_t)sh.n_cap;
     if (hipMalloc(&h->d_chain, sizeof(int32_t) * (words > 0 ? words : 1)) != hipSuccess) return NBOS_E_NOMEM;
-    const size_t chain_lds = (size_t)sh.n_cap * 8;
+    const size_t chain_lds = (size_t)sh.n_cap * 12;
     HIP_TRY(hipFuncSetAttribute((const void *)ldsk::nbos_closed_chain_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)chain_lds));
     hipLaunchKernelGGL(ldsk::nbos_closed_chain_kernel, dim3(cfg->n_traces), dim3(WAVE), chain_lds, h->stream, in->ev_offset,
