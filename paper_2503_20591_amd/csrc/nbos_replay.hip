@@ -350,8 +350,10 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     // there is one
     const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
     constexpr uint32_t kAllScaling = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN;
+    constexpr uint32_t kAutoScaler = NBOS_F_MIGRATE | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
     if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
     else if (policy == kAllScaling) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAllScaling>;
+    else if (policy == kAutoScaler) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAutoScaler>;
     else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<NBOS_F_MIGRATE>;
     else h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
   }
