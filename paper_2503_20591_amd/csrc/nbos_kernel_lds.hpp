@@ -955,9 +955,13 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   // digest: d * P^n + sum over started lanes of code * P^(n - 1 - rank), the sum in three limbs
   const int rank = lane_rank(done);
   const uint64_t code = decision_code(vt, NBOS_D_START, sid, (uint32_t)lead, (uint32_t)ch);
-  const uint64_t term = mine ? code * c.m.ppow[mine ? n - 1u - (uint32_t)rank : 0u] : 0ull;
-  const uint64_t sum = wave_sum((uint32_t)term & 0x3FFFFFu) + (wave_sum((uint32_t)(term >> 22) & 0x1FFFFFu) << 22) +
-                       (wave_sum((uint32_t)(term >> 43)) << 43);
+  // the terms are added up by the LDS unit, in the spare slot behind the table of powers
+  wave_sync();
+  if (c.lane == 0) c.m.ppow[65] = 0;
+  if (mine) atomicAdd(&c.m.ppow[65], (unsigned long long)(code * c.m.ppow[n - 1u - (uint32_t)rank]));
+  wave_sync();
+  const unsigned long long sm = c.m.ppow[65];
+  const uint64_t sum = (uint64_t)uni((uint32_t)sm) | ((uint64_t)uni((uint32_t)(sm >> 32)) << 32);
   const unsigned long long pn = c.m.ppow[n];
   const uint64_t pnu = (uint64_t)uni((uint32_t)pn) | ((uint64_t)uni((uint32_t)(pn >> 32)) << 32);
   r.digest = r.digest * pnu + sum;
