@@ -235,10 +235,12 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
           const int k = out != 0 ? (int)__builtin_ctzll(out) : WAVE;
           if (k >= 2) {
             const uint64_t run = k >= WAVE ? ~0ull : ((1ull << k) - 1ull);
-            const uint64_t done = batch_round(c, r, run, c.qt, vd, sid, rec);
+            bool next_lost;
+            const uint64_t done = batch_round(c, r, run, c.qt, vd, sid, rec, next_lost);
             const int n = __builtin_popcountll(done);
             if (n <= 1) { cooldown = backoff; backoff = backoff < 64 ? 2 * backoff : 64; }
             else if (n >= 3) backoff = 1;
+            if (next_lost && cooldown == 0) cooldown = 1;     // the next timer's cell has just lost its election
             if (n > 0) {
               r.c_total += (uint32_t)n;
               const int32_t tl = lane_get(c.qt, n - 1);

@@ -885,9 +885,10 @@ __device__ __forceinline__ void on_session_end(Ctx<F> &c, Regs &r, uint32_t s, u
 
 // ---- one event-parallel round over the lanes in `run` (see the file header) -----------------------
 // Returns the mask of lanes whose cells were started. rec = the lane's prefetched session record.
+// next_lost: the lane after the started ones lost its election (another round would start nothing there).
 template <uint32_t F>
 __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run, int32_t vt, int32_t vd, uint32_t sid,
-                                                const SessRec &rec) {
+                                                const SessRec &rec, bool &next_lost) {
   wave_sync();
   const int G = c.p.G;
   const bool in_run = (run >> c.lane) & 1u;
@@ -920,8 +921,10 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   const int32_t first = c.m.mark[ch];        // the lowest lane that binds on the host this lane chose
   wave_sync();
   if (won) c.m.mark[ch] = MARK_FREE;
-  const uint64_t bad = run & wballot(in_run && (!won || first < c.lane));
+  const uint64_t lost = run & wballot(in_run && !won);
+  const uint64_t bad = lost | (run & wballot(in_run && first < c.lane));
   const uint64_t below = bad ? ((1ull << __builtin_ctzll(bad)) - 1ull) : ~0ull;
+  next_lost = bad != 0 && ((lost >> __builtin_ctzll(bad)) & 1u) != 0;     // the lane that ends the prefix lost its election
   const uint64_t done = run & below;
   if (done == 0) return 0;
   const bool mine = (done >> c.lane) & 1u;
@@ -1176,8 +1179,10 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
           const uint64_t blockers = todo & ~eligible;
           const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
           if ((run & (run - 1)) != 0) {          // at least two lanes
-            const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec);
-            cooldown = (done & (done - 1)) == 0 ? 1 : 0;    // none or one started: the next arrival goes alone
+            bool next_lost;
+            const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec, next_lost);
+            // none or one started, or the next arrival has just lost its election: it goes alone
+            cooldown = ((done & (done - 1)) == 0 || next_lost) ? 1 : 0;
             if (done != 0) { todo &= ~done; continue; }
           }
         }
