@@ -365,6 +365,12 @@ def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
     assert (st["status"] == 0).all()
     assert_same(rp, oracle, b, st, replays=list(range(0, b.n_replays, 37)) + [b.n_replays - 1])
     assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"]).all()
+    # the same handle run twice more: nothing of a run (cursors, waiting timers) leaks into the next
+    h = rp.Replay(b.config, rp.upload(b))
+    h.run(); h.run()
+    st2 = h.stats()
+    h.close()
+    assert st2.tobytes() == st.tobytes()
 
 
 def test_closed_loop_many_timers_at_one_instant(rp, oracle):
