@@ -22,8 +22,12 @@
 //         dirty, and only those are read again from LDS.
 // Timers: RETRY of a queued cell (Section 3.2.3) and the END of a session that was busy when its END
 //         arrived are the only timers that change decisions. The 64 earliest live sorted in
-//         registers (insert = ballot + DPP wave shift, pop = DPP wave shift); later ones wait in an
-//         unsorted LDS array that is only touched when the registers run empty or full.
+//         registers (insert = ballot + DPP wave shift, pop = DPP wave shift); later ones stay with
+//         their session (a flag in its record, their time implied by it) until the registers run empty.
+// Closed loop (paper Section 2.2; nbos_replay_reg_closed_kernel at the end of this file): only the
+//         first STARTs come from the stream, every other event of a session is a timer that is due a
+//         think time after the session's previous cell is over. See nbos_kernel_closed.hpp for the
+//         chain records this reads and for the same scheme on the any-size kernel.
 // Sessions in LDS, 8 bytes each: one word with the state, g, the retry count, the three replica hosts
 //         (6 bits each) and the last executor slot; one time word (busy-until, or the submit time while
 //         queued). The duration of a queued cell travels with its timer.
@@ -47,6 +51,7 @@ constexpr uint32_t RK_FLAGS = 0xFFFu;        // the bits below the hosts
 __device__ __forceinline__ uint32_t slot_host(uint32_t hw, uint32_t slot) { return (hw >> (12u + 6u * slot)) & 63u; }
 
 struct Lds {
+  int32_t *stage;    // closed loop: [64] sessions whose timers move into the registers
   int32_t *warm;     // [64][4] when each pre-warmed container of a host is available (only with the pool)
   int2 *sess;
   uint32_t *hist;
@@ -65,13 +70,19 @@ struct Regs {
   uint32_t o_min_k;
   int32_t status;
   uint64_t dirty;                        // lanes of the current tile whose prefetched record is stale
+  // closed loop: the event being handled, its duration and kind (packed as in Ctx::qx), its session's next
+  // event and the think time before that; the time window the next refill takes
+  int32_t cl_e, cl_x, cl_nx, cl_nth, cl_win;
 };
 
 // F: the policy flags when they are known at compile time (the common sets get an instance of their
 // own, which drops the code of everything that is switched off), or kRuntimeFlags.
 constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
+constexpr uint32_t kRuntimeClosed = 0xFFFFFFFEu;     // policy flags at run time, closed-loop reading of the trace
 constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
                                   NBOS_F_STICKY_EXECUTOR | NBOS_F_WARM_POOL;
+constexpr int32_t CLX_LOADED = (int32_t)0x80000000;
+constexpr int32_t CL_WIN_MAX = 1 << 24;
 
 template <int NJ, uint32_t F>
 struct Ctx {
@@ -90,7 +101,17 @@ struct Ctx {
   uint32_t qk;
   uint32_t vsid;             // session id of this lane's event in the current tile (~0 if none)
   int32_t fu;                // lane g-1 (g = 1..8): no host can have g idle GPUs before this time
-  __device__ __forceinline__ uint32_t flags() const { return F == kRuntimeFlags ? p.flags : F; }
+  // closed loop: the replay's cursors, the events of the trace; and with every sorted timer what firing
+  // it needs: qd = the event's index, qx = its duration | kind << 28 | CLX_LOADED (0: not loaded yet),
+  // qnx / qnth = its chain record
+  int32_t *cl_cur;
+  const int32_t *cl_dur, *cl_sk;
+  const int2 *cl_chain;
+  int32_t qx, qnx, qnth;
+  static constexpr bool closed = F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
+  __device__ __forceinline__ uint32_t flags() const {
+    return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
+  }
 };
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
@@ -170,17 +191,135 @@ __device__ __forceinline__ void ovf_rescan(Ctx<NJ, F> &c, Regs &r) {
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void ovf_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
   const uint32_t s = k & 0xFFFFu;
-  if (c.lane == 0) { atomicOr((unsigned int *)&c.m.sess[s].x, RK_OVF); c.ovf_dur[s] = d; }
+  if constexpr (Ctx<NJ, F>::closed) {
+    // the session's one timer waits in its record: a retry is implied by it as ever, the time of a
+    // next event replaces the busy-until time (a closed loop never asks for it)
+    if (c.lane == 0) {
+      atomicOr((unsigned int *)&c.m.sess[s].x, RK_OVF);
+      if ((k >> 16) != QK_RETRY) c.m.sess[s].y = t;
+    }
+  } else {
+    if (c.lane == 0) { atomicOr((unsigned int *)&c.m.sess[s].x, RK_OVF); c.ovf_dur[s] = d; }
+  }
   r.dirty |= wballot(c.vsid == s);
   if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) { r.o_min_t = t; r.o_min_k = k; }
   r.o_n++;
+}
+
+// closed loop, registers empty: all timers that are due within a window after the earliest one move
+// from the session records into the registers at once, at most 64 (whole instants, so everything
+// taken is earlier than everything left behind whatever the kinds; the window adapts to fill 32 to
+// 56 registers; more than 64 timers at one instant: the single earliest), and what firing them will
+// need is gathered one lane per timer. The same scheme as in the any-size kernel's closed loop.
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void cl_refill(Ctx<NJ, F> &c, Regs &r) {
+  wave_sync();
+  int cnt;
+  int32_t left;                                  // earliest time left behind
+  int32_t win = r.cl_win;
+  for (;;) {
+    const int64_t lim = (int64_t)r.o_min_t + win;
+    const int32_t T = lim < NEVER - 1 ? (int32_t)lim : NEVER - 1;
+    cnt = 0;
+    int32_t mn = NEVER;
+    for (int s0 = 0; s0 < c.n_sess; s0 += WAVE) {
+      const int s = s0 + c.lane;
+      int32_t d = NEVER;
+      if (s < c.n_sess) {
+        const int2 rec = c.m.sess[s];
+        const uint32_t fl = (uint32_t)rec.x;
+        if (fl & RK_OVF) d = (fl & 7u) == SS_QUEUED ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y;
+      }
+      const bool hit = d <= T;
+      const uint64_t b = wballot(hit);
+      if (b != 0) {
+        const int pos = cnt + lane_rank(b);
+        if (hit && pos < WAVE) c.m.stage[pos] = s;
+        cnt += __builtin_popcountll(b);
+      }
+      mn = hit ? mn : (d < mn ? d : mn);
+    }
+    left = (int32_t)wave_min((uint32_t)mn);
+    if (cnt == 0) {                              // the stored bound was below the earliest time: use that
+      if (left == NEVER) { r.o_n = 0; r.o_min_t = NEVER; return; }      // nothing waits (not reached: o_n counts them)
+      r.o_min_t = left;
+      continue;
+    }
+    if (cnt <= WAVE) break;
+    if (win == 0) {
+      // more than 64 timers at the instant o_min_t: the earliest by kind and session alone
+      wave_sync();
+      uint32_t best = 0xFFFFFFFFu;
+      for (int s = c.lane; s < c.n_sess; s += WAVE) {
+        const int2 rec = c.m.sess[s];
+        const uint32_t fl = (uint32_t)rec.x;
+        if (fl & RK_OVF) {
+          const bool retry = (fl & 7u) == SS_QUEUED;
+          const int32_t d = retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y;
+          if (d == T) best = umin(best, ((retry ? QK_RETRY : QK_NEXT) << 16) | (uint32_t)s);
+        }
+      }
+      best = wave_min(best);
+      if (c.lane == 0) c.m.stage[0] = (int32_t)(best & 0xFFFFu);
+      cnt = 1;
+      left = T;
+      break;
+    }
+    win = (int32_t)((int64_t)win * 40 / cnt);    // aim at 40 of the 64 registers
+    wave_sync();
+  }
+  if (cnt < WAVE / 2 && win < CL_WIN_MAX) r.cl_win = win == 0 ? 1 : win + (win + 1) / 2;
+  else if (cnt > 7 * WAVE / 8) r.cl_win = win - win / 4;
+  else r.cl_win = win;
+  wave_sync();
+  // lane i < cnt takes the timer of session stage[i]
+  const bool take = c.lane < cnt;
+  uint32_t key = 0xFFFFFFFFu;
+  int32_t t = NEVER, e = 0;
+  if (take) {
+    const int s = c.m.stage[c.lane];
+    const int2 rec = c.m.sess[s];
+    const uint32_t fl = (uint32_t)rec.x;
+    const bool retry = (fl & 7u) == SS_QUEUED;
+    t = retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y;
+    key = ((retry ? QK_RETRY : QK_NEXT) << 16) | (uint32_t)s;
+    c.m.sess[s].x = (int)(fl & ~RK_OVF);
+  }
+  // the cursors were written by lane 0 when the timers were scheduled: the fence makes this wave's own
+  // stores visible to its other lanes
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  int32_t x = 0, nx = -1, nth = 0;
+  if (take) {
+    e = c.cl_cur[key & 0xFFFFu];
+    const int2 ch = c.cl_chain[e];
+    x = c.cl_dur[e] | (int32_t)(((uint32_t)c.cl_sk[e] >> 24) << 28) | CLX_LOADED;
+    nx = ch.x; nth = ch.y;
+  }
+  int rank = 0;
+  for (int j = 0; j < cnt; j++) {
+    const int32_t tj = lane_get(t, j);
+    const uint32_t kj = (uint32_t)lane_get((int)key, j);
+    rank += (tj < t || (tj == t && kj < key)) ? 1 : 0;
+  }
+  const int dst = take ? rank : c.lane;          // a permutation: the timers taken in order, the rest where they are
+  c.qt = __builtin_amdgcn_ds_permute(dst << 2, t);
+  c.qk = (uint32_t)__builtin_amdgcn_ds_permute(dst << 2, (int)key);
+  c.qd = __builtin_amdgcn_ds_permute(dst << 2, e);
+  c.qx = __builtin_amdgcn_ds_permute(dst << 2, x);
+  c.qnx = __builtin_amdgcn_ds_permute(dst << 2, nx);
+  c.qnth = __builtin_amdgcn_ds_permute(dst << 2, nth);
+  r.q_n = cnt;
+  r.o_n -= cnt;
+  r.o_min_t = r.o_n > 0 ? left : NEVER;
+  r.o_min_k = 0;                                 // a lower bound: pushes for that very instant wait in the records
 }
 
 // ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
 // Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
 // registers are empty only if the overflow array is.
 template <int NJ, uint32_t F>
-__device__ __forceinline__ void timer_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d) {
+__device__ __forceinline__ void timer_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d,
+                                           int32_t x = 0, int32_t nx = -1, int32_t nth = 0) {
   uint32_t k = (kind << 16) | id;
   if (r.q_n == WAVE) {
     int32_t mt = lane_get(c.qt, WAVE - 1);
@@ -203,6 +342,13 @@ __device__ __forceinline__ void timer_push(Ctx<NJ, F> &c, Regs &r, int32_t t, ui
   uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
   if (c.lane > pos) { c.qt = st; c.qd = sd; c.qk = sk; }
   if (c.lane == pos) { c.qt = t; c.qd = d; c.qk = k; }
+  if constexpr (Ctx<NJ, F>::closed) {
+    const int32_t sx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x138, 0xF, 0xF, false);
+    const int32_t sn = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x138, 0xF, 0xF, false);
+    const int32_t sh = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x138, 0xF, 0xF, false);
+    if (c.lane > pos) { c.qx = sx; c.qnx = sn; c.qnth = sh; }
+    if (c.lane == pos) { c.qx = x; c.qnx = nx; c.qnth = nth; }
+  }
   r.q_n++;
   if (pos == 0) r.q_head_t = t;
 }
@@ -214,7 +360,12 @@ __device__ __forceinline__ void timer_pop(Ctx<NJ, F> &c, Regs &r) {
   c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
   c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
   r.q_n--;
-  if (r.q_n == 0 && r.o_n > 0) {
+  if constexpr (Ctx<NJ, F>::closed) {
+    c.qx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
+    c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
+    c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
+    if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
+  } else if (r.q_n == 0 && r.o_n > 0) {
     wave_sync();
     const uint32_t s = r.o_min_k & 0xFFFFu;
     const int32_t d = uni(c.ovf_dur[s]);
@@ -304,6 +455,19 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx<NJ, F> &c, int g) {
   return (int32_t)wave_min((uint32_t)best);
 }
 
+// ---- closed loop: the session's next event is due one think time after `base` --------------------
+// r.cl_nx / r.cl_nth: the event after the one being handled and the think time before it. The timer
+// carries the event's index; the cursor keeps it for the time the timer waits outside the registers.
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void cl_schedule(Ctx<NJ, F> &c, Regs &r, uint32_t s, int32_t base) {
+  const int32_t e = r.cl_nx;
+  if (e < 0) return;
+  const int64_t t = (int64_t)base + r.cl_nth;
+  if (t >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+  if (c.lane == 0) c.cl_cur[s] = e;
+  timer_push(c, r, (int32_t)t, QK_NEXT, s, e);
+}
+
 // ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void session_start(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
@@ -364,6 +528,7 @@ __device__ __forceinline__ void session_start(Ctx<NJ, F> &c, Regs &r, uint32_t s
   c64_add(c.m, c.lane, CL_RESV, -(int64_t)g * now);
   c32_add(c.m, c.lane, CS_NREP, 3u);
   c64_add(c.m, c.lane, CL_REPL, -(int64_t)3 * now);
+  if constexpr (Ctx<NJ, F>::closed) cl_schedule(c, r, s, now);
 }
 
 // the replicas of session s give their subscriptions back at time `now`
@@ -386,6 +551,9 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,
                                            uint32_t outcome) {
   const int g = (int)((fl >> 3) & 7u) + 1;
+  if constexpr (Ctx<NJ, F>::closed) {         // the lag of a closed loop is not bounded in advance
+    if ((int64_t)start + dur >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+  }
   const int32_t finish = start + dur;
   const int32_t delay = start - t_submit;
   r.c_started++;
@@ -415,6 +583,7 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
   r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
   decide(c, r, now, outcome, s, (uint32_t)slot, (uint32_t)host);
   if (__builtin_expect((fl & SF_ENDING) != 0, 0)) timer_push(c, r, finish, QK_END, s, 0);
+  if constexpr (Ctx<NJ, F>::closed) cl_schedule(c, r, s, finish);
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
@@ -553,7 +722,13 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
       if (c.lane == 0) c.m.sess[s].x = (int)nfl;
     }
     r.dirty |= wballot(c.vsid == s);
-    timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
+    if constexpr (Ctx<NJ, F>::closed) {
+      // every timer carries its event (the cursor still points at the cell under way)
+      if ((int64_t)t_submit + (int64_t)retries * c.p.retry_iv >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+      timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, r.cl_e, r.cl_x, r.cl_nx, r.cl_nth);
+    } else {
+      timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
+    }
     return;
   }
   c32_add(c.m, c.lane, CS_ABORTED, 1u);
@@ -561,6 +736,7 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
   const uint32_t nfl = (fl & ~(7u | (15u << 8))) | SS_PLACED;
   sess_write(c, r, s, hw, 0, nfl);
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
+  if constexpr (Ctx<NJ, F>::closed) cl_schedule(c, r, s, now);
 }
 
 // ---- runs of retries that fail again ---------------------------------------------------------------
@@ -713,6 +889,61 @@ __device__ __forceinline__ void on_session_end(Ctx<NJ, F> &c, Regs &r, uint32_t 
   }
 }
 
+// ---- closed-loop kernel: LDS layout of one replay and its initial state (S0) ---------------------------
+// (the open-loop kernel below has both written out in its prologue: sharing them cost it 0.7 %)
+__device__ __forceinline__ Lds lds_carve_closed(const KParams &p, unsigned char *q) {
+  Lds m;
+  m.c64 = (unsigned long long *)q; q += 8 * 8;
+  m.c32 = (uint32_t *)q;       q += 16 * 4;
+  m.hist = (uint32_t *)q;      q += 32 * 4;
+  m.sess = (int2 *)q;          q += (size_t)p.n_cap * 8;     // at a fixed offset: its accesses fold it in
+  m.stage = (int32_t *)q;      q += WAVE * 4;
+  m.warm = (int32_t *)q;                                     // only there with the pool
+  return m;
+}
+
+// hosts 0..H0-1 ready at time 0, the rest off (in the caller's registers); sessions unplaced
+__device__ __forceinline__ void lds_init_closed(const KParams &p, const Lds &m, int lane, int s_lo, int n_sess) {
+  if (lane < 8) m.c64[lane] = 0;
+  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
+  if (lane < 32) m.hist[lane] = 0;
+  if (p.warm_n > 0) {
+    for (int i = lane; i < WAVE * 4; i += WAVE) m.warm[i] = 0;     // initial hosts: warm from time 0
+  }
+  for (int s = lane; s < n_sess; s += WAVE) {
+    uint32_t g = p.sess_gpus[s_lo + s];
+    m.sess[s] = make_int2((int)(SS_UNPLACED | ((g - 1u) << 3)), 0);
+  }
+  __syncthreads();
+}
+
+// ---- S10: close the integrals at t_end and write the result record ---------------------------------
+__device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, const Regs &r, int rep, int lane) {
+  __syncthreads();
+  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
+  nbos_stats *out = p.stats + rep;
+  if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
+  if (lane == 0) {
+    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
+    out->status = r.status; out->n_decisions = r.n_dec;
+    out->sessions_placed = m.c32[CS_PLACED]; out->sessions_rejected = m.c32[CS_REJECTED];
+    out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
+    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = m.c32[CS_ABORTED];
+    out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
+    out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
+    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
+    out->migrations_warm = m.c32[CS_MIGRWARM];
+    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
+    out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
+    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_exec + g_wait;
+    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
+    out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
+    out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
+    out->replica_ms = (int64_t)m.c64[CL_REPL] + (int64_t)(int32_t)m.c32[CS_NREP] * t_end;
+    out->digest = r.digest;
+  }
+}
+
 // At most 128 vector registers (4 waves per SIMD): with 8-byte session records a compute unit then holds
 // 16 replays of 1,000 sessions at once.
 template <int NJ, uint32_t F>
@@ -733,6 +964,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
   m.sess = (int2 *)q;          q += (size_t)p.n_cap * 8;     // at a fixed offset: its accesses fold it in
+  m.stage = nullptr;
   m.warm = (int32_t *)q;                                     // only there with the pool
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
@@ -908,30 +1140,117 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
     if (final) break;
   }
 
-  // S10: close the integrals at t_end and write the result record
-  __syncthreads();
-  const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
-  nbos_stats *out = p.stats + rep;
-  if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
-  if (lane == 0) {
-    const int64_t sum_delay = (int64_t)m.c64[CL_SUMDELAY], g_wait = (int64_t)m.c64[CL_GWAIT];
-    out->status = r.status; out->n_decisions = r.n_dec;
-    out->sessions_placed = m.c32[CS_PLACED]; out->sessions_rejected = m.c32[CS_REJECTED];
-    out->cells_total = r.c_total; out->cells_immediate = r.c_imm; out->cells_started = r.c_started;
-    out->cells_queued = m.c32[CS_QUEUED]; out->cells_aborted = m.c32[CS_ABORTED];
-    out->cells_dropped_busy = r.c_busy; out->cells_dropped_unplaced = r.c_unplaced;
-    out->executor_reused = r.reused; out->migrations = m.c32[CS_MIGR];
-    out->scale_out_hosts = m.c32[CS_SO]; out->scale_in_hosts = m.c32[CS_SI]; out->peak_hosts = m.c32[CS_PEAK];
-    out->migrations_warm = m.c32[CS_MIGRWARM];
-    out->max_delay_ms = (int32_t)m.c32[CS_MAXDELAY]; out->t_end_ms = t_end;
-    out->sum_delay_ms = sum_delay; out->sum_tct_ms = r.sum_dur + sum_delay;
-    out->gpu_ms_executed = r.g_exec; out->gpu_ms_committed = r.g_exec + g_wait;
-    out->gpu_ms_provisioned = (int64_t)m.c64[CL_PROV] + (int64_t)m.c32[CS_NON] * p.G * t_end;
-    out->reservation_gpu_ms = (int64_t)m.c64[CL_RESV] + (int64_t)(int32_t)m.c32[CS_OPENG] * t_end;
-    out->sub_gpu_ms = (int64_t)m.c64[CL_SUB] + (int64_t)(int32_t)m.c32[CS_SUMS] * t_end;
-    out->replica_ms = (int64_t)m.c64[CL_REPL] + (int64_t)(int32_t)m.c32[CS_NREP] * t_end;
-    out->digest = r.digest;
+  write_stats(p, m, r, rep, lane);
+}
+
+// ---- closed-loop reading of the trace (see the file header and nbos_kernel_closed.hpp) -----------------
+// Arrivals from the stream are the first STARTs only (the STARTs that head a chain record); every other
+// event is a timer of kind QK_NEXT. Timers whose events were not loaded when they were scheduled load
+// them together when the first of them gets to the head.
+template <int NJ, uint32_t F>
+__global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_closed_kernel(KParams p) {
+  static_assert(Ctx<NJ, F>::closed, "instantiate with a closed-loop flag set");
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int rep = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (rep >= p.n_replays) return;
+
+  const int trace = p.trace_of_replay[rep];
+  const int64_t ev_lo = p.ev_offset[trace], ev_hi = p.ev_offset[trace + 1];
+  const int s_lo = p.sess_offset[trace];
+  const int n_sess = p.sess_offset[trace + 1] - s_lo;
+
+  const Lds m = lds_carve_closed(p, lds_raw);
+  lds_init_closed(p, m, lane, s_lo, n_sess);
+
+  const int32_t caplim = p.cap_milli[rep] * p.G * 3;
+  Ctx<NJ, F> c{p, m, lane, n_sess, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr, nullptr};
+#pragma unroll
+  for (int j = 0; j < NJ; j++) c.fin[j] = 0;
+  c.hr = lane < p.H0 ? 0 : NEVER;
+  c.hs = 0;
+  c.qt = NEVER; c.qd = 0; c.qk = 0xFFFFFFFFu;
+  c.vsid = 0xFFFFFFFFu;
+  c.fu = 0;
+  c.cl_cur = p.cl_cursor + (int64_t)rep * p.n_cap;
+  c.cl_dur = p.ev_dur + ev_lo; c.cl_sk = p.ev_sk + ev_lo; c.cl_chain = p.cl_chain + ev_lo;
+  c.qx = 0; c.qnx = -1; c.qnth = 0;
+  Regs r;
+  memset(&r, 0, sizeof r);
+  r.digest = 0xCBF29CE484222325ULL;
+  r.q_head_t = NEVER;
+  r.o_min_t = NEVER;
+  r.cl_win = 1024;
+
+  bool final = false;
+  for (int64_t base = ev_lo; r.status == NBOS_OK; base += WAVE) {
+    uint64_t todo = 0;
+    int32_t vt = 0, vnx = -1, vnth = -1;
+    uint32_t vs = 0;
+    if (base < ev_hi) {
+      if (base + lane < ev_hi) {
+        vt = p.ev_time[base + lane]; vs = (uint32_t)p.ev_sk[base + lane];
+        const int2 ch = p.cl_chain[base + lane];
+        vnx = ch.x; vnth = ch.y;
+      }
+      todo = wballot((vs >> 24) == NBOS_EV_START && vnth >= 0);
+    } else {
+      final = true;
+    }
+    while (r.status == NBOS_OK) {
+      int i = 0;
+      int32_t t = NEVER;
+      if (todo != 0) { i = (int)__builtin_ctzll(todo); t = lane_get(vt, i); }
+      else if (!final) break;
+      wave_sync();
+      if (r.q_n > 0 && r.q_head_t <= t) {
+        // ---- S2: the earliest timer is due ----
+        if (!(lane_get(c.qx, 0) & CLX_LOADED) && ((uint32_t)lane_get((int)c.qk, 0) >> 16) != QK_END) {
+          if (c.lane < r.q_n && !(c.qx & CLX_LOADED) && (c.qk >> 16) != QK_END) {
+            const int2 ch = c.cl_chain[c.qd];
+            c.qx = c.cl_dur[c.qd] | (int32_t)(((uint32_t)c.cl_sk[c.qd] >> 24) << 28) | CLX_LOADED;
+            c.qnx = ch.x; c.qnth = ch.y;
+          }
+        }
+        const int32_t now = r.q_head_t;
+        const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
+        const int32_t e = lane_get(c.qd, 0);
+        const int32_t x = lane_get(c.qx, 0), nx = lane_get(c.qnx, 0), nth = lane_get(c.qnth, 0);
+        timer_pop(c, r);
+        r.t_end = r.t_end > now ? r.t_end : now;
+        const uint32_t s = key & 0xFFFFu, kind = key >> 16;
+        wave_sync();
+        const int2 cur = m.sess[s];
+        const uint32_t hw = uni((uint32_t)cur.x), fl = hw;
+        const int32_t tm = uni(cur.y);
+        if (kind == QK_END) { end_session(c, r, s, hw, fl, now); continue; }
+        r.cl_e = e; r.cl_x = x; r.cl_nx = nx; r.cl_nth = nth;
+        const int32_t dur = x & 0x0FFFFFFF;
+        if (kind == QK_RETRY) {
+          attempt(c, r, s, hw, fl, now, tm, dur);
+        } else if ((((uint32_t)x >> 28) & 3u) == NBOS_EV_CELL) {     // the session submits its next cell (S4-S8)
+          r.c_total++;
+          const uint32_t st = fl & 7u;
+          // (a session whose next event is due is idle: its time word may hold that due time)
+          if (st == SS_PLACED && !(fl & SF_ENDING)) attempt(c, r, s, hw, fl & ~(15u << 8), now, now, dur);
+          else if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++;
+          else r.c_unplaced++;
+        } else {
+          on_session_end(c, r, s, hw, now, fl, now);              // S9: idle, so it ends at once
+        }
+        continue;
+      }
+      if (todo == 0) break;                 // draining and no timer is left
+      todo &= todo - 1;
+      const uint32_t s = (uint32_t)lane_get((int)vs, i) & 0xFFFFFFu;
+      const uint32_t fl = uni((uint32_t)m.sess[s].x);
+      r.t_end = r.t_end > t ? r.t_end : t;
+      r.cl_e = (int32_t)(base - ev_lo) + i; r.cl_nx = lane_get(vnx, i); r.cl_nth = lane_get(vnth, i);
+      session_start(c, r, s, fl, t);        // S3, S7; a placed session's first event is scheduled there
+    }
+    if (final) break;
   }
+  write_stats(p, m, r, rep, lane);
 }
 
 }  // namespace regk

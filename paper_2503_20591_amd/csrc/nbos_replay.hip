@@ -2,8 +2,8 @@
 // and kernel dispatch. Two kernels implement the same replay (see their headers):
 //   nbos_kernel_reg.hpp   hosts_max <= 64: host state in registers, no LDS round trip per cell
 //   nbos_kernel_lds.hpp   any hosts_max up to 1024: host state in LDS
-// A third replays the Batch baseline policy on the same traces (nbos_kernel_batch.hpp), a fourth reads
-// the traces as closed loops on the any-size kernel's code (nbos_kernel_closed.hpp).
+// A third replays the Batch baseline policy on the same traces (nbos_kernel_batch.hpp); the traces are
+// read as closed loops by a variant of either kernel (the end of nbos_kernel_reg.hpp, nbos_kernel_closed.hpp).
 // Everything is integer arithmetic; all control flow is wave-uniform.
 
 #include <hip/hip_runtime.h>
@@ -73,6 +73,21 @@ const void *reg_kernel_for(int nj) {
     case 6: return (const void *)regk::nbos_replay_reg_kernel<6, F>;
     case 7: return (const void *)regk::nbos_replay_reg_kernel<7, F>;
     default: return (const void *)regk::nbos_replay_reg_kernel<8, F>;
+  }
+}
+
+// the same for the closed-loop reading of the traces
+template <uint32_t F>
+const void *reg_closed_kernel_for(int nj) {
+  switch (nj) {
+    case 1: return (const void *)regk::nbos_replay_reg_closed_kernel<1, F>;
+    case 2: return (const void *)regk::nbos_replay_reg_closed_kernel<2, F>;
+    case 3: return (const void *)regk::nbos_replay_reg_closed_kernel<3, F>;
+    case 4: return (const void *)regk::nbos_replay_reg_closed_kernel<4, F>;
+    case 5: return (const void *)regk::nbos_replay_reg_closed_kernel<5, F>;
+    case 6: return (const void *)regk::nbos_replay_reg_closed_kernel<6, F>;
+    case 7: return (const void *)regk::nbos_replay_reg_closed_kernel<7, F>;
+    default: return (const void *)regk::nbos_replay_reg_closed_kernel<8, F>;
   }
 }
 
@@ -322,6 +337,17 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + n_cap * 12 + (n_cap + 2) * 2;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
+  } else if (closed_loop && cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS)) {
+    // hosts in registers; 8 bytes per session, 64 staged sessions
+    h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8 + WAVE * 4;
+    if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
+    sh->q_cap = 0;
+    const int nj = (cfg->hosts_max + 7) / 8;
+    const uint32_t policy = cfg->flags & regk::kPolicyFlags;
+    if (policy == NBOS_F_MIGRATE && !(ng && ng[0] == '1'))
+      h->kernel = reg_closed_kernel_for<NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP>(nj);
+    else
+      h->kernel = reg_closed_kernel_for<regk::kRuntimeClosed>(nj);
   } else if (closed_loop) {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
     h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +

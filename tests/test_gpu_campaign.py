@@ -62,8 +62,8 @@ def test_mid_size_random_cases(oracle, monkeypatch, block):
             sa, sb = int(b.sess_offset[t]), int(b.sess_offset[t + 1])
             want.append(oracle.replay(b.config, b.ev_time[a:e], b.ev_dur[a:e], b.ev_sk[a:e], b.sess_gpus[sa:sb],
                                       int(b.cap_milli[r])))
-        for in_lds in ((False, True) if mode not in ("closed", "batch") else (False,)):
-            for rounds in ((None, "1", "0") if (in_lds or mode == "closed") else (None,)):
+        for in_lds in ((False, True) if mode != "batch" else (False,)):
+            for rounds in ((None, "1", "0") if in_lds else (None,)):
                 if rounds is None:
                     monkeypatch.delenv("NBOS_REPLAY_BATCH", raising=False)
                 else:

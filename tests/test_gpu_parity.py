@@ -297,37 +297,41 @@ def as_closed(b):
     return b
 
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
 @pytest.mark.parametrize("seed", range(60))
-def test_closed_loop_random_cases(rp, oracle, seed):
+def test_closed_loop_random_cases(rp, oracle, seed, in_lds):
+    # clusters of up to 64 hosts run on the register kernel's closed loop unless the other one is asked for
     b = as_closed(tg.random_case(seed))
-    st, logs = gpu_run(rp, b, log=True)
-    assert_same(rp, oracle, b, st, logs, check=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+    assert_same(rp, oracle, b, st, logs, check=not in_lds)
 
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
 @pytest.mark.parametrize("seed", range(30))
-def test_closed_loop_policy_flag_cases(rp, oracle, seed):
+def test_closed_loop_policy_flag_cases(rp, oracle, seed, in_lds):
     # with the dynamic limit, the sticky executor and the pre-warmed containers
     b = as_closed(tg.random_case(seed, policy_flags=True))
-    st, logs = gpu_run(rp, b, log=True)
-    assert_same(rp, oracle, b, st, logs, check=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+    assert_same(rp, oracle, b, st, logs, check=not in_lds)
 
 
-@pytest.mark.parametrize("name,n", [("c2l", 6), ("c4l", 2)])
-def test_closed_loop_named_workloads(rp, oracle, name, n):
+@pytest.mark.parametrize("name,n,in_lds", [("c2l", 6, False), ("c2l", 6, True), ("c4l", 2, False)])
+def test_closed_loop_named_workloads(rp, oracle, name, n, in_lds):
     b = tg.workload(name, n_replays=n)
-    st, logs = gpu_run(rp, b, log=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
     assert_same(rp, oracle, b, st, logs)
     assert (st["cells_dropped_busy"] == 0).all()          # a session never submits while its cell runs
     assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"]).all()
 
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
 @pytest.mark.parametrize("name,n", [("c3", 4), ("c5", 16), ("c1", 1)])
-def test_closed_loop_on_the_other_traces(rp, oracle, name, n):
+def test_closed_loop_on_the_other_traces(rp, oracle, name, n, in_lds):
     # 1,000 sessions on 64 hosts: nearly every session's timer waits in its record, not in the
     # 64 sorted slots (refill takes several at once, pushes evict the latest)
     b = as_closed(tg.workload(name, n_replays=n))
-    st, logs = gpu_run(rp, b, log=True)
-    assert_same(rp, oracle, b, st, logs, check=name != "c3")
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+    assert_same(rp, oracle, b, st, logs, check=name != "c3" and not in_lds)
 
 
 @pytest.mark.parametrize("seed", range(0, 60, 2))
@@ -335,7 +339,7 @@ def test_closed_loop_random_cases_with_forced_rounds(rp, oracle, monkeypatch, se
     # small clusters run without the event-parallel rounds by default: here with them
     monkeypatch.setenv("NBOS_REPLAY_BATCH", "1")
     b = as_closed(tg.random_case(seed, policy_flags=seed % 4 == 0))
-    st, logs = gpu_run(rp, b, log=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=True)
     assert_same(rp, oracle, b, st, logs, check=True)
 
 
@@ -343,10 +347,10 @@ def test_closed_loop_named_workloads_with_forced_rounds(rp, oracle, monkeypatch)
     monkeypatch.setenv("NBOS_REPLAY_BATCH", "1")
     for name, n in (("c2l", 3), ("c3", 2), ("c5", 8)):
         b = as_closed(tg.workload(name, n_replays=n))
-        st, logs = gpu_run(rp, b, log=True)
+        st, logs = gpu_run(rp, b, log=True, in_lds=True)
         assert_same(rp, oracle, b, st, logs)
     # all sessions' cells due at the same instants, again and again
-    test_closed_loop_many_timers_at_one_instant(rp, oracle)
+    test_closed_loop_many_timers_at_one_instant(rp, oracle, True)
 
 
 def test_closed_loop_without_the_parallel_rounds(rp, oracle, monkeypatch):
@@ -373,7 +377,8 @@ def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
     assert st2.tobytes() == st.tobytes()
 
 
-def test_closed_loop_many_timers_at_one_instant(rp, oracle):
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
+def test_closed_loop_many_timers_at_one_instant(rp, oracle, in_lds):
     # 300 sessions placed at time 0 whose first cells are all due at the same millisecond, and again
     # later: far more than 64 timers for one instant wait outside the sorted slots, so they are
     # taken one by one in (kind, session) order; mixed with retries of queued cells
@@ -387,12 +392,13 @@ def test_closed_loop_many_timers_at_one_instant(rp, oracle):
                retry_interval_ms=1000, max_retries=3)
     gp = rng.choice([1, 2, 4], n)
     b = _tiny(cfg, ev, gp, [100000, 6000])
-    st, logs = gpu_run(rp, b, log=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
     assert_same(rp, oracle, b, st, logs, check=True)
     assert st["cells_queued"].max() > 64
 
 
-def test_closed_loop_time_range(rp, oracle):
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
+def test_closed_loop_time_range(rp, oracle, in_lds):
     # Three sessions keep all three hosts busy for a day, twice; the fourth session's first two cells
     # are given up after a minute each, so its third cell, nominally at the latest time a trace may
     # hold, comes two minutes late: with a one-day duration it would end beyond 2^31 - 1 ms. Both
@@ -414,10 +420,10 @@ def test_closed_loop_time_range(rp, oracle):
         with pytest.raises(ValueError) as e:
             oracle.replay(b.config, b.ev_time, b.ev_dur, b.ev_sk, b.sess_gpus, 100000)
         assert e.value.args[1] == -2
-        st, _ = gpu_run(rp, b)
+        st, _ = gpu_run(rp, b, in_lds=in_lds)
         assert (st["status"] == rp.E_RANGE).all()
     b = batch(day - 59_998)
-    st, logs = gpu_run(rp, b, log=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
     assert_same(rp, oracle, b, st, logs, check=True)
     assert st["t_end_ms"][0] == 2**31 - 2
 
