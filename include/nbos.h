@@ -138,9 +138,9 @@ typedef enum {
                                       the first END are ignored; cells of sessions that were not
                                       placed never arrive (cells_total counts arrivals). Due events
                                       run after retries of the same instant, by ascending session.
-                                      Runs on a kernel of its own (hosts in LDS, any cluster
-                                      size); not with NBOS_F_SCALE_IN, NBOS_F_AUTOSCALE or
-                                      NBOS_F_BATCH_MODE. A replay whose lag
+                                      Runs on closed-loop variants of both kernels (hosts in
+                                      registers up to 64 hosts, else in LDS); not with
+                                      NBOS_F_SCALE_IN, NBOS_F_AUTOSCALE or NBOS_F_BATCH_MODE. A replay whose lag
                                       pushes a time to 2^31 - 1 ends with status NBOS_E_RANGE.    */
 
 /* ---- event encoding ------------------------------------------------------ */
