@@ -1143,6 +1143,82 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   write_stats(p, m, r, rep, lane);
 }
 
+// ---- closed loop: runs of retries that fail again (failing_retries() for this kernel) -----------------
+// Same tests, same order. The retry's timer either stays in the sorted registers at its new place, or,
+// if it is no longer earlier than everything that waits in the session records, goes there. A retry
+// with no retries left is left for the general path (giving a cell up schedules the session's next
+// event). Returns the time of the last retry handled, or -1.
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int32_t cl_failing_retries(Ctx<NJ, F> &c, Regs &r, int32_t t_limit) {
+  int32_t last = -1;
+  const bool may_skip = !(c.flags() & NBOS_F_AUTOSCALE) &&
+                        (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT);
+  while (r.q_n > 0 && r.q_head_t <= t_limit) {
+    const int32_t now = r.q_head_t;
+    const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
+    if ((key >> 16) != QK_RETRY) break;
+    const uint32_t s = key & 0xFFFFu;
+    wave_sync();
+    const int2 rec = c.m.sess[s];
+    const uint32_t hw = uni((uint32_t)rec.x), fl = hw;
+    const int32_t t_submit = uni(rec.y);
+    int retries = (int)((fl >> 8) & 15u);
+    if (retries >= c.p.max_retries) break;                     // it would be given up: general path
+    const int g = (int)((fl >> 3) & 7u) + 1;
+    if (now >= lane_get(c.fu, g - 1)) {
+      const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
+      const int C = committed(c, now);
+      const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);
+      if (idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2))) break;          // the election succeeds
+      if (idle_ok == 0) {
+        const int32_t bound = earliest_idle(c, g);
+        if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
+      } else if (c.flags() & NBOS_F_MIGRATE) {
+        const int S = (int)(c.hs & 0xFFFFu);
+        if (idle_ok & wballot(S <= cap_room(c, g))) break;                        // a migration target
+      }
+    }
+    if (c.flags() & NBOS_F_SCALE_OUT) {
+      wave_sync();
+      if ((int)uni(c.m.c32[CS_NON]) < c.p.Hmax) break;                            // a host can be added
+    }
+    // it fails again: bump the retry count (skipping retries that are bound to fail as well)
+    retries++;
+    if (may_skip) {
+      const int32_t bound = lane_get(c.fu, g - 1);
+      while (retries < c.p.max_retries && t_submit + retries * c.p.retry_iv < bound) retries++;
+    }
+    if ((int64_t)t_submit + (int64_t)retries * c.p.retry_iv >= 0x7FFFFFFFLL) break;   // out of range: general path
+    last = now;
+    const uint32_t nfl = (fl & ~(15u << 8)) | ((uint32_t)retries << 8);
+    if (c.lane == 0) c.m.sess[s].x = (int)nfl;
+    const int32_t t_new = t_submit + retries * c.p.retry_iv;
+    const int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);          // wave_shl:1
+    const int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
+    const uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
+    const int32_t sx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
+    const int32_t sn = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
+    const int32_t sh = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
+    if (r.o_n > 0 && !(t_new < r.o_min_t || (t_new == r.o_min_t && key < r.o_min_k))) {
+      // no longer earlier than all that waits in the records: the timer goes there, off the registers
+      ovf_push(c, r, t_new, key, 0);
+      c.qt = st; c.qd = sd; c.qk = sk; c.qx = sx; c.qnx = sn; c.qnth = sh;
+      r.q_n--;
+      if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
+      r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
+    } else {
+      // it moves from lane 0 to its new place: the entries before that shift down one lane
+      const bool before = c.lane >= 1 && c.lane < r.q_n && (c.qt < t_new || (c.qt == t_new && c.qk < key));
+      const int pos = __builtin_popcountll(wballot(before));
+      const int32_t d_own = lane_get(c.qd, 0), x_own = lane_get(c.qx, 0), n_own = lane_get(c.qnx, 0), h_own = lane_get(c.qnth, 0);
+      if (c.lane < pos) { c.qt = st; c.qd = sd; c.qk = sk; c.qx = sx; c.qnx = sn; c.qnth = sh; }
+      if (c.lane == pos) { c.qt = t_new; c.qd = d_own; c.qk = key; c.qx = x_own; c.qnx = n_own; c.qnth = h_own; }
+      r.q_head_t = lane_get(c.qt, 0);
+    }
+  }
+  return last;
+}
+
 // ---- closed-loop reading of the trace (see the file header and nbos_kernel_closed.hpp) -----------------
 // Arrivals from the stream are the first STARTs only (the STARTs that head a chain record); every other
 // event is a timer of kind QK_NEXT. Timers whose events were not loaded when they were scheduled load
@@ -1205,6 +1281,10 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_closed_kernel(KParams
       wave_sync();
       if (r.q_n > 0 && r.q_head_t <= t) {
         // ---- S2: the earliest timer is due ----
+        {
+          const int32_t last = cl_failing_retries(c, r, t);
+          if (last >= 0) { r.t_end = r.t_end > last ? r.t_end : last; continue; }
+        }
         if (!(lane_get(c.qx, 0) & CLX_LOADED) && ((uint32_t)lane_get((int)c.qk, 0) >> 16) != QK_END) {
           if (c.lane < r.q_n && !(c.qx & CLX_LOADED) && (c.qk >> 16) != QK_END) {
             const int2 ch = c.cl_chain[c.qd];
