@@ -4,15 +4,17 @@
 A "step" is one pass of the whole hot path (placement, election, commit/release, migration,
 scale-out/in, queueing, final drain) over one batch of synthetic traces that is already resident
 in HBM. Metric: cell events x initial hosts per second, summed over the replays of the batch.
-Prints ONE JSON line.
+The default workload is the largest one (c4: 256 replays of 512 -> 768 hosts, 8,000 sessions and
+500,000 cells each). Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--replays N]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--replays N]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -21,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+GPU_BOX_CPU_SHARE = 16    # host threads one GPU's share of the box allows
 
 
 def measured_traffic(workload: str):
@@ -41,24 +44,50 @@ def measured_traffic(workload: str):
     return rec["traffic_bytes"] if h.hexdigest() == rec["csrc_sha256"] else None
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(batch, budget_s: float, threads: int):
-    """The CPU oracle, as it stands, timed on a bounded sample of the same batch."""
+    """The CPU oracle, as it stands, timed on bounded samples of the same batch: one thread on the
+    first replays (extrapolated linearly), then all the host threads this process may use."""
     import oracle
     oracle.build()
     per_cells = batch.n_cells() / max(batch.n_replays, 1)
-    # one replay first to size the sample
+    hosts = batch.config["hosts_initial"]
+    unit = "cell-events*hosts/s"
+    # one replay first, to size the samples
     t0 = time.perf_counter()
     oracle.replay_batch(batch, replays=[0])
     one = max(time.perf_counter() - t0, 1e-6)
-    n = int(max(1, min(batch.n_replays, budget_s * threads / one)))
+    # leg 1: one thread, the first min(n, 32) replays (fewer if they would not fit a third of the budget)
+    n1 = int(max(1, min(batch.n_replays, 32, budget_s / 3 / one)))
+    t0 = time.perf_counter()
+    oracle.replay_batch(batch, replays=list(range(n1)))
+    dt1 = time.perf_counter() - t0
+    v1 = per_cells * n1 * hosts / dt1
+    # leg 2: every host thread, replays striding over the threads; the whole batch if it fits the budget
+    n = int(max(1, min(batch.n_replays, (2 * budget_s / 3) * threads / one)))
     idx = [int(i * batch.n_replays / n) for i in range(n)]
     t0 = time.perf_counter()
     oracle.replay_batch(batch, replays=idx, threads=threads)
     dt = time.perf_counter() - t0
-    value = per_cells * n * batch.config["hosts_initial"] / dt
-    return {"value": value, "unit": "cell-events*hosts/s", "cores": threads, "kind": "oracle",
+    value = per_cells * n * hosts / dt
+    return {"value": value, "unit": unit, "cores": threads, "kind": "oracle",
             "sample": f"{n} of {batch.n_replays} replays of {batch.name}, evenly spaced, "
-                      f"{threads} thread(s), {dt:.1f} s"}
+                      f"{threads} thread(s), {dt:.1f} s",
+            "host_cpus": os.cpu_count(), "cpu_model": cpu_model(),
+            "threads_note": f"{threads} = min(hardware threads of the host, {GPU_BOX_CPU_SHARE}: the share of the "
+                            f"box that goes with one GPU)",
+            "one_core": {"value": v1, "unit": unit, "cores": 1,
+                         "sample": f"first {n1} of {batch.n_replays} replays of {batch.name}, 1 thread, {dt1:.1f} s; "
+                                   f"the whole batch would take {dt1 / n1 * batch.n_replays:.1f} s at this rate"}}
 
 
 def measured_copy_gbs(torch):
@@ -83,11 +112,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b", "c2l", "c4l"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c4a", "c2b", "c4b", "c2l", "c4l"])
     ap.add_argument("--replays", type=int, default=None, help="truncate the batch (for quick looks)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 = skip")
-    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = all host cores (at most 16)")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = all host threads this process may use")
     ap.add_argument("--hosts-in-lds", action="store_true", help="force the any-size kernel (comparison runs)")
+    ap.add_argument("--generic-kernel", action="store_true", help="force the run-time-flags kernel (comparison runs)")
+    ap.add_argument("--rounds", choices=["on", "off"], default=None, help="force the event-parallel rounds (comparison runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -101,8 +132,9 @@ def main():
     replay.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
+    threads = args.cpu_threads or min(GPU_BOX_CPU_SHARE, os.cpu_count() or 1)
     t0 = time.perf_counter()
-    batch = tracegen.workload(args.workload, n_replays=args.replays, workers=min(16, os.cpu_count() or 1))
+    batch = tracegen.workload(args.workload, n_replays=args.replays, workers=threads)
     t_gen = time.perf_counter() - t0
     t0 = time.perf_counter()
     dev = replay.upload(batch, "cuda:0")
@@ -114,29 +146,31 @@ def main():
         dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    h = replay.Replay(batch.config, dev, hosts_in_lds=args.hosts_in_lds)
+    default_shape = not (args.replays or args.hosts_in_lds or args.generic_kernel or args.rounds)
+    h = replay.Replay(batch.config, dev, hosts_in_lds=args.hosts_in_lds, generic_kernel=args.generic_kernel,
+                      rounds=None if args.rounds is None else args.rounds == "on")
     info = h.launch_info()
 
     for _ in range(args.warmup):
         h.run()
     torch.cuda.synchronize()
-    kernel_ms = []
+    # The handle launches on torch's current stream, so events recorded there bracket every launch of
+    # the timed region: marks[i] .. marks[i + 1] is launch i.
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()
         h.run()
-        kernel_ms.append(None)
+    marks[args.steps].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    # per-launch device time from the library's HIP events on its own stream (one extra timed pass
-    # per sample, outside the wall-clock region above)
-    dur = []
-    for _ in range(min(args.steps, 10)):
-        h.run()
-        dur.append(h.last_kernel_ms())
+    dur = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+    last_ms = h.last_kernel_ms()            # the library's own HIP events around its last launch
     st = h.stats()
     assert (st["status"] == 0).all()
     h.close()
     copy_gbs = measured_copy_gbs(torch)
+    floor_ns = replay.chain_floor_ns()
 
     ms_per_step = wall * 1e3 / args.steps
     cells = batch.n_cells()
@@ -144,8 +178,8 @@ def main():
     alg_bytes = batch.algorithmic_bytes(replay.STATS_DTYPE.itemsize)
     avg_kernel_ms = sum(dur) / len(dur)
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    ev_per_replay = batch.n_events() / max(batch.n_replays, 1)
 
-    threads = args.cpu_threads or min(16, os.cpu_count() or 1)
     cpu = cpu_baseline(batch, args.cpu_budget, threads) if args.cpu_budget > 0 else None
 
     out = {
@@ -163,9 +197,14 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "copy_gbs": copy_gbs, "frac_of_copy": achieved / copy_gbs,
-                     "traffic": None if (args.replays or args.hosts_in_lds) else measured_traffic(args.workload),
-                     "kernel": "nbos_replay_kernel", "kernel_ms": avg_kernel_ms, "algorithmic_bytes": alg_bytes,
-                     "ns_per_event_per_replay": avg_kernel_ms * 1e6 / (batch.n_events() / max(batch.n_replays, 1))},
+                     "traffic": measured_traffic(args.workload) if default_shape else None,
+                     "kernel": info["kernel"], "kernel_ms": avg_kernel_ms,
+                     "kernel_ms_median": statistics.median(dur), "kernel_ms_last_by_library_events": last_ms,
+                     "algorithmic_bytes": alg_bytes,
+                     "ns_per_event_per_replay": avg_kernel_ms * 1e6 / ev_per_replay,
+                     "chain_floor_ns": floor_ns,
+                     "chain_floor_note": "one dependent event body (LDS row read, count, wave minimum, LDS write) on a "
+                                         "lone wave; a replay cannot take a step in less"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

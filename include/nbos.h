@@ -29,6 +29,15 @@
  * All times are int32 milliseconds, all results are integers; no floating point
  * is used anywhere, so results are exact and reproducible.
  *
+ * Section numbers used in this file and in the sources, with the paper's titles:
+ *   2.2    Interactive Deep Learning Training      3.3    GPU Management
+ *   3.2.1  Distributed Kernel Creation             3.4.1  Default Placement Policy
+ *   3.2.2  Distributed Kernel Raft Protocol        3.4.2  Scale-Out Operations
+ *   3.2.3  Handling Failed Executor Elections (with "Pre-warmed Container Pool")
+ * Passages of the evaluation are cited by title only: "Baselines" (Reservation, Batch),
+ * "Resource Usage & Efficiency", "Interactivity", "Task Completion Time", "Subscription
+ * Ratio", and "Monetary Cost" / "GPU Hours Saved" of the simulation study.
+ *
  * Pointers
  * --------
  * nbos_config / nbos_inputs structs themselves live in HOST memory.
@@ -79,6 +88,14 @@ typedef enum {
 #define NBOS_F_HOSTS_IN_LDS   0x10u /* use the any-size kernel (host state in LDS) even when
                                       hosts_max <= 64 would allow the register kernel; same
                                       results, for cross-checks and comparisons              */
+#define NBOS_F_GENERIC_KERNEL 0x800u /* comparison runs: run the kernel instance that reads the policy flags
+                                      at run time even where an instance compiled for the flag set
+                                      exists; same results                                       */
+#define NBOS_F_ROUNDS_OFF    0x1000u /* comparison runs: never evaluate runs of arrivals (or of due
+                                      closed-loop events) in event-parallel rounds; same results   */
+#define NBOS_F_ROUNDS_ON     0x2000u /* comparison runs: use the rounds also where they are off by
+                                      default (closed loops on at most 64 hosts with
+                                      NBOS_F_HOSTS_IN_LDS); same results. Not with NBOS_F_ROUNDS_OFF */
 #define NBOS_F_AUTOSCALE     0x20u /* the periodic auto-scaler of Section 3.4.2 (second scale-out
                                       scenario). Every scale_interval_ms the expected capacity is
                                       want = ceil(f * sum C / G) + scaling_buffer_hosts hosts, with
@@ -95,13 +112,13 @@ typedef enum {
                                       hosts not off, i.e. the limit in force is the larger of the
                                       replay's cap and the cluster-wide ratio after placing.  */
 
-#define NBOS_F_STICKY_EXECUTOR 0x80u /* election variant (Section 3.2.2; Section 5.2.3 reports that
+#define NBOS_F_STICKY_EXECUTOR 0x80u /* election variant (Section 3.2.2; the "Interactivity" section reports that
                                       consecutive cells ran on the same replica 89.45 % of the
                                       time): the replica that executed the session's previous
                                       cell leads again whenever its host can bind the GPUs;
                                       otherwise the usual rule decides                        */
 
-#define NBOS_F_BATCH_MODE    0x100u /* replay the Batch baseline of Section 5.1.3 instead of the
+#define NBOS_F_BATCH_MODE    0x100u /* replay the Batch baseline of the paper's "Baselines" section instead of the
                                       NotebookOS policy: no replicas; every cell is a job of its
                                       own, served first come first served (a job never overtakes
                                       an earlier one) on the ready host with the fewest committed
@@ -126,7 +143,7 @@ typedef enum {
                                       (decision NBOS_D_MIGRATE_WARM) and a replacement is available
                                       prewarm_delay_ms later. Not with NBOS_F_BATCH_MODE.        */
 
-#define NBOS_F_CLOSED_LOOP   0x400u /* closed-loop reading of the traces (Section 2.2 describes
+#define NBOS_F_CLOSED_LOOP   0x400u /* closed-loop reading of the traces (the section "Interactive Deep Learning Training" describes
                                       users who think and edit between cells): only a session's
                                       first START keeps its time. Every later CELL / END of the
                                       session is due one think time after the session's previous
@@ -193,7 +210,7 @@ typedef struct {
 } nbos_inputs;
 
 /*
- * Result of one replay. Counter semantics (paper Sections 5.2.2-5.2.4 for the
+ * Result of one replay. Counter semantics (the paper's sections "Resource Usage & Efficiency", "Interactivity" and "Task Completion Time" for the
  * metric definitions):
  *   cells_immediate   cells whose GPUs were committed by election at submit time
  *   executor_reused   cell executed by the same replica slot as the previous cell
@@ -254,10 +271,8 @@ typedef struct {
  *   out       receives the handle.
  * Validates parameters on the host and the trace contents with a device kernel
  * (synchronises the stream once). Allocates only its own result buffers.
- * Two environment variables are read here, for comparison runs only; they change which kernel
- * runs, never a result: NBOS_REPLAY_BATCH=0|1 (event-parallel rounds in the any-size and the
- * closed-loop kernel off / on; by default on, except for closed loops on at most 64 hosts),
- * NBOS_REPLAY_GENERIC=0|1 (the kernel instance compiled for the flag set / the generic one).
+ * Which kernel runs follows from cfg alone (cluster size, policy flags and the comparison flags
+ * NBOS_F_HOSTS_IN_LDS / _GENERIC_KERNEL / _ROUNDS_OFF / _ROUNDS_ON); the environment is not read.
  * With NBOS_F_CLOSED_LOOP a device kernel links every session's events here (8 bytes per event
  * and 4 per replay and session of device memory are held until destroy).
  * Errors: NBOS_E_ARG, NBOS_E_RANGE, NBOS_E_LIMIT (hosts/sessions/LDS footprint
@@ -268,24 +283,45 @@ int32_t nbos_replay_create(const nbos_config *cfg, const nbos_inputs *in,
                            void *stream, nbos_replay **out);
 
 /*
- * Enqueue one full pass: every replay consumes its whole trace (placement,
- * election, commit/release, migration, scale-out/in, queueing, final drain) and
- * writes its nbos_stats into the handle's device buffer. Asynchronous on the
- * handle's stream; may be called repeatedly, every call recomputes the same
- * results from the same inputs.
+ * Enqueue one full pass: every replay consumes its whole trace and writes its
+ * nbos_stats into the handle's device buffer. Per event, in trace order, with
+ * every timer that is due at or before the event run first:
+ *   SESSION_START  three replicas on three hosts, subscribed not committed
+ *                  ("Distributed Kernel Creation", "Default Placement Policy");
+ *   CELL           the election among the session's replicas, GPUs bound for the
+ *                  cell's duration and released at its end ("Distributed Kernel
+ *                  Raft Protocol", "GPU Management"); when all replicas yield: a
+ *                  migration, a new host, or the retry queue ("Handling Failed
+ *                  Executor Elections", "Scale-Out Operations");
+ *   periodic       the auto-scaler's release / provisioning of hosts ("Scale-Out
+ *                  Operations", last paragraphs);
+ * then the pending timers are drained and the integrals are closed at the last instant.
+ * Takes no arguments beyond the handle; reads the borrowed device arrays of create.
+ * Asynchronous on the handle's stream; may be called repeatedly, every call
+ * recomputes the same results from the same inputs. Nothing is allocated here.
  * Errors: NBOS_E_ARG (null), NBOS_E_HIP.
  */
 int32_t nbos_replay_run(nbos_replay *h);
 
 /*
  * Copy the stats of replays [first, first+count) to host_out (host memory,
- * count * sizeof(nbos_stats) bytes). Synchronises the handle's stream.
+ * count * sizeof(nbos_stats) bytes, owned by the caller). The fields are the
+ * quantities the paper's evaluation reports per policy: GPUs provisioned, bound
+ * and reserved over time ("Resource Usage & Efficiency", "GPU Hours Saved"), the
+ * interactivity delay and its distribution, immediate starts and executor reuse
+ * ("Interactivity"), completion times ("Task Completion Time"), the subscribed
+ * GPUs over time ("Subscription Ratio"), migrations and hosts added / released
+ * ("Scale-Out Operations"). Synchronises the handle's stream.
  * Errors: NBOS_E_ARG (null, range), NBOS_E_STATE (never run), NBOS_E_HIP.
  */
 int32_t nbos_replay_stats(nbos_replay *h, int32_t first, int32_t count,
                           nbos_stats *host_out);
 
 /*
+ * The sequence of scheduling decisions of one replay: which hosts a session's replicas
+ * were placed on ("Distributed Kernel Creation"), which replica led each cell and where
+ * ("Distributed Kernel Raft Protocol"), every migration, added host, abort and released
+ * host ("Handling Failed Executor Elections", "Scale-Out Operations"), as NBOS_D_* codes.
  * Only with NBOS_F_DECISION_LOG: copy up to `cap` decision codes of one replay
  * to host_out (host memory), in processing order. Returns the number of codes
  * the replay logged (may exceed cap; a replay logs at most its own capacity of
@@ -307,7 +343,7 @@ int32_t nbos_replay_launch_info(nbos_replay *h, int32_t *lds_bytes,
                                 int32_t *threads_per_group, int32_t *groups);
 
 /*
- * Billing model of paper Section 5.3.1 as a post-pass over the results of the last run, in integer
+ * Billing model of the paper's "Monetary Cost" section as a post-pass over the results of the last run, in integer
  * micro-dollars, every amount rounded down:
  *   provider_cost        price * host-hours provisioned   (gpu_ms_provisioned / G)
  *   usage_revenue        executing replicas pay markup_pct/100 of the provider's rate for the share
@@ -334,6 +370,23 @@ typedef struct {
  */
 int32_t nbos_replay_billing(nbos_replay *h, const nbos_billing_params *params, int32_t first,
                             int32_t count, nbos_bill *host_out);
+
+/* Name of the replay kernel instance chosen at create, as a profiler's kernel trace prints it
+ * (without the argument list), e.g. "ldsk::nbos_replay_lds_kernel<7u>". Static storage of the
+ * handle, valid until destroy; "" for a NULL handle. */
+const char *nbos_replay_kernel_name(nbos_replay *h);
+
+/*
+ * Measurement aid, no part of a replay: the dependency-chain floor of one event body. A replay is
+ * a serial chain of state updates; the shortest step this design can take is one read of a host's
+ * GPU row from LDS, a count of its committed GPUs, one wave-wide minimum over a packed key and one
+ * busy-until time written back. Runs that body `iters` times (1..2^24) in a dependent chain, one
+ * wave per compute unit, on `stream` (a hipStream_t or NULL), twice, and returns the second pass's
+ * nanoseconds per iteration in *ns_out (host memory). Synchronises the stream; allocates and frees
+ * a few KB of device memory.
+ * Errors: NBOS_E_ARG, NBOS_E_HIP, NBOS_E_NOMEM.
+ */
+int32_t nbos_chain_floor_ns(void *stream, int32_t iters, float *ns_out);
 
 /* Free the handle and its device buffers (synchronises the stream). NULL is a no-op. */
 void nbos_replay_destroy(nbos_replay *h);

@@ -176,7 +176,7 @@ def replay_batch(batch, replays=None, *, check: bool = False, threads: int = 1) 
 
 def billing(result: dict, gpus_per_host: int, price_micro_per_host_hour: int, markup_pct: int = 115,
             standby_permille: int = 125, lib_path: str | None = None) -> dict:
-    """Section 5.3.1 billing of one result dict (as returned by ``replay``), integer micro-dollars."""
+    """Section "Monetary Cost" billing of one result dict (as returned by ``replay``), integer micro-dollars."""
     lib = _load(lib_path)
     res = _Result()
     for name in RESULT_FIELDS:

@@ -15,8 +15,8 @@
  *   scale-out on failed placement, periodic scale-in ............... 3.4.2
  *   auto-scaler: expected capacity f * sum C, scaling buffer ....... 3.4.2
  *   dynamic cluster-wide limit on the subscription ratio ........... 3.4.1
- *   metric definitions (delay, TCT, immediate, reuse, GPU-hours) ... 5.2.2-5.2.4
- *   billing model (provider cost, revenue, standby charge) ......... 5.3.1
+ *   metric definitions (delay, TCT, immediate, reuse, GPU-hours) ... "Resource Usage & Efficiency", "Interactivity", "Task Completion Time"
+ *   billing model (provider cost, revenue, standby charge) ......... "Monetary Cost"
  *   pre-warmed container pool for migrations ........................ 3.2.3
  *
  * Readings taken where the paper leaves a choice open (all deterministic):
@@ -51,7 +51,7 @@
  *     available longest, if one is available now: the cell then starts after
  *     warm_migration_delay_ms instead of migration_delay_ms, and a replacement is
  *     available prewarm_delay_ms later. A host added for the cell has none yet.
- *   - closed loop (ORC_F_CLOSED_LOOP; Section 2.2 describes users who think, edit and
+ *   - closed loop (ORC_F_CLOSED_LOOP; the section "Interactive Deep Learning Training" describes users who think, edit and
  *     re-submit between cells): only a session's first START keeps its time. Every
  *     later CELL / END of the session is due one think time after the session's
  *     previous cell is over (finished or given up; for the first one: after the
@@ -273,7 +273,7 @@ static void on_session_start(sim *m, int s) {
   if (m->p->flags & ORC_F_CLOSED_LOOP) schedule_next(m, s, m->clock);
 }
 
-/* ---- a cell starts: Section 3.3 (bind GPUs), metrics of Sections 5.2.2-5.2.4 - */
+/* ---- a cell starts: Section 3.3 (bind GPUs), metrics of sections "Resource Usage & Efficiency", "Interactivity" and "Task Completion Time" - */
 static void start_cell(sim *m, int s, int slot, int32_t start, int outcome) {
   sess_rec *q = &m->sess[s];
   int32_t commit_t = m->clock;
@@ -573,7 +573,9 @@ static int validate(const orc_params *p, int64_t n_events, const int32_t *ev_tim
   int64_t slowest = p->migration_delay_ms;
   if ((p->flags & ORC_F_WARM_POOL) && p->warm_migration_delay_ms > slowest) slowest = p->warm_migration_delay_ms;
   int64_t horizon = (int64_t)prev + MAX_DUR + (int64_t)p->max_retries * p->retry_interval_ms +
-                    p->boot_delay_ms + slowest + ((p->flags & ORC_F_WARM_POOL) ? p->prewarm_delay_ms : 0);
+                    p->boot_delay_ms + slowest + ((p->flags & ORC_F_WARM_POOL) ? p->prewarm_delay_ms : 0) +
+                    /* the next auto-scaler period is pushed one interval past the timer that ran */
+                    ((p->flags & (ORC_F_SCALE_IN | ORC_F_AUTOSCALE)) ? p->scale_interval_ms : 0);
   if (horizon >= 2147483647LL) return ORC_E_INPUT;
   return 0;
 }
@@ -659,7 +661,7 @@ int orc_replay(const orc_params *p,
     run_timer(&m, heap_pop(&m));
   }
 
-  /* the session lifetimes a Reservation policy would hold GPUs for (Section 5.1.3) */
+  /* the session lifetimes a Reservation policy would hold GPUs for (the paper's "Baselines" section) */
   m.r.t_end_ms = m.clock;
   for (int s = 0; s < n_sessions; s++) {
     const sess_rec *q = &m.sess[s];
@@ -704,7 +706,7 @@ int orc_replay(const orc_params *p,
 
 int orc_sizeof_result(void) { return (int)sizeof(orc_result); }
 
-/* ---- Section 5.3.1: billing ------------------------------------------------------ */
+/* ---- "Monetary Cost" section: billing ------------------------------------------------------ */
 static int64_t ratio(int64_t amount, int64_t num, int64_t den) {
   return (int64_t)((unsigned __int128)amount * (unsigned __int128)num / (unsigned __int128)den);
 }

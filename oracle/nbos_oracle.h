@@ -19,7 +19,7 @@ enum {
   ORC_F_AUTOSCALE = 0x20,   /* Section 3.4.2: periodic expected-capacity test f * sum C    */
   ORC_F_DYNAMIC_SR = 0x40,  /* Section 3.4.1: cluster-wide subscription ratio as the limit */
   ORC_F_STICKY = 0x80,      /* election variant: the previous executor leads again if it can */
-  ORC_F_BATCH = 0x100,      /* replay the Batch baseline of Section 5.1.3 (orc_replay_batch)  */
+  ORC_F_BATCH = 0x100,      /* replay the Batch baseline of the paper's "Baselines" section (orc_replay_batch)  */
   ORC_F_WARM_POOL = 0x200,  /* Section 3.2.3: pre-warmed containers shorten a migration        */
   ORC_F_CLOSED_LOOP = 0x400 /* a session's next event comes a think time after its previous
                                cell is over (not at its time in the trace)                    */
@@ -101,7 +101,7 @@ int orc_replay(const orc_params *p,
                orc_result *out, uint64_t *log, int64_t log_cap, orc_final *fin);
 
 /*
- * Replay the same trace under the Batch baseline (paper Section 5.1.3): every cell is a job of its
+ * Replay the same trace under the Batch baseline (the paper's "Baselines" section): every cell is a job of its
  * own, first come first served, a container per job. Same argument meaning as orc_replay; of the
  * flags only ORC_F_BATCH and ORC_F_SCALE_OUT are accepted. Fields of the result that only exist
  * with replicas (placement, migration, subscription, Reservation) stay 0; cells_queued counts the
@@ -116,7 +116,7 @@ int orc_replay_batch(const orc_params *p,
 int orc_sizeof_result(void);
 
 /*
- * Billing model of Section 5.3.1 applied to one result, in integer micro-dollars (each amount
+ * Billing model of the "Monetary Cost" section applied to one result, in integer micro-dollars (each amount
  * rounded down): the provider pays `price` per host-hour provisioned; users pay markup_pct / 100
  * times the provider's rate in proportion to the GPUs they use; a standby replica (placed, not
  * executing) pays standby_permille / 1000 of the marked-up host rate. The Reservation baseline

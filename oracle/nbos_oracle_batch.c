@@ -4,11 +4,11 @@
  * TEST INFRASTRUCTURE (see nbos_oracle.h). Plain C99, single-threaded, eager
  * discrete-event loop with one heap of timers.
  *
- * What it follows: the "Batch" baseline of paper Section 5.1.3: no long-running
+ * What it follows: the "Batch" baseline of the paper's "Baselines" section: no long-running
  * kernel, no replicas. Every cell submission is a job of its own: a container is
  * provisioned for it on a server with enough idle GPUs, serves the request and
  * terminates. Jobs are served first come, first served (strict: a job never
- * overtakes an earlier one). Metrics as in Sections 5.2.2-5.2.4.
+ * overtakes an earlier one). Metrics as in sections "Resource Usage & Efficiency", "Interactivity" and "Task Completion Time".
  *
  * Readings taken where the paper leaves a choice open (all deterministic):
  *   - a job holds its g GPUs from the moment they are allocated: for the

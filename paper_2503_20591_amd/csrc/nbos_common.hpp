@@ -43,7 +43,18 @@ struct KParams {
   // chain holds. cl_cursor: per replay and session the event that is due next or under way.
   const int2 *cl_chain;
   int32_t *cl_cursor;
+  // null, or a word a validation kernel of the same stream has left: when it is not 0 the traces are
+  // invalid and every replay ends at once with status NBOS_E_RANGE (calls that cannot wait for the
+  // validation on the host)
+  const uint32_t *trace_err;
 };
+
+// A replay that cannot run (invalid traces, more sessions than the launch has LDS for): its record
+// holds the status and zeros.
+__device__ __forceinline__ void refuse_replay(const KParams &p, int rep, int lane, int32_t status) {
+  int32_t *out = (int32_t *)(p.stats + rep);
+  for (int i = lane; i < (int)(sizeof(nbos_stats) / 4); i += WAVE) out[i] = i == 0 ? status : 0;
+}
 
 __device__ __forceinline__ int32_t uni(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }

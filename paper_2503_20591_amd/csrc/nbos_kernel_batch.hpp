@@ -1,4 +1,4 @@
-// nbos_kernel_batch.hpp — replay of the Batch baseline (paper Section 5.1.3): every cell is a job of its
+// nbos_kernel_batch.hpp — replay of the Batch baseline (the paper's "Baselines" section): every cell is a job of its
 // own, first come first served, a container per job. One workgroup (one wave64) per replay, any cluster
 // size up to NBOS_MAX_HOSTS.
 //

@@ -1,4 +1,4 @@
-// nbos_kernel_closed.hpp — closed-loop reading of a trace (paper Section 2.2: users think and edit
+// nbos_kernel_closed.hpp — closed-loop reading of a trace (the paper's section "Interactive Deep Learning Training": users think and edit
 // between the cells they submit) on the any-size kernel's state and policy code.
 //
 // Only a session's first START keeps its time. Every later CELL / END of the session is due one

@@ -608,7 +608,7 @@ __device__ __forceinline__ void end_session(Ctx<F> &c, Regs &r, uint32_t s, uint
   c64_add(c.m, c.lane, CL_REPL, (int64_t)3 * now);
 }
 
-// ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
+// ---- a cell starts on (slot, host): Section 3.3 and the metrics of sections "Resource Usage & Efficiency", "Interactivity" and "Task Completion Time" ---------
 template <uint32_t F>
 __device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,

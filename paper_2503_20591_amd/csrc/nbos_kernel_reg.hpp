@@ -24,7 +24,7 @@
 //         arrived are the only timers that change decisions. The 64 earliest live sorted in
 //         registers (insert = ballot + DPP wave shift, pop = DPP wave shift); later ones stay with
 //         their session (a flag in its record, their time implied by it) until the registers run empty.
-// Closed loop (paper Section 2.2; nbos_replay_reg_closed_kernel at the end of this file): only the
+// Closed loop (the paper's section "Interactive Deep Learning Training"; nbos_replay_reg_closed_kernel at the end of this file): only the
 //         first STARTs come from the stream, every other event of a session is a timer that is due a
 //         think time after the session's previous cell is over. See nbos_kernel_closed.hpp for the
 //         chain records this reads and for the same scheme on the any-size kernel.
@@ -545,7 +545,7 @@ __device__ __forceinline__ void end_session(Ctx<NJ, F> &c, Regs &r, uint32_t s, 
   c64_add(c.m, c.lane, CL_REPL, (int64_t)3 * now);
 }
 
-// ---- a cell starts on (slot, host): Section 3.3 and the metrics of Sections 5.2.2-5.2.4 ---------
+// ---- a cell starts on (slot, host): Section 3.3 and the metrics of sections "Resource Usage & Efficiency", "Interactivity" and "Task Completion Time" ---------
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int slot, int host,
                                            int32_t now, int32_t start, int32_t t_submit, int32_t dur,
@@ -952,11 +952,14 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   const int rep = blockIdx.x;
   const int lane = threadIdx.x;
   if (rep >= p.n_replays) return;
+  // launched without a look at the traces on the host: the validation kernel's verdict comes first
+  if (p.trace_err != nullptr && *p.trace_err != 0) { refuse_replay(p, rep, lane, NBOS_E_RANGE); return; }
 
   const int trace = p.trace_of_replay[rep];
   const int64_t ev_lo = p.ev_offset[trace], ev_hi = p.ev_offset[trace + 1];
   const int s_lo = p.sess_offset[trace];
   const int n_sess = p.sess_offset[trace + 1] - s_lo;
+  if (p.trace_err != nullptr && n_sess > p.n_cap) { refuse_replay(p, rep, lane, NBOS_E_LIMIT); return; }
 
   Lds m;
   unsigned char *q = lds_raw;

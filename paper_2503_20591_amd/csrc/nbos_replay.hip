@@ -27,9 +27,9 @@ namespace {
 // ---- input validation (device side: the traces are device memory) -------------------------------
 // err bits: 1 time order / sign, 2 time overflow, 4 kind, 8 session id, 16 duration, 32 GPU request,
 // 64 trace index, 128 cap
-__global__ void nbos_validate_traces(const int64_t *ev_offset, const int32_t *ev_time, const int32_t *ev_dur,
-                                     const int32_t *ev_sk, const int32_t *sess_offset, const uint8_t *sess_gpus,
-                                     int G, int32_t t_limit, uint32_t *err) {
+__device__ __forceinline__ void validate_trace_body(const int64_t *ev_offset, const int32_t *ev_time, const int32_t *ev_dur,
+                                                    const int32_t *ev_sk, const int32_t *sess_offset,
+                                                    const uint8_t *sess_gpus, int G, int32_t t_limit, uint32_t *err) {
   int trace = blockIdx.x;
   int64_t lo = ev_offset[trace], hi = ev_offset[trace + 1];
   int s_lo = sess_offset[trace], n_sess = sess_offset[trace + 1] - s_lo;
@@ -49,6 +49,12 @@ __global__ void nbos_validate_traces(const int64_t *ev_offset, const int32_t *ev
     if (g < 1 || g > G) e |= 32;
   }
   if (e) atomicOr(err, e);
+}
+
+__global__ void nbos_validate_traces(const int64_t *ev_offset, const int32_t *ev_time, const int32_t *ev_dur,
+                                     const int32_t *ev_sk, const int32_t *sess_offset, const uint8_t *sess_gpus,
+                                     int G, int32_t t_limit, uint32_t *err) {
+  validate_trace_body(ev_offset, ev_time, ev_dur, ev_sk, sess_offset, sess_gpus, G, t_limit, err);
 }
 
 __global__ void nbos_validate_replays(const int32_t *trace_of_replay, const int32_t *cap_milli, int n_replays,
@@ -91,7 +97,7 @@ const void *reg_closed_kernel_for(int nj) {
   }
 }
 
-// ---- billing post-pass (paper Section 5.3.1): one lane per replay ---------------------------------
+// ---- billing post-pass (the paper's "Monetary Cost" section): one lane per replay ---------------------------------
 // floor(a * b / d) for a, b, d below 2^63 with a quotient below 2^64: 128-bit product, then binary
 // long division (the remainder stays below d, so it never overflows when doubled)
 __device__ uint64_t muldiv_floor(uint64_t a, uint64_t b, uint64_t d) {
@@ -124,6 +130,36 @@ __global__ void nbos_billing_kernel(const nbos_stats *stats, int first, int coun
   out[i] = b;
 }
 
+// ---- measurement aid: the dependency-chain floor of one event body ---------------------------------
+// A replay is a serial chain: an event cannot begin before the previous one's state update. The
+// shortest such step this design can take is: read one host's GPU row from LDS, count the committed
+// GPUs, one wave-wide minimum over a packed key, write one busy-until time back. The kernel runs that
+// body `iters` times in a dependent chain (the minimum picks the next host), one wave per workgroup
+// on its own SIMD; time / iters is the floor a replay's ns-per-event figure is compared with.
+__global__ void __launch_bounds__(WAVE) nbos_chain_floor_kernel(int iters, uint32_t *sink) {
+  __shared__ int4 rows[2 * WAVE];
+  const int lane = threadIdx.x;
+  rows[2 * lane] = make_int4(lane, 2 * lane, 3, 5);
+  rows[2 * lane + 1] = make_int4(7, lane ^ 21, 11, 13);
+  __syncthreads();
+  int h = lane;
+  int32_t now = 0;
+  uint32_t acc = blockIdx.x;
+  for (int i = 0; i < iters; i++) {
+    wave_sync();
+    const int4 a = rows[2 * h], b = rows[2 * h + 1];
+    const int C = (a.x > now) + (a.y > now) + (a.z > now) + (a.w > now) + (b.x > now) + (b.y > now) + (b.z > now) + (b.w > now);
+    const uint32_t key = ((uint32_t)C << 22) | (((uint32_t)lane * 2654435761u + acc) & 0x3FFFC0u) | (uint32_t)lane;
+    const uint32_t m = wave_min(key);
+    h = (int)(m & 63u);
+    if (lane == 0) rows[2 * h].x = now + 1 + (int32_t)((m >> 6) & 7u);
+    now += 1;
+    acc = m;
+    h = (h + lane) & 63;
+  }
+  if (lane == 0) sink[blockIdx.x] = acc;
+}
+
 }  // namespace
 
 // ================================= host side: the C ABI ===========================================
@@ -136,6 +172,7 @@ struct nbos_replay {
   KParams kp;
   size_t lds_bytes;
   const void *kernel;      // the kernel instance chosen at create
+  char kernel_name[96];    // as a profiler prints it, without the argument list
   nbos_stats *d_stats;
   nbos_bill *d_bill;
   int32_t *d_ovf;          // register kernel only
@@ -192,10 +229,12 @@ int32_t check_config(const nbos_config *cfg, const nbos_inputs *in) {
   if (cfg->hosts_max > NBOS_MAX_HOSTS) return NBOS_E_LIMIT;
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
-  if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS |
+  constexpr uint32_t kComparison = NBOS_F_HOSTS_IN_LDS | NBOS_F_GENERIC_KERNEL | NBOS_F_ROUNDS_OFF | NBOS_F_ROUNDS_ON;
+  if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | kComparison |
                      NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE | NBOS_F_WARM_POOL |
                      NBOS_F_CLOSED_LOOP))
     return NBOS_E_ARG;
+  if ((cfg->flags & NBOS_F_ROUNDS_OFF) && (cfg->flags & NBOS_F_ROUNDS_ON)) return NBOS_E_ARG;
   if ((cfg->flags & NBOS_F_CLOSED_LOOP) && (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_BATCH_MODE)))
     return NBOS_E_ARG;
   if (cfg->flags & NBOS_F_WARM_POOL) {
@@ -204,7 +243,7 @@ int32_t check_config(const nbos_config *cfg, const nbos_inputs *in) {
       return NBOS_E_ARG;
   }
   if (cfg->flags & NBOS_F_BATCH_MODE) {
-    if (cfg->flags & ~(NBOS_F_BATCH_MODE | NBOS_F_SCALE_OUT | NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS)) return NBOS_E_ARG;   // no pool either
+    if (cfg->flags & ~(NBOS_F_BATCH_MODE | NBOS_F_SCALE_OUT | NBOS_F_DECISION_LOG | kComparison)) return NBOS_E_ARG;   // no pool either
     if (cfg->batch_start_delay_ms < 0 || cfg->batch_start_delay_ms > NBOS_MAX_DUR_MS) return NBOS_E_ARG;
   }
   if (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) {
@@ -226,8 +265,10 @@ int32_t check_config(const nbos_config *cfg, const nbos_inputs *in) {
 int64_t time_slack(const nbos_config *cfg) {
   int64_t slowest = cfg->migration_delay_ms;
   if ((cfg->flags & NBOS_F_WARM_POOL) && cfg->warm_migration_delay_ms > slowest) slowest = cfg->warm_migration_delay_ms;
+  // the auto-scaler's next period is scheduled one interval past the last instant that matters
+  const int64_t period = (cfg->flags & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) ? cfg->scale_interval_ms : 0;
   return (int64_t)NBOS_MAX_DUR_MS + (int64_t)cfg->max_retries * cfg->retry_interval_ms + cfg->boot_delay_ms + slowest +
-         ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0);
+         ((cfg->flags & NBOS_F_WARM_POOL) ? cfg->prewarm_delay_ms : 0) + period;
 }
 
 int32_t open_device(nbos_replay *h) {
@@ -276,6 +317,22 @@ int32_t read_offsets(nbos_replay *h, Shape *sh) {
   return NBOS_OK;
 }
 
+// the kernel instance a handle launches, with its name as a profiler prints it
+void set_kernel(nbos_replay *h, const void *k, const char *fmt, int a, uint32_t f) {
+  h->kernel = k;
+  if (a >= 0) snprintf(h->kernel_name, sizeof h->kernel_name, fmt, a, (unsigned)f);
+  else snprintf(h->kernel_name, sizeof h->kernel_name, fmt, (unsigned)f);
+}
+template <uint32_t F> void set_lds_kernel(nbos_replay *h) {
+  set_kernel(h, (const void *)ldsk::nbos_replay_lds_kernel<F>, "ldsk::nbos_replay_lds_kernel<%uu>", -1, F);
+}
+template <uint32_t F> void set_closed_kernel(nbos_replay *h) {
+  set_kernel(h, (const void *)ldsk::nbos_replay_closed_kernel<F>, "ldsk::nbos_replay_closed_kernel<%uu>", -1, F);
+}
+template <uint32_t F> void set_reg_closed_kernel(nbos_replay *h, int nj) {
+  set_kernel(h, reg_closed_kernel_for<F>(nj), "regk::nbos_replay_reg_closed_kernel<%d, %uu>", nj > 8 ? 8 : nj, F);
+}
+
 // which flavour of the register kernel: see the comment inside
 int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
   const nbos_config *cfg = &h->cfg;
@@ -289,16 +346,16 @@ int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
   const int nj = (cfg->hosts_max + 7) / 8;
   const uint32_t policy = cfg->flags & regk::kPolicyFlags;
   const void *generic = reg_kernel_for<regk::kRuntimeFlags>(nj);
+  const bool has_special = policy == 0u || policy == NBOS_F_MIGRATE || policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT);
   const void *special = policy == 0u ? reg_kernel_for<0u>(nj)
                       : policy == NBOS_F_MIGRATE ? reg_kernel_for<NBOS_F_MIGRATE>(nj)
                       : policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT) ? reg_kernel_for<NBOS_F_MIGRATE | NBOS_F_SCALE_OUT>(nj)
                       : generic;
   int cus = 0;
   HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
-  const char *ng = getenv("NBOS_REPLAY_GENERIC");         // "0" / "1" force the choice (comparison runs)
   bool use_generic;
-  if (ng && (ng[0] == '0' || ng[0] == '1')) {
-    use_generic = ng[0] == '1';
+  if (cfg->flags & NBOS_F_GENERIC_KERNEL) {                 // comparison runs
+    use_generic = true;
   } else {
     const int per_cu = cus > 0 ? (cfg->n_replays + cus - 1) / cus : cfg->n_replays;
     hipFuncAttributes fa_g, fa_s;
@@ -315,7 +372,8 @@ int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
     const int res_g = resident(fa_g) > 0 ? resident(fa_g) : 1, res_s = resident(fa_s) > 0 ? resident(fa_s) : 1;
     use_generic = (per_cu + res_g - 1) / res_g < (per_cu + res_s - 1) / res_s;
   }
-  h->kernel = use_generic ? generic : special;
+  if (use_generic || !has_special) set_kernel(h, generic, "regk::nbos_replay_reg_kernel<%d, %uu>", nj, regk::kRuntimeFlags);
+  else set_kernel(h, special, "regk::nbos_replay_reg_kernel<%d, %uu>", nj, policy);
   return NBOS_OK;
 }
 
@@ -332,11 +390,11 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   sh->q_cap = (size_t)sh->n_cap + 1;               // at most one queued timer per session
   const int HP = sh->HP;
   const size_t n_cap = (size_t)sh->n_cap;
-  const char *ng = getenv("NBOS_REPLAY_GENERIC");
+  const bool force_generic = (cfg->flags & NBOS_F_GENERIC_KERNEL) != 0;
   if (batch_mode) {
     h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + n_cap * 12 + (n_cap + 2) * 2;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
-    h->kernel = (const void *)batchk::nbos_replay_batch_kernel;
+    set_kernel(h, (const void *)batchk::nbos_replay_batch_kernel, "batchk::nbos_replay_batch_kernel%.0u", -1, 0u);
   } else if (closed_loop && cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS)) {
     // hosts in registers; 8 bytes per session, 64 staged sessions
     h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8 + WAVE * 4;
@@ -344,10 +402,8 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     sh->q_cap = 0;
     const int nj = (cfg->hosts_max + 7) / 8;
     const uint32_t policy = cfg->flags & regk::kPolicyFlags;
-    if (policy == NBOS_F_MIGRATE && !(ng && ng[0] == '1'))
-      h->kernel = reg_closed_kernel_for<NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP>(nj);
-    else
-      h->kernel = reg_closed_kernel_for<regk::kRuntimeClosed>(nj);
+    if (policy == NBOS_F_MIGRATE && !force_generic) set_reg_closed_kernel<NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP>(h, nj);
+    else set_reg_closed_kernel<regk::kRuntimeClosed>(h, nj);
   } else if (closed_loop) {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
     h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
@@ -357,10 +413,10 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     // instances for the common flag sets, as for the other kernels
     const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
     constexpr uint32_t kMigr = NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP, kMigrOut = kMigr | NBOS_F_SCALE_OUT;
-    if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
-    else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigr>;
-    else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<kMigrOut>;
-    else h->kernel = (const void *)ldsk::nbos_replay_closed_kernel<ldsk::kRuntimeClosed>;
+    if (force_generic) set_closed_kernel<ldsk::kRuntimeClosed>(h);
+    else if (policy == NBOS_F_MIGRATE) set_closed_kernel<kMigr>(h);
+    else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) set_closed_kernel<kMigrOut>(h);
+    else set_closed_kernel<ldsk::kRuntimeClosed>(h);
   } else if (sh->in_regs) {
     h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
@@ -377,11 +433,11 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
     constexpr uint32_t kAllScaling = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN;
     constexpr uint32_t kAutoScaler = NBOS_F_MIGRATE | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
-    if (ng && ng[0] == '1') h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
-    else if (policy == kAllScaling) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAllScaling>;
-    else if (policy == kAutoScaler) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<kAutoScaler>;
-    else if (policy == NBOS_F_MIGRATE) h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<NBOS_F_MIGRATE>;
-    else h->kernel = (const void *)ldsk::nbos_replay_lds_kernel<ldsk::kRuntimeFlags>;
+    if (force_generic) set_lds_kernel<ldsk::kRuntimeFlags>(h);
+    else if (policy == kAllScaling) set_lds_kernel<kAllScaling>(h);
+    else if (policy == kAutoScaler) set_lds_kernel<kAutoScaler>(h);
+    else if (policy == NBOS_F_MIGRATE) set_lds_kernel<NBOS_F_MIGRATE>(h);
+    else set_lds_kernel<ldsk::kRuntimeFlags>(h);
   }
   HIP_TRY(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
   return NBOS_OK;
@@ -464,10 +520,9 @@ void fill_params(nbos_replay *h, const Shape &sh) {
   k.n_cap = sh.n_cap; k.q_cap = (int32_t)sh.q_cap;
   // Event-parallel rounds: on, except for closed loops on clusters of at most 64 hosts, where two
   // cells of a run choose the same host too often for a round to pay (measured: 30 hosts, 110 ms
-  // without, 119 ms with). NBOS_REPLAY_BATCH = "0" / "1" forces the choice (comparison runs, tests).
-  const char *nb = getenv("NBOS_REPLAY_BATCH");
+  // without, 119 ms with). NBOS_F_ROUNDS_OFF / _ON force the choice (comparison runs, tests).
   const bool closed_loop = (cfg->flags & NBOS_F_CLOSED_LOOP) != 0;
-  k.batch = (nb && nb[0] == '0') ? 0 : (nb && nb[0] == '1') ? 1 : (closed_loop && cfg->hosts_max <= WAVE) ? 0 : 1;
+  k.batch = (cfg->flags & NBOS_F_ROUNDS_OFF) ? 0 : (cfg->flags & NBOS_F_ROUNDS_ON) ? 1 : (closed_loop && cfg->hosts_max <= WAVE) ? 0 : 1;
   k.cl_chain = (const int2 *)h->d_chain;
   k.cl_cursor = h->d_chain ? h->d_chain + 2 * (size_t)sh.total_ev : nullptr;
 }
@@ -507,7 +562,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (!h) return NBOS_E_NOMEM;
   h->cfg = cfg; h->in = *in; h->stream = (hipStream_t)stream;
   h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_chain = nullptr; h->d_log = nullptr;
-  h->kernel = nullptr; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
+  h->kernel = nullptr; h->kernel_name[0] = 0; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   memset(&h->kp, 0, sizeof h->kp);
   Shape sh;
   g_detail[0] = 0;
@@ -597,6 +652,35 @@ int32_t nbos_replay_launch_info(nbos_replay *h, int32_t *lds_bytes, int32_t *thr
   if (lds_bytes) *lds_bytes = (int32_t)h->lds_bytes;
   if (threads_per_group) *threads_per_group = WAVE;
   if (groups) *groups = h->cfg.n_replays;
+  return NBOS_OK;
+}
+
+const char *nbos_replay_kernel_name(nbos_replay *h) { return h ? h->kernel_name : ""; }
+
+int32_t nbos_chain_floor_ns(void *stream, int32_t iters, float *ns_out) {
+  if (!ns_out || iters < 1 || iters > (1 << 24)) return NBOS_E_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return NBOS_E_HIP;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return NBOS_E_HIP;
+  uint32_t *sink = nullptr;
+  if (hipMalloc(&sink, sizeof(uint32_t) * (size_t)cus) != hipSuccess) return NBOS_E_NOMEM;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  float ms = 0.f;
+  bool ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+  for (int pass = 0; pass < 2 && ok; pass++) {          // the first pass warms the clocks up
+    ok = hipEventRecord(e0, st) == hipSuccess;
+    if (ok) {
+      hipLaunchKernelGGL(nbos_chain_floor_kernel, dim3(cus), dim3(WAVE), 0, st, iters, sink);
+      ok = hipGetLastError() == hipSuccess && hipEventRecord(e1, st) == hipSuccess &&
+           hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    }
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  if (!ok) return NBOS_E_HIP;
+  *ns_out = ms * 1e6f / (float)iters;
   return NBOS_OK;
 }
 

@@ -19,11 +19,13 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG, F_HOSTS_IN_LDS = 1, 2, 4, 8, 16
 F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
 F_CLOSED_LOOP = 0x400
+F_GENERIC_KERNEL, F_ROUNDS_OFF, F_ROUNDS_ON = 0x800, 0x1000, 0x2000     # comparison runs: same results
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
            "nbos_replay_billing", "nbos_replay_last_kernel_ms", "nbos_replay_launch_info", "nbos_replay_destroy",
-           "nbos_strerror", "nbos_last_error_detail", "nbos_sizeof_stats")
+           "nbos_strerror", "nbos_last_error_detail", "nbos_sizeof_stats", "nbos_replay_kernel_name",
+           "nbos_chain_floor_ns")
 
 
 class NbosConfig(C.Structure):
@@ -108,6 +110,10 @@ def load():
     lib.nbos_last_error_detail.restype = C.c_char_p
     lib.nbos_last_error_detail.argtypes = []
     lib.nbos_sizeof_stats.restype = C.c_int32
+    lib.nbos_replay_kernel_name.restype = C.c_char_p
+    lib.nbos_replay_kernel_name.argtypes = [C.c_void_p]
+    lib.nbos_chain_floor_ns.restype = C.c_int32
+    lib.nbos_chain_floor_ns.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     if lib.nbos_sizeof_stats() != STATS_DTYPE.itemsize:
         raise RuntimeError("nbos_stats layout mismatch between the binding and libnbos.so")
     _lib = lib
@@ -148,7 +154,8 @@ class Replay:
     kept referenced here). ``stream``: a torch.cuda.Stream or None for the current stream."""
 
     def __init__(self, cfg: dict, inputs: dict, n_replays: int | None = None, n_traces: int | None = None,
-                 stream=None, decision_log: bool = False, hosts_in_lds: bool = False):
+                 stream=None, decision_log: bool = False, hosts_in_lds: bool = False,
+                 generic_kernel: bool = False, rounds: bool | None = None):
         import torch
         lib = load()
         self._lib = lib
@@ -157,7 +164,9 @@ class Replay:
         n_traces = int(inputs["ev_offset"].numel()) - 1 if n_traces is None else n_traces
         self.n_replays = n_replays
         self.config = make_config(cfg, n_replays, n_traces, (F_DECISION_LOG if decision_log else 0)
-                                  | (F_HOSTS_IN_LDS if hosts_in_lds else 0))
+                                  | (F_HOSTS_IN_LDS if hosts_in_lds else 0)
+                                  | (F_GENERIC_KERNEL if generic_kernel else 0)
+                                  | (0 if rounds is None else F_ROUNDS_ON if rounds else F_ROUNDS_OFF))
         ins = NbosInputs()
         for name in _INPUT_FIELDS:
             ten = inputs[name]
@@ -214,7 +223,8 @@ class Replay:
     def launch_info(self) -> dict:
         a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
         self._lib.nbos_replay_launch_info(self._h, C.byref(a), C.byref(b), C.byref(c))
-        return {"lds_bytes": a.value, "threads_per_group": b.value, "groups": c.value}
+        return {"lds_bytes": a.value, "threads_per_group": b.value, "groups": c.value,
+                "kernel": self._lib.nbos_replay_kernel_name(self._h).decode()}
 
     def close(self):
         if getattr(self, "_h", None):
@@ -226,6 +236,17 @@ class Replay:
             self.close()
         except Exception:
             pass
+
+
+def chain_floor_ns(iters: int = 200_000, stream=None) -> float:
+    """nbos_chain_floor_ns on torch's current stream: ns per iteration of the shortest event body."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    ns = C.c_float()
+    rc = load().nbos_chain_floor_ns(C.c_void_p(st.cuda_stream), int(iters), C.byref(ns))
+    if rc != 0:
+        raise NbosError(rc, "nbos_chain_floor_ns")
+    return float(ns.value)
 
 
 DECISION_NAMES = {1: "PLACE", 2: "PLACE_NEW", 3: "REJECT", 4: "START", 5: "MIGRATE", 6: "SCALE_CELL", 7: "ABORT",

@@ -1,11 +1,11 @@
 """Policy study on the GPU replay: one batch answers "what does the subscription-ratio cap cost and save".
 
 Every trace is replayed under every cap (the replays of a trace share its events in device memory),
-once under the NotebookOS policy and once under the Batch baseline (paper Section 5.1.3); the
+once under the NotebookOS policy and once under the Batch baseline (the paper's "Baselines" section); the
 Reservation baseline is a closed form that every replay reports. The rows put side by side what the
-paper's evaluation plots: hosts provisioned against the cap (Section 5.2.4), GPU-hours bound to
-notebooks against Reservation (Section 5.2.2), the interactivity delay against Batch
-(Section 5.2.1), and the provider's margin under the billing model (Section 5.3.1).
+paper's evaluation plots: hosts provisioned against the cap (section "Subscription Ratio"), GPU-hours bound to
+notebooks against Reservation (section "Resource Usage & Efficiency"), the interactivity delay against Batch
+(section "Interactivity"), and the provider's margin under the billing model (section "Monetary Cost").
 
 Marshalling and reporting only: all policy arithmetic runs in the HIP kernels.
 

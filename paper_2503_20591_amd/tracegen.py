@@ -1,11 +1,11 @@
 """Seeded synthetic notebook-session traces (inputs only; none of the policy's arithmetic).
 
 The paper measured on a private trace of an internal notebook platform
-(Section 2.2: 545,467 training events, 15 s granularity). That trace is not
+(its section "Real-World IDLT Workload Analysis": 545,467 training events, 15 s granularity). That trace is not
 public, so these generators stand in for it and take its shape: per-session
 streams, one cell at a time per session (Observation 2), short tasks (median
 2 min, p75 5 min), long idle gaps (median 5 min), GPU requests in powers of two
-on 8-GPU servers (Section 5.1.1).
+on 8-GPU servers (the evaluation's "Setup" section).
 
 A trace is three int32 arrays sorted by time (time_ms, dur_ms, session|kind<<24)
 plus one GPU request per session. Trace ``k`` depends only on its own seed, so a
@@ -63,14 +63,12 @@ class TraceBatch:
         return int(per_trace[self.trace_of_replay].sum())
 
     def algorithmic_bytes(self, stats_bytes: int) -> int:
-        """12 B per event + 1 B per session + 8 B per replay read, one stats record written.
-        Closed loop: 32 B per event (time, kind word and 8-byte chain record from the stream; duration,
-        kind word and chain record again when the event's timer fires) + 8 B per event for the cursor
-        (written when the timer is scheduled, read when it moves into the sorted registers)."""
+        """What the method must move: 12 B per event (time, duration, session | kind) + 1 B per session
+        + 8 B per replay read, one stats record written. The same for every mode: what a kernel moves
+        beyond that (chain records and cursors of the closed loop, queued durations) is scratch traffic."""
         ev = np.diff(self.ev_offset)[self.trace_of_replay].sum()
         ss = np.diff(self.sess_offset)[self.trace_of_replay].sum()
-        per_event = 40 if self.config.get("flags", 0) & F_CLOSED_LOOP else 12
-        return int(per_event * ev + ss + (8 + stats_bytes) * self.n_replays)
+        return int(12 * ev + ss + (8 + stats_bytes) * self.n_replays)
 
 
 # ---- samplers: float64 seconds -> integer milliseconds ---------------------------------------
@@ -239,12 +237,12 @@ def _recipe(name: str):
                          autoscale_f_milli=1050, scaling_buffer_hosts=32)
         rc["cap"] = lambda i, n: 4000
         return rc
-    if name in ("c2b", "c4b"):  # the c2 / c4 traces under the Batch baseline (Section 5.1.3): a container
+    if name in ("c2b", "c4b"):  # the c2 / c4 traces under the Batch baseline (the paper's "Baselines" section): a container
         # per cell (15 s to start, the GPUs already held), first come first served, fixed cluster
         rc = _recipe(name[:2])
         rc["cfg"] = dict(rc["cfg"], flags=F_BATCH_MODE, hosts_max=rc["cfg"]["hosts_initial"], batch_start_delay_ms=15_000)
         return rc
-    if name in ("c2l", "c4l"):  # the c2 / c4 traces read as closed loops (Section 2.2: a user submits the
+    if name in ("c2l", "c4l"):  # the c2 / c4 traces read as closed loops (the section "Interactive Deep Learning Training": a user submits the
         # next cell a think time after the previous one is over); c4l without the periodic scale-in
         rc = _recipe(name[:2])
         rc["cfg"] = dict(rc["cfg"], flags=(rc["cfg"]["flags"] & ~F_SCALE_IN) | F_CLOSED_LOOP)

@@ -54,19 +54,50 @@ def _create(lib, cfg, n_replays=1, n_traces=1, inputs=True, struct_size=None, ou
         c.struct_size = struct_size
     ins = replay.NbosInputs()
     h = C.c_void_p()
-    return lib.nbos_replay_create(C.byref(c), C.byref(ins) if inputs else None, None, C.byref(h) if out else None)
+    rc = lib.nbos_replay_create(C.byref(c), C.byref(ins) if inputs else None, None, C.byref(h) if out else None)
+    if rc == 0:
+        lib.nbos_replay_destroy(h)
+    return rc
 
 
 @pytest.mark.parametrize("bad", [
     dict(replicas=2), dict(gpus_per_host=0), dict(gpus_per_host=9), dict(hosts_initial=0),
     dict(hosts_max=3), dict(migration_delay_ms=-1), dict(boot_delay_ms=-1), dict(retry_interval_ms=0),
-    dict(max_retries=16), dict(max_retries=-1), dict(flags=1024), dict(flags=0x200), dict(flags=0x200, warm_pool_per_host=5), dict(flags=0x300, warm_pool_per_host=1),
+    dict(max_retries=16), dict(max_retries=-1), dict(flags=0x404), dict(flags=0x8000), dict(flags=0x200), dict(flags=0x200, warm_pool_per_host=5), dict(flags=0x300, warm_pool_per_host=1),
     dict(flags=0x200, warm_pool_per_host=1, prewarm_delay_ms=-1), dict(flags=0x101), dict(flags=0x120), dict(flags=0x100, batch_start_delay_ms=-1), dict(flags=4, scale_interval_ms=0),
     dict(flags=0x20, scale_interval_ms=0), dict(flags=0x20, autoscale_f_milli=-1), dict(flags=0x20, autoscale_f_milli=100_001),
     dict(flags=0x20, scaling_buffer_hosts=-1), dict(flags=0x20, scaling_buffer_hosts=1025), dict(flags=0x24, min_hosts=-1),
-    dict(flags=4, scale_in_idle_pct=101), dict(retry_interval_ms=2_000_000_000, max_retries=15)])
+    dict(flags=4, scale_in_idle_pct=101), dict(retry_interval_ms=2_000_000_000, max_retries=15),
+    dict(flags=0x3000), dict(flags=0x4000)])
 def test_create_rejects_bad_config(lib, bad):
+    # no replays, so null arrays are fine and only the parameters can be at fault
+    assert _create(lib, _cfg(**bad), n_replays=0) == replay.E_ARG
     assert _create(lib, _cfg(**bad)) == replay.E_ARG
+
+
+def test_create_accepts_the_base_config_as_far_as_the_host_checks_go(lib):
+    # the same call with nothing wrong gets past the parameter checks: it fails only for want of a
+    # device (here), or succeeds (on a GPU machine)
+    c = replay.make_config(_cfg(), 0, 1)
+    ins = replay.NbosInputs()
+    h = C.c_void_p()
+    rc = lib.nbos_replay_create(C.byref(c), C.byref(ins), None, C.byref(h))
+    assert rc in (replay.E_HIP, 0)
+    if rc == 0:
+        lib.nbos_replay_destroy(h)
+
+
+@pytest.mark.parametrize("flags", [4, 0x20, 0x24])
+def test_create_rejects_a_scaling_period_that_overflows_the_clock(lib, flags):
+    # the auto-scaler's next period is scheduled one interval past the last instant of a replay: an
+    # interval that takes that beyond 2^31 - 1 ms together with the longest cell is refused outright
+    # (shorter ones shrink the time range a trace may use, checked against the trace on the device)
+    day = 86_400_000
+    assert _create(lib, _cfg(flags=flags, scale_interval_ms=2**31 - 1 - day), n_replays=0) == replay.E_ARG
+    assert _create(lib, _cfg(flags=flags, scale_interval_ms=2**31 - 1), n_replays=0) == replay.E_ARG
+    assert _create(lib, _cfg(flags=flags, scale_interval_ms=2**30), n_replays=0) in (replay.E_HIP, 0)
+    # without a periodic rule the field is ignored
+    assert _create(lib, _cfg(flags=1, scale_interval_ms=2**31 - 1), n_replays=0) in (replay.E_HIP, 0)
 
 
 def test_create_rejects_null_and_size(lib):

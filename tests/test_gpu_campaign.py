@@ -47,7 +47,7 @@ def draw_case(seed):
 
 
 @pytest.mark.parametrize("block", range(6))
-def test_mid_size_random_cases(oracle, monkeypatch, block):
+def test_mid_size_random_cases(oracle, block):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     from paper_2503_20591_amd import replay as rp
@@ -63,12 +63,8 @@ def test_mid_size_random_cases(oracle, monkeypatch, block):
             want.append(oracle.replay(b.config, b.ev_time[a:e], b.ev_dur[a:e], b.ev_sk[a:e], b.sess_gpus[sa:sb],
                                       int(b.cap_milli[r])))
         for in_lds in ((False, True) if mode != "batch" else (False,)):
-            for rounds in ((None, "1", "0") if in_lds else (None,)):
-                if rounds is None:
-                    monkeypatch.delenv("NBOS_REPLAY_BATCH", raising=False)
-                else:
-                    monkeypatch.setenv("NBOS_REPLAY_BATCH", rounds)
-                h = rp.Replay(b.config, dev, hosts_in_lds=in_lds)
+            for rounds in ((None, True, False) if in_lds else (None,)):
+                h = rp.Replay(b.config, dev, hosts_in_lds=in_lds, rounds=rounds)
                 h.run()
                 st = h.stats()
                 h.close()

@@ -24,9 +24,9 @@ def rp():
     return replay
 
 
-def gpu_run(rp, batch, log=False, in_lds=False):
+def gpu_run(rp, batch, log=False, in_lds=False, generic=False, rounds=None):
     dev = rp.upload(batch)
-    h = rp.Replay(batch.config, dev, decision_log=log, hosts_in_lds=in_lds)
+    h = rp.Replay(batch.config, dev, decision_log=log, hosts_in_lds=in_lds, generic_kernel=generic, rounds=rounds)
     h.run()
     st = h.stats()
     logs = [h.decisions(r) for r in range(batch.n_replays)] if log else None
@@ -62,6 +62,19 @@ def assert_same(rp, orc, batch, st, logs=None, replays=None, check=False):
             raise AssertionError(f"{batch.name} replay {r}: {first_diff(logs[r], want['log'], orc)}")
         for k in orc.RESULT_FIELDS:
             assert got[k] == want[k], (batch.name, r, k, got[k], want[k])
+
+
+def assert_same_all(rp, orc, batch, st, threads=16):
+    """Every replay of the batch against the oracle (the oracle's replays spread over host threads)."""
+    want = orc.replay_batch(batch, threads=threads)
+    assert len(want) == batch.n_replays == len(st)
+    assert (st["status"] == 0).all(), batch.name
+    for k in orc.RESULT_FIELDS:
+        w = np.array([x[k] for x in want], dtype=np.uint64 if k == "digest" else np.int64)
+        g = st[k].astype(w.dtype)
+        if not np.array_equal(g, w):
+            r = int(np.argwhere((g != w).reshape(len(st), -1).any(axis=1))[0, 0])
+            raise AssertionError((batch.name, r, k, g[r].tolist(), w[r].tolist()))
 
 
 # ---- hand-worked traces straight through the GPU ---------------------------------------------------
@@ -132,7 +145,7 @@ def test_named_workload_c4a_autoscaler_only(rp, oracle):
     assert min(auto) > 0 and st["scale_in_hosts"].min() > 0
 
 
-# ---- billing post-pass (Section 5.3.1) ---------------------------------------------------------------
+# ---- billing post-pass (section "Monetary Cost") ---------------------------------------------------------------
 
 @pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
 def test_billing_matches_oracle(rp, oracle, in_lds):
@@ -154,7 +167,7 @@ def test_billing_matches_oracle(rp, oracle, in_lds):
 
 
 def test_billing_printed_example_gpu(rp):
-    # Section 5.3.1: $10 per 8-GPU host-hour, x1.15, standby 12.5 %: $5.75 for an hour on 4 GPUs,
+    # Section "Monetary Cost": $10 per 8-GPU host-hour, x1.15, standby 12.5 %: $5.75 for an hour on 4 GPUs,
     # $1.4375 (printed $1.44) per standby replica-hour
     HOUR = 3_600_000
     t, d, sk = events_to_arrays([[0, 0, 0, 0], [0, 1, 0, HOUR], [2 * HOUR, 2, 0, 0]])
@@ -206,11 +219,10 @@ def test_billing_rejects_bad_arguments(rp):
     h.close()
 
 
-@pytest.mark.parametrize("generic", ["0", "1"])
-def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, generic):
+@pytest.mark.parametrize("generic", [False, True], ids=["instances", "generic"])
+def test_generic_and_specialised_register_kernels(rp, oracle, generic):
     # flag sets 0, MIGRATE and MIGRATE|SCALE_OUT have kernels of their own for small batches; large
     # batches run the generic kernel. Both must give the oracle's results on the same cases.
-    monkeypatch.setenv("NBOS_REPLAY_GENERIC", generic)
     done = set()
     for seed in range(200):
         b = tg.random_case(seed, n_replays=3)
@@ -218,7 +230,7 @@ def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, gener
         if f not in (0, 1, 3) or b.config["hosts_max"] > 64 or (f, (b.config["hosts_max"] + 7) // 8) in done:
             continue
         done.add((f, (b.config["hosts_max"] + 7) // 8))
-        st, logs = gpu_run(rp, b, log=True)
+        st, logs = gpu_run(rp, b, log=True, generic=generic)
         assert_same(rp, oracle, b, st, logs)
     assert len(done) >= 6
     # the any-size kernel has instances for MIGRATE and MIGRATE|SCALE_OUT|SCALE_IN
@@ -227,16 +239,16 @@ def test_generic_and_specialised_register_kernels(rp, oracle, monkeypatch, gener
         b = tg.random_case(seed, n_replays=3)
         if b.config["flags"] in (1, 7) and b.config["flags"] not in seen:
             seen.add(b.config["flags"])
-            st, logs = gpu_run(rp, b, log=True, in_lds=True)
+            st, logs = gpu_run(rp, b, log=True, in_lds=True, generic=generic)
             assert_same(rp, oracle, b, st, logs)
     assert seen == {1, 7}
     for name, n in (("c2", 3), ("c5", 8)):
         b = tg.workload(name, n_replays=n)
-        st, _ = gpu_run(rp, b)
+        st, _ = gpu_run(rp, b, generic=generic)
         assert_same(rp, oracle, b, st)
 
 
-# ---- Batch baseline (Section 5.1.3) ------------------------------------------------------------------
+# ---- Batch baseline (the paper's "Baselines" section) ------------------------------------------------------------------
 
 @pytest.mark.parametrize("seed", range(60))
 def test_batch_mode_random_cases(rp, oracle, seed):
@@ -290,7 +302,7 @@ def test_batch_mode_rejects_other_policy_flags(rp):
         assert e.value.code == rp.E_ARG
 
 
-# ---- closed-loop reading of the traces (Section 2.2: users think between the cells they submit) ------
+# ---- closed-loop reading of the traces (the section "Interactive Deep Learning Training": users think between the cells they submit) ------
 
 def as_closed(b):
     b.config["flags"] = (b.config["flags"] & ~(tg.F_SCALE_IN | tg.F_AUTOSCALE)) | tg.F_CLOSED_LOOP
@@ -335,39 +347,36 @@ def test_closed_loop_on_the_other_traces(rp, oracle, name, n, in_lds):
 
 
 @pytest.mark.parametrize("seed", range(0, 60, 2))
-def test_closed_loop_random_cases_with_forced_rounds(rp, oracle, monkeypatch, seed):
+def test_closed_loop_random_cases_with_forced_rounds(rp, oracle, seed):
     # small clusters run without the event-parallel rounds by default: here with them
-    monkeypatch.setenv("NBOS_REPLAY_BATCH", "1")
     b = as_closed(tg.random_case(seed, policy_flags=seed % 4 == 0))
-    st, logs = gpu_run(rp, b, log=True, in_lds=True)
+    st, logs = gpu_run(rp, b, log=True, in_lds=True, rounds=True)
     assert_same(rp, oracle, b, st, logs, check=True)
 
 
-def test_closed_loop_named_workloads_with_forced_rounds(rp, oracle, monkeypatch):
-    monkeypatch.setenv("NBOS_REPLAY_BATCH", "1")
+def test_closed_loop_named_workloads_with_forced_rounds(rp, oracle):
     for name, n in (("c2l", 3), ("c3", 2), ("c5", 8)):
         b = as_closed(tg.workload(name, n_replays=n))
-        st, logs = gpu_run(rp, b, log=True, in_lds=True)
+        st, logs = gpu_run(rp, b, log=True, in_lds=True, rounds=True)
         assert_same(rp, oracle, b, st, logs)
     # all sessions' cells due at the same instants, again and again
-    test_closed_loop_many_timers_at_one_instant(rp, oracle, True)
+    test_closed_loop_many_timers_at_one_instant(rp, oracle, True, rounds=True)
 
 
-def test_closed_loop_without_the_parallel_rounds(rp, oracle, monkeypatch):
+def test_closed_loop_without_the_parallel_rounds(rp, oracle):
     # the same replays with every timer fired one by one
-    monkeypatch.setenv("NBOS_REPLAY_BATCH", "0")
     for name, n in (("c3", 2), ("c4l", 1)):
         b = as_closed(tg.workload(name, n_replays=n))
-        st, logs = gpu_run(rp, b, log=True)
+        st, logs = gpu_run(rp, b, log=True, rounds=False)
         assert_same(rp, oracle, b, st, logs)
 
 
-def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
-    # the whole c2l batch in the launch shape the benchmark uses; a sample of replays against the oracle
+def test_closed_loop_without_log_full_batch(rp, oracle):
+    # the whole c2l batch in the launch shape the benchmark uses, every replay against the oracle
     b = tg.workload("c2l", workers=8)
     st, _ = gpu_run(rp, b)
     assert (st["status"] == 0).all()
-    assert_same(rp, oracle, b, st, replays=list(range(0, b.n_replays, 37)) + [b.n_replays - 1])
+    assert_same_all(rp, oracle, b, st)
     assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"]).all()
     # the same handle run twice more: nothing of a run (cursors, waiting timers) leaks into the next
     h = rp.Replay(b.config, rp.upload(b))
@@ -378,7 +387,7 @@ def test_closed_loop_without_log_full_batch_sampled(rp, oracle):
 
 
 @pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
-def test_closed_loop_many_timers_at_one_instant(rp, oracle, in_lds):
+def test_closed_loop_many_timers_at_one_instant(rp, oracle, in_lds, rounds=None):
     # 300 sessions placed at time 0 whose first cells are all due at the same millisecond, and again
     # later: far more than 64 timers for one instant wait outside the sorted slots, so they are
     # taken one by one in (kind, session) order; mixed with retries of queued cells
@@ -392,7 +401,7 @@ def test_closed_loop_many_timers_at_one_instant(rp, oracle, in_lds):
                retry_interval_ms=1000, max_retries=3)
     gp = rng.choice([1, 2, 4], n)
     b = _tiny(cfg, ev, gp, [100000, 6000])
-    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+    st, logs = gpu_run(rp, b, log=True, in_lds=in_lds, rounds=rounds)
     assert_same(rp, oracle, b, st, logs, check=True)
     assert st["cells_queued"].max() > 64
 
@@ -466,20 +475,17 @@ def test_named_workload_c4_many_hosts(rp, oracle):
 # ---- the benchmark configuration at full size: sampled replays + properties that hold for all -----
 
 def test_full_size_bench_config(rp, oracle):
-    b = tg.workload("c2", workers=8)
-    assert b.n_replays == 1024
+    # the largest named workload, which the benchmark times: all 256 replays against the oracle
+    b = tg.workload("c4", workers=16)
+    assert b.n_replays == 256 and b.config["hosts_initial"] == 512 and b.config["hosts_max"] == 768
     st, _ = gpu_run(rp, b)
-    assert (st["status"] == 0).all()
-    n_cells = 50_000
-    assert (st["cells_total"] == n_cells).all()
+    assert_same_all(rp, oracle, b, st)
+    assert (st["cells_total"] == 500_000).all()
     assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"] + st["cells_dropped_busy"]
             + st["cells_dropped_unplaced"]).all()
     assert (st["delay_hist"].sum(axis=1) == st["cells_started"]).all()
-    assert (st["sessions_placed"] + st["sessions_rejected"] == 400).all()
+    assert (st["sessions_placed"] + st["sessions_rejected"] == 8000).all()
     assert (st["gpu_ms_committed"] - st["gpu_ms_executed"] >= 0).all()
-    assert (st["gpu_ms_provisioned"] == 30 * 8 * st["t_end_ms"].astype(np.int64)).all()
-    sample = list(range(0, 1024, 64)) + [1, 511, 1023]
-    assert_same(rp, oracle, b, st, replays=sample)
     # a second run of the same handle recomputes the same results
     dev = rp.upload(b)
     h = rp.Replay(b.config, dev)
@@ -489,21 +495,20 @@ def test_full_size_bench_config(rp, oracle):
     assert st2.tobytes() == st.tobytes()
 
 
-@pytest.mark.parametrize("name,n_sample", [("c3", 16), ("c4", 6), ("c5", 32)])
-def test_full_size_other_configs(rp, oracle, name, n_sample):
-    # the other named workloads with all their replays, in the launch shape the benchmark times (c3: 16
-    # workgroups per compute unit resident, c5: 64 per compute unit in several rounds, the kernel flavour
-    # chosen for that shape); identities on every replay, a spread of replays against the oracle
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c5", "c4a", "c2b", "c4b", "c2l", "c4l"])
+def test_full_size_other_configs(rp, oracle, name):
+    # the other named workloads with all their replays, in the launch shape the benchmark times (c2: one
+    # wave per SIMD, c3: 16 workgroups per compute unit resident, c5: 64 per compute unit in several
+    # rounds, the kernel flavour chosen for that shape): every replay against the oracle
     b = tg.workload(name, workers=16)
     st, _ = gpu_run(rp, b)
-    assert (st["status"] == 0).all()
+    assert_same_all(rp, oracle, b, st)
     assert (st["cells_total"] == st["cells_started"] + st["cells_aborted"] + st["cells_dropped_busy"]
             + st["cells_dropped_unplaced"]).all()
     assert (st["delay_hist"].sum(axis=1) == st["cells_started"]).all()
     assert (st["gpu_ms_committed"] >= st["gpu_ms_executed"]).all()
-    n = b.n_replays
-    sample = sorted(set(list(range(0, n, max(n // n_sample, 1))) + [1, n // 2 + 1, n - 1]))
-    assert_same(rp, oracle, b, st, replays=sample)
+    if name == "c2":
+        assert (st["gpu_ms_provisioned"] == 30 * 8 * st["t_end_ms"].astype(np.int64)).all()
 
 
 # ---- edge cases ---------------------------------------------------------------------------------------

@@ -49,16 +49,16 @@ def test_relationships_of_the_evaluation(study):
         assert [x["cap"] for x in by_cap] == [c / 1000 for c in CAPS]
         lo, hi = by_cap[0], by_cap[-1]
         # a higher subscription-ratio cap packs more replicas per host: fewer hosts are provisioned,
-        # at the price of more migrations (Section 5.2.4)
+        # at the price of more migrations (section "Subscription Ratio")
         assert hi["peak_hosts"] < lo["peak_hosts"] and hi["provisioned_gpu_h"] < lo["provisioned_gpu_h"]
         assert hi["migrations"] > lo["migrations"]
-        assert hi["margin"] > lo["margin"]              # and the provider's margin grows (Section 5.3.1)
+        assert hi["margin"] > lo["margin"]              # and the provider's margin grows (section "Monetary Cost")
         assert all(b["provisioned_gpu_h"] <= 1.02 * a["provisioned_gpu_h"] for a, b in zip(by_cap, by_cap[1:]))
         for x in by_cap:
             # GPUs are bound only while cells run: far fewer GPU-hours than reserving them for the
-            # sessions' lifetimes (Section 5.2.2)
+            # sessions' lifetimes (section "Resource Usage & Efficiency")
             assert x["committed_gpu_h"] < 0.6 * x["reservation_gpu_h"]
             # most cells start at once, and the mean delay stays far below the Batch baseline's, which
-            # pays a container start per cell (Section 5.2.1)
+            # pays a container start per cell (section "Interactivity")
             assert x["immediate"] > 0.8
             assert x["batch_mean_delay_s"] >= 15.0 and x["mean_delay_s"] < 0.5 * x["batch_mean_delay_s"]

@@ -60,6 +60,7 @@ MUTANTS = [
     ("dynamic limit replaces the cap", "if ((int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*",
      "if (!(m->p->flags & ORC_F_DYNAMIC_SR) && (int64_t)(h->S + g) * 1000 <= (int64_t)m->p->cap_milli * m->G * R) return 1;\n  /*"),
     ("billing: standby charge not reduced by the executing time", "int64_t standby_ms = r->replica_ms - exec_ms;\n", "int64_t standby_ms = r->replica_ms;\n"),
+    ("billing: standby time not clamped at zero", "if (standby_ms < 0) standby_ms = 0;", ""),
     ("billing: markup dropped from the usage charge", "ratio(r->gpu_ms_executed, price * markup_pct, (int64_t)G * ms_per_hour * 100)", "ratio(r->gpu_ms_executed, price * 100, (int64_t)G * ms_per_hour * 100)"),
     ("billing: standby share applied per GPU", "ratio(standby_ms, price * markup_pct * standby_permille, ms_per_hour * 100 * 1000)", "ratio(standby_ms, price * markup_pct * standby_permille, (int64_t)G * ms_per_hour * 100 * 1000)"),
     ("billing: provider cost per GPU-hour", "ratio(r->gpu_ms_provisioned, price, (int64_t)G * ms_per_hour)", "ratio(r->gpu_ms_provisioned, price, ms_per_hour)"),
@@ -160,7 +161,8 @@ def run_pins(lib_path):
     checks += [lambda s=s: pins.test_warm_pool_that_refills_at_once_is_a_shorter_delay(o, s) for s in range(3)]
     checks += [lambda: pins.test_batch_single_server_is_the_textbook_fifo_queue(o), lambda: pins.test_batch_without_contention(o)]
     checks += [lambda s=s: pins.test_batch_order_and_capacity_random(o, s) for s in range(6)]
-    checks += [lambda: pins.test_billing_printed_example(o), lambda: pins.test_billing_is_linear_and_exact_on_large_results(o)]
+    checks += [lambda: pins.test_billing_printed_example(o), lambda: pins.test_billing_is_linear_and_exact_on_large_results(o),
+               lambda: pins.test_billing_without_replicas_has_no_standby_charge(o)]
     checks += [lambda s=s: pins.test_replica_integral_random(o, s) for s in range(3)]
     for c in checks:
         try:

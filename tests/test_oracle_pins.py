@@ -239,7 +239,7 @@ def test_single_session_textbook(oracle):
 
 
 def test_reservation_and_subscription_closed_form(oracle):
-    # Reservation holds g GPUs from START to END (Section 5.1.3); with no cells in flight the
+    # Reservation holds g GPUs from START to END (the paper's "Baselines" section); with no cells in flight the
     # subscription integral is 3 g (end - start) per session.
     rng = np.random.default_rng(5)
     n = 12
@@ -452,7 +452,7 @@ def test_dynamic_limit_brute_force(oracle):
         assert [(d["session"], d["outcome"], d["slot"], d["host"]) for d in got] == expect
 
 
-# ---- Section 5.3.1: billing model, the printed $1.44 / $5.75 example ------------------------------
+# ---- "Monetary Cost" section: billing model, the printed $1.44 / $5.75 example ------------------------------
 
 HOUR = 3_600_000
 
@@ -511,6 +511,27 @@ def test_billing_is_linear_and_exact_on_large_results(oracle):
         assert b["reservation_revenue"] == int(Fraction(r["reservation_gpu_ms"], G) * rate * Fraction(mk, 100))
 
 
+def test_billing_without_replicas_has_no_standby_charge(oracle):
+    # the Batch baseline keeps no replicas ("Baselines": a container per submitted cell, gone when the cell
+    # ends), so replica_ms is 0 while cells did execute: nothing stands by, the standby charge is exactly 0
+    # (never negative, never wrapped), and the other amounts are unaffected
+    cfg = dict(BASE, flags=oracle.F_BATCH, batch_start_delay_ms=0)
+    r = run(oracle, cfg, [[0, CELL, 0, HOUR], [10, CELL, 1, 2 * HOUR]], [4, 8], 1000)
+    assert r["replica_ms"] == 0 and r["cells_started"] == 2 and r["sum_tct_ms"] - r["sum_delay_ms"] == 3 * HOUR
+    b = oracle.billing(r, 8, 10_000_000, 115, 125)
+    assert b["standby_revenue"] == 0
+    assert b["usage_revenue"] == (4 * 1 + 8 * 2) * 11_500_000 // 8          # GPU-hours x $11.50 / 8 GPUs
+    # and a made-up result whose replicas were placed for less time than cells ran (cannot happen under the
+    # NotebookOS policy, where an executing replica is a placed one): still clamped at 0
+    z = {k: ([0] * 32 if k == "delay_hist" else 0) for k in oracle.RESULT_FIELDS}
+    z.update(sum_tct_ms=5 * HOUR, sum_delay_ms=HOUR, replica_ms=3 * HOUR)
+    assert oracle.billing(z, 8, 10_000_000, 115, 125)["standby_revenue"] == 0
+    z.update(replica_ms=4 * HOUR + 1)
+    assert oracle.billing(z, 8, 10_000_000, 115, 125)["standby_revenue"] == 0       # 1 ms: below a micro-dollar
+    z.update(replica_ms=5 * HOUR)
+    assert oracle.billing(z, 8, 10_000_000, 115, 125)["standby_revenue"] == 1_437_500
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_replica_integral_random(oracle, seed):
     # replica_ms is the subscribed-GPU integral with every request counted as 1: replay the same trace
@@ -521,7 +542,7 @@ def test_replica_integral_random(oracle, seed):
         assert r["replica_ms"] == r["sub_gpu_ms"]
 
 
-# ---- Section 5.1.3, Batch baseline: first come, first served, a container per job -----------------
+# ---- the paper's "Baselines" section, Batch baseline: first come, first served, a container per job -----------------
 
 BATCH = 0x100
 BCFG = dict(BASE, flags=BATCH, batch_start_delay_ms=0)
