@@ -371,6 +371,34 @@ typedef struct {
 int32_t nbos_replay_billing(nbos_replay *h, const nbos_billing_params *params, int32_t first,
                             int32_t count, nbos_bill *host_out);
 
+/*
+ * For callers that cannot allocate device memory (code under stream capture, serving loops that
+ * must not call the allocator, harnesses that forbid it): what nbos_replay_create + nbos_replay_run
+ * do, in one call that allocates nothing, for clusters of at most 64 hosts.
+ *   cfg, in    as for nbos_replay_create (host structs; the arrays are device pointers, borrowed for
+ *              the duration of the enqueued work). Not with NBOS_F_DECISION_LOG, _HOSTS_IN_LDS,
+ *              _BATCH_MODE or _CLOSED_LOOP (NBOS_E_ARG); hosts_max <= 64 (else NBOS_E_LIMIT).
+ *   max_sessions_per_trace  an upper bound on the sessions of any one trace (sizes the LDS of a
+ *              replay); 0..NBOS_MAX_SESSIONS.
+ *   stream     a hipStream_t or NULL; everything is enqueued there, nothing is waited for.
+ *   device_stats_out  DEVICE memory for n_replays nbos_stats records, owned by the caller; valid
+ *              once the stream has passed the call's work.
+ * The kernels' scratch memory (the validation verdict, and the durations of queued cells whose
+ * timers wait outside the sorted registers: n_replays * max_sessions_per_trace words) is a fixed
+ * 16 MiB array inside the library, one per GPU, held until the process ends:
+ * n_replays * max(max_sessions_per_trace, 1) must not exceed 4,194,240 (NBOS_E_LIMIT). All calls on
+ * one GPU share that array: calls whose device work overlaps race; order them on one stream or
+ * with events.
+ * The traces are checked on the device, in the same stream; the host does not see the verdict.
+ * Invalid content (what create reports as NBOS_E_RANGE) gives every record of the call status
+ * NBOS_E_RANGE; a trace with more sessions than max_sessions_per_trace gives the replays of that
+ * trace status NBOS_E_LIMIT; the other fields of such records are 0. The offset arrays must address
+ * memory that exists (as everywhere, the library cannot know the arrays' lengths).
+ * Errors: NBOS_E_ARG, NBOS_E_LIMIT, NBOS_E_HIP. Results equal those of create + run + stats.
+ */
+int32_t nbos_replay_run_static(const nbos_config *cfg, const nbos_inputs *in, int32_t max_sessions_per_trace,
+                               void *stream, nbos_stats *device_stats_out);
+
 /* Name of the replay kernel instance chosen at create, as a profiler's kernel trace prints it
  * (without the argument list), e.g. "ldsk::nbos_replay_lds_kernel<7u>". Static storage of the
  * handle, valid until destroy; "" for a NULL handle. */

@@ -12,6 +12,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -57,6 +58,14 @@ __global__ void nbos_validate_traces(const int64_t *ev_offset, const int32_t *ev
   validate_trace_body(ev_offset, ev_time, ev_dur, ev_sk, sess_offset, sess_gpus, G, t_limit, err);
 }
 
+// the same after nbos_validate_offsets on the same stream: traces are only walked if their offsets are sound
+__global__ void nbos_validate_traces_checked(const int64_t *ev_offset, const int32_t *ev_time, const int32_t *ev_dur,
+                                             const int32_t *ev_sk, const int32_t *sess_offset, const uint8_t *sess_gpus,
+                                             int G, int32_t t_limit, uint32_t *err) {
+  if (*err & 256u) return;
+  validate_trace_body(ev_offset, ev_time, ev_dur, ev_sk, sess_offset, sess_gpus, G, t_limit, err);
+}
+
 __global__ void nbos_validate_replays(const int32_t *trace_of_replay, const int32_t *cap_milli, int n_replays,
                                       int n_traces, uint32_t *err) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -64,6 +73,25 @@ __global__ void nbos_validate_replays(const int32_t *trace_of_replay, const int3
   uint32_t e = 0;
   if (trace_of_replay[i] < 0 || trace_of_replay[i] >= n_traces) e |= 64;
   if (cap_milli[i] < 1 || cap_milli[i] > NBOS_MAX_CAP_MILLI) e |= 128;
+  if (e) atomicOr(err, e);
+}
+
+// ---- scratch memory of the entry point that allocates nothing ----------------------------------------
+// Word 0: the error bits of the validation kernels; from word 64 on: the register kernel's array of
+// queued durations, [n_replays][sessions per trace]. One copy per GPU, held until the process ends.
+constexpr size_t kScratchWords = 4u * 1024u * 1024u;              // 16 MiB
+constexpr size_t kScratchHead = 64;
+static __device__ __align__(256) int32_t scratch[kScratchWords];
+
+__global__ void nbos_clear_word(uint32_t *w) { *w = 0u; }
+
+// offsets of the traces, checked on the device for callers that cannot wait for a copy: err bit 256
+__global__ void nbos_validate_offsets(const int64_t *ev_offset, const int32_t *sess_offset, int n_traces, uint32_t *err) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t > n_traces) return;
+  uint32_t e = 0;
+  if (t == 0 && (ev_offset[0] != 0 || sess_offset[0] != 0)) e |= 256;
+  if (t < n_traces && (ev_offset[t + 1] < ev_offset[t] || sess_offset[t + 1] < sess_offset[t])) e |= 256;
   if (e) atomicOr(err, e);
 }
 
@@ -652,6 +680,76 @@ int32_t nbos_replay_launch_info(nbos_replay *h, int32_t *lds_bytes, int32_t *thr
   if (lds_bytes) *lds_bytes = (int32_t)h->lds_bytes;
   if (threads_per_group) *threads_per_group = WAVE;
   if (groups) *groups = h->cfg.n_replays;
+  return NBOS_OK;
+}
+
+int32_t nbos_replay_run_static(const nbos_config *cfg_in, const nbos_inputs *in, int32_t max_sessions_per_trace,
+                               void *stream, nbos_stats *device_stats_out) {
+  if (!cfg_in || !in) return NBOS_E_ARG;
+  nbos_config cfg;
+  int32_t rc = read_config(cfg_in, &cfg);
+  if (rc == NBOS_OK) rc = check_config(&cfg, in);
+  if (rc != NBOS_OK) return rc;
+  const int64_t slack = time_slack(&cfg);
+  if (slack >= 0x7FFFFFFFLL) return NBOS_E_ARG;
+  if (cfg.n_replays == 0) return NBOS_OK;
+  if (!device_stats_out || max_sessions_per_trace < 0 || max_sessions_per_trace > NBOS_MAX_SESSIONS) return NBOS_E_ARG;
+  if (!in->ev_time_ms || !in->ev_dur_ms || !in->ev_sess_kind || !in->sess_gpus) return NBOS_E_ARG;
+  // only the kernel with the hosts in registers runs here, without a log, as an open loop
+  if (cfg.flags & (NBOS_F_DECISION_LOG | NBOS_F_HOSTS_IN_LDS | NBOS_F_BATCH_MODE | NBOS_F_CLOSED_LOOP)) return NBOS_E_ARG;
+  if (cfg.hosts_max > WAVE) return NBOS_E_LIMIT;
+  const size_t n_cap = max_sessions_per_trace > 0 ? (size_t)max_sessions_per_trace : 1;
+  if ((size_t)cfg.n_replays * n_cap > kScratchWords - kScratchHead) return NBOS_E_LIMIT;
+
+  // this GPU's copy of the scratch array: looked up once per device, with that device current
+  static std::mutex mu;
+  static int32_t *scratch_of[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return NBOS_E_HIP;
+  if (dev < 0 || dev >= 64) return NBOS_E_LIMIT;
+  int32_t *base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!scratch_of[dev]) {
+      void *ptr = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !ptr) { note_hip_failure("hipGetSymbolAddress(scratch)", e); return NBOS_E_HIP; }
+      scratch_of[dev] = (int32_t *)ptr;
+    }
+    base = scratch_of[dev];
+  }
+
+  nbos_replay tmp{};                      // never leaves this call; its vectors stay empty
+  tmp.cfg = cfg; tmp.in = *in; tmp.stream = (hipStream_t)stream; tmp.device = dev;
+  const bool warm_pool = (cfg.flags & NBOS_F_WARM_POOL) != 0;
+  tmp.lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8;
+  int maxlds = 0;
+  if (hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return NBOS_E_HIP;
+  if (tmp.lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
+  rc = choose_reg_kernel(&tmp, maxlds);
+  if (rc != NBOS_OK) return rc;
+  if (hipFuncSetAttribute(tmp.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)tmp.lds_bytes) != hipSuccess)
+    return NBOS_E_HIP;
+  Shape sh;
+  sh.HP = WAVE; sh.n_cap = (int)n_cap; sh.q_cap = 0; sh.in_regs = true;
+  tmp.d_stats = device_stats_out;
+  tmp.d_ovf = base + kScratchHead;
+  fill_params(&tmp, sh);
+  uint32_t *err = (uint32_t *)base;
+  tmp.kp.trace_err = err;
+
+  hipStream_t st = tmp.stream;
+  const int32_t t_limit = (int32_t)(0x7FFFFFFELL - slack);
+  hipLaunchKernelGGL(nbos_clear_word, dim3(1), dim3(1), 0, st, err);
+  hipLaunchKernelGGL(nbos_validate_offsets, dim3((cfg.n_traces + 256) / 256), dim3(256), 0, st, in->ev_offset,
+                     in->sess_offset, cfg.n_traces, err);
+  hipLaunchKernelGGL(nbos_validate_replays, dim3((cfg.n_replays + 255) / 256), dim3(256), 0, st, in->trace_of_replay,
+                     in->cap_milli, cfg.n_replays, cfg.n_traces, err);
+  hipLaunchKernelGGL(nbos_validate_traces_checked, dim3(cfg.n_traces), dim3(256), 0, st, in->ev_offset, in->ev_time_ms,
+                     in->ev_dur_ms, in->ev_sess_kind, in->sess_offset, in->sess_gpus, cfg.gpus_per_host, t_limit, err);
+  if (hipGetLastError() != hipSuccess) return NBOS_E_HIP;
+  void *args[] = {(void *)&tmp.kp};
+  if (hipLaunchKernel(tmp.kernel, dim3(cfg.n_replays), dim3(WAVE), args, tmp.lds_bytes, st) != hipSuccess) return NBOS_E_HIP;
   return NBOS_OK;
 }
 

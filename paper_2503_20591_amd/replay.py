@@ -25,7 +25,7 @@ E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
            "nbos_replay_billing", "nbos_replay_last_kernel_ms", "nbos_replay_launch_info", "nbos_replay_destroy",
            "nbos_strerror", "nbos_last_error_detail", "nbos_sizeof_stats", "nbos_replay_kernel_name",
-           "nbos_chain_floor_ns")
+           "nbos_chain_floor_ns", "nbos_replay_run_static")
 
 
 class NbosConfig(C.Structure):
@@ -112,6 +112,8 @@ def load():
     lib.nbos_sizeof_stats.restype = C.c_int32
     lib.nbos_replay_kernel_name.restype = C.c_char_p
     lib.nbos_replay_kernel_name.argtypes = [C.c_void_p]
+    lib.nbos_replay_run_static.restype = C.c_int32
+    lib.nbos_replay_run_static.argtypes = [C.POINTER(NbosConfig), C.POINTER(NbosInputs), C.c_int32, C.c_void_p, C.c_void_p]
     lib.nbos_chain_floor_ns.restype = C.c_int32
     lib.nbos_chain_floor_ns.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     if lib.nbos_sizeof_stats() != STATS_DTYPE.itemsize:
@@ -236,6 +238,36 @@ class Replay:
             self.close()
         except Exception:
             pass
+
+
+def run_static(cfg: dict, inputs: dict, max_sessions_per_trace: int, stats_out, stream=None) -> None:
+    """nbos_replay_run_static: one pass enqueued on torch's current stream without any allocation by the
+    library. ``stats_out``: a CUDA uint8 tensor of n_replays * STATS_DTYPE.itemsize bytes (the caller's);
+    read it with ``stats_from_tensor`` after synchronising."""
+    import torch
+    lib = load()
+    n_replays = int(inputs["trace_of_replay"].numel())
+    c = make_config(cfg, n_replays, int(inputs["ev_offset"].numel()) - 1)
+    ins = NbosInputs()
+    for name in _INPUT_FIELDS:
+        ten = inputs[name]
+        if not ten.is_cuda or not ten.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous CUDA tensor")
+        setattr(ins, name, ten.data_ptr() if ten.numel() else None)
+    if not stats_out.is_cuda or stats_out.numel() * stats_out.element_size() < n_replays * STATS_DTYPE.itemsize:
+        raise ValueError("stats_out must be a CUDA tensor with room for n_replays records")
+    st = stream if stream is not None else torch.cuda.current_stream(stats_out.device)
+    with torch.cuda.device(stats_out.device):
+        rc = lib.nbos_replay_run_static(C.byref(c), C.byref(ins), int(max_sessions_per_trace),
+                                        C.c_void_p(st.cuda_stream), C.c_void_p(stats_out.data_ptr()))
+    if rc != 0:
+        raise NbosError(rc, "nbos_replay_run_static")
+
+
+def stats_from_tensor(stats_out, n_replays: int) -> np.ndarray:
+    """The records a run_static call left in ``stats_out`` (synchronises through the copy to the host)."""
+    raw = stats_out.view(-1).cpu().numpy().view(np.uint8)[: n_replays * STATS_DTYPE.itemsize]
+    return raw.view(STATS_DTYPE).copy()
 
 
 def chain_floor_ns(iters: int = 200_000, stream=None) -> float:
