@@ -27,7 +27,7 @@ struct KParams {
   const int32_t *trace_of_replay, *cap_milli;
   nbos_stats *stats;
   uint64_t *dlog;          // null unless the decision log is on
-  int32_t *ovf_dur;        // register kernel: [n_replays][n_cap] durations of queued cells whose timer is
+  int32_t *ovf_dur;        // open loop: [n_replays][n_cap] durations of queued cells whose timer is
                            // outside the sorted registers
   int64_t dlog_stride;     // codes per replay
   int32_t n_replays, H0, Hmax, HP, G;

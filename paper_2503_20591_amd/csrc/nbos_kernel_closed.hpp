@@ -15,7 +15,7 @@
 //                            everything else is a timer (kind QK_NEXT, after the retries of the same
 //                            instant, by ascending session). A session has at most one timer, so the
 //                            timers that do not fit into the 64 sorted registers wait in the session
-//                            records (see cl_refill), and no queue can overflow. A timer in the
+//                            records (see refill), and no queue can overflow. A timer in the
 //                            registers carries the index of its event and, once loaded, the event's
 //                            duration, kind and chain record: timers that come in by a refill have
 //                            them gathered for all of them at once, timers scheduled straight into
@@ -146,7 +146,7 @@ __device__ __forceinline__ void cl_after_round(Ctx<F> &c, Regs &r, int n) {
     timer_push(c, r, lane_get(ts, j), QK_NEXT, (uint32_t)lane_get((int)ss, j), lane_get(es, j));
   }
   if (r.q_n == 0 && r.o_n > 0) {
-    cl_refill(c, r);
+    refill(c, r);
     r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
   }
 }

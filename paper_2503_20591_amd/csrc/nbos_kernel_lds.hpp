@@ -13,7 +13,9 @@
 //   mark[h]      scratch for the event-parallel rounds (lowest lane that chose the host), idle = ~0.
 //   sess[s]      12 bytes: hosts word (3 x 10 bits + last executor slot), time word (busy-until, or
 //                submit time while queued), flags.
-//   overflow     timers beyond the 64 that live sorted in registers.
+//   due[s]       time of the session's timer while it waits outside the 64 sorted registers (NEVER: none
+//                waits there); its kind is kept in the flags word, the duration of a queued cell in a
+//                per-replay array in device memory.
 //
 // Serial path: one item (arrival, queued timer, auto-scaler period) per loop iteration; lane = host
 // (strided) for every scan over hosts, ballot for feasibility, packed-key wave minimum for the choice
@@ -57,10 +59,8 @@ struct Lds {
   int32_t *warm;               // [HP][4] when each pre-warmed container of a host is available (only with the pool)
   uint32_t *hsn;
   SessRec *sess;
-  int32_t *o_t, *o_d;
-  uint32_t *o_k;
-  int32_t *due;                // closed loop: [n_cap] time of a session's timer while it waits outside the registers, else NEVER
-  int32_t *stage;              // closed loop: [64] sessions whose timers move into the registers
+  int32_t *due;                // [n_cap] time of a session's timer while it waits outside the registers, else NEVER
+  int32_t *stage;              // [64] sessions whose timers move into the registers
 };
 
 struct Regs {
@@ -69,7 +69,7 @@ struct Regs {
   uint64_t digest;
   int32_t lazy_max, t_end;
   int32_t q_n, q_head_t;
-  int32_t o_n, o_min_t, o_min_i;
+  int32_t o_n, o_min_t;      // timers that wait in the session records: how many, a lower bound of the earliest
   uint32_t o_min_k;
   int32_t status;
   int32_t min_s;             // least subscription among hosts that are on, or -1 when stale
@@ -105,15 +105,19 @@ struct Ctx {
   const int32_t *cl_dur, *cl_sk;
   const int2 *cl_chain;
   int32_t qx, qnx, qnth;
+  // lane g-1 (g = 1..8): no host that passes the subscription cap for a request of g GPUs can have g idle
+  // GPUs before this time (0: nothing known). See cap_bound_* below.
+  int32_t fc;
+  int32_t *ovf_dur;          // open loop: [n_sess] durations of queued cells whose timer waits outside the registers
   static constexpr bool closed = F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
   __device__ __forceinline__ uint32_t flags() const {
     return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
   }
 };
 
-// closed loop: a session has at most one timer (its next event, or the retry or deferred end of the
-// cell under way), so a timer that does not fit into the sorted registers waits in the session's own
-// record: the kind in the flags word, the time in due[s] (NEVER: no timer waits there)
+// A session has at most one timer (the retry or deferred end of the cell under way; in a closed loop
+// also its next event), so a timer that does not fit into the sorted registers waits in the session's
+// own record: the kind in the flags word, the time in due[s] (NEVER: no timer waits there)
 constexpr uint32_t CL_KIND_SHIFT = 13;
 constexpr int32_t CLX_LOADED = (int32_t)0x80000000;
 constexpr int32_t CL_WIN_MAX = 1 << 24;
@@ -173,53 +177,33 @@ __device__ __forceinline__ void sess_write_flag(Ctx<F> &c, Regs &r, uint32_t s, 
   r.dirty |= wballot(c.vsid == s);
 }
 
-// ---- timers: overflow array in LDS (unsorted) ---------------------------------------------------
-template <uint32_t F>
-__device__ __forceinline__ void ovf_rescan(Ctx<F> &c, Regs &r) {
-  wave_sync();
-  uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
-  int bi = 0;
-  for (int i = c.lane; i < r.o_n; i += WAVE) {
-    uint32_t t = (uint32_t)c.m.o_t[i], l = c.m.o_k[i];
-    if (t < bt || (t == bt && l < bl)) { bt = t; bl = l; bi = i; }
-  }
-  uint32_t mt = wave_min(bt);
-  uint32_t ml = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
-  uint64_t who = wballot(bt == mt && bl == ml);
-  int src = (int)__builtin_ctzll(who | (1ull << 63));
-  r.o_min_i = lane_get(bi, src);
-  r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
-  r.o_min_k = ml;
-}
-
+// ---- timers outside the sorted registers wait in the session records ---------------------------------
 template <uint32_t F>
 __device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
-  if constexpr (Ctx<F>::closed) {
-    const uint32_t s = k & 0xFFFFu;
-    if (c.lane == 0) {
-      const uint32_t z = (uint32_t)c.m.sess[s].z;
-      c.m.sess[s].z = (int)((z & ~(3u << CL_KIND_SHIFT)) | ((k >> 16) << CL_KIND_SHIFT));
-      c.m.due[s] = t;
+  const uint32_t s = k & 0xFFFFu;
+  if (c.lane == 0) {
+    const uint32_t z = (uint32_t)c.m.sess[s].z;
+    c.m.sess[s].z = (int)((z & ~(3u << CL_KIND_SHIFT)) | ((k >> 16) << CL_KIND_SHIFT));
+    c.m.due[s] = t;
+    if constexpr (!Ctx<F>::closed) {
+      if ((k >> 16) == QK_RETRY) c.ovf_dur[s] = d;
     }
-  } else {
-    if (r.o_n >= c.p.q_cap) { r.status = NBOS_E_LIMIT; return; }
-    if (c.lane == 0) { c.m.o_t[r.o_n] = t; c.m.o_k[r.o_n] = k; c.m.o_d[r.o_n] = d; }
   }
-  if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) {
-    r.o_min_t = t; r.o_min_k = k; r.o_min_i = r.o_n;
-  }
+  if constexpr (!Ctx<F>::closed) r.dirty |= wballot(c.vsid == s);      // the flags word of the record has changed
+  if (r.o_n == 0 || t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k)) { r.o_min_t = t; r.o_min_k = k; }
   r.o_n++;
 }
 
-// closed loop, registers empty: all timers that are due within a window after the earliest one move
+// Registers empty: all timers that are due within a window after the earliest one move
 // from the session records into the registers at once, at most 64. A window takes whole instants, so
 // everything taken is earlier than everything left behind whatever the kinds. The window adapts to
 // the density of the timers (32 to 56 of the registers filled is the aim); if more than 64 timers wait
 // for one and the same instant, the single earliest (time, kind, session) is taken. What firing the
-// timers will need - their events' duration, kind and chain record - is gathered here, one lane per
-// timer, in two round trips to device memory for the lot.
+// timers will need - the duration of a queued cell; in a closed loop their events' duration, kind and
+// chain record - is gathered here, one lane per timer, in one or two round trips to device memory for
+// the lot.
 template <uint32_t F>
-__device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
+__device__ __forceinline__ void refill(Ctx<F> &c, Regs &r) {
   wave_sync();
   int cnt;
   int32_t left;                                  // earliest time left behind
@@ -286,15 +270,19 @@ __device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
     c.m.due[s] = NEVER;
     key = ((((uint32_t)c.m.sess[s].z >> CL_KIND_SHIFT) & 3u) << 16) | (uint32_t)s;
   }
-  // the cursors were written by lane 0 when the timers were scheduled: the fence makes this wave's own
-  // stores visible to its other lanes
+  // the cursors / durations were written by lane 0 when the timers were scheduled: the fence makes this
+  // wave's own stores visible to its other lanes
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-  if (take) e = c.cl_cur[key & 0xFFFFu];
   int32_t x = 0, nx = -1, nth = 0;
-  if (take && (key >> 16) != QK_END) {
-    const int2 ch = c.cl_chain[e];
-    x = c.cl_dur[e] | (int32_t)(((uint32_t)c.cl_sk[e] >> 24) << 28) | CLX_LOADED;
-    nx = ch.x; nth = ch.y;
+  if constexpr (Ctx<F>::closed) {
+    if (take) e = c.cl_cur[key & 0xFFFFu];
+    if (take && (key >> 16) != QK_END) {
+      const int2 ch = c.cl_chain[e];
+      x = c.cl_dur[e] | (int32_t)(((uint32_t)c.cl_sk[e] >> 24) << 28) | CLX_LOADED;
+      nx = ch.x; nth = ch.y;
+    }
+  } else {
+    if (take && (key >> 16) == QK_RETRY) e = c.ovf_dur[key & 0xFFFFu];       // qd carries the queued cell's duration
   }
   int rank = 0;
   for (int j = 0; j < cnt; j++) {
@@ -307,9 +295,11 @@ __device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
   c.qt = __builtin_amdgcn_ds_permute(dst << 2, t);
   c.qk = (uint32_t)__builtin_amdgcn_ds_permute(dst << 2, (int)key);
   c.qd = __builtin_amdgcn_ds_permute(dst << 2, e);
-  c.qx = __builtin_amdgcn_ds_permute(dst << 2, x);
-  c.qnx = __builtin_amdgcn_ds_permute(dst << 2, nx);
-  c.qnth = __builtin_amdgcn_ds_permute(dst << 2, nth);
+  if constexpr (Ctx<F>::closed) {
+    c.qx = __builtin_amdgcn_ds_permute(dst << 2, x);
+    c.qnx = __builtin_amdgcn_ds_permute(dst << 2, nx);
+    c.qnth = __builtin_amdgcn_ds_permute(dst << 2, nth);
+  }
   r.q_n = cnt;
   r.o_n -= cnt;
   r.o_min_t = r.o_n > 0 ? left : NEVER;
@@ -317,8 +307,8 @@ __device__ __forceinline__ void cl_refill(Ctx<F> &c, Regs &r) {
 }
 
 // ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
-// Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
-// registers are empty only if the overflow array is.
+// Invariant: every entry in the registers is earlier than every timer that waits in the session records, and the
+// registers are empty only if none waits there.
 template <uint32_t F>
 __device__ __forceinline__ void timer_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d,
                                            int32_t x = 0, int32_t nx = -1, int32_t nth = 0) {
@@ -365,20 +355,8 @@ __device__ __forceinline__ void timer_pop(Ctx<F> &c, Regs &r) {
     c.qx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
     c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
     c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
-    if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
-  } else if (r.q_n == 0 && r.o_n > 0) {
-    wave_sync();
-    int i = r.o_min_i, last = r.o_n - 1;
-    int32_t t = uni(c.m.o_t[i]), d = uni(c.m.o_d[i]);
-    uint32_t k = uni(c.m.o_k[i]);
-    int32_t lt = c.m.o_t[last], ld = c.m.o_d[last];
-    uint32_t lk = c.m.o_k[last];
-    if (i != last && c.lane == 0) { c.m.o_t[i] = lt; c.m.o_k[i] = lk; c.m.o_d[i] = ld; }
-    r.o_n = last;
-    if (c.lane == 0) { c.qt = t; c.qd = d; c.qk = k; }
-    r.q_n = 1;
-    ovf_rescan(c, r);
   }
+  if (r.q_n == 0 && r.o_n > 0) refill(c, r);
   r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
 }
 
@@ -423,6 +401,7 @@ __device__ __forceinline__ int boot_host(Ctx<F> &c, Regs &r, int32_t now, uint32
     if (c.lane < 4) c.m.warm[4 * h + c.lane] = ra + c.p.prewarm;
   }
   c.fu = c.fu < ra ? c.fu : ra;               // a new host may have idle GPUs from then on
+  c.fc = c.fc < ra ? c.fc : ra;
   r.min_s = -1;
   c32_add(c.m, c.lane, CS_NON, 1u);
   c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
@@ -475,32 +454,56 @@ __device__ __forceinline__ void order2(int32_t &a, int32_t &b) {
   a = lo; b = hi;
 }
 
+// the busy-until times of one host's GPUs in ascending order (GPUs beyond G count as never free):
+// the 19-comparator network for 8 inputs; returns the g-th smallest
+__device__ __forceinline__ int32_t kth_free_time(const int4 a, const int4 b, int G, int g) {
+  int32_t v0 = a.x, v1 = G > 1 ? a.y : NEVER, v2 = G > 2 ? a.z : NEVER, v3 = G > 3 ? a.w : NEVER;
+  int32_t v4 = G > 4 ? b.x : NEVER, v5 = G > 5 ? b.y : NEVER, v6 = G > 6 ? b.z : NEVER, v7 = G > 7 ? b.w : NEVER;
+  order2(v0, v1); order2(v2, v3); order2(v4, v5); order2(v6, v7);
+  order2(v0, v2); order2(v1, v3); order2(v4, v6); order2(v5, v7);
+  order2(v1, v2); order2(v5, v6);
+  order2(v0, v4); order2(v1, v5); order2(v2, v6); order2(v3, v7);
+  order2(v2, v4); order2(v3, v5);
+  order2(v1, v2); order2(v3, v4); order2(v5, v6);
+  return g == 1 ? v0 : g == 2 ? v1 : g == 3 ? v2 : g == 4 ? v3 : g == 5 ? v4 : g == 6 ? v5 : g == 7 ? v6 : v7;
+}
+
 // Earliest time at which some host that is on could have g idle GPUs if nothing new were committed:
 // min over hosts of max(ready_at, g-th smallest busy-until time of the host's GPUs). Later commits
 // only push it back, so no election or migration for a request of g GPUs can succeed before it, as
-// long as no host is added (boot_host lowers the stored bound). One lane sorts one host's row with
-// the 19-comparator network for 8 inputs.
+// long as no host is added (boot_host lowers the stored bound). `capped`: the same minimum over the
+// hosts that hold at most `room` subscribed GPUs, i.e. that pass the subscription cap for the request
+// (Section 3.4.1): no migration target before it, as long as no host is added and no host's
+// subscription shrinks (cap_bound_host_freed lowers the stored bound then). One lane sorts one host's row.
 template <uint32_t F>
-__device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g) {
+__device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g, int32_t room, int32_t &capped) {
   wave_sync();
   const int G = c.p.G;
-  int32_t best = NEVER;
+  int32_t best = NEVER, best_cap = NEVER;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
-    const int4 a = c.m.fin[2 * h], b = c.m.fin[2 * h + 1];
-    int32_t v0 = a.x, v1 = G > 1 ? a.y : NEVER, v2 = G > 2 ? a.z : NEVER, v3 = G > 3 ? a.w : NEVER;
-    int32_t v4 = G > 4 ? b.x : NEVER, v5 = G > 5 ? b.y : NEVER, v6 = G > 6 ? b.z : NEVER, v7 = G > 7 ? b.w : NEVER;
-    order2(v0, v1); order2(v2, v3); order2(v4, v5); order2(v6, v7);
-    order2(v0, v2); order2(v1, v3); order2(v4, v6); order2(v5, v7);
-    order2(v1, v2); order2(v5, v6);
-    order2(v0, v4); order2(v1, v5); order2(v2, v6); order2(v3, v7);
-    order2(v2, v4); order2(v3, v5);
-    order2(v1, v2); order2(v3, v4); order2(v5, v6);
-    int32_t y = g == 1 ? v0 : g == 2 ? v1 : g == 3 ? v2 : g == 4 ? v3 : g == 5 ? v4 : g == 6 ? v5 : g == 7 ? v6 : v7;
+    int32_t y = kth_free_time(c.m.fin[2 * h], c.m.fin[2 * h + 1], G, g);
     const int32_t ra = c.m.ready_at[h];
     y = y > ra ? y : ra;
     best = best < y ? best : y;
+    const int32_t yc = (int32_t)(c.m.hsn[h] & 0xFFFFu) <= room ? y : NEVER;
+    best_cap = best_cap < yc ? best_cap : yc;
   }
+  capped = (int32_t)wave_min((uint32_t)best_cap);
   return (int32_t)wave_min((uint32_t)best);
+}
+
+// Host h now holds s_new subscribed GPUs, fewer than before (a session ended, a replica moved away): it
+// may newly pass the cap for requests of up to slim - s_new GPUs, so the stored bounds of those requests
+// drop to the time at which this host could have the GPUs idle. Lane g-1 works out the bound for g.
+template <uint32_t F>
+__device__ __forceinline__ void cap_bound_host_freed(Ctx<F> &c, int h, int32_t s_new) {
+  if (c.flags() & NBOS_F_DYNAMIC_SR) return;          // the limit moves with the cluster's sums: no bound is kept
+  wave_sync();
+  const int g = (c.lane & 7) + 1;
+  int32_t y = kth_free_time(c.m.fin[2 * h], c.m.fin[2 * h + 1], c.p.G, g);
+  const int32_t ra = c.m.ready_at[h];
+  y = y > ra ? y : ra;
+  if (c.lane < NGPU && s_new + g <= c.slim && y < c.fc) c.fc = y;
 }
 
 // ---- closed loop: the session's next event is due one think time after `base` --------------------
@@ -601,6 +604,14 @@ __device__ __forceinline__ void end_session(Ctx<F> &c, Regs &r, uint32_t s, uint
     c.m.hsn[h] -= sub;                          // three distinct hosts, one lane each
   }
   r.min_s = -1;
+  if (!(c.flags() & NBOS_F_DYNAMIC_SR)) {
+    wave_sync();
+#pragma unroll
+    for (int i = 0; i < 3; i++) {
+      const int h = (int)((hw >> (10 * i)) & 1023u);
+      cap_bound_host_freed(c, h, (int32_t)(uni(c.m.hsn[h]) & 0xFFFFu));
+    }
+  }
   sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
   c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(-3 * g));
   c64_add(c.m, c.lane, CL_SUB, (int64_t)(3 * g) * now);
@@ -699,17 +710,35 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
   // (b), (c): a target exists? Only then is the replica to move worked out.
   uint32_t tkey = 0xFFFFFFFFu;
   if (!hopeless && (c.flags() & NBOS_F_MIGRATE)) {
-    // the cap alone may rule every host out: S_h + g <= limit fails even for the least subscribed
-    if (r.min_s < 0) r.min_s = min_subscription(c);
-    const int32_t room = cap_room(c, g);
-    if (r.min_s <= room) {
+    if (c.flags() & NBOS_F_DYNAMIC_SR) {
+      // the cap alone may rule every host out: S_h + g <= limit fails even for the least subscribed
+      if (r.min_s < 0) r.min_s = min_subscription(c);
+      const int32_t room = cap_room(c, g);
+      if (r.min_s <= room) {
+        bool any_idle;
+        tkey = best_host(c, now, g, room, true, -1, -1, any_idle);
+        if (!any_idle) {
+          // No host at all with g idle GPUs: work out when the first one could have them, once, for
+          // every later attempt with a request of g or more.
+          int32_t unused;
+          const int32_t bound = earliest_idle(c, g, room, unused);
+          if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
+        }
+      }
+    } else if (now >= lane_get(c.fc, g - 1)) {
+      // (before that time no host that passes the cap can have the GPUs idle: nothing to look for)
+      const int32_t room = c.slim - g;
       bool any_idle;
       tkey = best_host(c, now, g, room, true, -1, -1, any_idle);
-      if (!any_idle) {
-        // No host at all with g idle GPUs: work out when the first one could have them, once, for
-        // every later attempt with a request of g or more.
-        const int32_t bound = earliest_idle(c, g);
-        if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
+      if (tkey == 0xFFFFFFFFu) {
+        // No target: work out when the first host could have g idle GPUs, and the first one among those
+        // under the cap, once, for every later attempt with a request of g or more.
+        int32_t under_cap;
+        const int32_t bound = earliest_idle(c, g, room, under_cap);
+        if (c.lane >= g - 1) {
+          if (c.fu < bound) c.fu = bound;
+          if (c.fc < under_cap) c.fc = under_cap;
+        }
       }
     }
   }
@@ -749,6 +778,8 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       }
       if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[dst] += moved; }
       r.min_s = -1;
+      wave_sync();
+      cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu));
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, outcome);
@@ -757,6 +788,8 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       const int32_t start = now + c.p.boot + c.p.migr;
       if (c.lane == 0) c.m.hsn[hv] -= moved;
       r.min_s = -1;
+      wave_sync();
+      cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu));
       const int h = boot_host(c, r, now, moved);
       wave_sync();
       c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
@@ -977,7 +1010,6 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
 }
 
 // ---- LDS layout of one replay and its initial state (S0) -------------------------------------------
-// CL: closed loop (no overflow array; due[] and stage[] instead)
 template <bool CL>
 __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   Lds m;
@@ -990,20 +1022,10 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
   m.hsn = (uint32_t *)q;            q += (size_t)p.HP * 4;
   m.warm = (int32_t *)q;            q += p.warm_n > 0 ? (size_t)p.HP * 16 : 0;
-  m.stage = nullptr;
-  if (CL) {                         // 16-byte aligned: the refill reads four times at once
-    m.due = (int32_t *)q;             q += (size_t)((p.n_cap + 3) / 4 * 4) * 4;
-    m.stage = (int32_t *)q;           q += WAVE * 4;
-  }
-  m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
-  if (CL) {
-    m.o_t = nullptr; m.o_k = nullptr; m.o_d = nullptr;
-  } else {
-    m.o_t = (int32_t *)q;             q += (size_t)p.q_cap * 4;
-    m.o_k = (uint32_t *)q;            q += (size_t)p.q_cap * 4;
-    m.o_d = (int32_t *)q;
-    m.due = nullptr;
-  }
+  // 16-byte aligned: the refill reads four times at once
+  m.due = (int32_t *)q;             q += (size_t)((p.n_cap + 3) / 4 * 4) * 4;
+  m.stage = (int32_t *)q;           q += WAVE * 4;
+  m.sess = (SessRec *)q;
   return m;
 }
 
@@ -1030,9 +1052,7 @@ __device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int lan
     const uint32_t g = p.sess_gpus[s_lo + s];
     m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
   }
-  if (CL) {
-    for (int s = lane; s < (p.n_cap + 3) / 4 * 4; s += WAVE) m.due[s] = NEVER;
-  }
+  for (int s = lane; s < (p.n_cap + 3) / 4 * 4; s += WAVE) m.due[s] = NEVER;
   __syncthreads();
 }
 
@@ -1082,12 +1102,15 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
   Ctx<F> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
         NEVER, 0, 0xFFFFFFFFu, 0xFFFFFFFFu, 0};
+  c.n_sess = n_sess;
+  c.ovf_dur = p.ovf_dur + (int64_t)rep * p.n_cap;
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
   r.q_head_t = NEVER;
   r.o_min_t = NEVER;
   r.min_s = -1;
+  r.cl_win = 1024;
 
   const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   const bool batching = p.batch != 0;

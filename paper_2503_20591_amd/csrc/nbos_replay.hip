@@ -203,7 +203,7 @@ struct nbos_replay {
   char kernel_name[96];    // as a profiler prints it, without the argument list
   nbos_stats *d_stats;
   nbos_bill *d_bill;
-  int32_t *d_ovf;          // register kernel only
+  int32_t *d_ovf;          // open-loop replay kernels: durations of queued cells, [n_replays][n_cap]
   int32_t *d_chain;        // closed loop only: the chain records of all events, then the cursors
   uint64_t *d_log;
   std::vector<int64_t> ev_off;
@@ -451,10 +451,11 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     const int32_t rc = choose_reg_kernel(h, maxlds);
     if (rc != NBOS_OK) return rc;
   } else {
-    const size_t fixed = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12;
-    if (fixed + 12 * 64 > (size_t)maxlds) return NBOS_E_LIMIT;
-    if (fixed + sh->q_cap * 12 > (size_t)maxlds) sh->q_cap = ((size_t)maxlds - fixed) / 12;
-    h->lds_bytes = fixed + sh->q_cap * 12;
+    // 12 bytes of record and 4 of timer per session; 64 staged sessions
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
+                   (n_cap + 3) / 4 * 16 + WAVE * 4;
+    if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
+    sh->q_cap = 0;
     // same idea as for the register kernel; its batches are small (the LDS footprint allows few
     // workgroups per compute unit), so the instance compiled for the flag set is used whenever
     // there is one
@@ -503,7 +504,9 @@ int32_t allocate_buffers(nbos_replay *h, const Shape &sh) {
   if (n == 0) return NBOS_OK;
   if (hipMalloc(&h->d_stats, sizeof(nbos_stats) * n) != hipSuccess) return NBOS_E_NOMEM;
   if (hipMalloc(&h->d_bill, sizeof(nbos_bill) * n) != hipSuccess) return NBOS_E_NOMEM;
-  if (sh.in_regs && hipMalloc(&h->d_ovf, sizeof(int32_t) * n * (size_t)sh.n_cap) != hipSuccess) return NBOS_E_NOMEM;
+  // durations of queued cells whose timers wait outside the sorted registers (open-loop replay kernels)
+  const bool queued_durations = !(cfg->flags & (NBOS_F_BATCH_MODE | NBOS_F_CLOSED_LOOP));
+  if (queued_durations && hipMalloc(&h->d_ovf, sizeof(int32_t) * n * (size_t)sh.n_cap) != hipSuccess) return NBOS_E_NOMEM;
   if (cfg->flags & NBOS_F_CLOSED_LOOP) {
     // one allocation: chain[total_ev] (two words each), cursor[n_replays][n_cap]; the chains are linked here
     const size_t words = 2 * (size_t)sh.total_ev + n * (size_t)sh.n_cap;
