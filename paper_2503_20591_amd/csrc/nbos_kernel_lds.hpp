@@ -121,6 +121,13 @@ struct Ctx {
 constexpr uint32_t CL_KIND_SHIFT = 13;
 constexpr int32_t CLX_LOADED = (int32_t)0x80000000;
 constexpr int32_t CL_WIN_MAX = 1 << 24;
+// Open loop: the duration word of a sorted RETRY timer (a duration is below 2^27) also says what is known
+// about the retry. QD_LOOKED: the election of the queued cell has been worked out for the timer's time;
+// QD_EFAIL: it fails there, whatever is bound until then (binding only takes idle GPUs away), and the
+// retry is not the last one; bits 27-29 then hold the request g - 1. See retry_lookahead.
+constexpr uint32_t QD_LOOKED = 1u << 31, QD_EFAIL = 1u << 30;
+constexpr int QD_G_SHIFT = 27;
+constexpr int32_t QD_DUR_MASK = (1 << QD_G_SHIFT) - 1;
 
 __device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
   if (lane == 0) atomicAdd(&m.c32[idx], v);
@@ -186,7 +193,7 @@ __device__ __forceinline__ void ovf_push(Ctx<F> &c, Regs &r, int32_t t, uint32_t
     c.m.sess[s].z = (int)((z & ~(3u << CL_KIND_SHIFT)) | ((k >> 16) << CL_KIND_SHIFT));
     c.m.due[s] = t;
     if constexpr (!Ctx<F>::closed) {
-      if ((k >> 16) == QK_RETRY) c.ovf_dur[s] = d;
+      if ((k >> 16) == QK_RETRY) c.ovf_dur[s] = d & QD_DUR_MASK;
     }
   }
   if constexpr (!Ctx<F>::closed) r.dirty |= wballot(c.vsid == s);      // the flags word of the record has changed
@@ -916,6 +923,103 @@ __device__ __forceinline__ void on_session_end(Ctx<F> &c, Regs &r, uint32_t s, u
   }
 }
 
+// ---- retries that fail again, looked at ahead of time (open loop) -----------------------------------
+// A retry of a queued cell (Section 3.2.3) that fails once more changes nothing but the session's retry
+// count and the time of its timer. Whether it fails is known early: (a) its election fails at the timer's
+// time if none of the session's hosts has g idle GPUs then, on the busy-until times as they stand: whatever
+// is bound before the timer fires only takes idle GPUs away; (b) no migration target exists before the
+// stored bound of c.fu / c.fc; (c) no host can be added while the cluster is at its maximum. (a) is worked
+// out here for all sorted timers at once, lane = timer, and stays true; (b) and (c) are tests of uniform
+// values when the timer fires. Such a retry then costs a few instructions, and, since it touches nothing
+// that an election reads, the event-parallel rounds need not stop at it (retry_horizon).
+template <uint32_t F>
+__device__ __forceinline__ void retry_lookahead(Ctx<F> &c, const Regs &r) {
+  wave_sync();
+  const int G = c.p.G;
+  const bool cand = c.lane < r.q_n && (c.qk >> 16) == QK_RETRY && !((uint32_t)c.qd & QD_LOOKED);
+  if (cand) {
+    const SessRec rec = c.m.sess[c.qk & 0xFFFFu];
+    const uint32_t hw = (uint32_t)rec.x, fl = (uint32_t)rec.z;
+    const int g = (int)((fl >> 3) & 7u) + 1;
+    const int32_t vt = c.qt;
+    const uint32_t h0 = hw & 1023u, h1 = (hw >> 10) & 1023u, h2 = (hw >> 20) & 1023u;
+    const int C0 = committed(c, (int)h0, vt), C1 = committed(c, (int)h1, vt), C2 = committed(c, (int)h2, vt);
+    const bool can = (c.m.ready_at[h0] <= vt && C0 + g <= G) || (c.m.ready_at[h1] <= vt && C1 + g <= G) ||
+                     (c.m.ready_at[h2] <= vt && C2 + g <= G);
+    const bool more = (int)((fl >> 8) & 15u) < c.p.max_retries;        // not the retry that gives the cell up
+    uint32_t d = (uint32_t)c.qd | QD_LOOKED;
+    if (!can && more) d |= QD_EFAIL | ((uint32_t)(g - 1) << QD_G_SHIFT);
+    c.qd = (int32_t)d;
+  }
+}
+
+// hosts can be added right now (a failed election then gets a host instead of a place in the queue)
+template <uint32_t F>
+__device__ __forceinline__ bool can_grow(const Ctx<F> &c) {
+  if (!(c.flags() & NBOS_F_SCALE_OUT)) return false;
+  wave_sync();
+  return (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
+}
+
+// per lane = sorted timer: it is a retry that is known to fail quietly if it fires now
+template <uint32_t F>
+__device__ __forceinline__ bool retry_is_quiet(const Ctx<F> &c, const Regs &r) {
+  const uint32_t d = (uint32_t)c.qd;
+  const int32_t bound_own = c.fu > c.fc ? c.fu : c.fc;                  // lane g-1: no target before this time
+  const int32_t bound = __builtin_amdgcn_ds_bpermute((int)((d >> QD_G_SHIFT) & 7u) << 2, bound_own);
+  return c.lane < r.q_n && (c.qk >> 16) == QK_RETRY && (d & QD_EFAIL) != 0 &&
+         (!(c.flags() & NBOS_F_MIGRATE) || c.qt < bound);
+}
+
+// Up to which time a run of arrivals may be evaluated without looking at the timers: the time of the first
+// sorted timer that is not a quietly failing retry (or of whatever waits outside the registers), and not
+// beyond the time at which the earliest of the quiet ones comes back (one retry interval later).
+template <uint32_t F>
+__device__ __forceinline__ int32_t retry_horizon(Ctx<F> &c, const Regs &r, int32_t until) {
+  if (r.q_n == 0) return r.q_head_t;
+  if (((uint32_t)lane_get((int)c.qk, 0) >> 16) != QK_RETRY) return r.q_head_t;
+  if (can_grow(c)) return r.q_head_t;
+  // retries due up to `until` that have not been looked at yet
+  if (wballot(c.lane < r.q_n && (c.qk >> 16) == QK_RETRY && !((uint32_t)c.qd & QD_LOOKED) && c.qt <= until) != 0)
+    retry_lookahead(c, r);
+  const uint64_t loud = wballot(c.lane < r.q_n && !retry_is_quiet(c, r));
+  const int first = loud != 0 ? (int)__builtin_ctzll(loud) : r.q_n;
+  if (first == 0) return r.q_head_t;
+  int32_t lim = first < r.q_n ? lane_get(c.qt, first) : (r.o_n > 0 ? r.o_min_t : NEVER);
+  const int64_t back = (int64_t)r.q_head_t + c.p.retry_iv;
+  if (back < lim) lim = (int32_t)back;
+  return lim;
+}
+
+// The earliest timer is a retry that fails quietly: count it and move its timer one interval on.
+// Returns false if it is no such retry (nothing but the marks of retry_lookahead is changed then).
+template <uint32_t F>
+__device__ __forceinline__ bool fire_quiet_retry(Ctx<F> &c, Regs &r) {
+  const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
+  if ((key >> 16) != QK_RETRY) return false;
+  if (!((uint32_t)lane_get(c.qd, 0) & QD_LOOKED)) retry_lookahead(c, r);
+  const uint32_t d0 = (uint32_t)lane_get(c.qd, 0);
+  if (!(d0 & QD_EFAIL)) return false;
+  const int32_t now = r.q_head_t;
+  const int g = (int)((d0 >> QD_G_SHIFT) & 7u) + 1;
+  if (c.flags() & NBOS_F_MIGRATE) {
+    const int32_t bu = lane_get(c.fu, g - 1), bc = lane_get(c.fc, g - 1);
+    if (now >= (bu > bc ? bu : bc)) return false;
+  }
+  if (can_grow(c)) return false;
+  const uint32_t s = key & 0xFFFFu;
+  wave_sync();
+  const uint32_t fl = uni((uint32_t)c.m.sess[s].z);
+  const int32_t t_submit = uni(c.m.sess[s].y);
+  const int retries = (int)((fl >> 8) & 15u) + 1;                       // below max_retries before: see retry_lookahead
+  if (c.lane == 0) c.m.sess[s].z = (int)((fl & ~(15u << 8)) | ((uint32_t)retries << 8));
+  r.dirty |= wballot(c.vsid == s);
+  r.t_end = r.t_end > now ? r.t_end : now;
+  timer_pop(c, r);
+  timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, (int32_t)(d0 & (uint32_t)QD_DUR_MASK));
+  return true;
+}
+
 // ---- one event-parallel round over the lanes in `run` (see the file header) -----------------------
 // Returns the mask of lanes whose cells were started. rec = the lane's prefetched session record.
 // next_lost: the lane after the started ones lost its election (another round would start nothing there).
@@ -1114,6 +1218,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
 
   const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   const bool batching = p.batch != 0;
+  // Retries are looked at ahead of time (retry_lookahead) unless the cap moves with the cluster's sums: then
+  // no bound on the next migration target is kept and hardly any retry is known to fail
+  const bool look_ahead = !(c.flags() & NBOS_F_DYNAMIC_SR);
   // hash buckets (power of two <= HP) for spotting two events of one session in a tile
   const uint32_t dup_mask = (1u << (31 - __builtin_clz((uint32_t)p.HP))) - 1u;
   int32_t tick_t = ticking ? p.scale_iv : NEVER;
@@ -1131,9 +1238,11 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
     bool fast = false;                      // this lane's event is a cell of an idle placed session
     uint64_t todo = 0;
     uint32_t sid = 0;
+    int32_t last_t = 0;                     // time of the tile's last event
     if (base < ev_hi) {
       vt = nt; vd = nd; vs = ns;
       const int64_t cur = base;
+      last_t = lane_get(vt, (int)(ev_hi - cur < WAVE ? ev_hi - cur - 1 : WAVE - 1));
       base += WAVE;
       if (base + lane < ev_hi) { nt = p.ev_time[base + lane]; nd = p.ev_dur[base + lane]; ns = p.ev_sk[base + lane]; }
       const bool valid = cur + lane < ev_hi;
@@ -1198,7 +1307,13 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
         const uint64_t clean = fastmask & ~r.dirty;
         if (batching && cooldown == 0 && (clean & bit) != 0) {
           // ---- event-parallel round over the run of fast arrivals that starts at lane i ----
-          const uint64_t eligible = clean & wballot(vt < due_t);
+          // the run may go on past retries that are known to fail quietly
+          int32_t run_due = due_t;
+          if (look_ahead && due_t == r.q_head_t && due_t <= last_t) {
+            const int32_t hz = retry_horizon(c, r, last_t);
+            run_due = hz < tick_t ? hz : tick_t;
+          }
+          const uint64_t eligible = clean & wballot(vt < run_due);
           const uint64_t blockers = todo & ~eligible;
           const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
           if ((run & (run - 1)) != 0) {          // at least two lanes
@@ -1261,9 +1376,13 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
           continue;
         }
         if (!fire_q) break;                   // only reached while draining: nothing is left
+        if (look_ahead && fire_quiet_retry(c, r)) {
+          due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          continue;
+        }
         const int32_t now = r.q_head_t;
         const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
-        const int32_t dur = lane_get(c.qd, 0);
+        const int32_t dur = lane_get(c.qd, 0) & QD_DUR_MASK;
         timer_pop(c, r);
         r.t_end = r.t_end > now ? r.t_end : now;
         const uint32_t s = key & 0xFFFFu;
