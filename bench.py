@@ -119,6 +119,7 @@ def main():
     ap.add_argument("--hosts-in-lds", action="store_true", help="force the any-size kernel (comparison runs)")
     ap.add_argument("--generic-kernel", action="store_true", help="force the run-time-flags kernel (comparison runs)")
     ap.add_argument("--rounds", choices=["on", "off"], default=None, help="force the event-parallel rounds (comparison runs)")
+    ap.add_argument("--one-wave", action="store_true", help="no helper waves on large clusters (comparison runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -146,9 +147,9 @@ def main():
         dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    default_shape = not (args.replays or args.hosts_in_lds or args.generic_kernel or args.rounds)
+    default_shape = not (args.replays or args.hosts_in_lds or args.generic_kernel or args.rounds or args.one_wave)
     h = replay.Replay(batch.config, dev, hosts_in_lds=args.hosts_in_lds, generic_kernel=args.generic_kernel,
-                      rounds=None if args.rounds is None else args.rounds == "on")
+                      rounds=None if args.rounds is None else args.rounds == "on", one_wave=args.one_wave)
     info = h.launch_info()
 
     for _ in range(args.warmup):

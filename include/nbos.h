@@ -96,6 +96,9 @@ typedef enum {
 #define NBOS_F_ROUNDS_ON     0x2000u /* comparison runs: use the rounds also where they are off by
                                       default (closed loops on at most 64 hosts with
                                       NBOS_F_HOSTS_IN_LDS); same results. Not with NBOS_F_ROUNDS_OFF */
+#define NBOS_F_ONE_WAVE      0x4000u /* comparison runs: one wave per replay also on clusters of 256 hosts
+                                      or more, where three helper waves would share the scans over
+                                      all hosts; same results                                      */
 #define NBOS_F_AUTOSCALE     0x20u /* the periodic auto-scaler of Section 3.4.2 (second scale-out
                                       scenario). Every scale_interval_ms the expected capacity is
                                       want = ceil(f * sum C / G) + scaling_buffer_hosts hosts, with

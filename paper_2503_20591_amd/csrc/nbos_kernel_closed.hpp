@@ -152,11 +152,11 @@ __device__ __forceinline__ void cl_after_round(Ctx<F> &c, Regs &r, int n) {
 }
 
 template <uint32_t F>
-__global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
+__global__ void __launch_bounds__(4 * WAVE) nbos_replay_closed_kernel(KParams p) {
   static_assert(Ctx<F>::closed, "instantiate with a closed-loop flag set");
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & (WAVE - 1);
   if (rep >= p.n_replays) return;
 
   const int trace = p.trace_of_replay[rep];
@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
   const int n_sess = p.sess_offset[trace + 1] - s_lo;
 
   const Lds m = lds_carve<true>(p, lds_raw);
-  lds_init<true>(p, m, lane, s_lo, n_sess);
+  lds_init<true>(p, m, s_lo, n_sess);
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
   Ctx<F> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
@@ -178,6 +178,11 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
   r.o_min_t = NEVER;
   r.min_s = -1;
   r.cl_win = 1024;
+  c.nw = (int)(blockDim.x / WAVE);
+  c.wid = (int)(threadIdx.x / WAVE);
+  if (c.wid != 0) {
+    helper_loop(c);
+  } else {
   const bool batching = p.batch != 0;
   int cooldown = 0, backoff = 1;            // timers to fire one by one before the next parallel round: doubles
                                             // (up to 64) while rounds start at most one cell, back to 1 when they pay
@@ -292,7 +297,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_closed_kernel(KParams p) {
   wave_sync();
   const int32_t bl = (int32_t)uni(m.c32[CS_BLAZY]);             // finish times bound by the rounds
   r.lazy_max = r.lazy_max > bl ? r.lazy_max : bl;
-  write_stats(p, m, r, rep, lane);
+  helpers_go(c, HC_EXIT, 0, 0, 0);
+  }  // wave 0
+  write_stats(p, m, r, rep);
 }
 
 }  // namespace ldsk

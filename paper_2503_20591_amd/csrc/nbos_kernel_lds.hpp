@@ -1,5 +1,7 @@
 // nbos_kernel_lds.hpp — replay kernel with host state in LDS: any cluster size up to NBOS_MAX_HOSTS.
-// Used when hosts_max > 64 (or on request). One workgroup (one wave64) per replay.
+// Used when hosts_max > 64 (or on request). One workgroup per replay: one wave64 runs the replay; on
+// clusters of 256 hosts or more three more waves of the workgroup (each on a SIMD of its own, asleep at
+// a barrier in between) take their share of every scan over all hosts (see "helper waves" below).
 //
 // LDS per replay
 //   fin[h][8]    per-GPU "busy until" times, one 32-byte row per host. A GPU is committed at time t
@@ -61,6 +63,7 @@ struct Lds {
   SessRec *sess;
   int32_t *due;                // [n_cap] time of a session's timer while it waits outside the registers, else NEVER
   int32_t *stage;              // [64] sessions whose timers move into the registers
+  int32_t *mail;               // [32] what the helper waves are to do, and what they found (see helpers_go)
 };
 
 struct Regs {
@@ -109,6 +112,7 @@ struct Ctx {
   // GPUs before this time (0: nothing known). See cap_bound_* below.
   int32_t fc;
   int32_t *ovf_dur;          // open loop: [n_sess] durations of queued cells whose timer waits outside the registers
+  int nw, wid;               // waves in the workgroup, this wave's number (0 runs the replay)
   static constexpr bool closed = F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
   __device__ __forceinline__ uint32_t flags() const {
     return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
@@ -387,6 +391,32 @@ __device__ __forceinline__ void bind_gpus(Ctx<F> &c, int h, int g, int32_t now, 
   if (fr && rank < g) row[c.lane] = finish;
 }
 
+// ---- helper waves ------------------------------------------------------------------------------------
+// A scan over all hosts is split by chunks of 64 hosts: wave w of the nw waves of the workgroup takes the
+// chunks w, w + nw, ... The wave that runs the replay (wave 0) writes what is to be scanned into the mail
+// words and meets the helpers at a barrier; each wave scans its chunks and reduces them; the helpers leave
+// their results in the mail words, a second barrier, and wave 0 combines the nw results. Between scans the
+// helpers sleep at the first barrier and take no issue slots. Every scan costs wave 0 exactly two barriers,
+// every helper the same two; HC_EXIT ends the helpers' loop with one barrier on both sides.
+// mail[0..3] = command, time, request g, room under the cap; mail[8 + 4 w + i] = result i of wave w.
+enum { HC_EXIT = 0, HC_BEST_HOST, HC_EARLIEST_IDLE, HC_PLACE, HC_TICK };
+
+template <uint32_t F>
+__device__ __forceinline__ void helpers_go(const Ctx<F> &c, int cmd, int32_t now, int g, int32_t room) {
+  if (c.nw == 1) return;
+  if (c.lane == 0) *(int4 *)c.m.mail = make_int4(cmd, now, g, room);
+  __syncthreads();
+}
+template <uint32_t F>
+__device__ __forceinline__ void helpers_done(const Ctx<F> &c) {
+  if (c.nw > 1) __syncthreads();
+}
+// result i of helper wave w, as a uniform value (after helpers_done)
+template <uint32_t F>
+__device__ __forceinline__ uint32_t helper_result(const Ctx<F> &c, int w, int i) {
+  return uni((uint32_t)c.m.mail[8 + 4 * w + i]);
+}
+
 // lowest host index that is off (the caller has checked that one exists)
 template <uint32_t F>
 __device__ __forceinline__ int find_off_host(const Ctx<F> &c) {
@@ -417,31 +447,42 @@ __device__ __forceinline__ int boot_host(Ctx<F> &c, Regs &r, int32_t now, uint32
   return h;
 }
 
-// Best host for one more replica with request g: ready, under the cap (S <= room), optionally with g
-// idle GPUs now; smallest (committed, subscribed, index). Hosts ex0 / ex1 are skipped. Returns the packed key
+// Best host for one more replica with request g that is to bind its GPUs at once: ready, under the cap
+// (S <= room), with g idle GPUs now; smallest (committed, subscribed, index). Returns the packed key
 // (host in the low 10 bits) or 0xFFFFFFFF. any_idle: some ready host has g idle GPUs, cap aside.
+// _part: this wave's chunks of hosts.
 template <uint32_t F>
-__device__ __forceinline__ uint32_t best_host(const Ctx<F> &c, int32_t now, int g, int32_t room, bool need_idle,
-                                              int ex0, int ex1, bool &any_idle) {
-  wave_sync();
+__device__ __forceinline__ uint32_t best_host_part(const Ctx<F> &c, int32_t now, int g, int32_t room, bool &any_idle) {
   uint32_t best = 0xFFFFFFFFu;
   bool idle_seen = false;
-  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+  for (int h = c.wid * WAVE + c.lane; h < c.p.HP; h += WAVE * c.nw) {
     const int32_t ra = c.m.ready_at[h];
     const int S = (int)(c.m.hsn[h] & 0xFFFFu);
-    const bool capped = ra <= now && S <= room && h != ex0 && h != ex1;
+    const bool capped = ra <= now && S <= room;
     // the GPU rows are only read for a chunk of hosts in which somebody passes the cap (or while it
     // is still open whether any host has g idle GPUs)
-    if (wballot(capped) == 0 && (idle_seen || !need_idle)) continue;
+    if (wballot(capped) == 0 && idle_seen) continue;
     const int C = committed(c, h, now);
     const bool roomy = ra <= now && C + g <= c.p.G;
     idle_seen = idle_seen || wballot(roomy) != 0;
-    const bool ok = need_idle ? (capped && roomy) : capped;
     const uint32_t key = ((uint32_t)C << 22) | ((uint32_t)S << 10) | (uint32_t)h;
-    if (ok) best = umin(best, key);
+    if (capped && roomy) best = umin(best, key);
   }
   any_idle = idle_seen;
   return wave_min(best);
+}
+
+template <uint32_t F>
+__device__ __forceinline__ uint32_t best_host(const Ctx<F> &c, int32_t now, int g, int32_t room, bool &any_idle) {
+  wave_sync();
+  helpers_go(c, HC_BEST_HOST, now, g, room);
+  uint32_t key = best_host_part(c, now, g, room, any_idle);
+  helpers_done(c);
+  for (int w = 1; w < c.nw; w++) {
+    key = umin(key, helper_result(c, w, 0));
+    any_idle = any_idle || helper_result(c, w, 1) != 0;
+  }
+  return key;
 }
 
 // least subscribed-GPU count among the hosts that are on (ready or being provisioned)
@@ -483,11 +524,10 @@ __device__ __forceinline__ int32_t kth_free_time(const int4 a, const int4 b, int
 // (Section 3.4.1): no migration target before it, as long as no host is added and no host's
 // subscription shrinks (cap_bound_host_freed lowers the stored bound then). One lane sorts one host's row.
 template <uint32_t F>
-__device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g, int32_t room, int32_t &capped) {
-  wave_sync();
+__device__ __forceinline__ int32_t earliest_idle_part(const Ctx<F> &c, int g, int32_t room, int32_t &capped) {
   const int G = c.p.G;
   int32_t best = NEVER, best_cap = NEVER;
-  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+  for (int h = c.wid * WAVE + c.lane; h < c.p.HP; h += WAVE * c.nw) {
     int32_t y = kth_free_time(c.m.fin[2 * h], c.m.fin[2 * h + 1], G, g);
     const int32_t ra = c.m.ready_at[h];
     y = y > ra ? y : ra;
@@ -497,6 +537,20 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g, int32_t
   }
   capped = (int32_t)wave_min((uint32_t)best_cap);
   return (int32_t)wave_min((uint32_t)best);
+}
+
+template <uint32_t F>
+__device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g, int32_t room, int32_t &capped) {
+  wave_sync();
+  helpers_go(c, HC_EARLIEST_IDLE, 0, g, room);
+  int32_t best = earliest_idle_part(c, g, room, capped);
+  helpers_done(c);
+  for (int w = 1; w < c.nw; w++) {
+    const int32_t b = (int32_t)helper_result(c, w, 0), bc = (int32_t)helper_result(c, w, 1);
+    best = best < b ? best : b;
+    capped = capped < bc ? capped : bc;
+  }
+  return best;
 }
 
 // Host h now holds s_new subscribed GPUs, fewer than before (a session ended, a replica moved away): it
@@ -526,27 +580,25 @@ __device__ __forceinline__ void cl_schedule(Ctx<F> &c, Regs &r, uint32_t s, int3
   timer_push(c, r, (int32_t)t, QK_NEXT, s, e);
 }
 
-// ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
+// Placement candidates among this wave's chunks of hosts (Sections 3.2.1, 3.4.1): ready and under the cap;
+// one pass computes every host's key (strided over the lanes), three minima pick the three best
+// (0xFFFFFFFF where there are fewer).
 template <uint32_t F>
-__device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
-  if ((fl & 7u) != SS_UNPLACED) return;
-  const int g = (int)((fl >> 3) & 7u) + 1;
-  // one pass computes every host's key (strided over the lanes), three minima pick the hosts
+__device__ __forceinline__ void place_part(const Ctx<F> &c, int32_t now, int32_t room, uint32_t &m0, uint32_t &m1,
+                                           uint32_t &m2) {
   constexpr int MAXCH = NBOS_MAX_HOSTS / WAVE;
   uint32_t keys[MAXCH];
-  const int32_t room = cap_room(c, g);
-  wave_sync();
 #pragma unroll
   for (int j = 0; j < MAXCH; j++) {
     keys[j] = 0xFFFFFFFFu;
-    if (j * WAVE < c.p.HP) {
-      const int h = j * WAVE + c.lane;
+    const int h = (j * c.nw + c.wid) * WAVE + c.lane;
+    if (h - c.lane < c.p.HP) {
       const int S = (int)(c.m.hsn[h] & 0xFFFFu);
       if (c.m.ready_at[h] <= now && S <= room)
         keys[j] = ((uint32_t)committed(c, h, now) << 22) | ((uint32_t)S << 10) | (uint32_t)h;
     }
   }
-  int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
+  uint32_t out[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
 #pragma unroll
   for (int round = 0; round < 3; round++) {
     uint32_t best = 0xFFFFFFFFu;
@@ -554,12 +606,39 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
     for (int j = 0; j < MAXCH; j++) best = umin(best, keys[j]);
     const uint32_t m = wave_min(best);
     if (m == 0xFFFFFFFFu) break;
-    const int h = (int)(m & 1023u);
-    if (round == 0) pick0 = h; else if (round == 1) pick1 = h; else pick2 = h;
-    k = round + 1;
+    out[round] = m;
 #pragma unroll
     for (int j = 0; j < MAXCH; j++) keys[j] = keys[j] == m ? 0xFFFFFFFFu : keys[j];
   }
+  m0 = out[0]; m1 = out[1]; m2 = out[2];
+}
+
+// ---- SESSION_START: Sections 3.2.1, 3.4.1, 3.4.2 -----------------------------------------------
+template <uint32_t F>
+__device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, uint32_t fl, int32_t now) {
+  if ((fl & 7u) != SS_UNPLACED) return;
+  const int g = (int)((fl >> 3) & 7u) + 1;
+  const int32_t room = cap_room(c, g);
+  wave_sync();
+  helpers_go(c, HC_PLACE, now, g, room);
+  uint32_t m0, m1, m2;
+  place_part(c, now, room, m0, m1, m2);
+  if (c.nw > 1) {
+    // the three best of every wave meet in the mail words: the three best of those are the hosts
+    if (c.lane == 0) { c.m.mail[8] = (int)m0; c.m.mail[9] = (int)m1; c.m.mail[10] = (int)m2; }
+    helpers_done(c);
+    uint32_t key = 0xFFFFFFFFu;
+    if (c.lane < 4 * c.nw && (c.lane & 3) != 3) key = (uint32_t)c.m.mail[8 + c.lane];
+    m0 = wave_min(key);
+    key = key == m0 ? 0xFFFFFFFFu : key;
+    m1 = wave_min(key);
+    key = key == m1 ? 0xFFFFFFFFu : key;
+    m2 = wave_min(key);
+  }
+  int pick0 = -1, pick1 = -1, pick2 = -1, k = 0;
+  if (m0 != 0xFFFFFFFFu) { pick0 = (int)(m0 & 1023u); k = 1; }
+  if (m1 != 0xFFFFFFFFu) { pick1 = (int)(m1 & 1023u); k = 2; }
+  if (m2 != 0xFFFFFFFFu) { pick2 = (int)(m2 & 1023u); k = 3; }
   const int missing = 3 - k;
   if (missing > 0) {
     wave_sync();
@@ -723,7 +802,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       const int32_t room = cap_room(c, g);
       if (r.min_s <= room) {
         bool any_idle;
-        tkey = best_host(c, now, g, room, true, -1, -1, any_idle);
+        tkey = best_host(c, now, g, room, any_idle);
         if (!any_idle) {
           // No host at all with g idle GPUs: work out when the first one could have them, once, for
           // every later attempt with a request of g or more.
@@ -736,7 +815,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       // (before that time no host that passes the cap can have the GPUs idle: nothing to look for)
       const int32_t room = c.slim - g;
       bool any_idle;
-      tkey = best_host(c, now, g, room, true, -1, -1, any_idle);
+      tkey = best_host(c, now, g, room, any_idle);
       if (tkey == 0xFFFFFFFFu) {
         // No target: work out when the first host could have g idle GPUs, and the first one among those
         // under the cap, once, for every later attempt with a request of g or more.
@@ -864,24 +943,69 @@ __device__ __forceinline__ void release_host(Ctx<F> &c, Regs &r, int32_t now) {
   decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
 }
 
+// this wave's chunks of hosts: ready hosts, ready hosts without replicas, committed GPUs (auto-scaler only)
 template <uint32_t F>
-__device__ __forceinline__ void tick(Ctx<F> &c, Regs &r, int32_t now) {
-  wave_sync();
+__device__ __forceinline__ void tick_part(const Ctx<F> &c, int32_t now, int &A, int &Z, uint32_t &sum_c) {
   const bool autoscale = (c.flags() & NBOS_F_AUTOSCALE) != 0;
-  int A = 0, Z = 0;
+  A = 0; Z = 0;
   uint32_t busy = 0;                       // this lane's share of sum C
-  for (int base = 0; base < c.p.HP; base += WAVE) {
-    const int h = base + c.lane;
+  for (int h = c.wid * WAVE + c.lane; h < c.p.HP; h += WAVE * c.nw) {
     const bool ready = c.m.ready_at[h] <= now;
     A += __builtin_popcountll(wballot(ready));
     Z += __builtin_popcountll(wballot(ready && (c.m.hsn[h] >> 16) == 0));
     if (autoscale) busy += (uint32_t)committed(c, h, now);
   }
+  sum_c = autoscale ? (uint32_t)wave_sum(busy) : 0u;
+}
+
+// What the helper waves (wave 1 and up) do for the whole kernel: see "helper waves" above.
+template <uint32_t F>
+__device__ __forceinline__ void helper_loop(const Ctx<F> &c) {
+  for (;;) {
+    __syncthreads();
+    const int4 cmd = *(const int4 *)c.m.mail;
+    const int what = uni(cmd.x), g = uni(cmd.z);
+    const int32_t now = uni(cmd.y), room = uni(cmd.w);
+    if (what == HC_EXIT) break;
+    uint32_t r0 = 0, r1 = 0, r2 = 0;
+    if (what == HC_BEST_HOST) {
+      bool idle;
+      r0 = best_host_part(c, now, g, room, idle);
+      r1 = idle ? 1u : 0u;
+    } else if (what == HC_EARLIEST_IDLE) {
+      int32_t capped;
+      r0 = (uint32_t)earliest_idle_part(c, g, room, capped);
+      r1 = (uint32_t)capped;
+    } else if (what == HC_PLACE) {
+      place_part(c, now, room, r0, r1, r2);
+    } else {
+      int A, Z;
+      tick_part(c, now, A, Z, r2);
+      r0 = (uint32_t)A; r1 = (uint32_t)Z;
+    }
+    if (c.lane == 0) { c.m.mail[8 + 4 * c.wid] = (int)r0; c.m.mail[9 + 4 * c.wid] = (int)r1; c.m.mail[10 + 4 * c.wid] = (int)r2; }
+    __syncthreads();
+  }
+}
+
+template <uint32_t F>
+__device__ __forceinline__ void tick(Ctx<F> &c, Regs &r, int32_t now) {
+  wave_sync();
+  const bool autoscale = (c.flags() & NBOS_F_AUTOSCALE) != 0;
+  helpers_go(c, HC_TICK, now, 0, 0);
+  int A, Z;
+  uint32_t sum_c;
+  tick_part(c, now, A, Z, sum_c);
+  helpers_done(c);
+  for (int w = 1; w < c.nw; w++) {
+    A += (int)helper_result(c, w, 0);
+    Z += (int)helper_result(c, w, 1);
+    sum_c += helper_result(c, w, 2);
+  }
   int released = 0;
   if (autoscale) {
     // expected capacity f * sum C in whole hosts plus the scaling buffer; hosts being provisioned
     // count as capacity
-    const uint32_t sum_c = (uint32_t)wave_sum(busy);
     const uint32_t per_host = 1000u * (uint32_t)c.p.G;
     const int want = (int)(((uint32_t)c.p.f_milli * sum_c + per_host - 1u) / per_host) + c.p.buffer;
     int n_on = (int)uni(c.m.c32[CS_NON]);
@@ -1121,6 +1245,7 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   m.c32 = (uint32_t *)q;            q += 16 * 4;
   m.hist = (uint32_t *)q;           q += 32 * 4;
   m.ppow = (unsigned long long *)q; q += 66 * 8;
+  m.mail = (int32_t *)q;            q += 32 * 4;
   m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
   m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
   m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
@@ -1133,36 +1258,38 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   return m;
 }
 
-// hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
+// hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced (all threads of the workgroup take part)
 template <bool CL>
-__device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int lane, int s_lo, int n_sess) {
-  if (lane < 8) m.c64[lane] = 0;
-  if (lane < 16) m.c32[lane] = lane == CS_NON || lane == CS_PEAK ? (uint32_t)p.H0 : 0u;
-  if (lane < 32) m.hist[lane] = 0;
-  if (lane == 0) {
+__device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int s_lo, int n_sess) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  if (tid < 8) m.c64[tid] = 0;
+  if (tid < 16) m.c32[tid] = tid == CS_NON || tid == CS_PEAK ? (uint32_t)p.H0 : 0u;
+  if (tid < 32) { m.hist[tid] = 0; m.mail[tid] = 0; }
+  if (tid == 0) {
     unsigned long long pw = 1;
     for (int i = 0; i <= 64; i++) { m.ppow[i] = pw; pw *= 0x100000001B3ULL; }
   }
-  for (int i = lane; i < 2 * p.HP; i += WAVE) m.fin[i] = make_int4(0, 0, 0, 0);
-  for (int h = lane; h < p.HP; h += WAVE) {
+  for (int i = tid; i < 2 * p.HP; i += nt) m.fin[i] = make_int4(0, 0, 0, 0);
+  for (int h = tid; h < p.HP; h += nt) {
     m.ready_at[h] = h < p.H0 ? 0 : NEVER;
     m.mark[h] = MARK_FREE;
     m.hsn[h] = 0;
   }
   if (p.warm_n > 0) {
-    for (int i = lane; i < 4 * p.HP; i += WAVE) m.warm[i] = 0;     // initial hosts: warm from time 0
+    for (int i = tid; i < 4 * p.HP; i += nt) m.warm[i] = 0;     // initial hosts: warm from time 0
   }
-  for (int s = lane; s < n_sess; s += WAVE) {
+  for (int s = tid; s < n_sess; s += nt) {
     const uint32_t g = p.sess_gpus[s_lo + s];
     m.sess[s].x = 0; m.sess[s].y = 0; m.sess[s].z = (int)(SS_UNPLACED | ((g - 1u) << 3));
   }
-  for (int s = lane; s < (p.n_cap + 3) / 4 * 4; s += WAVE) m.due[s] = NEVER;
+  for (int s = tid; s < (p.n_cap + 3) / 4 * 4; s += nt) m.due[s] = NEVER;
   __syncthreads();
 }
 
 // ---- S10: close the integrals at t_end and write the result record ---------------------------------
-__device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, const Regs &r, int rep, int lane) {
-  __syncthreads();
+__device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, const Regs &r, int rep) {
+  __syncthreads();                          // every wave of the workgroup comes here; wave 0 holds the results
+  const int lane = threadIdx.x;
   const int32_t t_end = r.t_end > r.lazy_max ? r.t_end : r.lazy_max;
   nbos_stats *out = p.stats + rep;
   if (lane < 32) out->delay_hist[lane] = m.hist[lane] + (lane == 0 ? r.h0 : 0u);
@@ -1189,10 +1316,10 @@ __device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, cons
 }
 
 template <uint32_t F>
-__global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
+__global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & (WAVE - 1);
   if (rep >= p.n_replays) return;
 
   const int trace = p.trace_of_replay[rep];
@@ -1201,13 +1328,15 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   const int n_sess = p.sess_offset[trace + 1] - s_lo;
 
   const Lds m = lds_carve<false>(p, lds_raw);
-  lds_init<false>(p, m, lane, s_lo, n_sess);
+  lds_init<false>(p, m, s_lo, n_sess);
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
   Ctx<F> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
         NEVER, 0, 0xFFFFFFFFu, 0xFFFFFFFFu, 0};
   c.n_sess = n_sess;
   c.ovf_dur = p.ovf_dur + (int64_t)rep * p.n_cap;
+  c.nw = (int)(blockDim.x / WAVE);
+  c.wid = (int)(threadIdx.x / WAVE);
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
@@ -1215,6 +1344,9 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
   r.o_min_t = NEVER;
   r.min_s = -1;
   r.cl_win = 1024;
+  if (c.wid != 0) {
+    helper_loop(c);
+  } else {
 
   const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   const bool batching = p.batch != 0;
@@ -1400,8 +1532,10 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_lds_kernel(KParams p) {
     }
     if (final) break;
   }
+  helpers_go(c, HC_EXIT, 0, 0, 0);
+  }  // wave 0
 
-  write_stats(p, m, r, rep, lane);
+  write_stats(p, m, r, rep);
 }
 
 }  // namespace ldsk

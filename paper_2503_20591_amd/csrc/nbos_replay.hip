@@ -199,6 +199,7 @@ struct nbos_replay {
   int device;
   KParams kp;
   size_t lds_bytes;
+  int threads;             // per workgroup: one wave, or four on large clusters (three helper waves for the scans)
   const void *kernel;      // the kernel instance chosen at create
   char kernel_name[96];    // as a profiler prints it, without the argument list
   nbos_stats *d_stats;
@@ -257,7 +258,8 @@ int32_t check_config(const nbos_config *cfg, const nbos_inputs *in) {
   if (cfg->hosts_max > NBOS_MAX_HOSTS) return NBOS_E_LIMIT;
   if (cfg->migration_delay_ms < 0 || cfg->boot_delay_ms < 0 || cfg->retry_interval_ms < 1) return NBOS_E_ARG;
   if (cfg->max_retries < 0 || cfg->max_retries > NBOS_MAX_RETRIES) return NBOS_E_ARG;
-  constexpr uint32_t kComparison = NBOS_F_HOSTS_IN_LDS | NBOS_F_GENERIC_KERNEL | NBOS_F_ROUNDS_OFF | NBOS_F_ROUNDS_ON;
+  constexpr uint32_t kComparison = NBOS_F_HOSTS_IN_LDS | NBOS_F_GENERIC_KERNEL | NBOS_F_ROUNDS_OFF | NBOS_F_ROUNDS_ON |
+                                   NBOS_F_ONE_WAVE;
   if (cfg->flags & ~(NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_DECISION_LOG | kComparison |
                      NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR | NBOS_F_STICKY_EXECUTOR | NBOS_F_BATCH_MODE | NBOS_F_WARM_POOL |
                      NBOS_F_CLOSED_LOOP))
@@ -414,6 +416,8 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
   sh->in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
   sh->HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
+  // the kernels with host state in LDS give the scans over all hosts to four waves from 256 hosts on
+  h->threads = (!sh->in_regs && !batch_mode && sh->HP >= 4 * WAVE && !(cfg->flags & NBOS_F_ONE_WAVE)) ? 4 * WAVE : WAVE;
   sh->n_cap = sh->max_sess > 0 ? sh->max_sess : 1;
   sh->q_cap = (size_t)sh->n_cap + 1;               // at most one queued timer per session
   const int HP = sh->HP;
@@ -434,7 +438,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     else set_reg_closed_kernel<regk::kRuntimeClosed>(h, nj);
   } else if (closed_loop) {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
-    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + 128 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
                    (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     sh->q_cap = 0;
@@ -452,7 +456,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     if (rc != NBOS_OK) return rc;
   } else {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
-    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + 128 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
                    (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     sh->q_cap = 0;
@@ -593,7 +597,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (!h) return NBOS_E_NOMEM;
   h->cfg = cfg; h->in = *in; h->stream = (hipStream_t)stream;
   h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_chain = nullptr; h->d_log = nullptr;
-  h->kernel = nullptr; h->kernel_name[0] = 0; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
+  h->kernel = nullptr; h->kernel_name[0] = 0; h->threads = WAVE; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   memset(&h->kp, 0, sizeof h->kp);
   Shape sh;
   g_detail[0] = 0;
@@ -613,7 +617,7 @@ int32_t nbos_replay_run(nbos_replay *h) {
   if (hipEventRecord(h->e0, h->stream) != hipSuccess) return NBOS_E_HIP;
   if (h->cfg.n_replays > 0) {
     void *args[] = {(void *)&h->kp};
-    if (hipLaunchKernel(h->kernel, dim3(h->cfg.n_replays), dim3(WAVE), args, h->lds_bytes, h->stream) != hipSuccess)
+    if (hipLaunchKernel(h->kernel, dim3(h->cfg.n_replays), dim3(h->threads), args, h->lds_bytes, h->stream) != hipSuccess)
       return NBOS_E_HIP;
   }
   if (hipEventRecord(h->e1, h->stream) != hipSuccess) return NBOS_E_HIP;
@@ -681,7 +685,7 @@ int32_t nbos_replay_last_kernel_ms(nbos_replay *h, float *ms_out) {
 int32_t nbos_replay_launch_info(nbos_replay *h, int32_t *lds_bytes, int32_t *threads_per_group, int32_t *groups) {
   if (!h) return NBOS_E_ARG;
   if (lds_bytes) *lds_bytes = (int32_t)h->lds_bytes;
-  if (threads_per_group) *threads_per_group = WAVE;
+  if (threads_per_group) *threads_per_group = h->threads;
   if (groups) *groups = h->cfg.n_replays;
   return NBOS_OK;
 }
@@ -723,7 +727,7 @@ int32_t nbos_replay_run_static(const nbos_config *cfg_in, const nbos_inputs *in,
   }
 
   nbos_replay tmp{};                      // never leaves this call; its vectors stay empty
-  tmp.cfg = cfg; tmp.in = *in; tmp.stream = (hipStream_t)stream; tmp.device = dev;
+  tmp.cfg = cfg; tmp.in = *in; tmp.stream = (hipStream_t)stream; tmp.device = dev; tmp.threads = WAVE;
   const bool warm_pool = (cfg.flags & NBOS_F_WARM_POOL) != 0;
   tmp.lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8;
   int maxlds = 0;

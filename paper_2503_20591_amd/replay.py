@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnbos.so
 F_MIGRATE, F_SCALE_OUT, F_SCALE_IN, F_DECISION_LOG, F_HOSTS_IN_LDS = 1, 2, 4, 8, 16
 F_AUTOSCALE, F_DYNAMIC_SR, F_STICKY_EXECUTOR, F_BATCH_MODE, F_WARM_POOL = 0x20, 0x40, 0x80, 0x100, 0x200
 F_CLOSED_LOOP = 0x400
-F_GENERIC_KERNEL, F_ROUNDS_OFF, F_ROUNDS_ON = 0x800, 0x1000, 0x2000     # comparison runs: same results
+F_GENERIC_KERNEL, F_ROUNDS_OFF, F_ROUNDS_ON, F_ONE_WAVE = 0x800, 0x1000, 0x2000, 0x4000   # comparison runs: same results
 E_ARG, E_RANGE, E_LIMIT, E_HIP, E_NOMEM, E_STATE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("nbos_replay_create", "nbos_replay_run", "nbos_replay_stats", "nbos_replay_decisions",
@@ -157,7 +157,7 @@ class Replay:
 
     def __init__(self, cfg: dict, inputs: dict, n_replays: int | None = None, n_traces: int | None = None,
                  stream=None, decision_log: bool = False, hosts_in_lds: bool = False,
-                 generic_kernel: bool = False, rounds: bool | None = None):
+                 generic_kernel: bool = False, rounds: bool | None = None, one_wave: bool = False):
         import torch
         lib = load()
         self._lib = lib
@@ -167,7 +167,7 @@ class Replay:
         self.n_replays = n_replays
         self.config = make_config(cfg, n_replays, n_traces, (F_DECISION_LOG if decision_log else 0)
                                   | (F_HOSTS_IN_LDS if hosts_in_lds else 0)
-                                  | (F_GENERIC_KERNEL if generic_kernel else 0)
+                                  | (F_GENERIC_KERNEL if generic_kernel else 0) | (F_ONE_WAVE if one_wave else 0)
                                   | (0 if rounds is None else F_ROUNDS_ON if rounds else F_ROUNDS_OFF))
         ins = NbosInputs()
         for name in _INPUT_FIELDS:

@@ -68,7 +68,7 @@ def _create(lib, cfg, n_replays=1, n_traces=1, inputs=True, struct_size=None, ou
     dict(flags=0x20, scale_interval_ms=0), dict(flags=0x20, autoscale_f_milli=-1), dict(flags=0x20, autoscale_f_milli=100_001),
     dict(flags=0x20, scaling_buffer_hosts=-1), dict(flags=0x20, scaling_buffer_hosts=1025), dict(flags=0x24, min_hosts=-1),
     dict(flags=4, scale_in_idle_pct=101), dict(retry_interval_ms=2_000_000_000, max_retries=15),
-    dict(flags=0x3000), dict(flags=0x4000)])
+    dict(flags=0x3000), dict(flags=0x10000)])
 def test_create_rejects_bad_config(lib, bad):
     # no replays, so null arrays are fine and only the parameters can be at fault
     assert _create(lib, _cfg(**bad), n_replays=0) == replay.E_ARG

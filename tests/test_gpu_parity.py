@@ -24,9 +24,10 @@ def rp():
     return replay
 
 
-def gpu_run(rp, batch, log=False, in_lds=False, generic=False, rounds=None):
+def gpu_run(rp, batch, log=False, in_lds=False, generic=False, rounds=None, one_wave=False):
     dev = rp.upload(batch)
-    h = rp.Replay(batch.config, dev, decision_log=log, hosts_in_lds=in_lds, generic_kernel=generic, rounds=rounds)
+    h = rp.Replay(batch.config, dev, decision_log=log, hosts_in_lds=in_lds, generic_kernel=generic, rounds=rounds,
+                  one_wave=one_wave)
     h.run()
     st = h.stats()
     logs = [h.decisions(r) for r in range(batch.n_replays)] if log else None
@@ -464,12 +465,38 @@ def test_named_workloads(rp, oracle, name, n, in_lds):
     assert_same(rp, oracle, b, st, logs)
 
 
-def test_named_workload_c4_many_hosts(rp, oracle):
-    # 512 -> 768 hosts: twelve hosts per lane, scale-out, scale-in, END events
+@pytest.mark.parametrize("one_wave", [False, True], ids=["helper-waves", "one-wave"])
+def test_named_workload_c4_many_hosts(rp, oracle, one_wave):
+    # 512 -> 768 hosts: twelve chunks of 64 hosts per scan (shared by four waves, or all in one), scale-out,
+    # scale-in, END events
     b = tg.workload("c4", n_replays=2)
-    st, logs = gpu_run(rp, b, log=True)
+    dev = rp.upload(b)
+    h = rp.Replay(b.config, dev, decision_log=True, one_wave=one_wave)
+    assert h.launch_info()["threads_per_group"] == (64 if one_wave else 256)
+    h.close()
+    st, logs = gpu_run(rp, b, log=True, one_wave=one_wave)
     assert_same(rp, oracle, b, st, logs)
     assert st["scale_out_hosts"].min() > 0
+
+
+@pytest.mark.parametrize("name,n", [("c4a", 2), ("c4l", 2)])
+def test_large_clusters_without_helper_waves(rp, oracle, name, n):
+    # the auto-scaler workload and the closed loop on one wave per replay (the default there is four)
+    b = tg.workload(name, n_replays=n)
+    st, logs = gpu_run(rp, b, log=True, one_wave=True)
+    assert_same(rp, oracle, b, st, logs)
+
+
+@pytest.mark.parametrize("hosts", [192, 193, 256, 320, 1000, 1024])
+def test_helper_waves_on_ragged_host_counts(rp, oracle, hosts):
+    # 193 hosts and more run with helper waves: host counts that leave some waves without a chunk, or with a
+    # partly filled one; migration, scale-out from a smaller start, periodic scale-in, END events
+    cfg = tg.workload("c4", n_replays=1).config
+    b = tg.workload("c4" if hosts <= 768 else "c3", n_replays=1)      # (8,000 sessions fit beside 768 hosts at most)
+    b.config = dict(cfg, hosts_initial=max(hosts - 40, 1), hosts_max=hosts, min_hosts=hosts // 2)
+    b.cap_milli[:] = 400                      # a low cap: placements run out of hosts and add some
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
 
 
 # ---- the benchmark configuration at full size: sampled replays + properties that hold for all -----
