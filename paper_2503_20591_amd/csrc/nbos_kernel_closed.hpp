@@ -152,7 +152,7 @@ __device__ __forceinline__ void cl_after_round(Ctx<F> &c, Regs &r, int n) {
 }
 
 template <uint32_t F>
-__global__ void __launch_bounds__(4 * WAVE) nbos_replay_closed_kernel(KParams p) {
+__global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KParams p) {
   static_assert(Ctx<F>::closed, "instantiate with a closed-loop flag set");
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;

@@ -1,7 +1,7 @@
 // nbos_kernel_lds.hpp — replay kernel with host state in LDS: any cluster size up to NBOS_MAX_HOSTS.
 // Used when hosts_max > 64 (or on request). One workgroup per replay: one wave64 runs the replay; on
-// clusters of 256 hosts or more three more waves of the workgroup (each on a SIMD of its own, asleep at
-// a barrier in between) take their share of every scan over all hosts (see "helper waves" below).
+// clusters of 256 hosts or more, more waves of the workgroup (asleep at a barrier in between) take their
+// share of every scan over all hosts (see "helper waves" below).
 //
 // LDS per replay
 //   fin[h][8]    per-GPU "busy until" times, one 32-byte row per host. A GPU is committed at time t
@@ -63,7 +63,7 @@ struct Lds {
   SessRec *sess;
   int32_t *due;                // [n_cap] time of a session's timer while it waits outside the registers, else NEVER
   int32_t *stage;              // [64] sessions whose timers move into the registers
-  int32_t *mail;               // [32] what the helper waves are to do, and what they found (see helpers_go)
+  int32_t *mail;               // [MAIL_WORDS] what the helper waves are to do, and what they found (see helpers_go)
 };
 
 struct Regs {
@@ -400,6 +400,9 @@ __device__ __forceinline__ void bind_gpus(Ctx<F> &c, int h, int g, int32_t now, 
 // every helper the same two; HC_EXIT ends the helpers' loop with one barrier on both sides.
 // mail[0..3] = command, time, request g, room under the cap; mail[8 + 4 w + i] = result i of wave w.
 enum { HC_EXIT = 0, HC_BEST_HOST, HC_EARLIEST_IDLE, HC_PLACE, HC_TICK };
+// (more than four waves gain nothing measurable: 12 chunks of hosts on 4 / 6 / 8 / 12 waves take 269 / 265 / 266 /
+// 269 ms on the 768-host workload, and a workgroup of more than 256 threads leaves the compiler fewer registers)
+constexpr int MAX_WAVES = 4, MAIL_WORDS = 8 + 4 * MAX_WAVES;
 
 template <uint32_t F>
 __device__ __forceinline__ void helpers_go(const Ctx<F> &c, int cmd, int32_t now, int g, int32_t room) {
@@ -1115,32 +1118,73 @@ __device__ __forceinline__ int32_t retry_horizon(Ctx<F> &c, const Regs &r, int32
   return lim;
 }
 
-// The earliest timer is a retry that fails quietly: count it and move its timer one interval on.
-// Returns false if it is no such retry (nothing but the marks of retry_lookahead is changed then).
+// The due timers at the head of the sorted registers that are retries known to fail quietly - all of them up
+// to the first timer that is not, "due" meaning at or before t_limit - fire at once, lane = timer: each
+// counts its retry in its session's record and moves one retry interval on. The timers that are then no
+// longer earlier than everything that waits in the session records go there; the others are merged back
+// into the sorted registers (both parts are sorted already: a timer's new place is its rank in its own part
+// plus the number of timers of the other part before it). queued_lanes: lanes of the current tile whose
+// prefetched record showed a queued session (the records of the retries fired here are among those, or
+// stale already). Returns false if the earliest timer is no such retry (nothing but the marks of
+// retry_lookahead is changed then).
 template <uint32_t F>
-__device__ __forceinline__ bool fire_quiet_retry(Ctx<F> &c, Regs &r) {
-  const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
-  if ((key >> 16) != QK_RETRY) return false;
-  if (!((uint32_t)lane_get(c.qd, 0) & QD_LOOKED)) retry_lookahead(c, r);
-  const uint32_t d0 = (uint32_t)lane_get(c.qd, 0);
-  if (!(d0 & QD_EFAIL)) return false;
-  const int32_t now = r.q_head_t;
-  const int g = (int)((d0 >> QD_G_SHIFT) & 7u) + 1;
-  if (c.flags() & NBOS_F_MIGRATE) {
-    const int32_t bu = lane_get(c.fu, g - 1), bc = lane_get(c.fc, g - 1);
-    if (now >= (bu > bc ? bu : bc)) return false;
-  }
+__device__ __forceinline__ bool fire_quiet_retries(Ctx<F> &c, Regs &r, int32_t t_limit, uint64_t queued_lanes) {
+  if (((uint32_t)lane_get((int)c.qk, 0) >> 16) != QK_RETRY) return false;
+  if (wballot(c.lane < r.q_n && (c.qk >> 16) == QK_RETRY && !((uint32_t)c.qd & QD_LOOKED) && c.qt <= t_limit) != 0)
+    retry_lookahead(c, r);
+  if (!((uint32_t)lane_get(c.qd, 0) & QD_EFAIL)) return false;
   if (can_grow(c)) return false;
-  const uint32_t s = key & 0xFFFFu;
+  const uint64_t loud = ~wballot(retry_is_quiet(c, r) && c.qt <= t_limit);
+  const int n = loud != 0 ? (int)__builtin_ctzll(loud) : WAVE;        // (quiet timers are below q_n)
+  if (n == 0) return false;
+  const bool mine = c.lane < n;
+  const int32_t last = lane_get(c.qt, n - 1);
+  r.t_end = r.t_end > last ? r.t_end : last;
+  r.dirty |= queued_lanes;
   wave_sync();
-  const uint32_t fl = uni((uint32_t)c.m.sess[s].z);
-  const int32_t t_submit = uni(c.m.sess[s].y);
-  const int retries = (int)((fl >> 8) & 15u) + 1;                       // below max_retries before: see retry_lookahead
-  if (c.lane == 0) c.m.sess[s].z = (int)((fl & ~(15u << 8)) | ((uint32_t)retries << 8));
-  r.dirty |= wballot(c.vsid == s);
-  r.t_end = r.t_end > now ? r.t_end : now;
-  timer_pop(c, r);
-  timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, (int32_t)(d0 & (uint32_t)QD_DUR_MASK));
+  const uint32_t s = c.qk & 0xFFFFu;
+  int32_t nt = c.qt;
+  bool far = false;
+  if (mine) {
+    const uint32_t fl = (uint32_t)c.m.sess[s].z;
+    const int retries = (int)((fl >> 8) & 15u) + 1;                    // below max_retries before: see retry_lookahead
+    nt = c.m.sess[s].y + retries * c.p.retry_iv;
+    far = r.o_n > 0 && !(nt < r.o_min_t || (nt == r.o_min_t && c.qk < r.o_min_k));
+    uint32_t nfl = (fl & ~(15u << 8)) | ((uint32_t)retries << 8);
+    if (far) {
+      nfl = (nfl & ~(3u << CL_KIND_SHIFT)) | (QK_RETRY << CL_KIND_SHIFT);
+      c.m.due[s] = nt;
+      c.ovf_dur[s] = c.qd & QD_DUR_MASK;
+    }
+    c.m.sess[s].z = (int)nfl;
+  }
+  const uint64_t far_m = wballot(far);
+  const uint64_t near_m = wballot(mine && !far);
+  const bool kept = c.lane >= n && c.lane < r.q_n;
+  r.o_n += __builtin_popcountll(far_m);
+  // merge: the timers that stay where they are (kept) and those that moved on inside the registers (near)
+  int pos = kept ? c.lane - n : lane_rank(near_m);
+  for (uint64_t w = near_m; w != 0; w &= w - 1) {
+    const int j = (int)__builtin_ctzll(w);
+    const int32_t tj = lane_get(nt, j);
+    const uint32_t kj = (uint32_t)lane_get((int)c.qk, j);
+    const bool before_j = c.qt < tj || (c.qt == tj && c.qk < kj);     // (kept lanes: their own key)
+    const int kept_before = __builtin_popcountll(wballot(kept && before_j));
+    if (kept && !before_j) pos++;
+    if (c.lane == j) pos += kept_before;
+  }
+  const int alive = r.q_n - __builtin_popcountll(far_m);
+  const bool dead = !(kept || (mine && !far));
+  if (dead) pos = alive + lane_rank(wballot(dead));
+  const int32_t vt = dead ? NEVER : nt;
+  const int32_t vd = dead ? 0 : (mine ? (c.qd & QD_DUR_MASK) : c.qd);
+  const uint32_t vk = dead ? 0xFFFFFFFFu : c.qk;
+  c.qt = __builtin_amdgcn_ds_permute(pos << 2, vt);
+  c.qd = __builtin_amdgcn_ds_permute(pos << 2, vd);
+  c.qk = (uint32_t)__builtin_amdgcn_ds_permute(pos << 2, (int)vk);
+  r.q_n = alive;
+  if (r.q_n == 0 && r.o_n > 0) refill(c, r);
+  r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
   return true;
 }
 
@@ -1245,7 +1289,7 @@ __device__ __forceinline__ Lds lds_carve(const KParams &p, unsigned char *q) {
   m.c32 = (uint32_t *)q;            q += 16 * 4;
   m.hist = (uint32_t *)q;           q += 32 * 4;
   m.ppow = (unsigned long long *)q; q += 66 * 8;
-  m.mail = (int32_t *)q;            q += 32 * 4;
+  m.mail = (int32_t *)q;            q += MAIL_WORDS * 4;
   m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
   m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
   m.mark = (int32_t *)q;            q += (size_t)p.HP * 4;
@@ -1264,7 +1308,8 @@ __device__ __forceinline__ void lds_init(const KParams &p, const Lds &m, int s_l
   const int tid = threadIdx.x, nt = blockDim.x;
   if (tid < 8) m.c64[tid] = 0;
   if (tid < 16) m.c32[tid] = tid == CS_NON || tid == CS_PEAK ? (uint32_t)p.H0 : 0u;
-  if (tid < 32) { m.hist[tid] = 0; m.mail[tid] = 0; }
+  if (tid < 32) m.hist[tid] = 0;
+  if (tid < MAIL_WORDS) m.mail[tid] = 0;
   if (tid == 0) {
     unsigned long long pw = 1;
     for (int i = 0; i <= 64; i++) { m.ppow[i] = pw; pw *= 0x100000001B3ULL; }
@@ -1316,7 +1361,7 @@ __device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, cons
 }
 
 template <uint32_t F>
-__global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
+__global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int rep = blockIdx.x;
   const int lane = threadIdx.x & (WAVE - 1);
@@ -1425,6 +1470,9 @@ __global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
       r.lazy_max = r.lazy_max > bl ? r.lazy_max : bl;
     }
     const uint64_t fastmask = wballot(fast);
+    const uint64_t queued_lanes = wballot(((uint32_t)rec.z & 7u) == SS_QUEUED);
+    bool hz_known = false;
+    int32_t hz = 0;
     for (;;) {
       if (r.status != NBOS_OK) break;
       int i = 0;
@@ -1442,7 +1490,7 @@ __global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
           // the run may go on past retries that are known to fail quietly
           int32_t run_due = due_t;
           if (look_ahead && due_t == r.q_head_t && due_t <= last_t) {
-            const int32_t hz = retry_horizon(c, r, last_t);
+            if (!hz_known) { hz = retry_horizon(c, r, last_t); hz_known = true; }    // (rounds change nothing it looks at)
             run_due = hz < tick_t ? hz : tick_t;
           }
           const uint64_t eligible = clean & wballot(vt < run_due);
@@ -1458,6 +1506,7 @@ __global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
         }
         if (cooldown > 0) cooldown--;
         // ---- arrival i, serial ----
+        hz_known = false;
         todo &= ~bit;
         const uint32_t sk = (uint32_t)lane_get(vs, i);
         const uint32_t s = sk & 0xFFFFFFu;
@@ -1492,6 +1541,7 @@ __global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
         }
       } else {
         // ---- a timer may be due (S2); always taken while draining ----
+        hz_known = false;
         bool fire_q = r.q_n > 0, fire_t = ticking;
         if (final) {
           if (fire_t) fire_t = fire_q ? tick_t < r.q_head_t : tick_t < r.lazy_max;
@@ -1508,7 +1558,9 @@ __global__ void __launch_bounds__(4 * WAVE) nbos_replay_lds_kernel(KParams p) {
           continue;
         }
         if (!fire_q) break;                   // only reached while draining: nothing is left
-        if (look_ahead && fire_quiet_retry(c, r)) {
+        // (timers fire up to the next arrival, and up to the next auto-scaler period: that one runs after the
+        // timers of its own instant and before all later ones)
+        if (look_ahead && fire_quiet_retries(c, r, t < tick_t ? t : tick_t, queued_lanes)) {
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
           continue;
         }

@@ -417,7 +417,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   sh->in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
   sh->HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
   // the kernels with host state in LDS give the scans over all hosts to four waves from 256 hosts on
-  h->threads = (!sh->in_regs && !batch_mode && sh->HP >= 4 * WAVE && !(cfg->flags & NBOS_F_ONE_WAVE)) ? 4 * WAVE : WAVE;
+  h->threads = (!sh->in_regs && !batch_mode && sh->HP >= 4 * WAVE && !(cfg->flags & NBOS_F_ONE_WAVE)) ? ldsk::MAX_WAVES * WAVE : WAVE;
   sh->n_cap = sh->max_sess > 0 ? sh->max_sess : 1;
   sh->q_cap = (size_t)sh->n_cap + 1;               // at most one queued timer per session
   const int HP = sh->HP;
@@ -438,7 +438,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     else set_reg_closed_kernel<regk::kRuntimeClosed>(h, nj);
   } else if (closed_loop) {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
-    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + 128 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + ldsk::MAIL_WORDS * 4 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
                    (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     sh->q_cap = 0;
@@ -456,7 +456,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     if (rc != NBOS_OK) return rc;
   } else {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
-    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + 128 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
+    h->lds_bytes = 64 + 64 + 128 + 66 * 8 + ldsk::MAIL_WORDS * 4 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
                    (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     sh->q_cap = 0;
