@@ -586,6 +586,52 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
   if constexpr (Ctx<NJ, F>::closed) cl_schedule(c, r, s, finish);
 }
 
+// ---- executor election, Section 3.2.2 ----------------------------------------------------------------
+// Among the session's hosts in `cand` (ready, g idle GPUs; not empty): fewest committed GPUs, then lowest
+// host index. At most three bits of `cand` are set: walk them. Returns the host.
+template <int NJ, uint32_t F>
+__device__ __forceinline__ int elect(const Ctx<NJ, F> &c, uint32_t hw, int C, uint64_t idle_ok, uint64_t cand) {
+  const uint32_t key = ((uint32_t)C << 6) | (uint32_t)c.lane;
+  uint32_t best = (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand));
+  cand &= cand - 1;
+  if (cand != 0) {
+    best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
+    cand &= cand - 1;
+    if (cand != 0) best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
+  }
+  int hl = (int)(best & 63u);
+  if (c.flags() & NBOS_F_STICKY_EXECUTOR) {
+    // variant: the replica that ran the previous cell leads again if its host can bind
+    const uint32_t last = hw >> 30;
+    if (last != 0) {
+      const int hp = (int)slot_host(hw, last - 1u);
+      if ((idle_ok >> hp) & 1u) hl = hp;
+    }
+  }
+  return hl;
+}
+
+// A cell of an idle placed session starts by election at the instant it is submitted (open loop): what
+// start_cell does for a delay of 0, with nothing of the other cases in it.
+template <int NJ, uint32_t F>
+__device__ __forceinline__ void start_at_once(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, int slot, int host,
+                                              int32_t now, int32_t dur) {
+  const int g = (int)((hw >> 3) & 7u) + 1;
+  const int32_t finish = now + dur;
+  r.c_started++;
+  r.c_imm++;
+  r.h0++;
+  r.sum_dur += dur;
+  r.g_exec += (int64_t)g * dur;
+  if ((hw >> 30) == (uint32_t)slot + 1u) r.reused++;
+  // the record's word: hosts as they are, this slot the last executor; state "placed", retry count 0 already
+  const uint32_t nw = (hw & 0x3FFFFFFFu) | ((uint32_t)(slot + 1) << 30);
+  if (c.lane == 0) c.m.sess[s] = make_int2((int)nw, finish);
+  r.dirty |= wballot(c.vsid == s);
+  r.lazy_max = r.lazy_max > finish ? r.lazy_max : finish;
+  decide(c, r, now, NBOS_D_START, s, (uint32_t)slot, (uint32_t)host);
+}
+
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
@@ -602,25 +648,9 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
   }
   // (a) election, Section 3.2.2: among the session's hosts in idle_ok, fewest committed GPUs, then
   // lowest host index. At most three bits of `cand` are set: walk them.
-  uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
+  const uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
   if (cand != 0) {
-    const uint32_t key = ((uint32_t)C << 6) | (uint32_t)c.lane;
-    uint32_t best = (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand));
-    cand &= cand - 1;
-    if (cand != 0) {
-      best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
-      cand &= cand - 1;
-      if (cand != 0) best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
-    }
-    int hl = (int)(best & 63u);
-    if (c.flags() & NBOS_F_STICKY_EXECUTOR) {
-      // variant: the replica that ran the previous cell leads again if its host can bind
-      const uint32_t last = hw >> 30;
-      if (last != 0) {
-        const int hp = (int)slot_host(hw, last - 1u);
-        if ((idle_ok >> hp) & 1u) hl = hp;
-      }
-    }
+    const int hl = elect(c, hw, C, idle_ok, cand);
     const int lead = (uint32_t)hl == h0 ? 0 : ((uint32_t)hl == h1 ? 1 : 2);
     bind_gpus(c, hl, g, now, now + dur);
     if (now == t_submit) r.c_imm++;
@@ -1053,6 +1083,29 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
     const uint64_t fastmask = wballot(fast != 0);
     for (;;) {
       if (r.status != NBOS_OK) break;
+      // ---- runs of arrivals that start at once (S4, S5): cells of idle placed sessions, their records
+      // untouched since the prefetch, no timer due first, the election won. A loop of its own with
+      // nothing else in it; whatever does not fit leaves the arrival to the general path below.
+      while (todo != 0) {
+        const int i = (int)__builtin_ctzll(todo);
+        if ((((fastmask & ~r.dirty) >> i) & 1ull) == 0) break;
+        const int32_t t = lane_get(vt, i);
+        if (t >= due_t) break;
+        const uint32_t hw = (uint32_t)lane_get(rec.x, i);
+        const int g = (int)((hw >> 3) & 7u) + 1;
+        if (t < lane_get(c.fu, g - 1)) break;                 // no host has g idle GPUs yet
+        const int C = committed(c, t);
+        const uint64_t idle_ok = wballot(c.hr <= t && C + g <= c.p.G);
+        const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
+        const uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
+        if (cand == 0) break;                                 // every replica yields
+        const int hl = elect(c, hw, C, idle_ok, cand);
+        const int lead = (uint32_t)hl == h0 ? 0 : ((uint32_t)hl == h1 ? 1 : 2);
+        const int32_t dur = lane_get(vd, i);
+        bind_gpus(c, hl, g, t, t + dur);
+        start_at_once(c, r, (uint32_t)lane_get(vs, i) & 0xFFFFFFu, hw, lead, hl, t, dur);
+        todo &= todo - 1;
+      }
       int i = 0;
       int32_t t = NEVER;
       if (todo != 0) { i = (int)__builtin_ctzll(todo); t = lane_get(vt, i); }
