@@ -51,7 +51,7 @@ constexpr uint32_t RK_FLAGS = 0xFFFu;        // the bits below the hosts
 __device__ __forceinline__ uint32_t slot_host(uint32_t hw, uint32_t slot) { return (hw >> (12u + 6u * slot)) & 63u; }
 
 struct Lds {
-  int32_t *stage;    // closed loop: [64] sessions whose timers move into the registers
+  int32_t *stage;    // [64] sessions whose timers move into the registers
   int32_t *warm;     // [64][4] when each pre-warmed container of a host is available (only with the pool)
   int2 *sess;
   uint32_t *hist;
@@ -70,6 +70,7 @@ struct Regs {
   uint32_t o_min_k;
   int32_t status;
   uint64_t dirty;                        // lanes of the current tile whose prefetched record is stale
+  uint64_t slow_lanes;                   // lanes of the current tile whose prefetched record showed no idle placed session
   // closed loop: the event being handled, its duration and kind (packed as in Ctx::qx), its session's next
   // event and the think time before that; the time window the next refill takes
   int32_t cl_e, cl_x, cl_nx, cl_nth, cl_win;
@@ -168,26 +169,8 @@ __device__ __forceinline__ void sess_write_flag(Ctx<NJ, F> &c, Regs &r, uint32_t
 // ---- timers beyond the 64 sorted ones stay with their session -------------------------------------
 // Such a session carries RK_OVF. Its timer is implied by its record: a queued session retries at
 // submit time + retries * interval (the duration of its cell waits in a per-replay array in device
-// memory), a placed session that is ending ends at its busy-until time. The earliest of them is tracked; finding the next one scans the session table.
-template <int NJ, uint32_t F>
-__device__ __forceinline__ void ovf_rescan(Ctx<NJ, F> &c, Regs &r) {
-  wave_sync();
-  uint32_t bt = 0xFFFFFFFFu, bl = 0xFFFFFFFFu;
-  for (int s = c.lane; s < c.n_sess; s += WAVE) {
-    const int2 rec = c.m.sess[s];
-    const uint32_t fl = (uint32_t)rec.x;
-    if (fl & RK_OVF) {
-      const bool retry = (fl & 7u) == SS_QUEUED;
-      const uint32_t t = (uint32_t)(retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y);
-      const uint32_t l = ((retry ? QK_RETRY : QK_END) << 16) | (uint32_t)s;
-      if (t < bt || (t == bt && l < bl)) { bt = t; bl = l; }
-    }
-  }
-  const uint32_t mt = wave_min(bt);
-  r.o_min_k = wave_min(bt == mt ? bl : 0xFFFFFFFFu);
-  r.o_min_t = r.o_n > 0 ? (int32_t)mt : NEVER;
-}
-
+// memory), a placed session that is ending ends at its busy-until time. A lower bound of the earliest of them
+// is tracked; when the registers run empty, refill() moves up to 64 of them in at once.
 template <int NJ, uint32_t F>
 __device__ __forceinline__ void ovf_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t k, int32_t d) {
   const uint32_t s = k & 0xFFFFu;
@@ -206,13 +189,15 @@ __device__ __forceinline__ void ovf_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint
   r.o_n++;
 }
 
-// closed loop, registers empty: all timers that are due within a window after the earliest one move
+// Registers empty: all timers that are due within a window after the earliest one move
 // from the session records into the registers at once, at most 64 (whole instants, so everything
 // taken is earlier than everything left behind whatever the kinds; the window adapts to fill 32 to
 // 56 registers; more than 64 timers at one instant: the single earliest), and what firing them will
-// need is gathered one lane per timer. The same scheme as in the any-size kernel's closed loop.
+// need is gathered one lane per timer. The same scheme as in the any-size kernel. The kind of a timer
+// that is no retry: the deferred end of a busy session (open loop), the session's next event (closed loop).
 template <int NJ, uint32_t F>
-__device__ __forceinline__ void cl_refill(Ctx<NJ, F> &c, Regs &r) {
+__device__ __forceinline__ void refill(Ctx<NJ, F> &c, Regs &r) {
+  constexpr uint32_t kOther = Ctx<NJ, F>::closed ? QK_NEXT : QK_END;
   wave_sync();
   int cnt;
   int32_t left;                                  // earliest time left behind
@@ -256,7 +241,7 @@ __device__ __forceinline__ void cl_refill(Ctx<NJ, F> &c, Regs &r) {
         if (fl & RK_OVF) {
           const bool retry = (fl & 7u) == SS_QUEUED;
           const int32_t d = retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y;
-          if (d == T) best = umin(best, ((retry ? QK_RETRY : QK_NEXT) << 16) | (uint32_t)s);
+          if (d == T) best = umin(best, ((retry ? QK_RETRY : kOther) << 16) | (uint32_t)s);
         }
       }
       best = wave_min(best);
@@ -282,18 +267,25 @@ __device__ __forceinline__ void cl_refill(Ctx<NJ, F> &c, Regs &r) {
     const uint32_t fl = (uint32_t)rec.x;
     const bool retry = (fl & 7u) == SS_QUEUED;
     t = retry ? rec.y + (int32_t)((fl >> 8) & 15u) * c.p.retry_iv : rec.y;
-    key = ((retry ? QK_RETRY : QK_NEXT) << 16) | (uint32_t)s;
+    key = ((retry ? QK_RETRY : kOther) << 16) | (uint32_t)s;
     c.m.sess[s].x = (int)(fl & ~RK_OVF);
   }
-  // the cursors were written by lane 0 when the timers were scheduled: the fence makes this wave's own
-  // stores visible to its other lanes
+  // the cursors / durations were written by lane 0 when the timers were scheduled: the fence makes this
+  // wave's own stores visible to its other lanes
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   int32_t x = 0, nx = -1, nth = 0;
-  if (take) {
-    e = c.cl_cur[key & 0xFFFFu];
-    const int2 ch = c.cl_chain[e];
-    x = c.cl_dur[e] | (int32_t)(((uint32_t)c.cl_sk[e] >> 24) << 28) | CLX_LOADED;
-    nx = ch.x; nth = ch.y;
+  if constexpr (Ctx<NJ, F>::closed) {
+    if (take) {
+      e = c.cl_cur[key & 0xFFFFu];
+      const int2 ch = c.cl_chain[e];
+      x = c.cl_dur[e] | (int32_t)(((uint32_t)c.cl_sk[e] >> 24) << 28) | CLX_LOADED;
+      nx = ch.x; nth = ch.y;
+    }
+  } else {
+    if (take && (key >> 16) == QK_RETRY) e = c.ovf_dur[key & 0xFFFFu];    // qd carries the queued cell's duration
+    // the records taken have lost their mark: lanes of the tile that prefetched one read it again. Such a
+    // session was queued or ending when the tile was loaded (or its lanes are stale already)
+    r.dirty |= r.slow_lanes;
   }
   int rank = 0;
   for (int j = 0; j < cnt; j++) {
@@ -305,9 +297,11 @@ __device__ __forceinline__ void cl_refill(Ctx<NJ, F> &c, Regs &r) {
   c.qt = __builtin_amdgcn_ds_permute(dst << 2, t);
   c.qk = (uint32_t)__builtin_amdgcn_ds_permute(dst << 2, (int)key);
   c.qd = __builtin_amdgcn_ds_permute(dst << 2, e);
-  c.qx = __builtin_amdgcn_ds_permute(dst << 2, x);
-  c.qnx = __builtin_amdgcn_ds_permute(dst << 2, nx);
-  c.qnth = __builtin_amdgcn_ds_permute(dst << 2, nth);
+  if constexpr (Ctx<NJ, F>::closed) {
+    c.qx = __builtin_amdgcn_ds_permute(dst << 2, x);
+    c.qnx = __builtin_amdgcn_ds_permute(dst << 2, nx);
+    c.qnth = __builtin_amdgcn_ds_permute(dst << 2, nth);
+  }
   r.q_n = cnt;
   r.o_n -= cnt;
   r.o_min_t = r.o_n > 0 ? left : NEVER;
@@ -364,17 +358,8 @@ __device__ __forceinline__ void timer_pop(Ctx<NJ, F> &c, Regs &r) {
     c.qx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
     c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
     c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
-    if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
-  } else if (r.q_n == 0 && r.o_n > 0) {
-    wave_sync();
-    const uint32_t s = r.o_min_k & 0xFFFFu;
-    const int32_t d = uni(c.ovf_dur[s]);
-    if (c.lane == 0) { atomicAnd((unsigned int *)&c.m.sess[s].x, ~RK_OVF); c.qt = r.o_min_t; c.qd = d; c.qk = r.o_min_k; }
-    r.dirty |= wballot(c.vsid == s);
-    r.o_n--;
-    r.q_n = 1;
-    ovf_rescan(c, r);
   }
+  if (r.q_n == 0 && r.o_n > 0) refill(c, r);
   r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
 }
 
@@ -997,7 +982,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   m.c32 = (uint32_t *)q;       q += 16 * 4;
   m.hist = (uint32_t *)q;      q += 32 * 4;
   m.sess = (int2 *)q;          q += (size_t)p.n_cap * 8;     // at a fixed offset: its accesses fold it in
-  m.stage = nullptr;
+  m.stage = (int32_t *)q;      q += WAVE * 4;
   m.warm = (int32_t *)q;                                     // only there with the pool
 
   // S0: hosts 0..H0-1 ready at time 0, the rest off; sessions unplaced
@@ -1028,6 +1013,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   r.digest = 0xCBF29CE484222325ULL;
   r.q_head_t = NEVER;
   r.o_min_t = NEVER;
+  r.cl_win = 1024;
 
   const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   int32_t tick_t = ticking ? p.scale_iv : NEVER;
@@ -1081,6 +1067,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
       final = true;
     }
     const uint64_t fastmask = wballot(fast != 0);
+    r.slow_lanes = ~fastmask;
     for (;;) {
       if (r.status != NBOS_OK) break;
       // ---- runs of arrivals that start at once (S4, S5): cells of idle placed sessions, their records
@@ -1260,7 +1247,7 @@ __device__ __forceinline__ int32_t cl_failing_retries(Ctx<NJ, F> &c, Regs &r, in
       ovf_push(c, r, t_new, key, 0);
       c.qt = st; c.qd = sd; c.qk = sk; c.qx = sx; c.qnx = sn; c.qnth = sh;
       r.q_n--;
-      if (r.q_n == 0 && r.o_n > 0) cl_refill(c, r);
+      if (r.q_n == 0 && r.o_n > 0) refill(c, r);
       r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
     } else {
       // it moves from lane 0 to its new place: the entries before that shift down one lane

@@ -450,7 +450,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) set_closed_kernel<kMigrOut>(h);
     else set_closed_kernel<ldsk::kRuntimeClosed>(h);
   } else if (sh->in_regs) {
-    h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8;
+    h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8 + WAVE * 4;      // + 64 staged sessions
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     const int32_t rc = choose_reg_kernel(h, maxlds);
     if (rc != NBOS_OK) return rc;
@@ -729,7 +729,7 @@ int32_t nbos_replay_run_static(const nbos_config *cfg_in, const nbos_inputs *in,
   nbos_replay tmp{};                      // never leaves this call; its vectors stay empty
   tmp.cfg = cfg; tmp.in = *in; tmp.stream = (hipStream_t)stream; tmp.device = dev; tmp.threads = WAVE;
   const bool warm_pool = (cfg.flags & NBOS_F_WARM_POOL) != 0;
-  tmp.lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8;
+  tmp.lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8 + WAVE * 4;
   int maxlds = 0;
   if (hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return NBOS_E_HIP;
   if (tmp.lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
