@@ -1031,6 +1031,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   while (r.status == NBOS_OK) {
     int2 rec = make_int2(0, 0);             // prefetched session record of this lane's event
     uint32_t fast = 0;                      // this lane's event is a cell of an idle placed session
+    bool base_valid_cell = false;           // this lane's event is a cell
     uint64_t todo = 0;
     if (base < ev_hi) {
       // the prefetched tile becomes current; start loading the one after it
@@ -1057,6 +1058,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
       r.c_unplaced += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && dead));
       r.c_busy += (uint32_t)__builtin_popcountll(wballot(skip && is_cell && !dead));
       fast = (valid && is_cell && st == SS_PLACED && !running && !((uint32_t)rec.x & SF_ENDING)) ? 1u : 0u;
+      base_valid_cell = valid && is_cell;
       todo = wballot(valid && !skip);
       r.dirty = 0;
       if (ev_hi - cur <= WAVE) {
@@ -1067,18 +1069,29 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
       final = true;
     }
     const uint64_t fastmask = wballot(fast != 0);
+    const uint64_t cellmask = wballot(base_valid_cell);
     r.slow_lanes = ~fastmask;
     for (;;) {
       if (r.status != NBOS_OK) break;
-      // ---- runs of arrivals that start at once (S4, S5): cells of idle placed sessions, their records
-      // untouched since the prefetch, no timer due first, the election won. A loop of its own with
-      // nothing else in it; whatever does not fit leaves the arrival to the general path below.
+      // ---- runs of arrivals that start at once (S4, S5): cells of idle placed sessions (by the prefetched
+      // record, or, where that is stale, by the record as it is now), no timer due first, the election won.
+      // A loop of its own with nothing else in it; whatever does not fit leaves the arrival to the general
+      // path below.
       while (todo != 0) {
         const int i = (int)__builtin_ctzll(todo);
-        if ((((fastmask & ~r.dirty) >> i) & 1ull) == 0) break;
+        if (((cellmask >> i) & 1ull) == 0) break;
         const int32_t t = lane_get(vt, i);
         if (t >= due_t) break;
-        const uint32_t hw = (uint32_t)lane_get(rec.x, i);
+        uint32_t hw;
+        if ((((fastmask & ~r.dirty) >> i) & 1ull) != 0) {
+          hw = (uint32_t)lane_get(rec.x, i);
+        } else {
+          wave_sync();
+          const int2 cur = m.sess[(uint32_t)lane_get(vs, i) & 0xFFFFFFu];
+          hw = uni((uint32_t)cur.x);
+          // idle and placed, nothing pending (the general path copes with everything else)
+          if ((hw & (7u | SF_ENDING | RK_OVF | (15u << 8))) != SS_PLACED || uni(cur.y) > t) break;
+        }
         const int g = (int)((hw >> 3) & 7u) + 1;
         if (t < lane_get(c.fu, g - 1)) break;                 // no host has g idle GPUs yet
         const int C = committed(c, t);
