@@ -232,9 +232,12 @@ typedef struct {
  * Decision code = host | slot << 10 | outcome << 12 | session << 16 | time << 32.
  */
 typedef struct {
-  int32_t  status;              /* NBOS_OK; NBOS_E_LIMIT: retry queue overflowed; NBOS_E_RANGE (Batch
-                                   baseline, closed loop): a time left the int32 range.
-                                   The other fields are invalid then.                              */
+  int32_t  status;              /* NBOS_OK; NBOS_E_RANGE (Batch baseline, closed loop): a time left the
+                                   int32 range; nbos_replay_run_static only: NBOS_E_RANGE / NBOS_E_LIMIT as
+                                   documented there. The other fields are invalid then. (No queue
+                                   inside a replay can overflow: a session has at most one timer, and a
+                                   timer that is not among the 64 sorted ones waits in the session's
+                                   own record.)                                                    */
   uint32_t n_decisions;
   uint32_t sessions_placed, sessions_rejected;
   uint32_t cells_total, cells_immediate, cells_started, cells_queued, cells_aborted;

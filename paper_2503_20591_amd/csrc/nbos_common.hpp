@@ -36,7 +36,7 @@ struct KParams {
   int32_t f_milli, buffer; // auto-scaler: f * 1000 of the expected capacity, extra hosts
   int32_t batch_delay;     // Batch baseline: container start per job
   int32_t warm_n, warm_migr, prewarm;   // pre-warmed containers per host, warm migration delay, pre-warm time
-  int32_t n_cap, q_cap;    // LDS capacity: sessions, queue entries
+  int32_t n_cap;           // LDS capacity: sessions
   int32_t batch;           // event-parallel rounds on (LDS kernel)
   // closed loop only. cl_chain: per event of the traces {the next event of its session (index within
   // the trace, -1: none), the think time before that event}; the second word is -1 for an event no
@@ -92,6 +92,141 @@ __device__ __forceinline__ uint64_t wballot(bool p) { return __builtin_amdgcn_ba
 
 __device__ __forceinline__ int lane_rank(uint64_t mask) {   // set bits of mask below this lane
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// ---- what the replay kernels share ---------------------------------------------------------------------
+// Each kernel has its own context type C (the replay's parameters p, its LDS arrays m, the lane, the
+// per-lane registers) and its own wave-uniform register block R; the helpers below work on either.
+
+// Kernel instances: F is the set of policy flags when it is known at compile time (the common sets get
+// an instance of their own, which drops the code of everything that is switched off), or one of the two
+// values that leave the flags to run time.
+constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
+constexpr uint32_t kRuntimeClosed = 0xFFFFFFFEu;     // policy flags at run time, closed-loop reading of the trace
+constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
+                                  NBOS_F_STICKY_EXECUTOR | NBOS_F_WARM_POOL;
+constexpr bool closed_loop_instance(uint32_t F) {
+  return F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
+}
+template <uint32_t F>
+__device__ __forceinline__ uint32_t instance_flags(const KParams &p) {
+  return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
+}
+
+// closed loop: a sorted timer's event has been loaded (bit 31 of qx); the widest refill window
+constexpr int32_t CLX_LOADED = (int32_t)0x80000000;
+constexpr int32_t CL_WIN_MAX = 1 << 24;
+
+// Cold counters kept in LDS (lane 0 adds with ds_add, no return value). CS_BLAZY and the CL_B* sums are
+// only fed by the event-parallel rounds of the any-size kernel.
+enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
+       CS_NON, CS_SUMS, CS_OPENG, CS_BLAZY, CS_NREP, CS_MIGRWARM, CS_N32 };
+enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_BDUR, CL_BGEXEC, CL_REPL, CL_N64 };
+
+template <class L>
+__device__ __forceinline__ void c32_add(L &m, int lane, int idx, uint32_t v) {
+  if (lane == 0) atomicAdd(&m.c32[idx], v);
+}
+template <class L>
+__device__ __forceinline__ void c32_max(L &m, int lane, int idx, uint32_t v) {
+  if (lane == 0) atomicMax(&m.c32[idx], v);
+}
+template <class L>
+__device__ __forceinline__ void c64_add(L &m, int lane, int idx, int64_t v) {
+  if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
+}
+
+// Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
+// replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
+// (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
+template <class C>
+__device__ __forceinline__ int32_t cap_room(const C &c, int g) {
+  int32_t lim = c.slim;
+  if (c.flags() & NBOS_F_DYNAMIC_SR) {
+    wave_sync();
+    const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
+    if (n_on > 0) {
+      const int32_t mean = (int32_t)((tot + (uint32_t)g) / n_on);
+      lim = lim > mean ? lim : mean;
+    }
+  }
+  return lim - g;
+}
+
+// One decision of the policy as a 64-bit code: host (10 bits), replica slot (2), outcome (4), session
+// (16), time (32). The replay's digest is the FNV-style fold of its codes in order.
+constexpr uint64_t DIGEST_PRIME = 0x100000001B3ULL;
+__device__ __forceinline__ uint64_t decision_code(int32_t now, uint32_t outcome, uint32_t s, uint32_t slot,
+                                                  uint32_t host) {
+  return (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) | ((uint64_t)s << 16) |
+         ((uint64_t)(uint32_t)now << 32);
+}
+template <class C, class R>
+__device__ __forceinline__ void decide(C &c, R &r, int32_t now, uint32_t outcome, uint32_t s, uint32_t slot,
+                                       uint32_t host) {
+  const uint64_t code = decision_code(now, outcome, s, slot, host);
+  r.digest = r.digest * DIGEST_PRIME + code;
+  if (__builtin_expect(c.dlog != nullptr, 0)) {
+    if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
+  }
+  r.n_dec++;
+}
+
+// ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
+// Invariant: every entry in the registers is earlier than every timer that waits in the session
+// records, and the registers are empty only if none waits there. Each kernel brings its own
+// ovf_push (a timer goes to wait in its session's record) and refill (the earliest waiting timers come
+// into the registers).
+template <class C, class R>
+__device__ __forceinline__ void timer_push(C &c, R &r, int32_t t, uint32_t kind, uint32_t id, int32_t d,
+                                           int32_t x = 0, int32_t nx = -1, int32_t nth = 0) {
+  uint32_t k = (kind << 16) | id;
+  if (r.q_n == WAVE) {
+    int32_t mt = lane_get(c.qt, WAVE - 1);
+    uint32_t mk = (uint32_t)lane_get((int)c.qk, WAVE - 1);
+    if (t < mt || (t == mt && k < mk)) {
+      ovf_push(c, r, mt, mk, lane_get(c.qd, WAVE - 1));   // the latest register entry moves out
+      r.q_n = WAVE - 1;
+    } else {
+      ovf_push(c, r, t, k, d);
+      return;
+    }
+  } else if (r.o_n > 0 && !(t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k))) {
+    ovf_push(c, r, t, k, d);
+    return;
+  }
+  bool before = c.lane < r.q_n && (c.qt < t || (c.qt == t && c.qk < k));
+  int pos = __builtin_popcountll(wballot(before));
+  int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x138, 0xF, 0xF, false);          // wave_shr:1
+  int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x138, 0xF, 0xF, false);
+  uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
+  if (c.lane > pos) { c.qt = st; c.qd = sd; c.qk = sk; }
+  if (c.lane == pos) { c.qt = t; c.qd = d; c.qk = k; }
+  if constexpr (C::closed) {
+    const int32_t sx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x138, 0xF, 0xF, false);
+    const int32_t sn = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x138, 0xF, 0xF, false);
+    const int32_t sh = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x138, 0xF, 0xF, false);
+    if (c.lane > pos) { c.qx = sx; c.qnx = sn; c.qnth = sh; }
+    if (c.lane == pos) { c.qx = x; c.qnx = nx; c.qnth = nth; }
+  }
+  r.q_n++;
+  if (pos == 0) r.q_head_t = t;
+}
+
+// remove the earliest timer (lane 0); refill from the session records when the registers run empty
+template <class C, class R>
+__device__ __forceinline__ void timer_pop(C &c, R &r) {
+  c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                // wave_shl:1
+  c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
+  c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
+  r.q_n--;
+  if constexpr (C::closed) {
+    c.qx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
+    c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
+    c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
+  }
+  if (r.q_n == 0 && r.o_n > 0) refill(c, r);
+  r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
 }
 
 }  // namespace

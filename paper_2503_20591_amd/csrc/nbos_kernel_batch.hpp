@@ -66,7 +66,7 @@ struct Ctx {
 
 __device__ __forceinline__ void decide(Ctx &c, State &r, int32_t now, uint32_t outcome, uint32_t s, uint32_t host) {
   const uint64_t code = (uint64_t)host | ((uint64_t)outcome << 12) | ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
-  r.digest = r.digest * 0x100000001B3ULL + code;
+  r.digest = r.digest * DIGEST_PRIME + code;
   if (c.dlog) {
     if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
   }

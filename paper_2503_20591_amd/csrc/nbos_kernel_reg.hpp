@@ -37,11 +37,6 @@
 namespace {
 namespace regk {
 
-// cold counters kept in LDS (lane 0 adds with ds_add, no return value)
-enum { CS_PLACED, CS_REJECTED, CS_QUEUED, CS_ABORTED, CS_MIGR, CS_SO, CS_SI, CS_PEAK, CS_MAXDELAY,
-       CS_NON, CS_SUMS, CS_OPENG, CS_NREP, CS_MIGRWARM, CS_N32 };
-enum { CL_SUMDELAY, CL_GWAIT, CL_PROV, CL_RESV, CL_SUB, CL_REPL, CL_N64 };
-
 // Session record: x = state (bits 0-2) | g - 1 (3-5) | ENDING (6) | RK_OVF (7) | retries (8-11) |
 // host of slot 0, 1, 2 (6 bits each from bit 12) | last executor slot + 1 (30-31); y = time word.
 // The code below calls the word `hw` where it looks at the hosts and `fl` where it looks at the low
@@ -76,15 +71,6 @@ struct Regs {
   int32_t cl_e, cl_x, cl_nx, cl_nth, cl_win;
 };
 
-// F: the policy flags when they are known at compile time (the common sets get an instance of their
-// own, which drops the code of everything that is switched off), or kRuntimeFlags.
-constexpr uint32_t kRuntimeFlags = 0xFFFFFFFFu;
-constexpr uint32_t kRuntimeClosed = 0xFFFFFFFEu;     // policy flags at run time, closed-loop reading of the trace
-constexpr uint32_t kPolicyFlags = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR |
-                                  NBOS_F_STICKY_EXECUTOR | NBOS_F_WARM_POOL;
-constexpr int32_t CLX_LOADED = (int32_t)0x80000000;
-constexpr int32_t CL_WIN_MAX = 1 << 24;
-
 template <int NJ, uint32_t F>
 struct Ctx {
   const KParams &p;
@@ -109,50 +95,9 @@ struct Ctx {
   const int32_t *cl_dur, *cl_sk;
   const int2 *cl_chain;
   int32_t qx, qnx, qnth;
-  static constexpr bool closed = F == kRuntimeClosed || (F != kRuntimeFlags && (F & NBOS_F_CLOSED_LOOP) != 0);
-  __device__ __forceinline__ uint32_t flags() const {
-    return F == kRuntimeFlags ? (p.flags & ~NBOS_F_CLOSED_LOOP) : F == kRuntimeClosed ? (p.flags | NBOS_F_CLOSED_LOOP) : F;
-  }
+  static constexpr bool closed = closed_loop_instance(F);
+  __device__ __forceinline__ uint32_t flags() const { return instance_flags<F>(p); }
 };
-
-__device__ __forceinline__ void c32_add(Lds &m, int lane, int idx, uint32_t v) {
-  if (lane == 0) atomicAdd(&m.c32[idx], v);
-}
-__device__ __forceinline__ void c32_max(Lds &m, int lane, int idx, uint32_t v) {
-  if (lane == 0) atomicMax(&m.c32[idx], v);
-}
-__device__ __forceinline__ void c64_add(Lds &m, int lane, int idx, int64_t v) {
-  if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
-}
-
-// Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
-// replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
-// (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
-template <int NJ, uint32_t F>
-__device__ __forceinline__ int32_t cap_room(const Ctx<NJ, F> &c, int g) {
-  int32_t lim = c.slim;
-  if (c.flags() & NBOS_F_DYNAMIC_SR) {
-    wave_sync();
-    const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
-    if (n_on > 0) {
-      const int32_t mean = (int32_t)((tot + (uint32_t)g) / n_on);
-      lim = lim > mean ? lim : mean;
-    }
-  }
-  return lim - g;
-}
-
-template <int NJ, uint32_t F>
-__device__ __forceinline__ void decide(Ctx<NJ, F> &c, Regs &r, int32_t now, uint32_t outcome, uint32_t s,
-                                       uint32_t slot, uint32_t host) {
-  uint64_t code = (uint64_t)host | ((uint64_t)slot << 10) | ((uint64_t)outcome << 12) |
-                  ((uint64_t)s << 16) | ((uint64_t)(uint32_t)now << 32);
-  r.digest = r.digest * 0x100000001B3ULL + code;
-  if (__builtin_expect(c.dlog != nullptr, 0)) {
-    if (c.lane == 0 && (int64_t)r.n_dec < c.p.dlog_stride) c.dlog[r.n_dec] = code;
-  }
-  r.n_dec++;
-}
 
 // write a session record; lanes of the current tile that prefetched it go stale
 template <int NJ, uint32_t F>
@@ -306,61 +251,6 @@ __device__ __forceinline__ void refill(Ctx<NJ, F> &c, Regs &r) {
   r.o_n -= cnt;
   r.o_min_t = r.o_n > 0 ? left : NEVER;
   r.o_min_k = 0;                                 // a lower bound: pushes for that very instant wait in the records
-}
-
-// ---- timers: the 64 earliest, sorted ascending by (time, kind << 16 | id), entry i in lane i -----
-// Invariant: every entry in the registers is earlier than every entry in the overflow array, and the
-// registers are empty only if the overflow array is.
-template <int NJ, uint32_t F>
-__device__ __forceinline__ void timer_push(Ctx<NJ, F> &c, Regs &r, int32_t t, uint32_t kind, uint32_t id, int32_t d,
-                                           int32_t x = 0, int32_t nx = -1, int32_t nth = 0) {
-  uint32_t k = (kind << 16) | id;
-  if (r.q_n == WAVE) {
-    int32_t mt = lane_get(c.qt, WAVE - 1);
-    uint32_t mk = (uint32_t)lane_get((int)c.qk, WAVE - 1);
-    if (t < mt || (t == mt && k < mk)) {
-      ovf_push(c, r, mt, mk, lane_get(c.qd, WAVE - 1));   // the latest register entry moves out
-      r.q_n = WAVE - 1;
-    } else {
-      ovf_push(c, r, t, k, d);
-      return;
-    }
-  } else if (r.o_n > 0 && !(t < r.o_min_t || (t == r.o_min_t && k < r.o_min_k))) {
-    ovf_push(c, r, t, k, d);
-    return;
-  }
-  bool before = c.lane < r.q_n && (c.qt < t || (c.qt == t && c.qk < k));
-  int pos = __builtin_popcountll(wballot(before));
-  int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x138, 0xF, 0xF, false);          // wave_shr:1
-  int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x138, 0xF, 0xF, false);
-  uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x138, 0xF, 0xF, false);
-  if (c.lane > pos) { c.qt = st; c.qd = sd; c.qk = sk; }
-  if (c.lane == pos) { c.qt = t; c.qd = d; c.qk = k; }
-  if constexpr (Ctx<NJ, F>::closed) {
-    const int32_t sx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x138, 0xF, 0xF, false);
-    const int32_t sn = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x138, 0xF, 0xF, false);
-    const int32_t sh = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x138, 0xF, 0xF, false);
-    if (c.lane > pos) { c.qx = sx; c.qnx = sn; c.qnth = sh; }
-    if (c.lane == pos) { c.qx = x; c.qnx = nx; c.qnth = nth; }
-  }
-  r.q_n++;
-  if (pos == 0) r.q_head_t = t;
-}
-
-// remove the earliest timer (lane 0); refill from the overflow array when the registers run empty
-template <int NJ, uint32_t F>
-__device__ __forceinline__ void timer_pop(Ctx<NJ, F> &c, Regs &r) {
-  c.qt = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);                // wave_shl:1
-  c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
-  c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
-  r.q_n--;
-  if constexpr (Ctx<NJ, F>::closed) {
-    c.qx = __builtin_amdgcn_update_dpp(c.qx, c.qx, 0x130, 0xF, 0xF, false);
-    c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
-    c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
-  }
-  if (r.q_n == 0 && r.o_n > 0) refill(c, r);
-  r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
 }
 
 // ---- hosts ----------------------------------------------------------------------------------------

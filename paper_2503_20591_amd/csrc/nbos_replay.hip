@@ -315,7 +315,6 @@ struct Shape {
   int64_t total_ev = 0;
   int HP = 0;               // hosts_max rounded up to whole waves
   int n_cap = 1;            // session capacity of a replay's LDS
-  size_t q_cap = 0;         // any-size kernel: timers that fit beside the 64 sorted ones
   bool in_regs = false;     // the register kernel runs
 };
 
@@ -374,8 +373,8 @@ int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
   // generic kernel runs for the other flag sets, and if it ever needs fewer rounds for the batch
   // (a batch that does not fit at once runs in rounds; waves hide little of each other's latency).
   const int nj = (cfg->hosts_max + 7) / 8;
-  const uint32_t policy = cfg->flags & regk::kPolicyFlags;
-  const void *generic = reg_kernel_for<regk::kRuntimeFlags>(nj);
+  const uint32_t policy = cfg->flags & kPolicyFlags;
+  const void *generic = reg_kernel_for<kRuntimeFlags>(nj);
   const bool has_special = policy == 0u || policy == NBOS_F_MIGRATE || policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT);
   const void *special = policy == 0u ? reg_kernel_for<0u>(nj)
                       : policy == NBOS_F_MIGRATE ? reg_kernel_for<NBOS_F_MIGRATE>(nj)
@@ -402,7 +401,7 @@ int32_t choose_reg_kernel(nbos_replay *h, int maxlds) {
     const int res_g = resident(fa_g) > 0 ? resident(fa_g) : 1, res_s = resident(fa_s) > 0 ? resident(fa_s) : 1;
     use_generic = (per_cu + res_g - 1) / res_g < (per_cu + res_s - 1) / res_s;
   }
-  if (use_generic || !has_special) set_kernel(h, generic, "regk::nbos_replay_reg_kernel<%d, %uu>", nj, regk::kRuntimeFlags);
+  if (use_generic || !has_special) set_kernel(h, generic, "regk::nbos_replay_reg_kernel<%d, %uu>", nj, kRuntimeFlags);
   else set_kernel(h, special, "regk::nbos_replay_reg_kernel<%d, %uu>", nj, policy);
   return NBOS_OK;
 }
@@ -419,7 +418,6 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   // the kernels with host state in LDS give the scans over all hosts to four waves from 256 hosts on
   h->threads = (!sh->in_regs && !batch_mode && sh->HP >= 4 * WAVE && !(cfg->flags & NBOS_F_ONE_WAVE)) ? ldsk::MAX_WAVES * WAVE : WAVE;
   sh->n_cap = sh->max_sess > 0 ? sh->max_sess : 1;
-  sh->q_cap = (size_t)sh->n_cap + 1;               // at most one queued timer per session
   const int HP = sh->HP;
   const size_t n_cap = (size_t)sh->n_cap;
   const bool force_generic = (cfg->flags & NBOS_F_GENERIC_KERNEL) != 0;
@@ -431,24 +429,22 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     // hosts in registers; 8 bytes per session, 64 staged sessions
     h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
-    sh->q_cap = 0;
     const int nj = (cfg->hosts_max + 7) / 8;
-    const uint32_t policy = cfg->flags & regk::kPolicyFlags;
+    const uint32_t policy = cfg->flags & kPolicyFlags;
     if (policy == NBOS_F_MIGRATE && !force_generic) set_reg_closed_kernel<NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP>(h, nj);
-    else set_reg_closed_kernel<regk::kRuntimeClosed>(h, nj);
+    else set_reg_closed_kernel<kRuntimeClosed>(h, nj);
   } else if (closed_loop) {
     // 12 bytes of record and 4 of timer per session; 64 staged sessions
     h->lds_bytes = 64 + 64 + 128 + 66 * 8 + ldsk::MAIL_WORDS * 4 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
                    (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
-    sh->q_cap = 0;
     // instances for the common flag sets, as for the other kernels
-    const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
+    const uint32_t policy = cfg->flags & kPolicyFlags;
     constexpr uint32_t kMigr = NBOS_F_MIGRATE | NBOS_F_CLOSED_LOOP, kMigrOut = kMigr | NBOS_F_SCALE_OUT;
-    if (force_generic) set_closed_kernel<ldsk::kRuntimeClosed>(h);
+    if (force_generic) set_closed_kernel<kRuntimeClosed>(h);
     else if (policy == NBOS_F_MIGRATE) set_closed_kernel<kMigr>(h);
     else if (policy == (NBOS_F_MIGRATE | NBOS_F_SCALE_OUT)) set_closed_kernel<kMigrOut>(h);
-    else set_closed_kernel<ldsk::kRuntimeClosed>(h);
+    else set_closed_kernel<kRuntimeClosed>(h);
   } else if (sh->in_regs) {
     h->lds_bytes = 64 + 64 + 128 + (warm_pool ? (size_t)WAVE * 16 : 0) + n_cap * 8 + WAVE * 4;      // + 64 staged sessions
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
@@ -459,18 +455,17 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
     h->lds_bytes = 64 + 64 + 128 + 66 * 8 + ldsk::MAIL_WORDS * 4 + (size_t)HP * (32 + 12 + (warm_pool ? 16 : 0)) + n_cap * 12 +
                    (n_cap + 3) / 4 * 16 + WAVE * 4;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
-    sh->q_cap = 0;
     // same idea as for the register kernel; its batches are small (the LDS footprint allows few
     // workgroups per compute unit), so the instance compiled for the flag set is used whenever
     // there is one
-    const uint32_t policy = cfg->flags & ldsk::kPolicyFlags;
+    const uint32_t policy = cfg->flags & kPolicyFlags;
     constexpr uint32_t kAllScaling = NBOS_F_MIGRATE | NBOS_F_SCALE_OUT | NBOS_F_SCALE_IN;
     constexpr uint32_t kAutoScaler = NBOS_F_MIGRATE | NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE | NBOS_F_DYNAMIC_SR;
-    if (force_generic) set_lds_kernel<ldsk::kRuntimeFlags>(h);
+    if (force_generic) set_lds_kernel<kRuntimeFlags>(h);
     else if (policy == kAllScaling) set_lds_kernel<kAllScaling>(h);
     else if (policy == kAutoScaler) set_lds_kernel<kAutoScaler>(h);
     else if (policy == NBOS_F_MIGRATE) set_lds_kernel<NBOS_F_MIGRATE>(h);
-    else set_lds_kernel<ldsk::kRuntimeFlags>(h);
+    else set_lds_kernel<kRuntimeFlags>(h);
   }
   HIP_TRY(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
   return NBOS_OK;
@@ -552,7 +547,7 @@ void fill_params(nbos_replay *h, const Shape &sh) {
   k.batch_delay = cfg->batch_start_delay_ms;
   k.warm_n = (cfg->flags & NBOS_F_WARM_POOL) ? cfg->warm_pool_per_host : 0;
   k.warm_migr = cfg->warm_migration_delay_ms; k.prewarm = cfg->prewarm_delay_ms;
-  k.n_cap = sh.n_cap; k.q_cap = (int32_t)sh.q_cap;
+  k.n_cap = sh.n_cap;
   // Event-parallel rounds: on, except for closed loops on clusters of at most 64 hosts, where two
   // cells of a run choose the same host too often for a round to pay (measured: 30 hosts, 110 ms
   // without, 119 ms with). NBOS_F_ROUNDS_OFF / _ON force the choice (comparison runs, tests).
@@ -738,7 +733,7 @@ int32_t nbos_replay_run_static(const nbos_config *cfg_in, const nbos_inputs *in,
   if (hipFuncSetAttribute(tmp.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)tmp.lds_bytes) != hipSuccess)
     return NBOS_E_HIP;
   Shape sh;
-  sh.HP = WAVE; sh.n_cap = (int)n_cap; sh.q_cap = 0; sh.in_regs = true;
+  sh.HP = WAVE; sh.n_cap = (int)n_cap; sh.in_regs = true;
   tmp.d_stats = device_stats_out;
   tmp.d_ovf = base + kScratchHead;
   fill_params(&tmp, sh);

@@ -613,6 +613,26 @@ def test_many_pending_timers(rp, oracle, in_lds):
     assert st["cells_queued"].max() > 500
 
 
+@pytest.mark.parametrize("hosts", [70, 200])
+def test_thousands_of_timers_pending_at_once(rp, oracle, hosts):
+    # 8,000 sessions of 8 GPUs submit within eight seconds on a cluster that runs a few dozen cells at a time:
+    # thousands of retry timers wait outside the 64 sorted ones at once (the any-size kernel keeps them in the
+    # session records, so none can be turned away), are retried six times and given up; some sessions end
+    # while queued. 70 hosts: one wave per replay; 200 hosts: with helper waves.
+    n = 8000
+    rng = np.random.default_rng(3)
+    ev = [[s, 0, s, 0] for s in range(n)]
+    ev += [[10_000 + s, 1, s, int(rng.integers(20_000, 200_000))] for s in range(n)]
+    ev += [[30_000 + s, 2, s, 0] for s in range(0, n, 5)]
+    ev.sort(key=lambda e: e[0])
+    cfg = dict(BASE, hosts_initial=hosts, hosts_max=hosts, flags=tg.F_MIGRATE, migration_delay_ms=500,
+               retry_interval_ms=10_000, max_retries=6)
+    b = _tiny(cfg, ev, np.full(n, 8, np.uint8), [100000, 3000])
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs)
+    assert st["cells_queued"][0] > 6900 and (st["status"] == 0).all()   # the replay without a subscription cap
+
+
 def test_time_near_int32_limit(rp, oracle):
     cfg = dict(BASE, flags=1, migration_delay_ms=15000, retry_interval_ms=10000, max_retries=6)
     t0 = 2**31 - 2 - 86_400_000 - 6 * 10000 - 15000
