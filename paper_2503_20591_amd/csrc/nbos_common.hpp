@@ -136,13 +136,28 @@ __device__ __forceinline__ void c64_add(L &m, int lane, int idx, int64_t v) {
   if (lane == 0) atomicAdd(&m.c64[idx], (unsigned long long)v);
 }
 
+// Can the dynamic limit of Section 3.4.1 ever admit a host that the replay's own cap turns away? Not while
+// every host that is on holds at most slim subscribed GPUs and more hosts are on than a request has GPUs:
+// (S + g) n <= sum S + g <= n slim + g gives S + g <= slim + g / n, i.e. S + g <= slim for g < n. A host's
+// S only grows through a placement or a migration that passed the limit (so S + g <= slim as long as the
+// claim held so far) or starts at g on a host that was booted for the request (g <= G), so with slim >= G
+// the claim holds for the whole replay, provided the cluster never has G hosts or fewer: it starts with
+// H0 and the periodic release stops at min_hosts. Then the limit in force is the replay's cap, and the
+// kernels keep the bounds that rest on a fixed cap. Otherwise (small clusters, caps below one request
+// per empty host) the limit is worked out at every test.
+__device__ __forceinline__ bool dynamic_limit_matters(const KParams &p, uint32_t flags, int32_t slim) {
+  if (!(flags & NBOS_F_DYNAMIC_SR)) return false;
+  const int32_t fewest = (flags & NBOS_F_SCALE_IN) ? (p.H0 < p.min_hosts ? p.H0 : p.min_hosts) : p.H0;
+  return !(slim >= p.G && fewest > p.G);
+}
+
 // Largest S a host may hold and still take one more replica with request g (Section 3.4.1): the
 // replay's cap, or with the dynamic limit the cluster-wide ratio after placing when that is larger:
 // (S + g) / (G R) <= (sum S + g) / (n G R)  <=>  S + g <= floor((sum S + g) / n), n = hosts not off.
 template <class C>
 __device__ __forceinline__ int32_t cap_room(const C &c, int g) {
   int32_t lim = c.slim;
-  if (c.flags() & NBOS_F_DYNAMIC_SR) {
+  if ((c.flags() & NBOS_F_DYNAMIC_SR) && c.dyn) {
     wave_sync();
     const uint32_t n_on = uni(c.m.c32[CS_NON]), tot = uni(c.m.c32[CS_SUMS]);
     if (n_on > 0) {

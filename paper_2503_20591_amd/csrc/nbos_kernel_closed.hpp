@@ -180,6 +180,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
   r.cl_win = 1024;
   c.nw = (int)(blockDim.x / WAVE);
   c.wid = (int)(threadIdx.x / WAVE);
+  c.dyn = dynamic_limit_matters(p, c.flags(), c.slim);
   if (c.wid != 0) {
     helper_loop(c);
   } else {

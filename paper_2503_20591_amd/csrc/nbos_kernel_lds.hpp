@@ -102,6 +102,7 @@ struct Ctx {
   int32_t fc;
   int32_t *ovf_dur;          // open loop: [n_sess] durations of queued cells whose timer waits outside the registers
   int nw, wid;               // waves in the workgroup, this wave's number (0 runs the replay)
+  bool dyn;                  // the dynamic limit can differ from the replay's cap (see dynamic_limit_matters)
   static constexpr bool closed = closed_loop_instance(F);
   __device__ __forceinline__ uint32_t flags() const { return instance_flags<F>(p); }
 };
@@ -447,8 +448,9 @@ __device__ __forceinline__ int32_t earliest_idle(const Ctx<F> &c, int g, int32_t
 // may newly pass the cap for requests of up to slim - s_new GPUs, so the stored bounds of those requests
 // drop to the time at which this host could have the GPUs idle. Lane g-1 works out the bound for g.
 template <uint32_t F>
-__device__ __forceinline__ void cap_bound_host_freed(Ctx<F> &c, int h, int32_t s_new) {
-  if (c.flags() & NBOS_F_DYNAMIC_SR) return;          // the limit moves with the cluster's sums: no bound is kept
+__device__ __forceinline__ void cap_bound_host_freed(Ctx<F> &c, int h, int32_t s_new, int32_t now) {
+  if ((c.flags() & NBOS_F_DYNAMIC_SR) && c.dyn) return;   // the limit moves with the cluster's sums: no bound is kept
+  if (wballot(c.lane < NGPU && c.fc > now) == 0) return;  // every bound lies in the past already: as good as none
   wave_sync();
   const int g = (c.lane & 7) + 1;
   int32_t y = kth_free_time(c.m.fin[2 * h], c.m.fin[2 * h + 1], c.p.G, g);
@@ -580,12 +582,12 @@ __device__ __forceinline__ void end_session(Ctx<F> &c, Regs &r, uint32_t s, uint
     c.m.hsn[h] -= sub;                          // three distinct hosts, one lane each
   }
   r.min_s = -1;
-  if (!(c.flags() & NBOS_F_DYNAMIC_SR)) {
+  if (!((c.flags() & NBOS_F_DYNAMIC_SR) && c.dyn)) {
     wave_sync();
 #pragma unroll
     for (int i = 0; i < 3; i++) {
       const int h = (int)((hw >> (10 * i)) & 1023u);
-      cap_bound_host_freed(c, h, (int32_t)(uni(c.m.hsn[h]) & 0xFFFFu));
+      cap_bound_host_freed(c, h, (int32_t)(uni(c.m.hsn[h]) & 0xFFFFu), now);
     }
   }
   sess_write_flag(c, r, s, (fl & ~(7u | SF_ENDING)) | SS_ENDED);
@@ -639,9 +641,12 @@ __device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint3
 }
 
 // ---- one attempt to run the pending cell of session s at time `now` -----------------------------
+// Returns what the attempt did to the things retry_horizon looks at: NEVER = nothing (the cell started by
+// election: GPUs were bound, no timer pushed); a time = a retry timer for that time was pushed and nothing
+// else changed; -1 = anything else (subscriptions moved, a host was added, bounds were lowered).
 template <uint32_t F>
-__device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
-                                        int32_t t_submit, int32_t dur) {
+__device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
+                                           int32_t t_submit, int32_t dur) {
   wave_sync();
   const int G = c.p.G;
   const int g = (int)((fl >> 3) & 7u) + 1;
@@ -680,13 +685,13 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       if (fr && rank < g) row[k] = now + dur;
       if (now == t_submit) r.c_imm++;
       start_cell(c, r, s, hw, fl, lead, hl, now, now, t_submit, dur, NBOS_D_START);
-      return;
+      return (Ctx<F>::closed || (fl & SF_ENDING)) ? -1 : NEVER;      // (those push a timer of their own)
     }
   }
   // (b), (c): a target exists? Only then is the replica to move worked out.
   uint32_t tkey = 0xFFFFFFFFu;
   if (!hopeless && (c.flags() & NBOS_F_MIGRATE)) {
-    if (c.flags() & NBOS_F_DYNAMIC_SR) {
+    if ((c.flags() & NBOS_F_DYNAMIC_SR) && c.dyn) {
       // the cap alone may rule every host out: S_h + g <= limit fails even for the least subscribed
       if (r.min_s < 0) r.min_s = min_subscription(c);
       const int32_t room = cap_room(c, g);
@@ -755,7 +760,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[dst] += moved; }
       r.min_s = -1;
       wave_sync();
-      cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu));
+      cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu), now);
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, outcome);
@@ -765,7 +770,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       if (c.lane == 0) c.m.hsn[hv] -= moved;
       r.min_s = -1;
       wave_sync();
-      cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu));
+      cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu), now);
       const int h = boot_host(c, r, now, moved);
       wave_sync();
       c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
@@ -773,7 +778,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, h, now, start, t_submit, dur, NBOS_D_SCALE_CELL);
     }
-    return;
+    return -1;
   }
   // (d) queue and retry periodically, then give up, Section 3.2.3
   int retries = (int)((fl >> 8) & 15u);
@@ -788,12 +793,12 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
     }
     r.dirty |= wballot(c.vsid == s);
     if constexpr (Ctx<F>::closed) {
-      if ((int64_t)t_submit + (int64_t)retries * c.p.retry_iv >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return; }
+      if ((int64_t)t_submit + (int64_t)retries * c.p.retry_iv >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; return -1; }
     }
     // closed loop: every timer carries its event (the cursor still points at the cell under way)
     if constexpr (Ctx<F>::closed) timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, r.cl_e, r.cl_x, r.cl_nx, r.cl_nth);
     else timer_push(c, r, t_submit + retries * c.p.retry_iv, QK_RETRY, s, dur);
-    return;
+    return t_submit + retries * c.p.retry_iv;
   }
   c32_add(c.m, c.lane, CS_ABORTED, 1u);
   decide(c, r, now, NBOS_D_ABORT, s, 0, 0);
@@ -801,6 +806,7 @@ __device__ __forceinline__ void attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t
   sess_write(c, r, s, hw, 0, nfl);
   if (fl & SF_ENDING) end_session(c, r, s, hw, nfl, now);
   if constexpr (Ctx<F>::closed) cl_schedule(c, r, s, now);
+  return -1;
 }
 
 // Sum of a per-lane value below 2^26 over the wave as a 64-bit uniform value: exact 32-bit sums per
@@ -1269,6 +1275,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
   c.ovf_dur = p.ovf_dur + (int64_t)rep * p.n_cap;
   c.nw = (int)(blockDim.x / WAVE);
   c.wid = (int)(threadIdx.x / WAVE);
+  c.dyn = dynamic_limit_matters(p, c.flags(), c.slim);
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
@@ -1284,7 +1291,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
   const bool batching = p.batch != 0;
   // Retries are looked at ahead of time (retry_lookahead) unless the cap moves with the cluster's sums: then
   // no bound on the next migration target is kept and hardly any retry is known to fail
-  const bool look_ahead = !(c.flags() & NBOS_F_DYNAMIC_SR);
+  const bool look_ahead = !((c.flags() & NBOS_F_DYNAMIC_SR) && c.dyn);
   // hash buckets (power of two <= HP) for spotting two events of one session in a tile
   const uint32_t dup_mask = (1u << (31 - __builtin_clz((uint32_t)p.HP))) - 1u;
   int32_t tick_t = ticking ? p.scale_iv : NEVER;
@@ -1369,6 +1376,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
       wave_sync();
       uint32_t a_s, a_hw, a_fl;
       int32_t a_now, a_sub, a_dur;
+      bool hz_kept = false;
       if (__builtin_expect(t < due_t, 1)) {
         const uint64_t bit = 1ull << i;
         const uint64_t clean = fastmask & ~r.dirty;
@@ -1393,6 +1401,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
         }
         if (cooldown > 0) cooldown--;
         // ---- arrival i, serial ----
+        hz_kept = hz_known;                   // (the attempt below says whether the horizon is still good)
         hz_known = false;
         todo &= ~bit;
         const uint32_t sk = (uint32_t)lane_get(vs, i);
@@ -1466,8 +1475,15 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
         }
         a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(cur.y); a_dur = dur;
       }
-      attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+      const int32_t did = attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
       due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+      // an arrival that only bound GPUs, or only joined the queue, leaves the horizon of the rounds as it
+      // was (binding keeps quiet retries quiet; the new retry has not been looked at: it ends the horizon)
+      if (hz_kept && did >= 0) {
+        hz_known = true;
+        hz = hz < did ? hz : did;
+        if (r.o_n > 0 && r.o_min_t < hz) hz = r.o_min_t;      // (the push may have moved a sorted timer out)
+      }
     }
     if (final) break;
   }

@@ -95,6 +95,7 @@ struct Ctx {
   const int32_t *cl_dur, *cl_sk;
   const int2 *cl_chain;
   int32_t qx, qnx, qnth;
+  bool dyn;                  // the dynamic limit can differ from the replay's cap (see dynamic_limit_matters)
   static constexpr bool closed = closed_loop_instance(F);
   __device__ __forceinline__ uint32_t flags() const { return instance_flags<F>(p); }
 };
@@ -898,6 +899,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   c.qt = NEVER; c.qd = 0; c.qk = 0xFFFFFFFFu;
   c.vsid = 0xFFFFFFFFu;
   c.fu = 0;
+  c.dyn = dynamic_limit_matters(p, c.flags(), c.slim);
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
@@ -1194,6 +1196,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_closed_kernel(KParams
   c.qt = NEVER; c.qd = 0; c.qk = 0xFFFFFFFFu;
   c.vsid = 0xFFFFFFFFu;
   c.fu = 0;
+  c.dyn = dynamic_limit_matters(p, c.flags(), c.slim);
   c.cl_cur = p.cl_cursor + (int64_t)rep * p.n_cap;
   c.cl_dur = p.ev_dur + ev_lo; c.cl_sk = p.ev_sk + ev_lo; c.cl_chain = p.cl_chain + ev_lo;
   c.qx = 0; c.qnx = -1; c.qnth = 0;

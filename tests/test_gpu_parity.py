@@ -138,6 +138,38 @@ def test_autoscaler_on_a_large_cluster(rp, oracle, f_milli, buf, min_hosts):
     assert max(auto) > 0
 
 
+@pytest.mark.parametrize("in_lds", [False, True], ids=["regs", "lds"])
+def test_dynamic_limit_where_it_can_and_cannot_differ(rp, oracle, in_lds):
+    # Section 3.4.1's dynamic limit equals the replay's cap when the cap admits any request on an empty host
+    # and the cluster always has more hosts than a request has GPUs (the kernels then keep their fixed-cap
+    # bounds); one host or one GPU of room less and it is worked out at every test. Both sides of that line,
+    # on a loaded cluster that grows, shrinks and migrates: G = 4, 4 or 5 hosts at the start and as the floor
+    # of the periodic release, caps that leave room for 3 or 4 subscribed GPUs per host.
+    G = 4
+    caps = [84, 167, 250, 333, 334, 1000]         # floor(cap * G * 3 / 1000) = 1, 2, 3, 3, 4, 12
+    bites = 0
+    for seed, (h0, min_hosts, hmax) in enumerate([(4, 4, 12), (5, 4, 12), (5, 5, 20), (6, 5, 30), (3, 3, 30), (5, 5, 9)]):
+        tr = tg.make_trace(1000 + seed, 80, 2000, ramp_ms=120_000,
+                           gpus=lambda r, n: np.minimum(tg.gpus_uniform(r, n), G).astype(np.uint8),
+                           gap=lambda r, s: tg.exp_ms(r, 8.0, s), dur=lambda r, s: tg.lognormal_ms(r, 20.0, 1.0, s),
+                           with_end=True)
+        cfg = tg._base_config(hosts_initial=h0, hosts_max=hmax, gpus_per_host=G,
+                              flags=tg.F_MIGRATE | tg.F_SCALE_OUT | tg.F_SCALE_IN | tg.F_DYNAMIC_SR,
+                              migration_delay_ms=500, boot_delay_ms=2000, retry_interval_ms=3000,
+                              max_retries=4, scale_interval_ms=7000, scale_in_idle_pct=10, min_hosts=min_hosts)
+        b = tg._pack(cfg, [tr], [0] * len(caps), caps, f"dynlim{seed}")
+        st, logs = gpu_run(rp, b, log=True, in_lds=in_lds)
+        assert_same(rp, oracle, b, st, logs, check=not in_lds)
+        # the same replays under the fixed cap alone: where does the dynamic limit change the outcome?
+        fixed = tg._pack(dict(cfg, flags=cfg["flags"] & ~tg.F_DYNAMIC_SR), [tr], [0] * len(caps), caps, "fixed")
+        for k, res in enumerate(oracle.replay_batch(fixed)):
+            differs = int(res["digest"]) != int(st["digest"][k])
+            bites += differs
+            if caps[k] * G * 3 // 1000 >= G and min(h0, min_hosts) > G:
+                assert not differs
+    assert bites >= 8
+
+
 def test_named_workload_c4a_autoscaler_only(rp, oracle):
     b = tg.workload("c4a", n_replays=2)
     st, logs = gpu_run(rp, b, log=True)

@@ -422,6 +422,25 @@ def test_dynamic_limit_is_vacuous_on_large_clusters(oracle, seed):
     assert oracle.replay_batch(b, check=True) == x
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_dynamic_limit_is_vacuous_when_releases_stop_above_G_hosts(oracle, seed):
+    # The same argument with the periodic release switched on: the cluster starts with more than G hosts
+    # and a release needs more than min_hosts ready hosts, so with min_hosts > G it never has G or fewer.
+    b = tg.random_case(580 + seed, n_replays=3)
+    G = b.config["gpus_per_host"]
+    b.config["flags"] |= tg.F_SCALE_IN
+    b.config["scale_in_idle_pct"] = 0                     # release whenever a host is empty
+    b.config["scale_interval_ms"] = 1000
+    if b.config["hosts_initial"] <= G:
+        b.config["hosts_max"] += G + 1 - b.config["hosts_initial"]
+        b.config["hosts_initial"] = G + 1
+    b.config["min_hosts"] = G + 1
+    b.cap_milli = np.maximum(b.cap_milli, 334).astype(np.int32)
+    x = oracle.replay_batch(b, check=True)
+    b.config["flags"] |= DYN
+    assert oracle.replay_batch(b, check=True) == x
+
+
 def test_dynamic_limit_brute_force(oracle):
     # tiny clusters where the limit does bite: compare every placement with a direct evaluation of
     # (S_h + g) / (G R) <= max(cap, (sum S + g) / (n G R)) in exact fractions
