@@ -47,7 +47,17 @@ struct KParams {
   // invalid and every replay ends at once with status NBOS_E_RANGE (calls that cannot wait for the
   // validation on the host)
   const uint32_t *trace_err;
+  // null, or the replay each workgroup runs (a permutation of 0..n_replays-1): the order of the launch
+  const int32_t *order;
 };
+
+// Workgroups start in the order of their index, and consecutive ones go to different XCDs of the chip. The
+// library therefore hands the replays out longest first (see order_replays in nbos_replay.hip): the heavy
+// replays are spread over the XCDs and the short ones fill the tail of the launch.
+__device__ __forceinline__ int launch_slot_replay(const KParams &p) {
+  if ((int)blockIdx.x >= p.n_replays) return p.n_replays;       // (the callers return at once)
+  return p.order ? p.order[blockIdx.x] : (int)blockIdx.x;
+}
 
 // A replay that cannot run (invalid traces, more sessions than the launch has LDS for): its record
 // holds the status and zeros.

@@ -203,7 +203,7 @@ __device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
 
 __global__ void __launch_bounds__(WAVE) nbos_replay_batch_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int rep = blockIdx.x;
+  const int rep = launch_slot_replay(p);
   const int lane = threadIdx.x;
   if (rep >= p.n_replays) return;
 

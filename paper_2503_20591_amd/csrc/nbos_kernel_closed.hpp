@@ -155,7 +155,7 @@ template <uint32_t F>
 __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KParams p) {
   static_assert(Ctx<F>::closed, "instantiate with a closed-loop flag set");
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int rep = blockIdx.x;
+  const int rep = launch_slot_replay(p);
   const int lane = threadIdx.x & (WAVE - 1);
   if (rep >= p.n_replays) return;
 

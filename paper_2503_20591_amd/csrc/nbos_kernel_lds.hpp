@@ -1256,7 +1256,7 @@ __device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, cons
 template <uint32_t F>
 __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int rep = blockIdx.x;
+  const int rep = launch_slot_replay(p);
   const int lane = threadIdx.x & (WAVE - 1);
   if (rep >= p.n_replays) return;
 

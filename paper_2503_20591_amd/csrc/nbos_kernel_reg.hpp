@@ -855,7 +855,7 @@ __device__ __forceinline__ void write_stats(const KParams &p, const Lds &m, cons
 template <int NJ, uint32_t F>
 __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int rep = blockIdx.x;
+  const int rep = launch_slot_replay(p);
   const int lane = threadIdx.x;
   if (rep >= p.n_replays) return;
   // launched without a look at the traces on the host: the validation kernel's verdict comes first
@@ -1175,7 +1175,7 @@ template <int NJ, uint32_t F>
 __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_closed_kernel(KParams p) {
   static_assert(Ctx<NJ, F>::closed, "instantiate with a closed-loop flag set");
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int rep = blockIdx.x;
+  const int rep = launch_slot_replay(p);
   const int lane = threadIdx.x;
   if (rep >= p.n_replays) return;
 

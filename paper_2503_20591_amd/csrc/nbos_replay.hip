@@ -12,6 +12,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -205,6 +206,7 @@ struct nbos_replay {
   nbos_stats *d_stats;
   nbos_bill *d_bill;
   int32_t *d_ovf;          // open-loop replay kernels: durations of queued cells, [n_replays][n_cap]
+  int32_t *d_order;        // the replay each workgroup of the launch runs
   int32_t *d_chain;        // closed loop only: the chain records of all events, then the cursors
   uint64_t *d_log;
   std::vector<int64_t> ev_off;
@@ -220,6 +222,7 @@ void free_handle(nbos_replay *h) {
   if (h->d_stats) (void)hipFree(h->d_stats);
   if (h->d_bill) (void)hipFree(h->d_bill);
   if (h->d_ovf) (void)hipFree(h->d_ovf);
+  if (h->d_order) (void)hipFree(h->d_order);
   if (h->d_chain) (void)hipFree(h->d_chain);
   if (h->d_log) (void)hipFree(h->d_log);
   if (h->e0) (void)hipEventDestroy(h->e0);
@@ -528,6 +531,35 @@ int32_t allocate_buffers(nbos_replay *h, const Shape &sh) {
   return NBOS_OK;
 }
 
+// The order in which the launch hands the replays out. Workgroups start in the order of their index (as
+// many as fit the chip at once, the others as earlier ones end) and consecutive ones go to different XCDs,
+// so a replay's place in that order decides which replays share an XCD and which ones are still running
+// when the launch tails off. Longest first: the replays are sorted by the number of events of their trace
+// and then by their subscription cap, both descending (on a loaded cluster a higher cap places more
+// sessions, and placed sessions are what costs time; on an idle one the cap does not matter). Measured on
+// 4,096 replays of 64 hosts with four caps in turn, where every XCD used to get one cap only: 164 -> 104 ms;
+// on 16,384 replays of 16 to 24 hosts with random caps: 77 -> 66 ms. Results do not depend on the order:
+// every replay writes the records of its own index.
+int32_t order_replays(nbos_replay *h) {
+  const size_t n = (size_t)h->cfg.n_replays;
+  if (n < 2) return NBOS_OK;
+  std::vector<int32_t> cap(n), tor(n), order(n);
+  HIP_TRY(hipMemcpyAsync(cap.data(), h->in.cap_milli, sizeof(int32_t) * n, hipMemcpyDeviceToHost, h->stream));
+  HIP_TRY(hipMemcpyAsync(tor.data(), h->in.trace_of_replay, sizeof(int32_t) * n, hipMemcpyDeviceToHost, h->stream));
+  HIP_TRY(hipStreamSynchronize(h->stream));
+  for (size_t i = 0; i < n; i++) order[i] = (int32_t)i;
+  const std::vector<int64_t> &off = h->ev_off;          // (the validation has checked the trace indices)
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+    const int64_t ea = off[tor[a] + 1] - off[tor[a]], eb = off[tor[b] + 1] - off[tor[b]];
+    if (ea != eb) return ea > eb;
+    return cap[a] > cap[b];
+  });
+  if (hipMalloc(&h->d_order, sizeof(int32_t) * n) != hipSuccess) return NBOS_E_NOMEM;
+  HIP_TRY(hipMemcpyAsync(h->d_order, order.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice, h->stream));
+  HIP_TRY(hipStreamSynchronize(h->stream));               // (the host vector goes away)
+  return NBOS_OK;
+}
+
 // the kernels' parameter block
 void fill_params(nbos_replay *h, const Shape &sh) {
   const nbos_config *cfg = &h->cfg;
@@ -537,6 +569,7 @@ void fill_params(nbos_replay *h, const Shape &sh) {
   k.sess_offset = in->sess_offset; k.sess_gpus = in->sess_gpus;
   k.trace_of_replay = in->trace_of_replay; k.cap_milli = in->cap_milli;
   k.stats = h->d_stats; k.dlog = h->d_log; k.ovf_dur = h->d_ovf;       // dlog_stride: set with the log's allocation
+  k.order = h->d_order;
   k.n_replays = cfg->n_replays; k.H0 = cfg->hosts_initial; k.Hmax = cfg->hosts_max; k.HP = sh.HP;
   k.G = cfg->gpus_per_host; k.flags = cfg->flags;
   k.migr = cfg->migration_delay_ms; k.boot = cfg->boot_delay_ms; k.retry_iv = cfg->retry_interval_ms;
@@ -591,7 +624,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   nbos_replay *h = new (std::nothrow) nbos_replay();
   if (!h) return NBOS_E_NOMEM;
   h->cfg = cfg; h->in = *in; h->stream = (hipStream_t)stream;
-  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_chain = nullptr; h->d_log = nullptr;
+  h->d_stats = nullptr; h->d_bill = nullptr; h->d_ovf = nullptr; h->d_order = nullptr; h->d_chain = nullptr; h->d_log = nullptr;
   h->kernel = nullptr; h->kernel_name[0] = 0; h->threads = WAVE; h->e0 = nullptr; h->e1 = nullptr; h->ran = false;
   memset(&h->kp, 0, sizeof h->kp);
   Shape sh;
@@ -601,6 +634,7 @@ int32_t nbos_replay_create(const nbos_config *cfg_in, const nbos_inputs *in, voi
   if (rc == NBOS_OK) rc = choose_kernel(h, &sh);
   if (rc == NBOS_OK) rc = validate_on_device(h, slack);
   if (rc == NBOS_OK) rc = allocate_buffers(h, sh);
+  if (rc == NBOS_OK) rc = order_replays(h);
   if (rc != NBOS_OK) { free_handle(h); return rc; }
   fill_params(h, sh);
   *out = h;
