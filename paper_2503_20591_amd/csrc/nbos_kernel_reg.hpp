@@ -463,28 +463,21 @@ __device__ __forceinline__ void start_cell(Ctx<NJ, F> &c, Regs &r, uint32_t s, u
 }
 
 // ---- executor election, Section 3.2.2 ----------------------------------------------------------------
-// Among the session's hosts in `cand` (ready, g idle GPUs; not empty): fewest committed GPUs, then lowest
-// host index. At most three bits of `cand` are set: walk them. Returns the host.
+// key: per lane = host, (committed GPUs << 6) | host where the host is ready and has the GPUs idle, else all
+// ones. Among the session's three hosts: fewest committed GPUs, then lowest host index, i.e. the smallest
+// of their keys. Returns that key (host in the low 6 bits), or all ones when every replica yields.
 template <int NJ, uint32_t F>
-__device__ __forceinline__ int elect(const Ctx<NJ, F> &c, uint32_t hw, int C, uint64_t idle_ok, uint64_t cand) {
-  const uint32_t key = ((uint32_t)C << 6) | (uint32_t)c.lane;
-  uint32_t best = (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand));
-  cand &= cand - 1;
-  if (cand != 0) {
-    best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
-    cand &= cand - 1;
-    if (cand != 0) best = umin(best, (uint32_t)lane_get((int)key, (int)__builtin_ctzll(cand)));
-  }
-  int hl = (int)(best & 63u);
+__device__ __forceinline__ uint32_t elect(const Ctx<NJ, F> &c, uint32_t hw, uint32_t key) {
+  const uint32_t k0 = (uint32_t)lane_get((int)key, (int)slot_host(hw, 0)), k1 = (uint32_t)lane_get((int)key, (int)slot_host(hw, 1)),
+                 k2 = (uint32_t)lane_get((int)key, (int)slot_host(hw, 2));
+  uint32_t kb = umin(k0, umin(k1, k2));
   if (c.flags() & NBOS_F_STICKY_EXECUTOR) {
     // variant: the replica that ran the previous cell leads again if its host can bind
     const uint32_t last = hw >> 30;
-    if (last != 0) {
-      const int hp = (int)slot_host(hw, last - 1u);
-      if ((idle_ok >> hp) & 1u) hl = hp;
-    }
+    const uint32_t kp = last == 1u ? k0 : (last == 2u ? k1 : (last == 3u ? k2 : 0xFFFFFFFFu));
+    if (kp != 0xFFFFFFFFu) kb = kp;
   }
-  return hl;
+  return kb;
 }
 
 // A cell of an idle placed session starts by election at the instant it is submitted (open loop): what
@@ -518,15 +511,17 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
   const bool hopeless = now < lane_get(c.fu, g - 1);
   int C = 0;
   uint64_t idle_ok = 0;
+  uint32_t kb = 0xFFFFFFFFu;
   if (!hopeless) {
     C = committed(c, now);
-    idle_ok = wballot(c.hr <= now && C + g <= c.p.G);     // ready hosts with g idle GPUs
+    const bool can = c.hr <= now && C + g <= c.p.G;       // a ready host with g idle GPUs
+    idle_ok = wballot(can);
+    // (a) election, Section 3.2.2: among the session's hosts that can bind, fewest committed GPUs, then
+    // lowest host index: the smallest of the three hosts' keys
+    kb = elect(c, hw, can ? (((uint32_t)C << 6) | (uint32_t)c.lane) : 0xFFFFFFFFu);
   }
-  // (a) election, Section 3.2.2: among the session's hosts in idle_ok, fewest committed GPUs, then
-  // lowest host index. At most three bits of `cand` are set: walk them.
-  const uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
-  if (cand != 0) {
-    const int hl = elect(c, hw, C, idle_ok, cand);
+  if (kb != 0xFFFFFFFFu) {
+    const int hl = (int)(kb & 63u);
     const int lead = (uint32_t)hl == h0 ? 0 : ((uint32_t)hl == h1 ? 1 : 2);
     bind_gpus(c, hl, g, now, now + dur);
     if (now == t_submit) r.c_imm++;
@@ -675,10 +670,10 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
     if (give_up && (fl & SF_ENDING)) break;                    // ... and the session ends: general path
     const int g = (int)((fl >> 3) & 7u) + 1;
     if (now >= lane_get(c.fu, g - 1)) {
-      const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
       const int C = committed(c, now);
-      const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);
-      if (idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2))) break;          // the election succeeds
+      const bool can = c.hr <= now && C + g <= c.p.G;
+      if (elect(c, hw, can ? (uint32_t)c.lane : 0xFFFFFFFFu) != 0xFFFFFFFFu) break;   // the election succeeds
+      const uint64_t idle_ok = wballot(can);
       if (idle_ok == 0) {
         const int32_t bound = earliest_idle(c, g);
         if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
@@ -986,13 +981,14 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
         }
         const int g = (int)((hw >> 3) & 7u) + 1;
         if (t < lane_get(c.fu, g - 1)) break;                 // no host has g idle GPUs yet
+        // election (Section 3.2.2) on the vector side: every host's key (committed GPUs, index), or all
+        // ones where it cannot bind; the keys of the session's three hosts are read and compared
         const int C = committed(c, t);
-        const uint64_t idle_ok = wballot(c.hr <= t && C + g <= c.p.G);
-        const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
-        const uint64_t cand = idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2));
-        if (cand == 0) break;                                 // every replica yields
-        const int hl = elect(c, hw, C, idle_ok, cand);
-        const int lead = (uint32_t)hl == h0 ? 0 : ((uint32_t)hl == h1 ? 1 : 2);
+        const uint32_t key = (c.hr <= t && C + g <= c.p.G) ? (((uint32_t)C << 6) | (uint32_t)c.lane) : 0xFFFFFFFFu;
+        const uint32_t kb = elect(c, hw, key);
+        if (kb == 0xFFFFFFFFu) break;                         // every replica yields
+        const int hl = (int)(kb & 63u);
+        const int lead = (uint32_t)hl == slot_host(hw, 0) ? 0 : ((uint32_t)hl == slot_host(hw, 1) ? 1 : 2);
         const int32_t dur = lane_get(vd, i);
         bind_gpus(c, hl, g, t, t + dur);
         start_at_once(c, r, (uint32_t)lane_get(vs, i) & 0xFFFFFFu, hw, lead, hl, t, dur);
@@ -1114,10 +1110,10 @@ __device__ __forceinline__ int32_t cl_failing_retries(Ctx<NJ, F> &c, Regs &r, in
     if (retries >= c.p.max_retries) break;                     // it would be given up: general path
     const int g = (int)((fl >> 3) & 7u) + 1;
     if (now >= lane_get(c.fu, g - 1)) {
-      const uint32_t h0 = slot_host(hw, 0), h1 = slot_host(hw, 1), h2 = slot_host(hw, 2);
       const int C = committed(c, now);
-      const uint64_t idle_ok = wballot(c.hr <= now && C + g <= c.p.G);
-      if (idle_ok & ((1ull << h0) | (1ull << h1) | (1ull << h2))) break;          // the election succeeds
+      const bool can = c.hr <= now && C + g <= c.p.G;
+      if (elect(c, hw, can ? (uint32_t)c.lane : 0xFFFFFFFFu) != 0xFFFFFFFFu) break;   // the election succeeds
+      const uint64_t idle_ok = wballot(can);
       if (idle_ok == 0) {
         const int32_t bound = earliest_idle(c, g);
         if (c.lane >= g - 1 && c.fu < bound) c.fu = bound;
