@@ -26,9 +26,13 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 GPU_BOX_CPU_SHARE = 16    # host threads one GPU's share of the box allows
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per launch from the committed rocprofv3 counter runs (profiles/hbm_traffic.json),
-    or None when the kernel sources have changed since they were taken."""
+COMPUTE_UNITS = 256       # MI355X
+CLOCK_HZ = 2.4e9
+
+
+def counter_record(workload: str):
+    """What the committed rocprofv3 counter runs read for one launch of this workload
+    (profiles/hbm_traffic.json), or None when the kernel sources have changed since they were taken."""
     import glob
     import hashlib
     try:
@@ -41,7 +45,27 @@ def measured_traffic(workload: str):
     for f in sorted(glob.glob(os.path.join(ROOT, "paper_2503_20591_amd", "csrc", "*"))):
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
-    return rec["traffic_bytes"] if h.hexdigest() == rec["csrc_sha256"] else None
+    return rec if h.hexdigest() == rec["csrc_sha256"] else None
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), or None."""
+    rec = counter_record(workload)
+    return rec["traffic_bytes"] if rec else None
+
+
+def issue_rates(workload: str, kernel_s: float):
+    """Instructions the launch executes (counter runs) over the launch time measured here, per clock and
+    compute unit. A compute unit issues at most one scalar and one vector wave-instruction per clock
+    (one scalar unit; four SIMDs that take a wave64 vector instruction every four clocks)."""
+    rec = counter_record(workload)
+    if not rec or "insts_salu" not in rec:
+        return None
+    per = lambda n: n / (kernel_s * COMPUTE_UNITS * CLOCK_HZ)
+    return {"scalar_per_clock_per_cu": per(rec["insts_salu"]), "vector_per_clock_per_cu": per(rec["insts_valu"]),
+            "lds_per_clock_per_cu": per(rec["insts_lds"]), "peak_each": 1.0,
+            "instructions_per_launch": rec["insts_salu"] + rec["insts_valu"] + rec["insts_lds"],
+            "note": "instruction counts from the committed counter runs of this kernel, time from this run"}
 
 
 def cpu_model() -> str:
@@ -203,6 +227,7 @@ def main():
                      "kernel_ms_median": statistics.median(dur), "kernel_ms_last_by_library_events": last_ms,
                      "algorithmic_bytes": alg_bytes,
                      "ns_per_event_per_replay": avg_kernel_ms * 1e6 / ev_per_replay,
+                     "issue": issue_rates(args.workload, avg_kernel_ms * 1e-3) if default_shape else None,
                      "chain_floor_ns": floor_ns,
                      "chain_floor_note": "one dependent event body (LDS row read, count, wave minimum, LDS write) on a "
                                          "lone wave; a replay cannot take a step in less"},
