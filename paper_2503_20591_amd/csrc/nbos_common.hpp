@@ -8,6 +8,41 @@
 
 namespace {
 
+// ---- path profile (diagnostic build only: -DNBOS_PATH_PROFILE) -----------------------------------------
+// Where does a replay spend its time? The wave that runs the replay reads the cycle counter at the marks
+// below and adds the clocks since the previous mark to the category of the path just left (and a count);
+// the sums of every replay go to a device array that nbos_path_profile_read copies out. The marks cost
+// time of their own (two counter reads and two LDS atomics each), so a profiled launch runs about a tenth
+// longer; the shares are what it is for. In the product build every mark is empty.
+#ifdef NBOS_PATH_PROFILE
+enum { PC_TILE, PC_ROUND, PC_ELECT, PC_MIGR, PC_FAIL, PC_START, PC_END, PC_TIMER_OTHER, PC_TICK, PC_RETRY_ELECT,
+       PC_RETRY_MIGR, PC_RETRY_FAIL, PC_QUIET_RETRIES, PC_DROP, PC_LOOP_HORIZON, PC_LOOP_ROUND, PC_LOOP_TIMER,
+       PC_LOOP_STARTEND, PC_LOOP_ATTEMPT, PC_HORIZON, PC_A_ELECT, PC_A_TARGET, PC_A_VICTIM, PC_A_BIND, PC_N };
+constexpr int PATH_PROFILE_REPLAYS = 16384;      // replays beyond this many are not recorded
+static __device__ unsigned long long g_path_profile[PATH_PROFILE_REPLAYS * 2 * PC_N];
+__shared__ unsigned long long prof_t[PC_N];
+__shared__ unsigned long long prof_n[PC_N];
+#define PROF_BEGIN() if (threadIdx.x < PC_N) { prof_t[threadIdx.x] = 0; prof_n[threadIdx.x] = 0; } unsigned long long pt0 = __builtin_readcyclecounter()
+#define PROF(cat, cnt) do { const unsigned long long now_ = __builtin_readcyclecounter(); if (threadIdx.x == 0) { atomicAdd(&prof_t[cat], now_ - pt0); atomicAdd(&prof_n[cat], (unsigned long long)(cnt)); } pt0 = __builtin_readcyclecounter(); } while (0)
+// marks inside attempt(): clocks since the attempt began or since the mark before (these overlap PROF's)
+#define PROF_SUB_BEGIN() unsigned long long pa0 = __builtin_readcyclecounter()
+#define PROF_SUB(cat) do { const unsigned long long now_ = __builtin_readcyclecounter(); if (threadIdx.x == 0) { atomicAdd(&prof_t[cat], now_ - pa0); atomicAdd(&prof_n[cat], 1ull); } pa0 = __builtin_readcyclecounter(); } while (0)
+#define PROF_OUT(rep) do { __syncthreads(); if (threadIdx.x < PC_N && (rep) < PATH_PROFILE_REPLAYS) { g_path_profile[((rep) * 2) * PC_N + threadIdx.x] = prof_t[threadIdx.x]; g_path_profile[((rep) * 2 + 1) * PC_N + threadIdx.x] = prof_n[threadIdx.x]; } } while (0)
+// an attempt is booked by what came of it: the cell started by election, after a migration, or not at all
+#define PROF_ATTEMPT_BEGIN(m, r) const uint32_t prof_st0 = (r).c_started; wave_sync(); const uint32_t prof_mg0 = uni((m).c32[CS_MIGR])
+#define PROF_ATTEMPT_END(m, r, is_retry) do { wave_sync(); const uint32_t mg1_ = uni((m).c32[CS_MIGR]); \
+    const int cat_ = (r).c_started == prof_st0 ? ((is_retry) ? PC_RETRY_FAIL : PC_FAIL) : mg1_ != prof_mg0 ? ((is_retry) ? PC_RETRY_MIGR : PC_MIGR) : ((is_retry) ? PC_RETRY_ELECT : PC_ELECT); \
+    PROF(cat_, 1); } while (0)
+#else
+#define PROF_BEGIN() do { } while (0)
+#define PROF(cat, cnt) do { } while (0)
+#define PROF_SUB_BEGIN() do { } while (0)
+#define PROF_SUB(cat) do { } while (0)
+#define PROF_OUT(rep) do { } while (0)
+#define PROF_ATTEMPT_BEGIN(m, r) do { } while (0)
+#define PROF_ATTEMPT_END(m, r, is_retry) do { } while (0)
+#endif
+
 constexpr int WAVE = 64;
 constexpr int32_t NEVER = 0x7FFFFFFF;
 constexpr int NGPU = NBOS_MAX_GPUS;

@@ -647,6 +647,7 @@ __device__ __forceinline__ void start_cell(Ctx<F> &c, Regs &r, uint32_t s, uint3
 template <uint32_t F>
 __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint32_t hw, uint32_t fl, int32_t now,
                                            int32_t t_submit, int32_t dur) {
+  PROF_SUB_BEGIN();
   wave_sync();
   const int G = c.p.G;
   const int g = (int)((fl >> 3) & 7u) + 1;
@@ -688,6 +689,7 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
       return (Ctx<F>::closed || (fl & SF_ENDING)) ? -1 : NEVER;      // (those push a timer of their own)
     }
   }
+  PROF_SUB(PC_A_ELECT);
   // (b), (c): a target exists? Only then is the replica to move worked out.
   uint32_t tkey = 0xFFFFFFFFu;
   if (!hopeless && (c.flags() & NBOS_F_MIGRATE)) {
@@ -723,6 +725,7 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
       }
     }
   }
+  PROF_SUB(PC_A_TARGET);
   bool grow = false;
   if (tkey == 0xFFFFFFFFu && (c.flags() & NBOS_F_SCALE_OUT)) {
     wave_sync();
@@ -761,9 +764,11 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
       r.min_s = -1;
       wave_sync();
       cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu), now);
+      PROF_SUB(PC_A_VICTIM);
       bind_gpus(c, dst, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, dst, now, start, t_submit, dur, outcome);
+      PROF_SUB(PC_A_BIND);
     } else {
       // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
@@ -1267,6 +1272,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
 
   const Lds m = lds_carve<false>(p, lds_raw);
   lds_init<false>(p, m, s_lo, n_sess);
+  PROF_BEGIN();
 
   const int32_t caplim = p.cap_milli[rep] * p.G * 3;
   Ctx<F> c{p, m, lane, caplim / 1000, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr,
@@ -1364,6 +1370,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
       r.lazy_max = r.lazy_max > bl ? r.lazy_max : bl;
     }
     const uint64_t fastmask = wballot(fast);
+    PROF(PC_TILE, 1);
     const uint64_t queued_lanes = wballot(((uint32_t)rec.z & 7u) == SS_QUEUED);
     bool hz_known = false;
     int32_t hz = 0;
@@ -1376,6 +1383,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
       wave_sync();
       uint32_t a_s, a_hw, a_fl;
       int32_t a_now, a_sub, a_dur;
+      [[maybe_unused]] bool is_retry = false;      // (path profile)
       bool hz_kept = false;
       if (__builtin_expect(t < due_t, 1)) {
         const uint64_t bit = 1ull << i;
@@ -1385,7 +1393,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
           // the run may go on past retries that are known to fail quietly
           int32_t run_due = due_t;
           if (look_ahead && due_t == r.q_head_t && due_t <= last_t) {
-            if (!hz_known) { hz = retry_horizon(c, r, last_t); hz_known = true; }    // (rounds change nothing it looks at)
+            if (!hz_known) { PROF(PC_LOOP_HORIZON, 1); hz = retry_horizon(c, r, last_t); hz_known = true; PROF(PC_HORIZON, 1); }    // (rounds change nothing it looks at)
             run_due = hz < tick_t ? hz : tick_t;
           }
           const uint64_t eligible = clean & wballot(vt < run_due);
@@ -1393,7 +1401,9 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
           const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
           if ((run & (run - 1)) != 0) {          // at least two lanes
             bool next_lost;
+            PROF(PC_LOOP_ROUND, 1);
             const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec, next_lost);
+            PROF(PC_ROUND, __builtin_popcountll(done));
             // none or one started, or the next arrival has just lost its election: it goes alone
             cooldown = ((done & (done - 1)) == 0 || next_lost) ? 1 : 0;
             if (done != 0) { todo &= ~done; continue; }
@@ -1426,17 +1436,20 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
               a_s = s; a_hw = hw; a_fl = fl & ~(SF_QONCE | (15u << 8)); a_now = t; a_sub = t; a_dur = lane_get(vd, i);
             } else {
               if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++; else r.c_unplaced++;
+              PROF(PC_DROP, 1);
               continue;
             }
           } else {
-            if (kind == NBOS_EV_START) session_start(c, r, s, fl, t);      // S3, S7
-            else on_session_end(c, r, s, hw, tm, fl, t);
+            PROF(PC_LOOP_STARTEND, 1);
+            if (kind == NBOS_EV_START) { session_start(c, r, s, fl, t); PROF(PC_START, 1); }      // S3, S7
+            else { on_session_end(c, r, s, hw, tm, fl, t); PROF(PC_END, 1); }
             due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
             continue;
           }
         }
       } else {
         // ---- a timer may be due (S2); always taken while draining ----
+        PROF(PC_LOOP_TIMER, 1);
         hz_known = false;
         bool fire_q = r.q_n > 0, fire_t = ticking;
         if (final) {
@@ -1451,12 +1464,14 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
           tick(c, r, tick_t);
           tick_t += p.scale_iv;
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          PROF(PC_TICK, 1);
           continue;
         }
         if (!fire_q) break;                   // only reached while draining: nothing is left
         // (timers fire up to the next arrival, and up to the next auto-scaler period: that one runs after the
         // timers of its own instant and before all later ones)
         if (look_ahead && fire_quiet_retries(c, r, t < tick_t ? t : tick_t, queued_lanes)) {
+          PROF(PC_QUIET_RETRIES, 1);
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
           continue;
         }
@@ -1471,11 +1486,16 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
         if ((key >> 16) != QK_RETRY) {
           end_session(c, r, s, hw, fl, now);
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          PROF(PC_TIMER_OTHER, 1);
           continue;
         }
         a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(cur.y); a_dur = dur;
+        is_retry = true;
       }
+      PROF(PC_LOOP_ATTEMPT, 1);
+      PROF_ATTEMPT_BEGIN(m, r);
       const int32_t did = attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+      PROF_ATTEMPT_END(m, r, is_retry);
       due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
       // an arrival that only bound GPUs, or only joined the queue, leaves the horizon of the rounds as it
       // was (binding keeps quiet retries quiet; the new retry has not been looked at: it ends the horizon)
@@ -1491,6 +1511,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
   }  // wave 0
 
   write_stats(p, m, r, rep);
+  PROF_OUT(rep);
 }
 
 }  // namespace ldsk

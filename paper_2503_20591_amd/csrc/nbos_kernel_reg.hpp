@@ -905,6 +905,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
   const bool ticking = (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_AUTOSCALE)) != 0;
   int32_t tick_t = ticking ? p.scale_iv : NEVER;
   int32_t due_t = tick_t;                   // earliest queued timer or auto-scaler period
+  PROF_BEGIN();
 
   // S1: stream the events, one per lane per tile, next tile in flight
   int64_t base = ev_lo;                     // first event of the tile held in (nt, nd, ns)
@@ -956,6 +957,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
       final = true;
     }
     const uint64_t fastmask = wballot(fast != 0);
+    PROF(PC_TILE, 1);
     const uint64_t cellmask = wballot(base_valid_cell);
     r.slow_lanes = ~fastmask;
     for (;;) {
@@ -964,6 +966,8 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
       // record, or, where that is stale, by the record as it is now), no timer due first, the election won.
       // A loop of its own with nothing else in it; whatever does not fit leaves the arrival to the general
       // path below.
+      PROF(PC_LOOP_ROUND, 1);
+      [[maybe_unused]] const uint32_t prof_imm0 = r.c_imm;
       while (todo != 0) {
         const int i = (int)__builtin_ctzll(todo);
         if (((cellmask >> i) & 1ull) == 0) break;
@@ -994,6 +998,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
         start_at_once(c, r, (uint32_t)lane_get(vs, i) & 0xFFFFFFu, hw, lead, hl, t, dur);
         todo &= todo - 1;
       }
+      PROF(PC_ROUND, r.c_imm - prof_imm0);
       int i = 0;
       int32_t t = NEVER;
       if (todo != 0) { i = (int)__builtin_ctzll(todo); t = lane_get(vt, i); }
@@ -1001,6 +1006,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
       wave_sync();
       uint32_t a_s, a_hw, a_fl;
       int32_t a_now, a_sub, a_dur;
+      [[maybe_unused]] bool is_retry = false;      // (path profile)
       if (__builtin_expect(t < due_t, 1)) {
         // ---- arrival i ----
         const uint64_t bit = 1ull << i;
@@ -1028,19 +1034,23 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
               a_s = s; a_hw = hw; a_fl = fl & ~(15u << 8); a_now = t; a_sub = t; a_dur = lane_get(vd, i);
             } else {
               if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++; else r.c_unplaced++;
+              PROF(PC_DROP, 1);
               continue;
             }
           } else {
-            if (kind == NBOS_EV_START) session_start(c, r, s, fl, t);      // S3, S7
-            else on_session_end(c, r, s, hw, tm, fl, t);
+            PROF(PC_LOOP_STARTEND, 1);
+            if (kind == NBOS_EV_START) { session_start(c, r, s, fl, t); PROF(PC_START, 1); }      // S3, S7
+            else { on_session_end(c, r, s, hw, tm, fl, t); PROF(PC_END, 1); }
             due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
             continue;
           }
         }
       } else {
         // ---- a timer may be due (S2); always taken while draining ----
+        PROF(PC_LOOP_TIMER, 1);
         {
           const int32_t last = failing_retries(c, r, t, tick_t);
+          PROF(PC_QUIET_RETRIES, 1);
           if (last >= 0) {
             r.t_end = r.t_end > last ? r.t_end : last;
             due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
@@ -1060,6 +1070,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
           tick(c, r, tick_t);
           tick_t += p.scale_iv;
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          PROF(PC_TICK, 1);
           continue;
         }
         if (!fire_q) break;                   // only reached while draining: nothing is left
@@ -1074,17 +1085,23 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
         if ((key >> 16) != QK_RETRY) {
           end_session(c, r, s, hw, fl, now);
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
+          PROF(PC_TIMER_OTHER, 1);
           continue;
         }
         a_s = s; a_hw = hw; a_fl = fl; a_now = now; a_sub = uni(cur.y); a_dur = dur;
+        is_retry = true;
       }
+      PROF(PC_LOOP_ATTEMPT, 1);
+      PROF_ATTEMPT_BEGIN(m, r);
       attempt(c, r, a_s, a_hw, a_fl, a_now, a_sub, a_dur);
+      PROF_ATTEMPT_END(m, r, is_retry);
       due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
     }
     if (final) break;
   }
 
   write_stats(p, m, r, rep, lane);
+  PROF_OUT(rep);
 }
 
 // ---- closed loop: runs of retries that fail again (failing_retries() for this kernel) -----------------

@@ -416,6 +416,9 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   const bool closed_loop = (cfg->flags & NBOS_F_CLOSED_LOOP) != 0;
   int maxlds = 0;
   HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
+#ifdef NBOS_PATH_PROFILE
+  maxlds -= 512;                            // the profile's own counters are static LDS
+#endif
   sh->in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
   sh->HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
   // the kernels with host state in LDS give the scans over all hosts to four waves from 256 hosts on
@@ -788,6 +791,18 @@ int32_t nbos_replay_run_static(const nbos_config *cfg_in, const nbos_inputs *in,
   if (hipLaunchKernel(tmp.kernel, dim3(cfg.n_replays), dim3(WAVE), args, tmp.lds_bytes, st) != hipSuccess) return NBOS_E_HIP;
   return NBOS_OK;
 }
+
+#ifdef NBOS_PATH_PROFILE
+// Diagnostic build only (not declared in nbos.h): the path profile of the last launch of an open-loop replay
+// kernel, host_out[replay][0 = clocks, 1 = counts][category], PC_N categories, the first `replays` replays.
+int32_t nbos_path_profile_read(unsigned long long *host_out, int32_t replays, int32_t *categories) {
+  if (categories) *categories = PC_N;
+  if (!host_out || replays < 0 || replays > PATH_PROFILE_REPLAYS) return NBOS_E_ARG;
+  if (hipDeviceSynchronize() != hipSuccess) return NBOS_E_HIP;
+  return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_path_profile), sizeof(unsigned long long) * 2 * PC_N * (size_t)replays, 0,
+                             hipMemcpyDeviceToHost) == hipSuccess ? NBOS_OK : NBOS_E_HIP;
+}
+#endif
 
 const char *nbos_replay_kernel_name(nbos_replay *h) { return h ? h->kernel_name : ""; }
 
