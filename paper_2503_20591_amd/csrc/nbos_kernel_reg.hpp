@@ -649,14 +649,17 @@ __device__ __forceinline__ void attempt(Ctx<NJ, F> &c, Regs &r, uint32_t s, uint
 // needs anything else is left for the general path. A retry that fails with no retries left gives its
 // cell up right here. t_limit = time of the next arrival (timers due
 // at or before it run first), tick_t = next auto-scaler period (a timer due at the same time runs
-// before it). Returns the time of the last retry handled, or -1.
-template <int NJ, uint32_t F>
+// before it). Returns the time of the last retry handled, or -1. CROWDED: timers are waiting in the session
+// records as well (more than 64 pending); a retry that is then no longer earlier than all of those goes to
+// wait there too, and the registers are refilled when they run empty. Two instances, so that the common
+// case keeps its shorter loop.
+template <bool CROWDED, int NJ, uint32_t F>
 __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32_t t_limit, int32_t tick_t) {
   int32_t last = -1;
   const int32_t due = t_limit < tick_t ? t_limit : tick_t;
   const bool may_skip = !(c.flags() & NBOS_F_AUTOSCALE) &&
                         (c.flags() & (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT)) != (NBOS_F_SCALE_IN | NBOS_F_SCALE_OUT);
-  while (r.q_n > 0 && r.o_n == 0 && r.q_head_t <= due) {
+  while (r.q_n > 0 && (CROWDED || r.o_n == 0) && r.q_head_t <= due) {
     const int32_t now = r.q_head_t;
     const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
     if ((key >> 16) != QK_RETRY) break;
@@ -697,6 +700,7 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
       c.qd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
       c.qk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
       r.q_n--;
+      if constexpr (CROWDED) { if (r.q_n == 0 && r.o_n > 0) refill(c, r); }
       r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
       continue;
     }
@@ -711,12 +715,23 @@ __device__ __forceinline__ int32_t failing_retries(Ctx<NJ, F> &c, Regs &r, int32
     r.dirty |= wballot(c.vsid == s);
     // ... and move the entry from lane 0 to its new place: entries before it shift down one lane
     const int32_t t_new = t_submit + retries * c.p.retry_iv;
-    const bool before = c.lane >= 1 && c.lane < r.q_n && (c.qt < t_new || (c.qt == t_new && c.qk < key));
-    const int pos = __builtin_popcountll(wballot(before));
     const int32_t st = __builtin_amdgcn_update_dpp(c.qt, c.qt, 0x130, 0xF, 0xF, false);          // wave_shl:1
     const int32_t sd = __builtin_amdgcn_update_dpp(c.qd, c.qd, 0x130, 0xF, 0xF, false);
     const uint32_t sk = (uint32_t)__builtin_amdgcn_update_dpp((int)c.qk, (int)c.qk, 0x130, 0xF, 0xF, false);
     const int32_t d_own = lane_get(c.qd, 0);
+    if constexpr (CROWDED) {
+      if (r.o_n > 0 && !(t_new < r.o_min_t || (t_new == r.o_min_t && key < r.o_min_k))) {
+        // no longer earlier than all that waits in the records: the timer goes there, off the registers
+        ovf_push(c, r, t_new, key, d_own);
+        c.qt = st; c.qd = sd; c.qk = sk;
+        r.q_n--;
+        if (r.q_n == 0 && r.o_n > 0) refill(c, r);
+        r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
+        continue;
+      }
+    }
+    const bool before = c.lane >= 1 && c.lane < r.q_n && (c.qt < t_new || (c.qt == t_new && c.qk < key));
+    const int pos = __builtin_popcountll(wballot(before));
     if (c.lane < pos) { c.qt = st; c.qd = sd; c.qk = sk; }
     if (c.lane == pos) { c.qt = t_new; c.qd = d_own; c.qk = key; }
     r.q_head_t = lane_get(c.qt, 0);
@@ -1049,7 +1064,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
         // ---- a timer may be due (S2); always taken while draining ----
         PROF(PC_LOOP_TIMER, 1);
         {
-          const int32_t last = failing_retries(c, r, t, tick_t);
+          const int32_t last = r.o_n == 0 ? failing_retries<false>(c, r, t, tick_t) : failing_retries<true>(c, r, t, tick_t);
           PROF(PC_QUIET_RETRIES, 1);
           if (last >= 0) {
             r.t_end = r.t_end > last ? r.t_end : last;
