@@ -181,6 +181,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
   c.nw = (int)(blockDim.x / WAVE);
   c.wid = (int)(threadIdx.x / WAVE);
   c.dyn = dynamic_limit_matters(p, c.flags(), c.slim);
+  c.n_on = p.H0;
   if (c.wid != 0) {
     helper_loop(c);
   } else {

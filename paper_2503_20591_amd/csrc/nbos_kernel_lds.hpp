@@ -103,6 +103,7 @@ struct Ctx {
   int32_t *ovf_dur;          // open loop: [n_sess] durations of queued cells whose timer waits outside the registers
   int nw, wid;               // waves in the workgroup, this wave's number (0 runs the replay)
   bool dyn;                  // the dynamic limit can differ from the replay's cap (see dynamic_limit_matters)
+  int32_t n_on;              // hosts that are on (ready or being provisioned): the wave's own copy of the counter
   static constexpr bool closed = closed_loop_instance(F);
   __device__ __forceinline__ uint32_t flags() const { return instance_flags<F>(p); }
 };
@@ -332,6 +333,7 @@ __device__ __forceinline__ int boot_host(Ctx<F> &c, Regs &r, int32_t now, uint32
   c.fc = c.fc < ra ? c.fc : ra;
   r.min_s = -1;
   c32_add(c.m, c.lane, CS_NON, 1u);
+  c.n_on++;
   c64_add(c.m, c.lane, CL_PROV, -(int64_t)c.p.G * now);
   c32_add(c.m, c.lane, CS_SO, 1u);
   r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
@@ -533,8 +535,7 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
   if (m2 != 0xFFFFFFFFu) { pick2 = (int)(m2 & 1023u); k = 3; }
   const int missing = 3 - k;
   if (missing > 0) {
-    wave_sync();
-    const int n_on = (int)uni(c.m.c32[CS_NON]);
+    const int n_on = c.n_on;
     if (!((c.flags() & NBOS_F_SCALE_OUT) && n_on + missing <= c.p.Hmax)) {
       sess_write_flag(c, r, s, (fl & ~7u) | SS_REJECTED);
       c32_add(c.m, c.lane, CS_REJECTED, 1u);
@@ -557,10 +558,7 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
     }
     hw |= (uint32_t)h << (10 * i);
   }
-  if (missing > 0) {
-    wave_sync();
-    c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
-  }
+  if (missing > 0) c32_max(c.m, c.lane, CS_PEAK, (uint32_t)c.n_on);
   sess_write(c, r, s, hw, 0, (fl & ~7u) | SS_PLACED);
   c32_add(c.m, c.lane, CS_PLACED, 1u);
   c32_add(c.m, c.lane, CS_SUMS, (uint32_t)(3 * g));
@@ -727,10 +725,7 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
   }
   PROF_SUB(PC_A_TARGET);
   bool grow = false;
-  if (tkey == 0xFFFFFFFFu && (c.flags() & NBOS_F_SCALE_OUT)) {
-    wave_sync();
-    grow = (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
-  }
+  if (tkey == 0xFFFFFFFFu && (c.flags() & NBOS_F_SCALE_OUT)) grow = c.n_on < c.p.Hmax;
   if (tkey != 0xFFFFFFFFu || grow) {
     // the replica on the fullest ready host moves (ties: lowest host); booting ones only if all are
     const int any_ready = ok0 | ok1 | ok2;
@@ -777,8 +772,7 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
       wave_sync();
       cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu), now);
       const int h = boot_host(c, r, now, moved);
-      wave_sync();
-      c32_max(c.m, c.lane, CS_PEAK, uni(c.m.c32[CS_NON]));
+      c32_max(c.m, c.lane, CS_PEAK, (uint32_t)c.n_on);
       bind_gpus(c, h, g, now, start + dur);
       c32_add(c.m, c.lane, CS_MIGR, 1u);
       start_cell(c, r, s, hw, fl, victim, h, now, start, t_submit, dur, NBOS_D_SCALE_CELL);
@@ -839,6 +833,7 @@ __device__ __forceinline__ void release_host(Ctx<F> &c, Regs &r, int32_t now) {
   if (c.lane == 0) c.m.ready_at[victim] = NEVER;
   r.min_s = -1;
   c32_add(c.m, c.lane, CS_NON, (uint32_t)-1);
+  c.n_on--;
   c64_add(c.m, c.lane, CL_PROV, (int64_t)c.p.G * now);
   c32_add(c.m, c.lane, CS_SI, 1u);
   decide(c, r, now, NBOS_D_SCALE_IN, 0, 0, (uint32_t)victim);
@@ -909,7 +904,7 @@ __device__ __forceinline__ void tick(Ctx<F> &c, Regs &r, int32_t now) {
     // count as capacity
     const uint32_t per_host = 1000u * (uint32_t)c.p.G;
     const int want = (int)(((uint32_t)c.p.f_milli * sum_c + per_host - 1u) / per_host) + c.p.buffer;
-    int n_on = (int)uni(c.m.c32[CS_NON]);
+    int n_on = c.n_on;
     const int before = n_on;
     while (n_on < want && n_on < c.p.Hmax) {
       const int h = boot_host(c, r, now, 0u);
@@ -981,9 +976,7 @@ __device__ __forceinline__ void retry_lookahead(Ctx<F> &c, const Regs &r) {
 // hosts can be added right now (a failed election then gets a host instead of a place in the queue)
 template <uint32_t F>
 __device__ __forceinline__ bool can_grow(const Ctx<F> &c) {
-  if (!(c.flags() & NBOS_F_SCALE_OUT)) return false;
-  wave_sync();
-  return (int)uni(c.m.c32[CS_NON]) < c.p.Hmax;
+  return (c.flags() & NBOS_F_SCALE_OUT) && c.n_on < c.p.Hmax;
 }
 
 // per lane = sorted timer: it is a retry that is known to fail quietly if it fires now
@@ -1282,6 +1275,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
   c.nw = (int)(blockDim.x / WAVE);
   c.wid = (int)(threadIdx.x / WAVE);
   c.dyn = dynamic_limit_matters(p, c.flags(), c.slim);
+  c.n_on = p.H0;
   Regs r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;
