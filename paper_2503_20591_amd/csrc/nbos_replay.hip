@@ -417,7 +417,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   int maxlds = 0;
   HIP_TRY(hipDeviceGetAttribute(&maxlds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
 #ifdef NBOS_PATH_PROFILE
-  maxlds -= 512;                            // the profile's own counters are static LDS
+  maxlds -= 2 * 8 * PC_N;                   // the profile's own counters are static LDS
 #endif
   sh->in_regs = cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS) && !batch_mode && !closed_loop;
   sh->HP = (cfg->hosts_max + WAVE - 1) / WAVE * WAVE;
