@@ -1092,10 +1092,10 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
         const int32_t now = r.q_head_t;
         const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
         const int32_t dur = lane_get(c.qd, 0);
+        const uint32_t s = key & 0xFFFFu;
+        const int2 cur = m.sess[s];           // (asked for before the pop, which does not touch this record)
         timer_pop(c, r);
         r.t_end = r.t_end > now ? r.t_end : now;
-        const uint32_t s = key & 0xFFFFu;
-        const int2 cur = m.sess[s];
         const uint32_t hw = uni((uint32_t)cur.x), fl = hw;
         if ((key >> 16) != QK_RETRY) {
           end_session(c, r, s, hw, fl, now);
