@@ -81,34 +81,28 @@ __device__ __forceinline__ int committed(const Ctx &c, int h, int32_t now) {
 }
 
 // ready host with the fewest GPUs held at time T that has g idle ones; ties to the lowest index.
-// Returns committed << 10 | host, or 0xFFFFFFFF.
-__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t T, int g) {
+// Returns committed << 10 | host, or 0xFFFFFFFF; then `earliest` is the earliest time at which some host
+// that is on has g idle GPUs if nothing new is allocated: min over hosts of max(ready_at, g-th smallest
+// busy-until time) = max(ready_at, fin[g-1]) (the rows are kept sorted), from the values the scan has read
+// anyway.
+__device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t T, int g, int32_t &earliest) {
   wave_sync();
   uint32_t best = 0xFFFFFFFFu;
+  int32_t first = NEVER;
   for (int h = c.lane; h < c.p.HP; h += WAVE) {
     const int32_t *row = (const int32_t *)&c.m.fin[2 * h];
     const int32_t ra = c.m.ready_at[h];
-    const bool ok = ra <= T && row[g - 1] <= T;
+    const int32_t free_at = row[g - 1];
+    const int32_t y = free_at > ra ? free_at : ra;
+    first = first < y ? first : y;
+    const bool ok = y <= T;
     if (wballot(ok) == 0) continue;              // nobody in this chunk of hosts: leave the rows alone
     const int C = committed(c, h, T);
     if (ok) best = umin(best, ((uint32_t)C << 10) | (uint32_t)h);
   }
-  return wave_min(best);
-}
-
-// earliest time at which some host that is on has g idle GPUs if nothing new is allocated:
-// min over hosts of max(ready_at, g-th smallest busy-until time) = max(ready_at, fin[g-1]).
-__device__ __forceinline__ int32_t earliest_idle(const Ctx &c, int g) {
-  wave_sync();
-  int32_t best = NEVER;
-  for (int h = c.lane; h < c.p.HP; h += WAVE) {
-    const int32_t *row = (const int32_t *)&c.m.fin[2 * h];
-    const int32_t ra = c.m.ready_at[h];
-    int32_t y = row[g - 1];
-    y = y > ra ? y : ra;
-    best = best < y ? best : y;
-  }
-  return (int32_t)wave_min((uint32_t)best);
+  const uint32_t key = wave_min(best);
+  earliest = key == 0xFFFFFFFFu ? (int32_t)wave_min((uint32_t)first) : T;
+  return key;
 }
 
 // Serve the queue up to time `until`: the head gets its GPUs as soon as a host can give them.
@@ -122,8 +116,9 @@ __device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
     int32_t T = t_submit > r.last_T ? t_submit : r.last_T;          // the head meets the scheduler
     if (T > until) break;
     uint32_t key = 0xFFFFFFFFu;
+    int32_t first_free = NEVER;
     if (r.head_E < 0) {
-      key = best_host(c, T, g);
+      key = best_host(c, T, g, first_free);
       if (key == 0xFFFFFFFFu) {
         // nothing at T: ask for one more host (once), then the start time is a closed form
         if ((c.p.flags & NBOS_F_SCALE_OUT) && !r.head_asked) {
@@ -147,16 +142,18 @@ __device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
             }
             r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
             decide(c, r, T, NBOS_D_BATCH_HOST, (uint32_t)s, (uint32_t)h);
+            first_free = first_free < ra ? first_free : ra;     // the new host has all its GPUs idle once it is up
           }
           r.head_asked = true;
         }
-        r.head_E = earliest_idle(c, g);
+        r.head_E = first_free;
       }
     }
     if (key == 0xFFFFFFFFu) {
       if (r.head_E > until) break;                  // still waiting when the next event arrives
       T = r.head_E;
-      key = best_host(c, T, g);
+      int32_t unused;
+      key = best_host(c, T, g, unused);
     }
     // a long queue can push a job beyond the int32 time range: the replay ends as invalid
     if ((int64_t)T + c.p.batch_delay + dur >= 0x7FFFFFFFLL) { r.status = NBOS_E_RANGE; break; }
