@@ -476,11 +476,11 @@ __device__ __forceinline__ void cl_schedule(Ctx<F> &c, Regs &r, uint32_t s, int3
 
 // Placement candidates among this wave's chunks of hosts (Sections 3.2.1, 3.4.1): ready and under the cap;
 // one pass computes every host's key (strided over the lanes), three minima pick the three best
-// (0xFFFFFFFF where there are fewer).
-template <uint32_t F>
+// (0xFFFFFFFF where there are fewer). MAXCH: the most chunks of 64 hosts a wave can have (all 16 for a wave
+// on its own, 4 with MAX_WAVES waves).
+template <int MAXCH, uint32_t F>
 __device__ __forceinline__ void place_part(const Ctx<F> &c, int32_t now, int32_t room, uint32_t &m0, uint32_t &m1,
                                            uint32_t &m2) {
-  constexpr int MAXCH = NBOS_MAX_HOSTS / WAVE;
   uint32_t keys[MAXCH];
 #pragma unroll
   for (int j = 0; j < MAXCH; j++) {
@@ -516,7 +516,8 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
   wave_sync();
   helpers_go(c, HC_PLACE, now, g, room);
   uint32_t m0, m1, m2;
-  place_part(c, now, room, m0, m1, m2);
+  if (c.nw == MAX_WAVES) place_part<NBOS_MAX_HOSTS / WAVE / MAX_WAVES>(c, now, room, m0, m1, m2);
+  else place_part<NBOS_MAX_HOSTS / WAVE>(c, now, room, m0, m1, m2);
   if (c.nw > 1) {
     // the three best of every wave meet in the mail words: the three best of those are the hosts
     if (c.lane == 0) { c.m.mail[8] = (int)m0; c.m.mail[9] = (int)m1; c.m.mail[10] = (int)m2; }
@@ -550,7 +551,7 @@ __device__ __forceinline__ void session_start(Ctx<F> &c, Regs &r, uint32_t s, ui
     int h = i == 0 ? pick0 : (i == 1 ? pick1 : pick2);
     if (i < k) {
       r.min_s = -1;
-      if (c.lane == 0) c.m.hsn[h] += add;
+      if (c.lane == 0) atomicAdd(&c.m.hsn[h], add);          // (one ds_add, nothing to wait for)
       decide(c, r, now, NBOS_D_PLACE, s, (uint32_t)i, (uint32_t)h);
     } else {
       h = boot_host(c, r, now, add);
@@ -577,7 +578,7 @@ __device__ __forceinline__ void end_session(Ctx<F> &c, Regs &r, uint32_t s, uint
   const uint32_t sub = (uint32_t)g | (1u << 16);
   if (c.lane < 3) {
     const int h = (int)((hw >> (10 * c.lane)) & 1023u);
-    c.m.hsn[h] -= sub;                          // three distinct hosts, one lane each
+    atomicSub(&c.m.hsn[h], sub);                // three distinct hosts, one lane each
   }
   r.min_s = -1;
   if (!((c.flags() & NBOS_F_DYNAMIC_SR) && c.dyn)) {
@@ -755,7 +756,7 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
           c32_add(c.m, c.lane, CS_MIGRWARM, 1u);
         }
       }
-      if (c.lane == 0) { c.m.hsn[hv] -= moved; c.m.hsn[dst] += moved; }
+      if (c.lane == 0) { atomicSub(&c.m.hsn[hv], moved); atomicAdd(&c.m.hsn[dst], moved); }
       r.min_s = -1;
       wave_sync();
       cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu), now);
@@ -767,7 +768,7 @@ __device__ __forceinline__ int32_t attempt(Ctx<F> &c, Regs &r, uint32_t s, uint3
     } else {
       // (c) a new host for the cell, Section 3.4.2: reserved and bound before it is up
       const int32_t start = now + c.p.boot + c.p.migr;
-      if (c.lane == 0) c.m.hsn[hv] -= moved;
+      if (c.lane == 0) atomicSub(&c.m.hsn[hv], moved);
       r.min_s = -1;
       wave_sync();
       cap_bound_host_freed(c, hv, (int32_t)(uni(c.m.hsn[hv]) & 0xFFFFu), now);
@@ -873,7 +874,8 @@ __device__ __forceinline__ void helper_loop(const Ctx<F> &c) {
       r0 = (uint32_t)earliest_idle_part(c, g, room, capped);
       r1 = (uint32_t)capped;
     } else if (what == HC_PLACE) {
-      place_part(c, now, room, r0, r1, r2);
+      if (c.nw == MAX_WAVES) place_part<NBOS_MAX_HOSTS / WAVE / MAX_WAVES>(c, now, room, r0, r1, r2);
+      else place_part<NBOS_MAX_HOSTS / WAVE>(c, now, room, r0, r1, r2);
     } else {
       int A, Z;
       tick_part(c, now, A, Z, r2);
