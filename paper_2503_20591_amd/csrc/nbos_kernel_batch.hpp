@@ -40,9 +40,11 @@ struct Lds {
   uint32_t *c32, *hist;
   int4 *fin;
   int32_t *ready_at;
+  int32_t *cmy, *cmh;           // [8][NCH] per request size and chunk of 64 hosts: see chunk_min_rescan
   SessRec *sess;
   uint16_t *fifo;
 };
+constexpr int NCH = NBOS_MAX_HOSTS / WAVE;
 
 struct State {
   uint32_t n_dec, c_total, c_started, c_imm, c_busy;
@@ -80,29 +82,80 @@ __device__ __forceinline__ int committed(const Ctx &c, int h, int32_t now) {
          (NGPU - c.p.G);
 }
 
+// ---- per chunk of 64 hosts and request size g: the earliest time one of its hosts has g GPUs idle ----------
+// y_h(g) = max(ready_at, g-th smallest busy-until time) = max(ready_at, fin[g-1]) (the rows are kept sorted):
+// host h can take a job of g GPUs from y_h(g) on, if nothing new is allocated on it. cmy[g-1][chunk] is the
+// minimum of y_h(g) over the chunk's hosts and cmh the host it sits on (the lowest such host). A job's scan
+// then only looks at the chunks whose minimum is not later than its time, and the earliest time any host
+// can take it is the minimum over at most 16 values. y_h only changes when GPUs of h are allocated (it
+// grows: the minimum of h's chunk moves only if it sat on h) or when h is provisioned (it drops to ready_at).
+__device__ __forceinline__ void chunk_min_rescan(const Ctx &c, int ch, int gi) {
+  const int h = ch * WAVE + c.lane;
+  const int32_t *row = (const int32_t *)&c.m.fin[2 * h];
+  const int32_t ra = c.m.ready_at[h];
+  const int32_t f = row[gi];
+  const int32_t y = f > ra ? f : ra;
+  const int32_t mn = (int32_t)wave_min((uint32_t)y);
+  const int at = (int)__builtin_ctzll(wballot(y == mn));
+  if (c.lane == 0) { c.m.cmy[gi * NCH + ch] = mn; c.m.cmh[gi * NCH + ch] = ch * WAVE + at; }
+}
+
+// GPUs of host h have just been allocated: the minima that sat on h are worked out again (lane g-1 looks)
+__device__ __forceinline__ void chunk_min_host_bound(const Ctx &c, int h) {
+  if (c.p.HP == WAVE) return;                    // one chunk: the scans look at every host anyway
+  wave_sync();
+  const int ch = h >> 6;
+  const bool hit = c.lane < NGPU && c.m.cmh[c.lane * NCH + ch] == h;
+  for (uint64_t w = wballot(hit); w != 0; w &= w - 1) chunk_min_rescan(c, ch, (int)__builtin_ctzll(w));
+}
+
+// host h has just been provisioned, ready at ra, all its GPUs idle
+__device__ __forceinline__ void chunk_min_host_added(const Ctx &c, int h, int32_t ra) {
+  if (c.p.HP == WAVE) return;
+  wave_sync();
+  const int ch = h >> 6;
+  if (c.lane < c.p.G) {
+    const int at = c.lane * NCH + ch;
+    const int32_t mn = c.m.cmy[at];
+    if (ra < mn || (ra == mn && h < c.m.cmh[at])) { c.m.cmy[at] = ra; c.m.cmh[at] = h; }
+  }
+}
+
 // ready host with the fewest GPUs held at time T that has g idle ones; ties to the lowest index.
 // Returns committed << 10 | host, or 0xFFFFFFFF; then `earliest` is the earliest time at which some host
-// that is on has g idle GPUs if nothing new is allocated: min over hosts of max(ready_at, g-th smallest
-// busy-until time) = max(ready_at, fin[g-1]) (the rows are kept sorted), from the values the scan has read
-// anyway.
+// that is on has g idle GPUs if nothing new is allocated.
 __device__ __forceinline__ uint32_t best_host(const Ctx &c, int32_t T, int g, int32_t &earliest) {
   wave_sync();
+  if (c.p.HP == WAVE) {
+    // one chunk: lane = host, both answers from one look
+    const int32_t *row = (const int32_t *)&c.m.fin[2 * c.lane];
+    const int32_t ra = c.m.ready_at[c.lane];
+    const int32_t free_at = row[g - 1];
+    const int32_t y = free_at > ra ? free_at : ra;
+    uint32_t best = 0xFFFFFFFFu;
+    if (wballot(y <= T) != 0) {
+      const int C = committed(c, c.lane, T);
+      if (y <= T) best = ((uint32_t)C << 10) | (uint32_t)c.lane;
+    }
+    const uint32_t key = wave_min(best);
+    earliest = key == 0xFFFFFFFFu ? (int32_t)wave_min((uint32_t)y) : T;
+    return key;
+  }
+  const int32_t mine = c.lane < c.p.HP / WAVE ? c.m.cmy[(g - 1) * NCH + c.lane] : NEVER;
+  uint64_t chunks = wballot(mine <= T);            // the chunks in which somebody can take the job at T
+  if (chunks == 0) { earliest = (int32_t)wave_min((uint32_t)mine); return 0xFFFFFFFFu; }
   uint32_t best = 0xFFFFFFFFu;
-  int32_t first = NEVER;
-  for (int h = c.lane; h < c.p.HP; h += WAVE) {
+  for (; chunks != 0; chunks &= chunks - 1) {
+    const int h = (int)__builtin_ctzll(chunks) * WAVE + c.lane;
     const int32_t *row = (const int32_t *)&c.m.fin[2 * h];
     const int32_t ra = c.m.ready_at[h];
     const int32_t free_at = row[g - 1];
-    const int32_t y = free_at > ra ? free_at : ra;
-    first = first < y ? first : y;
-    const bool ok = y <= T;
-    if (wballot(ok) == 0) continue;              // nobody in this chunk of hosts: leave the rows alone
+    const bool ok = ra <= T && free_at <= T;
     const int C = committed(c, h, T);
     if (ok) best = umin(best, ((uint32_t)C << 10) | (uint32_t)h);
   }
-  const uint32_t key = wave_min(best);
-  earliest = key == 0xFFFFFFFFu ? (int32_t)wave_min((uint32_t)first) : T;
-  return key;
+  earliest = T;
+  return wave_min(best);
 }
 
 // Serve the queue up to time `until`: the head gets its GPUs as soon as a host can give them.
@@ -143,6 +196,7 @@ __device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
             r.lazy_max = r.lazy_max > ra ? r.lazy_max : ra;
             decide(c, r, T, NBOS_D_BATCH_HOST, (uint32_t)s, (uint32_t)h);
             first_free = first_free < ra ? first_free : ra;     // the new host has all its GPUs idle once it is up
+            chunk_min_host_added(c, h, ra);
           }
           r.head_asked = true;
         }
@@ -174,6 +228,7 @@ __device__ __forceinline__ void serve_queue(Ctx &c, State &r, int32_t until) {
       wave_sync();
       if (c.lane < 8) row[k] = nv;
     }
+    chunk_min_host_bound(c, h);
     int b = delay == 0 ? 0 : 32 - __builtin_clz((uint32_t)delay);
     b = b > 31 ? 31 : b;
     if (c.lane == 0) {
@@ -216,6 +271,8 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_batch_kernel(KParams p) {
   m.hist = (uint32_t *)q;           q += 32 * 4;
   m.fin = (int4 *)q;                q += (size_t)p.HP * 32;
   m.ready_at = (int32_t *)q;        q += (size_t)p.HP * 4;
+  m.cmy = (int32_t *)q;             q += NGPU * NCH * 4;
+  m.cmh = (int32_t *)q;             q += NGPU * NCH * 4;
   m.sess = (SessRec *)q;            q += (size_t)p.n_cap * 12;
   m.fifo = (uint16_t *)q;
 
@@ -228,6 +285,10 @@ __global__ void __launch_bounds__(WAVE) nbos_replay_batch_kernel(KParams p) {
   __syncthreads();
 
   Ctx c{p, m, lane, p.n_cap + 1, p.dlog ? p.dlog + (int64_t)rep * p.dlog_stride : nullptr};
+  if (p.HP > WAVE) {
+    for (int ch = 0; ch < p.HP / WAVE; ch++)
+      for (int gi = 0; gi < NGPU; gi++) chunk_min_rescan(c, ch, gi);
+  }
   State r;
   memset(&r, 0, sizeof r);
   r.digest = 0xCBF29CE484222325ULL;

@@ -428,7 +428,7 @@ int32_t choose_kernel(nbos_replay *h, Shape *sh) {
   const size_t n_cap = (size_t)sh->n_cap;
   const bool force_generic = (cfg->flags & NBOS_F_GENERIC_KERNEL) != 0;
   if (batch_mode) {
-    h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + n_cap * 12 + (n_cap + 2) * 2;
+    h->lds_bytes = 64 + 64 + 128 + (size_t)HP * (32 + 4) + 2 * NGPU * batchk::NCH * 4 + n_cap * 12 + (n_cap + 2) * 2;
     if (h->lds_bytes > (size_t)maxlds) return NBOS_E_LIMIT;
     set_kernel(h, (const void *)batchk::nbos_replay_batch_kernel, "batchk::nbos_replay_batch_kernel%.0u", -1, 0u);
   } else if (closed_loop && cfg->hosts_max <= WAVE && !(cfg->flags & NBOS_F_HOSTS_IN_LDS)) {
