@@ -305,6 +305,18 @@ def test_batch_mode_named_workloads(rp, oracle, name, n, hosts):
     assert (st["cells_started"] + st["cells_dropped_busy"] == st["cells_total"]).all()
 
 
+@pytest.mark.parametrize("h0,hmax,name", [(60, 70, "c2"), (64, 66, "c2"), (63, 129, "c5"), (120, 200, "c3")])
+def test_batch_mode_grows_across_chunks_of_hosts(rp, oracle, h0, hmax, name):
+    # the Batch kernel keeps minima per chunk of 64 hosts on clusters of more than 64: hosts are added on
+    # demand into a chunk that was empty, into one that is partly on, and the last chunk is ragged
+    b = tg.workload(name, n_replays=3)
+    as_batch(b, delay=5_000, scale_out=True)
+    b.config.update(hosts_initial=h0, hosts_max=hmax, boot_delay_ms=30_000)
+    st, logs = gpu_run(rp, b, log=True)
+    assert_same(rp, oracle, b, st, logs, check=True)
+    assert st["scale_out_hosts"].max() > 0 and st["cells_queued"].max() > 0
+
+
 def test_batch_mode_time_range(rp, oracle):
     # 30 one-day jobs on a single host: the 25th would end beyond 2^31 - 1 ms. Both sides call the
     # replay invalid (the oracle returns its input error, the kernel sets the replay's status).
