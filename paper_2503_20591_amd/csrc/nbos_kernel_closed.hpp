@@ -186,6 +186,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
     helper_loop(c);
   } else {
   const bool batching = p.batch != 0;
+  PROF_BEGIN();
   int cooldown = 0, backoff = 1;            // timers to fire one by one before the next parallel round: doubles
                                             // (up to 64) while rounds start at most one cell, back to 1 when they pay
 
@@ -243,8 +244,10 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
           if (k >= 2) {
             const uint64_t run = k >= WAVE ? ~0ull : ((1ull << k) - 1ull);
             bool next_lost;
+            PROF(PC_LOOP_ROUND, 1);
             const uint64_t done = batch_round(c, r, run, c.qt, vd, sid, rec, next_lost);
             const int n = __builtin_popcountll(done);
+            PROF(PC_ROUND, n);
             if (n <= 1) { cooldown = backoff; backoff = backoff < 64 ? 2 * backoff : 64; }
             else if (n >= 3) backoff = 1;
             if (next_lost && cooldown == 0) cooldown = 1;     // the next timer's cell has just lost its election
@@ -253,12 +256,14 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
               const int32_t tl = lane_get(c.qt, n - 1);
               r.t_end = r.t_end > tl ? r.t_end : tl;
               cl_after_round(c, r, n);
+              PROF(PC_TIMER_OTHER, n);           // (closed loop: the started cells' next events are scheduled)
               continue;
             }
           }
         }
         if (cooldown > 0) cooldown--;
         // ---- S2: the earliest timer is due ----
+        PROF(PC_LOOP_TIMER, 1);
         const int32_t now = r.q_head_t;
         const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
         const int32_t e = lane_get(c.qd, 0);
@@ -270,19 +275,28 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
         const SessRec cur = m.sess[s];
         const uint32_t hw = uni((uint32_t)cur.x), fl = uni((uint32_t)cur.z);
         const int32_t tm = uni(cur.y);
-        if (kind == QK_END) { end_session(c, r, s, hw, fl, now); continue; }
+        if (kind == QK_END) { end_session(c, r, s, hw, fl, now); PROF(PC_END, 1); continue; }
         r.cl_e = e; r.cl_x = x; r.cl_nx = nx; r.cl_nth = nth;
         const int32_t dur = x & 0x0FFFFFFF;
         if (kind == QK_RETRY) {
+          PROF(PC_LOOP_ATTEMPT, 1);
+          PROF_ATTEMPT_BEGIN(m, r);
           attempt(c, r, s, hw, fl, now, tm, dur);
+          PROF_ATTEMPT_END(m, r, true);
         } else if (((uint32_t)x >> 28 & 3u) == NBOS_EV_CELL) {        // the session submits its next cell (S4-S8)
           r.c_total++;
           const uint32_t st = fl & 7u;
-          if (st == SS_PLACED && tm <= now && !(fl & SF_ENDING)) attempt(c, r, s, hw, fl & ~(SF_QONCE | (15u << 8)), now, now, dur);
-          else if (st == SS_PLACED || st == SS_QUEUED) r.c_busy++;
-          else r.c_unplaced++;
+          if (st == SS_PLACED && tm <= now && !(fl & SF_ENDING)) {
+            PROF(PC_LOOP_ATTEMPT, 1);
+            PROF_ATTEMPT_BEGIN(m, r);
+            attempt(c, r, s, hw, fl & ~(SF_QONCE | (15u << 8)), now, now, dur);
+            PROF_ATTEMPT_END(m, r, false);
+          }
+          else if (st == SS_PLACED || st == SS_QUEUED) { r.c_busy++; PROF(PC_DROP, 1); }
+          else { r.c_unplaced++; PROF(PC_DROP, 1); }
         } else {
           on_session_end(c, r, s, hw, tm, fl, now);     // S9
+          PROF(PC_END, 1);
         }
         continue;
       }
@@ -292,7 +306,9 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
       const uint32_t fl = uni((uint32_t)m.sess[s].z);
       r.t_end = r.t_end > t ? r.t_end : t;
       r.cl_e = (int32_t)(base - ev_lo) + i; r.cl_nx = lane_get(vnx, i); r.cl_nth = lane_get(vnth, i);
+      PROF(PC_LOOP_STARTEND, 1);
       session_start(c, r, s, fl, t);        // S3, S7; a placed session's first event is scheduled there
+      PROF(PC_START, 1);
     }
     if (final) break;
   }
@@ -302,6 +318,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_closed_kernel(KP
   helpers_go(c, HC_EXIT, 0, 0, 0);
   }  // wave 0
   write_stats(p, m, r, rep);
+  PROF_OUT(rep);
 }
 
 }  // namespace ldsk

@@ -5,7 +5,8 @@
 Loads libnbos_pathprofile.so (the product sources compiled with -DNBOS_PATH_PROFILE; built on demand), runs
 each workload once and prints, for the mean replay and for the slowest one, the share of the clocks of the
 wave that runs the replay that each path of the main loop took, how often it ran, and the clocks per run.
-Marshalling and printing only; open-loop replay kernels only (the Batch and closed-loop kernels carry no marks).
+Marshalling and printing only; the open-loop replay kernels and the closed-loop any-size kernel carry the marks
+(there "other timer" is the scheduling of the next events of the cells a round has started; n = those cells).
 The marks cost time themselves, so the launch runs about a tenth longer than the product build's.
 """
 from __future__ import annotations
