@@ -241,7 +241,7 @@ template <class C, class R>
 __device__ __forceinline__ void timer_push(C &c, R &r, int32_t t, uint32_t kind, uint32_t id, int32_t d,
                                            int32_t x = 0, int32_t nx = -1, int32_t nth = 0) {
   uint32_t k = (kind << 16) | id;
-  if (r.q_n == WAVE) {
+  if (__builtin_expect(r.q_n == WAVE, 0)) {
     int32_t mt = lane_get(c.qt, WAVE - 1);
     uint32_t mk = (uint32_t)lane_get((int)c.qk, WAVE - 1);
     if (t < mt || (t == mt && k < mk)) {
@@ -285,7 +285,7 @@ __device__ __forceinline__ void timer_pop(C &c, R &r) {
     c.qnx = __builtin_amdgcn_update_dpp(c.qnx, c.qnx, 0x130, 0xF, 0xF, false);
     c.qnth = __builtin_amdgcn_update_dpp(c.qnth, c.qnth, 0x130, 0xF, 0xF, false);
   }
-  if (r.q_n == 0 && r.o_n > 0) refill(c, r);
+  if (__builtin_expect(r.q_n == 0 && r.o_n > 0, 0)) refill(c, r);
   r.q_head_t = r.q_n > 0 ? lane_get(c.qt, 0) : NEVER;
 }
 

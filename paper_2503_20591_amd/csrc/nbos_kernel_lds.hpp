@@ -1124,7 +1124,7 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   const uint64_t below = bad ? ((1ull << __builtin_ctzll(bad)) - 1ull) : ~0ull;
   next_lost = bad != 0 && ((lost >> __builtin_ctzll(bad)) & 1u) != 0;     // the lane that ends the prefix lost its election
   const uint64_t done = run & below;
-  if (done == 0) return 0;
+  if (__builtin_expect(done == 0, 0)) return 0;
   const bool mine = (done >> c.lane) & 1u;
   const int32_t finish = vt + vd;
   if (mine) {
@@ -1166,7 +1166,7 @@ __device__ __forceinline__ uint64_t batch_round(Ctx<F> &c, Regs &r, uint64_t run
   const unsigned long long pn = c.m.ppow[n];
   const uint64_t pnu = (uint64_t)uni((uint32_t)pn) | ((uint64_t)uni((uint32_t)(pn >> 32)) << 32);
   r.digest = r.digest * pnu + sum;
-  if (c.dlog) {
+  if (__builtin_expect(c.dlog != nullptr, 0)) {
     const int64_t at = (int64_t)r.n_dec + rank;
     if (mine && at < c.p.dlog_stride) c.dlog[at] = code;
   }
@@ -1371,7 +1371,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
     bool hz_known = false;
     int32_t hz = 0;
     for (;;) {
-      if (r.status != NBOS_OK) break;
+      if (__builtin_expect(r.status != NBOS_OK, 0)) break;
       int i = 0;
       int32_t t = NEVER;
       if (todo != 0) { i = (int)__builtin_ctzll(todo); t = lane_get(vt, i); }
@@ -1384,7 +1384,7 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
       if (__builtin_expect(t < due_t, 1)) {
         const uint64_t bit = 1ull << i;
         const uint64_t clean = fastmask & ~r.dirty;
-        if (batching && cooldown == 0 && (clean & bit) != 0) {
+        if (__builtin_expect(batching && cooldown == 0 && (clean & bit) != 0, 1)) {
           // ---- event-parallel round over the run of fast arrivals that starts at lane i ----
           // the run may go on past retries that are known to fail quietly
           int32_t run_due = due_t;
@@ -1395,14 +1395,14 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
           const uint64_t eligible = clean & wballot(vt < run_due);
           const uint64_t blockers = todo & ~eligible;
           const uint64_t run = blockers ? (todo & ((1ull << __builtin_ctzll(blockers)) - 1ull)) : todo;
-          if ((run & (run - 1)) != 0) {          // at least two lanes
+          if (__builtin_expect((run & (run - 1)) != 0, 1)) {          // at least two lanes
             bool next_lost;
             PROF(PC_LOOP_ROUND, 1);
             const uint64_t done = batch_round(c, r, run, vt, vd, sid, rec, next_lost);
             PROF(PC_ROUND, __builtin_popcountll(done));
             // none or one started, or the next arrival has just lost its election: it goes alone
             cooldown = ((done & (done - 1)) == 0 || next_lost) ? 1 : 0;
-            if (done != 0) { todo &= ~done; continue; }
+            if (__builtin_expect(done != 0, 1)) { todo &= ~done; continue; }
           }
         }
         if (cooldown > 0) cooldown--;
@@ -1456,14 +1456,14 @@ __global__ void __launch_bounds__(MAX_WAVES * WAVE) nbos_replay_lds_kernel(KPara
           if (fire_t) fire_t = tick_t <= t;
           if (fire_q && fire_t) { if (r.q_head_t <= tick_t) fire_t = false; else fire_q = false; }
         }
-        if (fire_t) {
+        if (__builtin_expect(fire_t, 0)) {
           tick(c, r, tick_t);
           tick_t += p.scale_iv;
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
           PROF(PC_TICK, 1);
           continue;
         }
-        if (!fire_q) break;                   // only reached while draining: nothing is left
+        if (__builtin_expect(!fire_q, 0)) break;   // only reached while draining: nothing is left
         // (timers fire up to the next arrival, and up to the next auto-scaler period: that one runs after the
         // timers of its own instant and before all later ones)
         if (look_ahead && fire_quiet_retries(c, r, t < tick_t ? t : tick_t, queued_lanes)) {

@@ -976,7 +976,7 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
     const uint64_t cellmask = wballot(base_valid_cell);
     r.slow_lanes = ~fastmask;
     for (;;) {
-      if (r.status != NBOS_OK) break;
+      if (__builtin_expect(r.status != NBOS_OK, 0)) break;
       // ---- runs of arrivals that start at once (S4, S5): cells of idle placed sessions (by the prefetched
       // record, or, where that is stale, by the record as it is now), no timer due first, the election won.
       // A loop of its own with nothing else in it; whatever does not fit leaves the arrival to the general
@@ -1081,14 +1081,14 @@ __global__ void __launch_bounds__(WAVE, 4) nbos_replay_reg_kernel(KParams p) {
           if (fire_t) fire_t = tick_t <= t;
           if (fire_q && fire_t) { if (r.q_head_t <= tick_t) fire_t = false; else fire_q = false; }
         }
-        if (fire_t) {
+        if (__builtin_expect(fire_t, 0)) {
           tick(c, r, tick_t);
           tick_t += p.scale_iv;
           due_t = r.q_head_t < tick_t ? r.q_head_t : tick_t;
           PROF(PC_TICK, 1);
           continue;
         }
-        if (!fire_q) break;                   // only reached while draining: nothing is left
+        if (__builtin_expect(!fire_q, 0)) break;   // only reached while draining: nothing is left
         const int32_t now = r.q_head_t;
         const uint32_t key = (uint32_t)lane_get((int)c.qk, 0);
         const int32_t dur = lane_get(c.qd, 0);
